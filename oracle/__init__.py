@@ -1,0 +1,184 @@
+"""CPU oracle for the encoding-decomposition QNN hot path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes/numpy front for oracle/qnn_oracle.c plus the layer-chaining loop.  Only
+tests/, the smoke check and the benchmark's cpu_baseline leg may import this package;
+the GPU library never does and shares no code with it.
+
+Every function cites the passage of the paper it follows; the C file's header lists
+what pins each of them.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        L = ctypes.CDLL(path)
+        i64, i32, f32 = ctypes.c_int64, ctypes.c_int, ctypes.c_float
+        p = ctypes.c_void_p
+        L.oracle_quantize.argtypes = [p, i64, f32, i32, p, p]
+        L.oracle_quantize16.argtypes = [p, i64, f32, i32, p, p]
+        L.oracle_pack_planes.argtypes = [p, i64, i64, i32, p]
+        L.oracle_unpack_planes.argtypes = [p, i64, i64, i32, p]
+        L.oracle_gemm.argtypes = [p, p, i64, i64, i64, p]
+        L.oracle_gemm8.argtypes = [p, p, i64, i64, i64, p]
+        L.oracle_gemm8_one.argtypes = [p, p, i64]
+        L.oracle_gemm8_one.restype = ctypes.c_int32
+        L.oracle_conv2d8.argtypes = [p, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p]
+        L.oracle_scale.argtypes = [p, p, i64, i64, p]
+        L.oracle_xnor_bitcount_dot.argtypes = [p, p, i64]
+        L.oracle_xnor_bitcount_dot.restype = ctypes.c_int32
+        L.oracle_multibranch_gemm.argtypes = [p, i32, p, i32, i64, i64, i64, p, p]
+        _LIB = L
+    return _LIB
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("oracle %s failed with code %d" % (what, rc))
+
+
+def quantize(x, clip, bits):
+    """Range limit + linear quantizer (Table 1 HTanh, Eq. 15, Eq. 10).
+
+    x: float32 array of any shape.  Returns (levels int16, codes uint8), same shape.
+    level = (2^bits - 1) * q_bits(HTanh(x / clip)), an odd integer.
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    level = np.empty(x.shape, dtype=np.int16)
+    code = np.empty(x.shape, dtype=np.uint8)
+    _check(lib().oracle_quantize16(_ptr(x), x.size, float(np.float32(clip)), int(bits),
+                                   _ptr(level), _ptr(code)), "quantize")
+    return level, code
+
+
+def pack_planes(levels, bits):
+    """Levels [rows][n] -> bit-planes [bits][rows][ceil(n/32)] uint32 (Eq. 4-6, Eq. 10)."""
+    lv = np.ascontiguousarray(levels, dtype=np.int16)
+    assert lv.ndim == 2
+    rows, n = lv.shape
+    nw = (n + 31) // 32
+    planes = np.zeros((bits, rows, nw), dtype=np.uint32)
+    _check(lib().oracle_pack_planes(_ptr(lv), rows, n, int(bits), _ptr(planes)), "pack_planes")
+    return planes
+
+
+def unpack_planes(planes, n):
+    """Decode bit-planes back to levels: v = sum_j 2^j c_j, c_j in {-1,+1} (Eq. 10)."""
+    pl = np.ascontiguousarray(planes, dtype=np.uint32)
+    bits, rows, nw = pl.shape
+    assert nw == (n + 31) // 32
+    level = np.empty((rows, n), dtype=np.int16)
+    _check(lib().oracle_unpack_planes(_ptr(pl), rows, n, bits, _ptr(level)), "unpack_planes")
+    return level
+
+
+def gemm(a_levels, w_levels):
+    """acc[r][c] = sum_t a[r][t] * w[c][t] on decoded levels (Eq. 1-2).  int32 out."""
+    a = np.ascontiguousarray(a_levels)
+    w = np.ascontiguousarray(w_levels)
+    rows, n = a.shape
+    cols, n2 = w.shape
+    assert n == n2
+    acc = np.empty((rows, cols), dtype=np.int32)
+    if a.dtype == np.int8 and w.dtype == np.int8:
+        _check(lib().oracle_gemm8(_ptr(a), _ptr(w), rows, cols, n, _ptr(acc)), "gemm8")
+    else:
+        a = np.ascontiguousarray(a, dtype=np.int16)
+        w = np.ascontiguousarray(w, dtype=np.int16)
+        _check(lib().oracle_gemm(_ptr(a), _ptr(w), rows, cols, n, _ptr(acc)), "gemm")
+    return acc
+
+
+def gemm_one(a_row, w_row):
+    """One GEMM output (for sampled checks at sizes where the full loop is slow)."""
+    a = np.ascontiguousarray(a_row, dtype=np.int8)
+    w = np.ascontiguousarray(w_row, dtype=np.int8)
+    assert a.shape == w.shape and a.ndim == 1
+    return int(lib().oracle_gemm8_one(_ptr(a), _ptr(w), a.size))
+
+
+def conv2d(a_levels, w_levels, stride, pad):
+    """Zero-padded convolution on decoded levels.  a: [B][H][W][Cin] int8, w:
+    [Cout][kh][kw][Cin] int8 -> int32 [B][Ho][Wo][Cout] (Section "Model Decomposition")."""
+    a = np.ascontiguousarray(a_levels, dtype=np.int8)
+    w = np.ascontiguousarray(w_levels, dtype=np.int8)
+    B, H, W, Cin = a.shape
+    Cout, kh, kw, Cin2 = w.shape
+    assert Cin == Cin2
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    acc = np.empty((B, Ho, Wo, Cout), dtype=np.int32)
+    _check(lib().oracle_conv2d8(_ptr(a), _ptr(w), B, H, W, Cin, Cout, kh, kw, stride, pad,
+                                _ptr(acc)), "conv2d")
+    return acc
+
+
+def scale(acc, scale_vec):
+    """out = (float)acc * scale[c]: the decoder's scale factor (1/alpha^2 of Section
+    "M-bit Encoding Functions", Eq. 18), one fp32 factor per output channel."""
+    a = np.ascontiguousarray(acc, dtype=np.int32)
+    s = np.ascontiguousarray(scale_vec, dtype=np.float32)
+    cols = a.shape[-1]
+    assert s.shape == (cols,)
+    out = np.empty(a.shape, dtype=np.float32)
+    _check(lib().oracle_scale(_ptr(a), _ptr(s), a.size // cols, cols, _ptr(out)), "scale")
+    return out
+
+
+def xnor_bitcount_dot(a_words, b_words, n):
+    """Binary dot of two {-1,+1}^n bit-vectors: 2*bitcount(xnor) - n (self-test helper)."""
+    a = np.ascontiguousarray(a_words, dtype=np.uint32)
+    b = np.ascontiguousarray(b_words, dtype=np.uint32)
+    return int(lib().oracle_xnor_bitcount_dot(_ptr(a), _ptr(b), n))
+
+
+def multibranch_gemm(a_planes, w_planes, n, want_branches=False):
+    """Literal M x K multi-branch binary product (Eq. 9 + Eq. 10, Fig. 1) on planes as
+    written by pack_planes (self-test helper; the GEMM oracle is gemm())."""
+    ap = np.ascontiguousarray(a_planes, dtype=np.uint32)
+    wp = np.ascontiguousarray(w_planes, dtype=np.uint32)
+    a_bits, rows, nw = ap.shape
+    w_bits, cols, nw2 = wp.shape
+    assert nw == nw2 == (n + 31) // 32
+    acc = np.empty((rows, cols), dtype=np.int32)
+    br = np.empty((rows, cols, w_bits, a_bits), dtype=np.int32) if want_branches else None
+    _check(lib().oracle_multibranch_gemm(_ptr(ap), a_bits, _ptr(wp), w_bits, rows, cols, n,
+                                         _ptr(acc), _ptr(br) if want_branches else None),
+           "multibranch_gemm")
+    return (acc, br) if want_branches else acc
+
+
+def conv_stack(x, layers):
+    """Chain of quantized convolutions (inference by multi-branch binary layers one after
+    another: Introduction; Section "Quantized Networks Training").
+
+    x: float32 [B][H][W][C].  layers: list of dicts with keys w (int8 levels
+    [Cout][kh][kw][Cin]), scale (float32 [Cout]), clip (float), a_bits, stride, pad.
+    Per layer: quantize(x, clip, a_bits) -> conv2d -> scale -> next x.
+    Returns a list of per-layer dicts {levels, acc, out}.
+    """
+    trace = []
+    cur = np.ascontiguousarray(x, dtype=np.float32)
+    for L in layers:
+        assert 1 <= L["a_bits"] <= 7, "int8 level path holds up to 7 bits"
+        lv, _ = quantize(cur, L["clip"], L["a_bits"])
+        acc = conv2d(lv.astype(np.int8), L["w"], L["stride"], L["pad"])
+        out = scale(acc, L["scale"])
+        trace.append({"levels": lv, "acc": acc, "out": out})
+        cur = out
+    return trace

@@ -1,0 +1,139 @@
+"""Seeded synthetic inputs for the five benchmark / parity configurations.
+
+Shared by the CPU oracle's tests and the GPU library's tests and benchmark, so both
+sides see identical tensors.  This module holds no arithmetic of the method beyond
+naming the level set (odd integers in [-(2^b - 1), 2^b - 1], Eq. 10 of the paper):
+it only draws random numbers and names shapes.
+
+The paper evaluates on CIFAR-10, ImageNet and VOC; none of those (nor trained
+weights) are used here.  The binary-product path is data independent in time, so
+tensors with the networks' layer shapes and the stated value distributions stand in.
+
+Seeds: numpy Generator(PCG64(190513389 + 1000 * config_index + tensor_index)).
+"""
+import numpy as np
+
+BASE_SEED = 190513389
+
+
+def rng(config_index, tensor_index):
+    return np.random.Generator(np.random.PCG64(BASE_SEED + 1000 * config_index + tensor_index))
+
+
+def odd_levels(gen, shape, bits, dtype=np.int8):
+    """Uniform draw over the 2^bits odd levels {-(2^b-1), ..., -1, 1, ..., 2^b-1}."""
+    top = (1 << bits) - 1
+    u = gen.integers(0, top + 1, size=shape, dtype=np.int64)
+    return (2 * u - top).astype(dtype)
+
+
+def channel_scales(gen, cols, lo=0.01, hi=0.1):
+    return gen.uniform(lo, hi, size=cols).astype(np.float32)
+
+
+# --------------------------------------------------------------------------- config 1
+def fc_2x2(config_index=0):
+    """Single FC layer, 2-bit weights and activations: A [64][512], W [256][512]."""
+    a = odd_levels(rng(config_index, 0), (64, 512), 2)
+    w = odd_levels(rng(config_index, 1), (256, 512), 2)
+    s = channel_scales(rng(config_index, 2), 256)
+    return {"a": a, "w": w, "scale": s, "a_bits": 2, "w_bits": 2}
+
+
+# --------------------------------------------------------------------------- config 2
+def gemm_square(w_bits, a_bits, size=4096, config_index=1):
+    """Square binary-decomposed GEMM operands: A [size][size], W [size][size] levels."""
+    a = odd_levels(rng(config_index, 10 * a_bits + 0), (size, size), a_bits)
+    w = odd_levels(rng(config_index, 10 * w_bits + 1), (size, size), w_bits)
+    s = channel_scales(rng(config_index, 2), size)
+    return {"a": a, "w": w, "scale": s, "a_bits": a_bits, "w_bits": w_bits}
+
+
+def gemm_float_activations(rows, n, config_index=1, tensor_index=5):
+    """fp32 activations ~N(0,1) for the encode step of the GEMM workload."""
+    return rng(config_index, tensor_index).standard_normal((rows, n), dtype=np.float32)
+
+
+# --------------------------------------------------------------------------- config 3
+def resnet_conv_2x2(batch=64, hw=56, cin=64, cout=64, config_index=2):
+    """ResNet-18-shaped 3x3 conv, stride 1, pad 1; fp32 NHWC input ~N(0,1), clip = 3 sigma
+    (sigma = float64 std of the generated tensor, rounded once to fp32)."""
+    x = rng(config_index, 0).standard_normal((batch, hw, hw, cin), dtype=np.float32)
+    w = odd_levels(rng(config_index, 1), (cout, 3, 3, cin), 2)
+    s = channel_scales(rng(config_index, 2), cout)
+    clip = float(np.float32(3.0 * np.std(x.astype(np.float64))))
+    return {"x": x, "w": w, "scale": s, "clip": clip, "a_bits": 2, "w_bits": 2,
+            "stride": 1, "pad": 1}
+
+
+# --------------------------------------------------------------------------- configs 4, 5
+def _uniform_level_variance(bits):
+    # variance of a uniform draw over the odd levels of `bits` bits: (4^b - 1) / 3
+    return (4.0 ** bits - 1.0) / 3.0
+
+
+def _gaussian_level_variance(bits, clip_sigmas=3.0):
+    # variance, in level units, of a unit-variance Gaussian put through a `bits`-bit ladder
+    # that clips at clip_sigmas: slope^2 plus the rounding noise of a step of 2 levels
+    top = (1 << bits) - 1
+    return (top / clip_sigmas) ** 2 + 1.0 / 3.0
+
+
+def _stack_layer(gen_w, gen_s, cin, cout, bits, stride, clip):
+    w = odd_levels(gen_w, (cout, 3, 3, cin), bits)
+    n = 9 * cin
+    # keep the post-scale activations near unit variance so that a fixed clip of 3.0 keeps
+    # exercising every level (and a little saturation) layer after layer
+    g = gen_s.uniform(0.5, 1.5, size=cout)
+    s = (g / np.sqrt(n * _uniform_level_variance(bits) * _gaussian_level_variance(bits)))
+    return {"w": w, "scale": s.astype(np.float32), "clip": float(clip), "a_bits": bits,
+            "w_bits": bits, "stride": stride, "pad": 1, "cin": cin, "cout": cout}
+
+
+RESNET18_PLAN = (
+    # (cin, cout, stride) for the 16 quantized 3x3 convs; the stem conv and the FC head are
+    # unquantized in the source network and are not part of this workload.
+    (64, 64, 1), (64, 64, 1), (64, 64, 1), (64, 64, 1),
+    (64, 128, 2), (128, 128, 1), (128, 128, 1), (128, 128, 1),
+    (128, 256, 2), (256, 256, 1), (256, 256, 1), (256, 256, 1),
+    (256, 512, 2), (512, 512, 1), (512, 512, 1), (512, 512, 1),
+)
+
+
+def resnet18_stack(batch=256, hw=56, bits=3, config_index=3, plan=RESNET18_PLAN):
+    """ResNet-18-shaped chain of quantized 3x3 convs; input at the stem's output shape."""
+    x = rng(config_index, 0).standard_normal((batch, hw, hw, plan[0][0]), dtype=np.float32)
+    layers = []
+    for li, (cin, cout, stride) in enumerate(plan):
+        layers.append(_stack_layer(rng(config_index, 10 + 2 * li), rng(config_index, 11 + 2 * li),
+                                   cin, cout, bits, stride, 3.0))
+    return {"x": x, "layers": layers}
+
+
+VGG_SSD_PLAN = (
+    # resolution groups of the VGG16-backbone detection stack: (hw, [(cin, cout), ...])
+    (300, ((64, 64),)),
+    (150, ((64, 128), (128, 128))),
+    (75, ((128, 256), (256, 256), (256, 256))),
+    (38, ((256, 512), (512, 512), (512, 512))),
+    (19, ((512, 512), (512, 512), (512, 512))),
+)
+
+
+def vgg_ssd_stack(batch=32, bits=4, config_index=4, plan=VGG_SSD_PLAN):
+    """Detection-style stack: per resolution group a fresh N(0,1) fp32 input (clip = 3 sigma)
+    feeding a chain of 3x3 stride-1 convs (pooling between groups is not modelled)."""
+    groups = []
+    t = 0
+    for gi, (hw, chans) in enumerate(plan):
+        x = rng(config_index, 100 + gi).standard_normal((batch, hw, hw, chans[0][0]),
+                                                        dtype=np.float32)
+        clip0 = float(np.float32(3.0 * np.std(x.astype(np.float64))))
+        layers = []
+        for li, (cin, cout) in enumerate(chans):
+            L = _stack_layer(rng(config_index, 10 + 2 * t), rng(config_index, 11 + 2 * t),
+                             cin, cout, bits, 1, clip0 if li == 0 else 3.0)
+            layers.append(L)
+            t += 1
+        groups.append({"x": x, "layers": layers})
+    return groups
