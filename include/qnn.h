@@ -1,0 +1,138 @@
+/*
+ * qnn.h -- C ABI of the MI355X (gfx950) library for the hot path of encoding-decomposition
+ * quantized networks ("Multi-Precision Quantized Neural Networks via Encoding Decomposition
+ * of {-1,+1}").
+ *
+ * An M-bit weight and a K-bit activation are each a sum of 2^i-weighted {-1,+1} planes
+ * (paper, Eq. 10), so a quantized GEMM / convolution is M x K binary products done with
+ * xor + bitcount on packed bit-vectors and recombined with 2^(i+j) (Eq. 9, Fig. 1), then
+ * multiplied by a scale factor (the 1/alpha^2 of the section "M-bit Encoding Functions",
+ * Eq. 18).
+ *
+ * Naming.  The paper calls the bit widths M and K (and swaps which is which between
+ * sections); here they are always `w_bits` (weights) and `a_bits` (activations).
+ *
+ * Data conventions (all entry points)
+ *   level  odd integer v = 2u - (2^b - 1), u in [0, 2^b - 1] its code (Eq. 10; remark after
+ *          Eq. 20: odd, |v| <= 2^b - 1).
+ *   planes uint32 bit-vectors along the reduction axis: plane j holds bit j of u (j = 0 is
+ *          the low bit, weight 2^0); bit 1 <=> +1, bit 0 <=> -1 (Table 2, x = x1 + 2 x2).
+ *          nw = ceil(n/32) words per row; bit t of word k is element 32k + t; PAD BITS ARE 0
+ *          in every plane of both operands.
+ *          activations: [a_bits][rows][nw];  weights: [w_bits][cols][nw].
+ *
+ * Pointers.  Every pointer marked DEVICE is device memory owned by the caller; the library
+ * never allocates, frees or keeps it.  `stream` is a hipStream_t passed as void* (NULL = the
+ * null stream).  Every call only enqueues work on `stream` and returns; outputs are valid
+ * after that stream has been synchronised.  Plane / accumulator / output pointers must be
+ * 16-byte aligned.
+ *
+ * Errors.  Return value 0 = QNN_OK, otherwise a negative QNN_ERR_* code; argument errors are
+ * found on the host before any HIP call is made (nothing is enqueued then).
+ * qnn_last_error() returns a thread-local message for the last failing call on this thread.
+ */
+#ifndef QNN_H_
+#define QNN_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QNN_OK 0
+#define QNN_ERR_INVALID_ARG (-1) /* null pointer, size < 0, bits outside [1,8], bad clip   */
+#define QNN_ERR_UNSUPPORTED (-2) /* dtype / kernel size / combination that is not built     */
+#define QNN_ERR_ALIGNMENT (-3)   /* pointer not 16-byte aligned                             */
+#define QNN_ERR_RANGE (-4)       /* n (2^w_bits - 1)(2^a_bits - 1) >= 2^31: int32 overflow  */
+#define QNN_ERR_LAUNCH (-5)      /* the HIP runtime refused the launch                      */
+
+#define QNN_DTYPE_F32 0  /* IEEE fp32 values                                   */
+#define QNN_DTYPE_BF16 1 /* bfloat16 values (widened exactly to fp32 first)    */
+#define QNN_DTYPE_I8 2   /* int8 levels (already quantized odd integers)       */
+
+/*
+ * qnn_encode_pack -- range limit, linear quantizer, plane split and bit-vector packing
+ * (Table 1 HTanh; Eq. 15; Eq. 10; Table 2; "stored by bit vectors", Introduction).
+ *
+ * For fp inputs, in fp32, one correctly rounded operation per step:
+ *   t = x * (1.0f / clip);  t = min(max(t, -1), 1);  h = (2^bits - 1) / 2;
+ *   u = floor(fma(t, h, h) + 0.5f), clamped to [0, 2^bits - 1]      (round half up)
+ * so x = 0 maps to level +1 and |x| >= clip saturates.  NaN inputs give an unspecified code.
+ * For QNN_DTYPE_I8 the input already holds levels: u = (v + 2^bits - 1) / 2; even or
+ * out-of-range levels are the caller's error and give unspecified planes. `clip` is ignored.
+ *
+ *   src     DEVICE, [rows] rows of n elements, consecutive rows `row_stride_elems` apart
+ *   planes  DEVICE out, [bits][rows][ceil(n/32)] uint32, pad bits written as 0
+ * rows == 0 or n == 0 is a successful no-op.
+ */
+int qnn_encode_pack(const void *src, int dtype, int64_t rows, int64_t n,
+                    int64_t row_stride_elems, float clip, int bits, uint32_t *planes,
+                    void *stream);
+
+/*
+ * qnn_binary_gemm -- the M x K multi-branch binary product and its recombination
+ * (Eq. 7-9 with Eq. 10; Fig. 1):
+ *   P_ij[r][c] = bitcount(W_i[c][:] xor A_j[r][:])           (binary dot y_ij = n - 2 P_ij)
+ *   acc[r][c]  = sum_ij 2^(i+j) y_ij = n (2^w_bits-1)(2^a_bits-1) - 2 sum_ij 2^(i+j) P_ij
+ * which equals the integer dot product of the decoded levels of row r of A and row c of W.
+ * Optionally fused with the scale of qnn_dequant_scale: out[r][c] = (float)acc[r][c]*scale[c].
+ *
+ *   a_planes DEVICE [a_bits][rows][nw], w_planes DEVICE [w_bits][cols][nw], nw = ceil(n/32)
+ *   acc      DEVICE out int32 [rows][cols], or NULL
+ *   scale    DEVICE fp32 [cols]; required iff out != NULL
+ *   out      DEVICE out fp32 [rows][cols], or NULL         (acc and out not both NULL)
+ * Bit widths 1..4 x 1..4 run register-blocked kernels; wider ones a plain kernel.
+ */
+int qnn_binary_gemm(const uint32_t *a_planes, int a_bits, const uint32_t *w_planes, int w_bits,
+                    int64_t rows, int64_t cols, int64_t n, int32_t *acc, const float *scale,
+                    float *out, void *stream);
+
+/*
+ * qnn_dequant_scale -- the decoder's scale factor (section "M-bit Encoding Functions": the
+ * product of two encoded vectors is alpha^2 times too large, 1/9 in Fig. 1; Eq. 18), one
+ * fp32 factor per output channel: out[r][c] = (float)acc[r][c] * scale[c], one int->fp32
+ * conversion and one fp32 multiply.
+ *   acc DEVICE int32 [rows][cols]; scale DEVICE fp32 [cols]; out DEVICE fp32 [rows][cols]
+ */
+int qnn_dequant_scale(const int32_t *acc, const float *scale, int64_t rows, int64_t cols,
+                      float *out, void *stream);
+
+/*
+ * qnn_conv2d -- the same multi-branch product with the reduction axis gathered implicitly
+ * from an NHWC bit-plane tensor (section "Model Decomposition": convolution layers reduce to
+ * the same vector product).  Reduction axis = (ky, kx, ci); channels are the packed axis,
+ * cw = ceil(Cin/32) words per pixel.  Taps outside the image contribute exactly 0 to acc
+ * (zero padding of the decoded integers; 0 is not itself a level).
+ *   Ho = (H + 2 pad - kh)/stride + 1, Wo likewise (floor).
+ *
+ *   a_planes DEVICE [a_bits][B][H][W][cw]
+ *   w_planes DEVICE [w_bits][Cout][kh][kw][cw]
+ *   scale    DEVICE fp32 [Cout]; required iff out or next_planes is given
+ *   acc      DEVICE out int32 [B][Ho][Wo][Cout], or NULL
+ *   out      DEVICE out fp32  [B][Ho][Wo][Cout], or NULL
+ *   next_planes DEVICE out [next_bits][B][Ho][Wo][ceil(Cout/32)], or NULL: the fused epilogue
+ *            out -> qnn_encode_pack(out, clip = next_clip, bits = next_bits), so the next
+ *            layer's planes are produced without the accumulator leaving the chip.
+ * At least one of acc / out / next_planes must be given.  kh, kw in [1,7].
+ */
+typedef struct qnn_conv_desc {
+    int64_t B, H, W, Cin, Cout;
+    int32_t kh, kw, stride, pad;
+    int32_t a_bits, w_bits;
+} qnn_conv_desc;
+
+int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32_t *w_planes,
+               const float *scale, int32_t *acc, float *out, uint32_t *next_planes,
+               float next_clip, int next_bits, void *stream);
+
+/* Message for the last error returned on the calling thread ("" if none). Never NULL. */
+const char *qnn_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int qnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QNN_H_ */

@@ -39,8 +39,14 @@ def lib():
         L.oracle_xnor_bitcount_dot.argtypes = [p, p, i64]
         L.oracle_xnor_bitcount_dot.restype = ctypes.c_int32
         L.oracle_multibranch_gemm.argtypes = [p, i32, p, i32, i64, i64, i64, p, p]
+        L.oracle_num_threads.restype = ctypes.c_int
         _LIB = L
     return _LIB
+
+
+def num_threads():
+    """Threads the row-parallel oracle loops use (reported with the CPU baseline)."""
+    return int(lib().oracle_num_threads())
 
 
 def _ptr(a):

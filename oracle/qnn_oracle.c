@@ -288,3 +288,11 @@ int oracle_multibranch_gemm(const uint32_t *a_planes, int a_bits, const uint32_t
     }
     return 0;
 }
+
+/* Number of OpenMP threads the row-parallel loops above use (for benchmark reports). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif

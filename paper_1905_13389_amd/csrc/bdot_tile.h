@@ -1,0 +1,154 @@
+// Register-blocked xor + bitcount tile engine shared by the binary GEMM and the implicit-im2col
+// binary convolution (paper: Eq. 9 with the {-1,+1} code of Eq. 10; "xnor and bitcount").
+//
+// A workgroup of 256 lanes (4 wave64) owns a BM x BN block of outputs, BM = 16*TM rows,
+// BN = 16*TN columns.  Lane (ty, tx) owns rows ty + 16*i and columns tx + 16*n, so that within
+// a wave the activation reads are 4 broadcast addresses and the weight reads are 16 distinct
+// LDS rows whose stride (20 words) spreads them over all banks.
+//
+// For every 32-bit word of the reduction axis and every (weight plane i, activation plane j)
+// the lane issues one v_xor_b32 and one v_bcnt_u32_b32 whose add operand is the running count,
+// so the inner loop holds nothing but those two instructions and the LDS reads feeding them.
+// Counts of plane pairs with equal i + j share one accumulator P_s (s = i + j): the
+// recombination sum_ij 2^(i+j) y_ij, y_ij = n - 2 P_ij, becomes
+//     acc = n (2^WB - 1)(2^AB - 1) - 2 sum_s 2^s P_s
+// applied once in the epilogue, with WB + AB - 1 accumulators per output instead of WB * AB.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qnn {
+
+constexpr int kTileThreads = 256;
+constexpr int kBK = 16;  // reduction words staged per step (64 bytes per row and plane)
+constexpr int kBKP = 20; // LDS row stride in words: 16-byte aligned, odd multiple of 4
+
+// KV = reduction words fetched from LDS per read (4: ds_read_b128, 2: ds_read_b64); the lane keeps
+// KV * (TM*AB + TN*WB) operand registers next to its TM*TN*(WB+AB-1) counters.
+template <int WB, int AB, int TM, int TN, int KV = 4> struct Tile {
+    static_assert(KV == 2 || KV == 4, "KV is 2 or 4 words");
+    static constexpr int BM = 16 * TM;
+    static constexpr int BN = 16 * TN;
+    static constexpr int S = WB + AB - 1;
+    static constexpr int A_ROWPLANES = AB * BM;
+    static constexpr int W_ROWPLANES = WB * BN;
+    static constexpr int A_UNITS = A_ROWPLANES * (kBK / 4); // one unit = 4 words of one row-plane
+    static constexpr int W_UNITS = W_ROWPLANES * (kBK / 4);
+    static constexpr int A_PER_THREAD = (A_UNITS + kTileThreads - 1) / kTileThreads;
+    static constexpr int W_PER_THREAD = (W_UNITS + kTileThreads - 1) / kTileThreads;
+    static constexpr int A_WORDS = A_ROWPLANES * kBKP;
+    static constexpr int STAGE_WORDS = (A_ROWPLANES + W_ROWPLANES) * kBKP;
+};
+
+// Lane tile per (w_bits, a_bits): TM*TN*(WB+AB-1) counters plus KV*(TM*AB + TN*WB) operand
+// registers must stay well inside the 256-register budget of a lane (2 waves per SIMD).
+template <int WB, int AB> struct TilePick { static constexpr int TM = 4, TN = 4, KV = (WB + AB >= 7 ? 2 : 4); };
+template <> struct TilePick<1, 1> { static constexpr int TM = 8, TN = 8, KV = 4; };
+template <> struct TilePick<1, 2> { static constexpr int TM = 8, TN = 4, KV = 4; };
+template <> struct TilePick<2, 1> { static constexpr int TM = 4, TN = 8, KV = 4; };
+template <> struct TilePick<2, 2> { static constexpr int TM = 8, TN = 4, KV = 4; };
+template <> struct TilePick<1, 3> { static constexpr int TM = 4, TN = 8, KV = 4; };
+template <> struct TilePick<3, 1> { static constexpr int TM = 8, TN = 4, KV = 4; };
+
+// Workgroup id -> tile id so that the workgroups an XCD receives (ids congruent mod 8 under
+// round-robin dispatch) cover one contiguous band of tiles and share operands in that XCD's L2.
+__device__ __forceinline__ int64_t xcd_band_remap(int64_t pid, int64_t nblocks)
+{
+    constexpr int64_t kXcds = 8;
+    if (nblocks < 2 * kXcds) return pid;
+    const int64_t xcd = pid % kXcds, local = pid / kXcds;
+    const int64_t per = (nblocks + kXcds - 1) / kXcds;
+    const int64_t rem = nblocks % kXcds;
+    const int64_t tall = rem == 0 ? kXcds : rem; // XCDs that receive `per` workgroups
+    if (xcd < tall) return xcd * per + local;
+    return tall * per + (xcd - tall) * (per - 1) + local;
+}
+
+// 4 reduction words of one row of a [plane][R][nw] row-major plane tensor; words past nw and
+// rows past R read as 0 (a zero word xors to the other operand's zero word: no contribution).
+__device__ __forceinline__ uint4 load_rowmajor4(const uint32_t *__restrict__ base, int64_t R,
+                                                int64_t nw, int plane, int64_t row, int64_t kword,
+                                                bool vec)
+{
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (row < R && kword < nw) {
+        const uint32_t *p = base + ((int64_t)plane * R + row) * nw + kword;
+        if (vec) {
+            v = *reinterpret_cast<const uint4 *>(p);
+        } else {
+            v.x = p[0];
+            if (kword + 1 < nw) v.y = p[1];
+            if (kword + 2 < nw) v.z = p[2];
+            if (kword + 3 < nw) v.w = p[3];
+        }
+    }
+    return v;
+}
+
+// count += bitcount(w xor a): exactly one v_xor_b32 and one v_bcnt_u32_b32 (whose third operand
+// is the running count).  Written as one asm statement so that the compiler can neither
+// re-associate the count chain into extra adds nor keep hundreds of xor results alive.
+__device__ __forceinline__ void xor_bcnt_acc(uint32_t w, uint32_t a, uint32_t &count)
+{
+    uint32_t t;
+    asm("v_xor_b32 %0, %2, %3\n\tv_bcnt_u32_b32 %1, %0, %1" : "=&v"(t), "+v"(count) : "v"(w), "v"(a));
+}
+
+// The xor + bitcount block: one kBK-word stage out of LDS into the P_s accumulators.
+template <int KV> __device__ __forceinline__ void lds_read_words(const uint32_t *p, uint32_t (&dst)[KV])
+{
+    if constexpr (KV == 4) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+        dst[0] = v.x, dst[1] = v.y, dst[2] = v.z, dst[3] = v.w;
+    } else {
+        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+        dst[0] = v.x, dst[1] = v.y;
+    }
+}
+
+template <int WB, int AB, int TM, int TN, int KV>
+__device__ __forceinline__ void tile_mac(const uint32_t *__restrict__ As,
+                                         const uint32_t *__restrict__ Ws, int ty, int tx,
+                                         uint32_t (&P)[TM][TN][WB + AB - 1])
+{
+    using T = Tile<WB, AB, TM, TN, KV>;
+#pragma unroll 1
+    for (int kq = 0; kq < kBK / KV; ++kq) {
+        uint32_t a[TM][AB][KV];
+        uint32_t w[TN][WB][KV];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < AB; ++j)
+                lds_read_words<KV>(As + (j * T::BM + ty + 16 * i) * kBKP + KV * kq, a[i][j]);
+#pragma unroll
+        for (int n = 0; n < TN; ++n)
+#pragma unroll
+            for (int j = 0; j < WB; ++j)
+                lds_read_words<KV>(Ws + (j * T::BN + tx + 16 * n) * kBKP + KV * kq, w[n][j]);
+#pragma unroll
+        for (int kk = 0; kk < KV; ++kk)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int n = 0; n < TN; ++n)
+#pragma unroll
+                    for (int wi = 0; wi < WB; ++wi)
+#pragma unroll
+                        for (int aj = 0; aj < AB; ++aj)
+                            xor_bcnt_acc(w[n][wi][kk], a[i][aj][kk], P[i][n][wi + aj]);
+    }
+}
+
+// acc = n_times_top - 2 sum_s 2^s P_s, in wrap-around 32-bit arithmetic (the true value fits
+// int32, checked on the host, so the wrapped result is exact).
+template <int S> __device__ __forceinline__ int32_t recombine(const uint32_t (&P)[S], uint32_t n_times_top)
+{
+    uint32_t sum = 0;
+#pragma unroll
+    for (int s = 0; s < S; ++s) sum += P[s] << s;
+    return (int32_t)(n_times_top - 2u * sum);
+}
+
+} // namespace qnn

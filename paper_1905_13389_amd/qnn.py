@@ -1,0 +1,150 @@
+"""ctypes binding of libqnn.so: same names and argument order as include/qnn.h.
+
+Marshalling only.  Tensors are torch CUDA tensors used as device-memory handles; the stream is
+torch's current stream.  There is no CPU fallback: a missing library or a failing call raises.
+"""
+import ctypes
+import os
+
+import torch  # loads the HIP runtime that libqnn.so binds to
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqnn.so")
+
+QNN_OK = 0
+QNN_ERR_INVALID_ARG = -1
+QNN_ERR_UNSUPPORTED = -2
+QNN_ERR_ALIGNMENT = -3
+QNN_ERR_RANGE = -4
+QNN_ERR_LAUNCH = -5
+
+QNN_DTYPE_F32 = 0
+QNN_DTYPE_BF16 = 1
+QNN_DTYPE_I8 = 2
+
+EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d",
+           "qnn_last_error", "qnn_version")
+
+
+class QnnError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("libqnn error %d: %s" % (code, message))
+        self.code = code
+
+
+class qnn_conv_desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
+                ("Cin", ctypes.c_int64), ("Cout", ctypes.c_int64),
+                ("kh", ctypes.c_int32), ("kw", ctypes.c_int32), ("stride", ctypes.c_int32),
+                ("pad", ctypes.c_int32), ("a_bits", ctypes.c_int32), ("w_bits", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library.  Built in-tree beforehand; if the file is missing it is compiled
+    once (hipcc cross-compiles without a GPU); any failure raises."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+        L.qnn_encode_pack.argtypes = [vp, i32, i64, i64, i64, f32, i32, vp, vp]
+        L.qnn_encode_pack.restype = i32
+        L.qnn_binary_gemm.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, vp]
+        L.qnn_binary_gemm.restype = i32
+        L.qnn_dequant_scale.argtypes = [vp, vp, i64, i64, vp, vp]
+        L.qnn_dequant_scale.restype = i32
+        L.qnn_conv2d.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
+        L.qnn_conv2d.restype = i32
+        L.qnn_last_error.argtypes = []
+        L.qnn_last_error.restype = ctypes.c_char_p
+        L.qnn_version.argtypes = []
+        L.qnn_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != QNN_OK:
+        raise QnnError(rc, lib().qnn_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+_DTYPES = {torch.float32: QNN_DTYPE_F32, torch.bfloat16: QNN_DTYPE_BF16, torch.int8: QNN_DTYPE_I8}
+
+
+def qnn_version():
+    return lib().qnn_version()
+
+
+def qnn_encode_pack(src, clip, bits, planes=None):
+    """src: CUDA tensor [..., n] (fp32 / bf16 values, or int8 levels), contiguous.  Returns planes
+    uint32-as-int32 [bits][rows][ceil(n/32)] with rows = product of the leading dimensions."""
+    assert src.is_cuda and src.is_contiguous() and src.dtype in _DTYPES
+    n = src.shape[-1]
+    rows = src.numel() // n if n else 0
+    nw = (n + 31) // 32
+    if planes is None:
+        planes = torch.empty((bits, rows, nw), dtype=torch.int32, device=src.device)
+    _check(lib().qnn_encode_pack(_ptr(src), _DTYPES[src.dtype], rows, n, n, float(clip), int(bits),
+                                 _ptr(planes), _stream()))
+    return planes
+
+
+def qnn_binary_gemm(a_planes, w_planes, n, want_acc=True, scale=None, acc=None, out=None):
+    """a_planes [a_bits][rows][nw], w_planes [w_bits][cols][nw] -> (acc int32 [rows][cols] or None,
+    out fp32 [rows][cols] or None)."""
+    a_bits, rows, nw = a_planes.shape
+    w_bits, cols, nw2 = w_planes.shape
+    assert nw == nw2 == (n + 31) // 32
+    dev = a_planes.device
+    if want_acc and acc is None:
+        acc = torch.empty((rows, cols), dtype=torch.int32, device=dev)
+    if scale is not None and out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=dev)
+    _check(lib().qnn_binary_gemm(_ptr(a_planes), a_bits, _ptr(w_planes), w_bits, rows, cols, n,
+                                 _ptr(acc), _ptr(scale), _ptr(out), _stream()))
+    return acc, out
+
+
+def qnn_dequant_scale(acc, scale, out=None):
+    rows, cols = acc.shape[:-1].numel(), acc.shape[-1]
+    if out is None:
+        out = torch.empty(acc.shape, dtype=torch.float32, device=acc.device)
+    _check(lib().qnn_dequant_scale(_ptr(acc), _ptr(scale), rows, cols, _ptr(out), _stream()))
+    return out
+
+
+def qnn_conv2d(a_planes, w_planes, shape, cin, stride, pad, scale=None, want_acc=True, want_out=False,
+               next_clip=None, next_bits=0, acc=None, out=None, next_planes=None):
+    """a_planes [a_bits][B*H*W][cw] for an NHWC tensor of shape=(B, H, W); w_planes
+    [w_bits][Cout][kh][kw][cw].  Returns (acc, out, next_planes); entries not requested are None."""
+    B, H, W = shape
+    a_bits = a_planes.shape[0]
+    w_bits, cout, kh, kw, cw = w_planes.shape
+    assert cw == (cin + 31) // 32 and a_planes.numel() == a_bits * B * H * W * cw
+    ho = (H + 2 * pad - kh) // stride + 1
+    wo = (W + 2 * pad - kw) // stride + 1
+    dev = a_planes.device
+    d = qnn_conv_desc(B, H, W, cin, cout, kh, kw, stride, pad, a_bits, w_bits)
+    if want_acc and acc is None:
+        acc = torch.empty((B, ho, wo, cout), dtype=torch.int32, device=dev)
+    if want_out and out is None:
+        out = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=dev)
+    if next_clip is not None and next_planes is None:
+        next_planes = torch.empty((next_bits, B * ho * wo, (cout + 31) // 32), dtype=torch.int32, device=dev)
+    _check(lib().qnn_conv2d(ctypes.byref(d), _ptr(a_planes), _ptr(w_planes), _ptr(scale), _ptr(acc),
+                            _ptr(out), _ptr(next_planes),
+                            float(next_clip) if next_clip is not None else 0.0, int(next_bits), _stream()))
+    return acc, out, next_planes

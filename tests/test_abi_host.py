@@ -1,0 +1,118 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol include/qnn.h declares,
+and rejects bad arguments before any HIP call (no GPU needed, no compute launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def qnn():
+    from paper_1905_13389_amd import qnn as q
+    q.lib()
+    return q
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "qnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(qnn):
+    names = _declared_functions()
+    assert set(names) == set(qnn.EXPORTS)
+    L = ctypes.CDLL(qnn.LIB_PATH)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_empty_error(qnn):
+    assert qnn.qnn_version() >= 100
+    assert isinstance(qnn.lib().qnn_last_error(), bytes)
+
+
+def test_conv_desc_layout_matches_header(qnn):
+    # 5 int64 then 6 int32 -> 64 bytes, no padding surprises
+    assert ctypes.sizeof(qnn.qnn_conv_desc) == 5 * 8 + 6 * 4
+
+
+FAKE = ctypes.c_void_p(0x1000)      # 16-byte aligned, never dereferenced: all of these fail earlier
+ODD = ctypes.c_void_p(0x1004)
+
+
+def test_encode_pack_argument_errors(qnn):
+    L = qnn.lib()
+    assert L.qnn_encode_pack(FAKE, 7, 4, 64, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED
+    assert L.qnn_encode_pack(FAKE, 0, 4, 64, 64, 1.0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(FAKE, 0, 4, 64, 64, 1.0, 9, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(FAKE, 0, -1, 64, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(FAKE, 0, 4, 64, 32, 1.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(FAKE, 0, 4, 64, 64, 0.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(FAKE, 0, 4, 64, 64, float("nan"), 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(FAKE, 0, 4, 64, 64, float("inf"), 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(None, 0, 4, 64, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_pack(FAKE, 0, 4, 64, 64, 1.0, 2, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert L.qnn_encode_pack(FAKE, 2, 4, 64, 64, 1.0, 8, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED
+    assert b"int8" in L.qnn_last_error()
+    # empty input is a successful no-op
+    assert L.qnn_encode_pack(None, 0, 0, 64, 64, 1.0, 2, None, None) == qnn.QNN_OK
+    assert L.qnn_encode_pack(None, 0, 4, 0, 0, 1.0, 2, None, None) == qnn.QNN_OK
+
+
+def test_binary_gemm_argument_errors(qnn):
+    L = qnn.lib()
+    g = L.qnn_binary_gemm
+    assert g(FAKE, 0, FAKE, 2, 4, 4, 64, FAKE, None, None, None) == qnn.QNN_ERR_INVALID_ARG
+    assert g(FAKE, 2, FAKE, 9, 4, 4, 64, FAKE, None, None, None) == qnn.QNN_ERR_INVALID_ARG
+    assert g(FAKE, 2, FAKE, 2, -4, 4, 64, FAKE, None, None, None) == qnn.QNN_ERR_INVALID_ARG
+    assert g(FAKE, 2, FAKE, 2, 4, 4, 64, None, None, None, None) == qnn.QNN_ERR_INVALID_ARG
+    assert g(FAKE, 2, FAKE, 2, 4, 4, 64, None, None, FAKE, None) == qnn.QNN_ERR_INVALID_ARG  # out, no scale
+    assert g(None, 2, FAKE, 2, 4, 4, 64, FAKE, None, None, None) == qnn.QNN_ERR_INVALID_ARG
+    assert g(ODD, 2, FAKE, 2, 4, 4, 64, FAKE, None, None, None) == qnn.QNN_ERR_ALIGNMENT
+    assert g(FAKE, 2, FAKE, 2, 4, 4, 64, ODD, None, None, None) == qnn.QNN_ERR_ALIGNMENT
+    # 8x8 bits: n * 255 * 255 must stay below 2^31 -> n <= 33025
+    assert g(FAKE, 8, FAKE, 8, 4, 4, 33026, FAKE, None, None, None) == qnn.QNN_ERR_RANGE
+    assert b"overflows int32" in L.qnn_last_error()
+    assert g(None, 2, None, 2, 0, 4, 64, FAKE, None, None, None) == qnn.QNN_OK
+
+
+def test_dequant_scale_argument_errors(qnn):
+    L = qnn.lib()
+    f = L.qnn_dequant_scale
+    assert f(None, FAKE, 4, 4, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert f(FAKE, FAKE, -1, 4, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert f(FAKE, FAKE, 4, 4, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert f(None, None, 0, 4, None, None) == qnn.QNN_OK
+
+
+def test_conv2d_argument_errors(qnn):
+    L = qnn.lib()
+
+    def call(desc, a=FAKE, w=FAKE, scale=None, acc=FAKE, out=None, nxt=None, clip=0.0, nbits=0):
+        return L.qnn_conv2d(ctypes.byref(desc) if desc is not None else None, a, w, scale, acc, out, nxt,
+                            clip, nbits, None)
+
+    D = qnn.qnn_conv_desc
+    ok = D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)
+    assert call(None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 0, 2)) == qnn.QNN_ERR_INVALID_ARG
+    assert call(D(1, 0, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_INVALID_ARG
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 0, 1, 2, 2)) == qnn.QNN_ERR_INVALID_ARG
+    assert call(D(1, 8, 8, 64, 64, 9, 9, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED
+    assert call(D(1, 2, 2, 64, 64, 5, 5, 1, 0, 2, 2)) == qnn.QNN_ERR_INVALID_ARG  # kernel > image
+    assert call(ok, acc=None) == qnn.QNN_ERR_INVALID_ARG                          # no output
+    assert call(ok, acc=None, out=FAKE) == qnn.QNN_ERR_INVALID_ARG                # out without scale
+    assert call(ok, scale=FAKE, nxt=FAKE, clip=1.0, nbits=0) == qnn.QNN_ERR_INVALID_ARG
+    assert call(ok, scale=FAKE, nxt=FAKE, clip=-1.0, nbits=2) == qnn.QNN_ERR_INVALID_ARG
+    assert call(ok, a=None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(ok, w=ODD) == qnn.QNN_ERR_ALIGNMENT
+    # 8x8 bits with 3x3x4096 channels overflows int32
+    assert call(D(1, 8, 8, 4096, 64, 3, 3, 1, 1, 8, 8)) == qnn.QNN_ERR_RANGE
+    # wide bits cannot use the fused epilogue
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 5, 5), scale=FAKE, nxt=FAKE, clip=1.0, nbits=2) \
+        == qnn.QNN_ERR_UNSUPPORTED
+    assert call(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK

@@ -1,0 +1,85 @@
+"""GPU parity: qnn_encode_pack and qnn_dequant_scale against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, planes_to_numpy, levels
+
+pytestmark = pytest.mark.gpu
+
+from paper_1905_13389_amd import qnn  # noqa: E402
+
+
+def _expect_planes(x32, clip, bits):
+    lv, _ = oracle.quantize(x32, clip, bits)
+    return oracle.pack_planes(lv.reshape(-1, x32.shape[-1]), bits)
+
+
+@pytest.mark.parametrize("bits", range(1, 9))
+@pytest.mark.parametrize("shape", [(1, 1), (3, 31), (5, 32), (4, 33), (7, 100), (2, 256), (3, 300),
+                                   (9, 1000), (64, 64), (33, 4096)])
+def test_encode_fp32(bits, shape):
+    gen = np.random.default_rng(bits * 1000 + shape[0] + shape[1])
+    x = gen.standard_normal(shape, dtype=np.float32)
+    clip = 1.7
+    got = planes_to_numpy(qnn.qnn_encode_pack(dev(x), clip, bits))
+    assert np.array_equal(got, _expect_planes(x, clip, bits))
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 8])
+def test_encode_thresholds_and_saturation(bits):
+    # values on and next to every threshold of the ladder, the clip points, zeros, infinities
+    top = (1 << bits) - 1
+    clip = np.float32(0.75)
+    thr = (2.0 * (np.arange(top) + 0.5) / top - 1.0) * clip
+    pts = np.concatenate([thr, np.nextafter(thr.astype(np.float32), np.float32(9)),
+                          np.nextafter(thr.astype(np.float32), np.float32(-9)),
+                          [0.0, -0.0, clip, -clip, 2 * clip, -2 * clip, np.inf, -np.inf, 1e-30, -1e-30]])
+    x = np.resize(pts.astype(np.float32), (4, 520))
+    got = planes_to_numpy(qnn.qnn_encode_pack(dev(x), float(clip), bits))
+    assert np.array_equal(got, _expect_planes(x, float(clip), bits))
+
+
+@pytest.mark.parametrize("bits", [2, 3, 5])
+def test_encode_bf16(bits):
+    gen = np.random.default_rng(77 + bits)
+    x = torch.from_numpy(gen.standard_normal((6, 200), dtype=np.float32)).to(torch.bfloat16)
+    got = planes_to_numpy(qnn.qnn_encode_pack(x.cuda(), 2.0, bits))
+    assert np.array_equal(got, _expect_planes(x.to(torch.float32).numpy(), 2.0, bits))
+
+
+@pytest.mark.parametrize("bits", range(1, 8))
+@pytest.mark.parametrize("shape", [(4, 512), (3, 70), (2, 33)])
+def test_encode_int8_levels(bits, shape):
+    gen = np.random.default_rng(bits + shape[1])
+    lv = levels(gen, shape, bits)
+    got = planes_to_numpy(qnn.qnn_encode_pack(dev(lv), 1.0, bits))
+    assert np.array_equal(got, oracle.pack_planes(lv.astype(np.int16), bits))
+
+
+def test_encode_nhwc_activation_shape():
+    # a conv activation: rows = pixels, n = channels; every level must occur, a little saturation
+    gen = np.random.default_rng(5)
+    x = gen.standard_normal((2, 9, 9, 64), dtype=np.float32)
+    clip = float(np.float32(3.0 * x.std()))
+    got = planes_to_numpy(qnn.qnn_encode_pack(dev(x), clip, 3))
+    want = _expect_planes(x, clip, 3)
+    assert got.shape == (3, 2 * 9 * 9, 2)
+    assert np.array_equal(got, want)
+    lv = oracle.unpack_planes(got, 64)
+    assert set(np.unique(lv).tolist()) == set(range(-7, 8, 2))
+
+
+def test_encode_empty():
+    x = torch.empty((0, 64), dtype=torch.float32, device="cuda")
+    assert qnn.qnn_encode_pack(x, 1.0, 2).shape == (2, 0, 2)
+
+
+@pytest.mark.parametrize("shape", [(1, 1), (7, 5), (64, 256), (33, 100), (1000, 64)])
+def test_dequant_scale(shape):
+    gen = np.random.default_rng(shape[0] * 7 + shape[1])
+    acc = gen.integers(-(1 << 23), 1 << 23, size=shape).astype(np.int32)
+    s = gen.uniform(0.01, 0.1, size=shape[1]).astype(np.float32)
+    got = qnn.qnn_dequant_scale(dev(acc), dev(s)).cpu().numpy()
+    assert np.array_equal(got, oracle.scale(acc, s))

@@ -1,0 +1,104 @@
+"""GPU parity: qnn_binary_gemm against the CPU oracle (integer matmul of decoded levels).
+int32 accumulators must match bit for bit; fp32 scaled outputs within 1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import qnn_workloads as wl
+from gpu_util import dev, pack_levels, levels
+
+pytestmark = pytest.mark.gpu
+
+from paper_1905_13389_amd import qnn  # noqa: E402
+
+RTOL = 1e-5
+
+
+def _run(a, w, a_bits, w_bits, scale=None):
+    ap, wp = pack_levels(a, a_bits), pack_levels(w, w_bits)
+    acc, out = qnn.qnn_binary_gemm(ap, wp, a.shape[1], scale=None if scale is None else dev(scale))
+    torch.cuda.synchronize()
+    return acc.cpu().numpy(), None if out is None else out.cpu().numpy()
+
+
+def test_config1_fc_2x2():
+    c = wl.fc_2x2()
+    acc, out = _run(c["a"], c["w"], 2, 2, c["scale"])
+    want = oracle.gemm(c["a"], c["w"])
+    assert np.array_equal(acc, want)
+    np.testing.assert_allclose(out, oracle.scale(want, c["scale"]), rtol=RTOL, atol=0)
+
+
+@pytest.mark.parametrize("w_bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("a_bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("shape", [(1, 1, 1), (130, 70, 100), (257, 129, 1000), (64, 300, 2080), (300, 64, 33)])
+def test_tiled_kernels_ragged(w_bits, a_bits, shape):
+    rows, cols, n = shape
+    gen = np.random.default_rng(w_bits * 100 + a_bits * 10 + rows)
+    a, w = levels(gen, (rows, n), a_bits), levels(gen, (cols, n), w_bits)
+    s = gen.uniform(0.01, 0.1, size=cols).astype(np.float32)
+    acc, out = _run(a, w, a_bits, w_bits, s)
+    want = oracle.gemm(a, w)
+    assert np.array_equal(acc, want)
+    np.testing.assert_allclose(out, oracle.scale(want, s), rtol=RTOL, atol=0)
+
+
+@pytest.mark.parametrize("bits", [(5, 5), (8, 2), (3, 7), (1, 6)])
+def test_wide_bit_kernel(bits):
+    w_bits, a_bits = bits
+    gen = np.random.default_rng(w_bits * 10 + a_bits)
+    rows, cols, n = 37, 19, 200
+    top_a, top_w = (1 << a_bits) - 1, (1 << w_bits) - 1
+    a = (2 * gen.integers(0, top_a + 1, size=(rows, n)) - top_a).astype(np.int16)
+    w = (2 * gen.integers(0, top_w + 1, size=(cols, n)) - top_w).astype(np.int16)
+    ap = dev(oracle.pack_planes(a, a_bits).view(np.int32))   # 8-bit levels do not fit the int8 input path
+    wp = dev(oracle.pack_planes(w, w_bits).view(np.int32))
+    acc, _ = qnn.qnn_binary_gemm(ap, wp, n)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), oracle.gemm(a, w))
+
+
+def test_extreme_levels_hit_the_bound():
+    # all-max inputs reach |acc| = n (2^M-1)(2^K-1); sign flips with the weights
+    n = 4096
+    a = np.full((16, n), 15, np.int8)
+    w = np.concatenate([np.full((8, n), 15, np.int8), np.full((8, n), -15, np.int8)])
+    acc, _ = _run(a, w, 4, 4)
+    assert np.all(acc[:, :8] == n * 225) and np.all(acc[:, 8:] == -n * 225)
+
+
+def test_only_out_requested():
+    gen = np.random.default_rng(3)
+    a, w = levels(gen, (40, 96), 2), levels(gen, (24, 96), 2)
+    s = gen.uniform(0.01, 0.1, size=24).astype(np.float32)
+    _, out = qnn.qnn_binary_gemm(pack_levels(a, 2), pack_levels(w, 2), 96, want_acc=False, scale=dev(s))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(oracle.gemm(a, w), s), rtol=RTOL, atol=0)
+
+
+@pytest.mark.parametrize("w_bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("a_bits", [1, 2, 3, 4])
+def test_config2_full_size_sampled(w_bits, a_bits):
+    # 4096^3 in the launch configuration the benchmark times; oracle on 6 full rows, 6 full
+    # columns and 512 scattered outputs, plus invariants that hold for every output
+    size = 4096
+    c = wl.gemm_square(w_bits, a_bits, size)
+    a, w = c["a"], c["w"]
+    ap, wp = pack_levels(a, a_bits), pack_levels(w, w_bits)
+    acc, out = qnn.qnn_binary_gemm(ap, wp, size, scale=dev(c["scale"]))
+    torch.cuda.synchronize()
+    acc = acc.cpu().numpy()
+    out = out.cpu().numpy()
+    gen = np.random.default_rng(w_bits * 10 + a_bits)
+    rsel = np.concatenate([[0, size - 1], gen.integers(0, size, 4)])
+    csel = np.concatenate([[0, size - 1], gen.integers(0, size, 4)])
+    assert np.array_equal(acc[rsel], oracle.gemm(a[rsel], w))
+    assert np.array_equal(acc[:, csel], oracle.gemm(a, w[csel]))
+    for r, col in zip(gen.integers(0, size, 512), gen.integers(0, size, 512)):
+        assert acc[r, col] == oracle.gemm_one(a[r], w[col])
+    top = ((1 << w_bits) - 1) * ((1 << a_bits) - 1)
+    assert np.all((acc & 1) == 0)                      # n even -> sum of n odd products is even
+    assert np.abs(acc).max() <= size * top
+    np.testing.assert_allclose(out[rsel], oracle.scale(acc[rsel], c["scale"]), rtol=RTOL, atol=0)
+    assert np.array_equal(out, acc.astype(np.float32) * c["scale"][None, :])
