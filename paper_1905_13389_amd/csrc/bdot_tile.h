@@ -4,7 +4,7 @@
 // A workgroup of 256 lanes (4 wave64) owns a BM x BN block of outputs, BM = 16*TM rows,
 // BN = 16*TN columns.  Lane (ty, tx) owns rows ty + 16*i and columns tx + 16*n, so that within
 // a wave the activation reads are 4 broadcast addresses and the weight reads are 16 distinct
-// LDS rows whose stride (20 words) spreads them over all banks.
+// LDS rows whose stride (an odd multiple of 4 words) spreads them over all banks.
 //
 // For every 32-bit word of the reduction axis and every (weight plane i, activation plane j)
 // the lane issues one v_xor_b32 and one v_bcnt_u32_b32 whose add operand is the running count,
@@ -21,24 +21,29 @@
 namespace qnn {
 
 constexpr int kTileThreads = 256;
-constexpr int kBK = 16;  // reduction words staged per step (64 bytes per row and plane)
-constexpr int kBKP = 20; // LDS row stride in words: 16-byte aligned, odd multiple of 4
+constexpr int kBK = 16; // default number of reduction words staged per step (64 bytes per row and plane)
 
 // KV = reduction words fetched from LDS per read (4: ds_read_b128, 2: ds_read_b64); the lane keeps
 // KV * (TM*AB + TN*WB) operand registers next to its TM*TN*(WB+AB-1) counters.
-template <int WB, int AB, int TM, int TN, int KV = 4> struct Tile {
+// KB = reduction words an LDS stage can hold (a multiple of 4).  The LDS row stride BKP is the
+// next odd multiple of 4 words, which keeps rows 16-byte aligned and spreads the 16 rows a wave
+// reads at once over all banks.
+template <int WB, int AB, int TM, int TN, int KV = 4, int KB = kBK> struct Tile {
     static_assert(KV == 2 || KV == 4, "KV is 2 or 4 words");
+    static_assert(KB % 4 == 0, "stages are loaded in 16-byte units");
+    static constexpr int UQ = KB / 4; // 16-byte units per row and plane
+    static constexpr int BKP = (UQ % 2 == 1) ? KB : KB + 4;
     static constexpr int BM = 16 * TM;
     static constexpr int BN = 16 * TN;
     static constexpr int S = WB + AB - 1;
     static constexpr int A_ROWPLANES = AB * BM;
     static constexpr int W_ROWPLANES = WB * BN;
-    static constexpr int A_UNITS = A_ROWPLANES * (kBK / 4); // one unit = 4 words of one row-plane
-    static constexpr int W_UNITS = W_ROWPLANES * (kBK / 4);
+    static constexpr int A_UNITS = A_ROWPLANES * UQ; // one unit = 4 words of one row-plane
+    static constexpr int W_UNITS = W_ROWPLANES * UQ;
     static constexpr int A_PER_THREAD = (A_UNITS + kTileThreads - 1) / kTileThreads;
     static constexpr int W_PER_THREAD = (W_UNITS + kTileThreads - 1) / kTileThreads;
-    static constexpr int A_WORDS = A_ROWPLANES * kBKP;
-    static constexpr int STAGE_WORDS = (A_ROWPLANES + W_ROWPLANES) * kBKP;
+    static constexpr int A_WORDS = A_ROWPLANES * BKP;
+    static constexpr int STAGE_WORDS = (A_ROWPLANES + W_ROWPLANES) * BKP;
 };
 
 // Lane tile per (w_bits, a_bits): TM*TN*(WB+AB-1) counters plus KV*(TM*AB + TN*WB) operand
@@ -86,13 +91,74 @@ __device__ __forceinline__ uint4 load_rowmajor4(const uint32_t *__restrict__ bas
     return v;
 }
 
-// count += bitcount(w xor a): exactly one v_xor_b32 and one v_bcnt_u32_b32 (whose third operand
-// is the running count).  Written as one asm statement so that the compiler can neither
-// re-associate the count chain into extra adds nor keep hundreds of xor results alive.
-__device__ __forceinline__ void xor_bcnt_acc(uint32_t w, uint32_t a, uint32_t &count)
+// All WB x AB plane pairs of one weight word column and one activation word column:
+// count[i + j] += bitcount(w[i] xor a[j]), exactly one v_xor_b32 and one v_bcnt_u32_b32 (whose
+// third operand is the running count) per pair.  One asm statement per call, so the compiler can
+// neither re-associate the count chains into extra adds, nor keep hundreds of xor results alive,
+// nor pad every pair with the wait state it conservatively puts between asm statements.
+#define QNN_XB(w, a, p) "v_xor_b32 %[t], %[" #w "], %[" #a "]\n\tv_bcnt_u32_b32 %[" #p "], %[t], %[" #p "]\n\t"
+#define QNN_ROW1(w, p0) QNN_XB(w, a0, p0)
+#define QNN_ROW2(w, p0, p1) QNN_XB(w, a0, p0) QNN_XB(w, a1, p1)
+#define QNN_ROW3(w, p0, p1, p2) QNN_XB(w, a0, p0) QNN_XB(w, a1, p1) QNN_XB(w, a2, p2)
+#define QNN_ROW4(w, p0, p1, p2, p3) QNN_XB(w, a0, p0) QNN_XB(w, a1, p1) QNN_XB(w, a2, p2) QNN_XB(w, a3, p3)
+#define QNN_P1 [p0] "+v"(c[0])
+#define QNN_P2 QNN_P1, [p1] "+v"(c[1])
+#define QNN_P3 QNN_P2, [p2] "+v"(c[2])
+#define QNN_P4 QNN_P3, [p3] "+v"(c[3])
+#define QNN_P5 QNN_P4, [p4] "+v"(c[4])
+#define QNN_P6 QNN_P5, [p5] "+v"(c[5])
+#define QNN_P7 QNN_P6, [p6] "+v"(c[6])
+#define QNN_W1 [w0] "v"(w[0])
+#define QNN_W2 QNN_W1, [w1] "v"(w[1])
+#define QNN_W3 QNN_W2, [w2] "v"(w[2])
+#define QNN_W4 QNN_W3, [w3] "v"(w[3])
+#define QNN_A1 [a0] "v"(a[0])
+#define QNN_A2 QNN_A1, [a1] "v"(a[1])
+#define QNN_A3 QNN_A2, [a2] "v"(a[2])
+#define QNN_A4 QNN_A3, [a3] "v"(a[3])
+#define QNN_PAIRS(body, P, W, A) asm(body : [t] "=&v"(t), P : W, A)
+
+template <int WB, int AB>
+__device__ __forceinline__ void xor_bcnt_pairs(const uint32_t (&w)[WB], const uint32_t (&a)[AB],
+                                               uint32_t (&c)[WB + AB - 1])
 {
     uint32_t t;
-    asm("v_xor_b32 %0, %2, %3\n\tv_bcnt_u32_b32 %1, %0, %1" : "=&v"(t), "+v"(count) : "v"(w), "v"(a));
+    if constexpr (WB == 1 && AB == 1) QNN_PAIRS(QNN_ROW1(w0, p0), QNN_P1, QNN_W1, QNN_A1);
+    else if constexpr (WB == 1 && AB == 2) QNN_PAIRS(QNN_ROW2(w0, p0, p1), QNN_P2, QNN_W1, QNN_A2);
+    else if constexpr (WB == 1 && AB == 3) QNN_PAIRS(QNN_ROW3(w0, p0, p1, p2), QNN_P3, QNN_W1, QNN_A3);
+    else if constexpr (WB == 1 && AB == 4) QNN_PAIRS(QNN_ROW4(w0, p0, p1, p2, p3), QNN_P4, QNN_W1, QNN_A4);
+    else if constexpr (WB == 2 && AB == 1) QNN_PAIRS(QNN_ROW1(w0, p0) QNN_ROW1(w1, p1), QNN_P2, QNN_W2, QNN_A1);
+    else if constexpr (WB == 2 && AB == 2)
+        QNN_PAIRS(QNN_ROW2(w0, p0, p1) QNN_ROW2(w1, p1, p2), QNN_P3, QNN_W2, QNN_A2);
+    else if constexpr (WB == 2 && AB == 3)
+        QNN_PAIRS(QNN_ROW3(w0, p0, p1, p2) QNN_ROW3(w1, p1, p2, p3), QNN_P4, QNN_W2, QNN_A3);
+    else if constexpr (WB == 2 && AB == 4)
+        QNN_PAIRS(QNN_ROW4(w0, p0, p1, p2, p3) QNN_ROW4(w1, p1, p2, p3, p4), QNN_P5, QNN_W2, QNN_A4);
+    else if constexpr (WB == 3 && AB == 1)
+        QNN_PAIRS(QNN_ROW1(w0, p0) QNN_ROW1(w1, p1) QNN_ROW1(w2, p2), QNN_P3, QNN_W3, QNN_A1);
+    else if constexpr (WB == 3 && AB == 2)
+        QNN_PAIRS(QNN_ROW2(w0, p0, p1) QNN_ROW2(w1, p1, p2) QNN_ROW2(w2, p2, p3), QNN_P4, QNN_W3, QNN_A2);
+    else if constexpr (WB == 3 && AB == 3)
+        QNN_PAIRS(QNN_ROW3(w0, p0, p1, p2) QNN_ROW3(w1, p1, p2, p3) QNN_ROW3(w2, p2, p3, p4), QNN_P5, QNN_W3,
+                  QNN_A3);
+    else if constexpr (WB == 3 && AB == 4)
+        QNN_PAIRS(QNN_ROW4(w0, p0, p1, p2, p3) QNN_ROW4(w1, p1, p2, p3, p4) QNN_ROW4(w2, p2, p3, p4, p5), QNN_P6,
+                  QNN_W3, QNN_A4);
+    else if constexpr (WB == 4 && AB == 1)
+        QNN_PAIRS(QNN_ROW1(w0, p0) QNN_ROW1(w1, p1) QNN_ROW1(w2, p2) QNN_ROW1(w3, p3), QNN_P4, QNN_W4, QNN_A1);
+    else if constexpr (WB == 4 && AB == 2)
+        QNN_PAIRS(QNN_ROW2(w0, p0, p1) QNN_ROW2(w1, p1, p2) QNN_ROW2(w2, p2, p3) QNN_ROW2(w3, p3, p4), QNN_P5,
+                  QNN_W4, QNN_A2);
+    else if constexpr (WB == 4 && AB == 3)
+        QNN_PAIRS(QNN_ROW3(w0, p0, p1, p2) QNN_ROW3(w1, p1, p2, p3) QNN_ROW3(w2, p2, p3, p4)
+                      QNN_ROW3(w3, p3, p4, p5),
+                  QNN_P6, QNN_W4, QNN_A3);
+    else {
+        static_assert(WB == 4 && AB == 4, "plane pairs are built for 1..4 x 1..4 bits");
+        QNN_PAIRS(QNN_ROW4(w0, p0, p1, p2, p3) QNN_ROW4(w1, p1, p2, p3, p4) QNN_ROW4(w2, p2, p3, p4, p5)
+                      QNN_ROW4(w3, p3, p4, p5, p6),
+                  QNN_P7, QNN_W4, QNN_A4);
+    }
 }
 
 // The xor + bitcount block: one kBK-word stage out of LDS into the P_s accumulators.
@@ -107,37 +173,42 @@ template <int KV> __device__ __forceinline__ void lds_read_words(const uint32_t 
     }
 }
 
-template <int WB, int AB, int TM, int TN, int KV>
+// `nkq` = number of KV-word groups of this stage that hold reduction words (fewer for the last
+// stage of a reduction: nothing is spent on the zero tail).
+template <int WB, int AB, int TM, int TN, int KV, int KB>
 __device__ __forceinline__ void tile_mac(const uint32_t *__restrict__ As,
-                                         const uint32_t *__restrict__ Ws, int ty, int tx,
+                                         const uint32_t *__restrict__ Ws, int ty, int tx, int nkq,
                                          uint32_t (&P)[TM][TN][WB + AB - 1])
 {
-    using T = Tile<WB, AB, TM, TN, KV>;
+    using T = Tile<WB, AB, TM, TN, KV, KB>;
 #pragma unroll 1
-    for (int kq = 0; kq < kBK / KV; ++kq) {
-        uint32_t a[TM][AB][KV];
-        uint32_t w[TN][WB][KV];
+    for (int kq = 0; kq < nkq; ++kq) {
+        uint32_t a[TM][KV][AB]; // [row][word][plane]
+        uint32_t w[TN][KV][WB];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < AB; ++j)
-                lds_read_words<KV>(As + (j * T::BM + ty + 16 * i) * kBKP + KV * kq, a[i][j]);
+            for (int j = 0; j < AB; ++j) {
+                uint32_t v[KV];
+                lds_read_words<KV>(As + (j * T::BM + ty + 16 * i) * T::BKP + KV * kq, v);
+#pragma unroll
+                for (int kk = 0; kk < KV; ++kk) a[i][kk][j] = v[kk];
+            }
 #pragma unroll
         for (int n = 0; n < TN; ++n)
 #pragma unroll
-            for (int j = 0; j < WB; ++j)
-                lds_read_words<KV>(Ws + (j * T::BN + tx + 16 * n) * kBKP + KV * kq, w[n][j]);
+            for (int j = 0; j < WB; ++j) {
+                uint32_t v[KV];
+                lds_read_words<KV>(Ws + (j * T::BN + tx + 16 * n) * T::BKP + KV * kq, v);
+#pragma unroll
+                for (int kk = 0; kk < KV; ++kk) w[n][kk][j] = v[kk];
+            }
 #pragma unroll
         for (int kk = 0; kk < KV; ++kk)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int n = 0; n < TN; ++n)
-#pragma unroll
-                    for (int wi = 0; wi < WB; ++wi)
-#pragma unroll
-                        for (int aj = 0; aj < AB; ++aj)
-                            xor_bcnt_acc(w[n][wi][kk], a[i][aj][kk], P[i][n][wi + aj]);
+                for (int n = 0; n < TN; ++n) xor_bcnt_pairs<WB, AB>(w[n][kk], a[i][kk], P[i][n]);
     }
 }
 

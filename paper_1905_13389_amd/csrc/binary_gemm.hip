@@ -66,13 +66,13 @@ __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2,
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS)
-                *reinterpret_cast<uint4 *>(As + (idx >> 2) * kBKP + 4 * (idx & 3)) = ra[u];
+                *reinterpret_cast<uint4 *>(As + (idx >> 2) * T::BKP + 4 * (idx & 3)) = ra[u];
         }
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS)
-                *reinterpret_cast<uint4 *>(Ws + (idx >> 2) * kBKP + 4 * (idx & 3)) = rw[u];
+                *reinterpret_cast<uint4 *>(Ws + (idx >> 2) * T::BKP + 4 * (idx & 3)) = rw[u];
         }
     };
 
@@ -84,7 +84,9 @@ __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2,
         const int buf = (int)(c & 1);
         const bool more = c + 1 < nchunks;
         if (more) fetch((c + 1) * kBK);
-        tile_mac<WB, AB, TM, TN, KV>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, P);
+        const int64_t left = p.nw - c * kBK; // reduction words still to do
+        const int nkq = left >= kBK ? kBK / KV : (int)((left + KV - 1) / KV);
+        tile_mac<WB, AB, TM, TN, KV, kBK>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P);
         if (more) stash(buf ^ 1);
         __syncthreads();
     }

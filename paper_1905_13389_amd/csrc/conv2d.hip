@@ -17,7 +17,25 @@ namespace qnn {
 
 constexpr int kMaxGroups = 1024; // reduction words (or word groups) addressable through the tap table
 constexpr int kMaxTaps = 49;
+constexpr int kConvKB = 20; // an LDS stage holds up to 20 reduction words per row and plane
 
+// n / d for n < 2^31 and a divisor fixed per launch: q = (mulhi(n, mul) + n) >> shift.
+struct FastDiv {
+    uint32_t mul, shift, d;
+};
+static FastDiv make_fastdiv(uint32_t d)
+{
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    FastDiv f;
+    f.shift = l;
+    f.mul = (uint32_t)(((((uint64_t)1) << 32) * ((((uint64_t)1) << l) - d)) / d + 1);
+    f.d = d;
+    return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.mul) + n) >> f.shift; }
+
+// Everything the plain kernel needs (64-bit sizes).
 struct ConvParams {
     const uint32_t *a; // [AB][B][H][W][cw]
     const uint32_t *w; // [WB][Cout][kh][kw][cw]
@@ -25,36 +43,48 @@ struct ConvParams {
     int kh, kw, stride, pad;
     int64_t cw, nw, M; // words per pixel, reduction words, output pixels
     int64_t a_plane_stride;
-    uint32_t n_times_top; // kh kw Cin (2^WB-1)(2^AB-1)
-    int top_a;
+    const float *scale;
+    int32_t *acc;
+    float *out;
+};
+
+// The register-blocked kernel's view: 32-bit indices (checked on the host), few fields.
+struct ConvTileParams {
+    const uint32_t *a, *w;
     const float *scale;
     int32_t *acc;
     float *out;
     uint32_t *next; // [next_bits][M][cwo]
+    int H, W, HW, Cin, Cout, M, cw, nw, cwo;
+    int kh, kw, stride, pad;
+    int a_plane_stride;
+    uint32_t n_times_top; // kh kw Cin (2^WB-1)(2^AB-1)
+    int top_a;
     int next_bits, next_top;
     float next_inv_clip, next_half_top;
-    int64_t cwo;
     int wvec; // nw % 4 == 0
-    int64_t tiles_n, nblocks;
+    FastDiv div_howo, div_wo;
+    int tiles_m, tiles_n, row_tile_step; // persistent schedule: see bconv_tile_kernel
+    int kb, nchunks;                     // reduction words per LDS stage (multiple of 4), stages per tile
 };
 
 // gather 4 consecutive reduction words of one output pixel; VW = gcd(cw, 4) words share a tap
 template <int VW>
-__device__ __forceinline__ uint4 gather4(const ConvParams &p, const uint32_t *__restrict__ plane,
-                                         const uint32_t *tap_table, bool row_ok, int64_t pix_base,
-                                         int hi0, int wi0, int64_t kword)
+__device__ __forceinline__ uint4 gather4(const ConvTileParams &p, const uint32_t *__restrict__ plane,
+                                         const uint32_t *tap_table, bool row_ok, int pix_base, int hi0,
+                                         int wi0, int kword)
 {
     uint32_t v[4] = {0u, 0u, 0u, 0u};
     if (row_ok) {
 #pragma unroll
         for (int g = 0; g < 4 / VW; ++g) {
-            const int64_t kw0 = kword + g * VW;
+            const int kw0 = kword + g * VW;
             if (kw0 < p.nw) {
                 const uint32_t e = tap_table[kw0 / VW];
                 const int ky = (int)(e >> 24), kx = (int)((e >> 16) & 255), ci = (int)(e & 0xffff);
                 const int hi = hi0 + ky, wi = wi0 + kx;
-                if (hi >= 0 && hi < p.H && wi >= 0 && wi < p.W) {
-                    const uint32_t *src = plane + (pix_base + (int64_t)hi * p.W + wi) * p.cw + ci;
+                if ((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W) {
+                    const uint32_t *src = plane + (int64_t)(pix_base + hi * p.W + wi) * p.cw + ci;
                     if constexpr (VW == 4) {
                         const uint4 t = *reinterpret_cast<const uint4 *>(src);
                         v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
@@ -71,70 +101,102 @@ __device__ __forceinline__ uint4 gather4(const ConvParams &p, const uint32_t *__
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
+// OR of a value over each aligned group of 8 lanes (every lane of the group gets the result).
+__device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true); // row_half_mirror
+    return v;
+}
+
+// Persistent workgroups.  Workgroup b keeps one column tile (b % tiles_n) for its whole life and
+// walks the row tiles b / tiles_n, + row_tile_step, ...; the reduction stages of consecutive tiles
+// form one software pipeline: while the xor + bitcount block runs on one LDS stage, the next
+// stage -- of this tile or the first of the next tile -- is already on its way from global memory.
+// The tap table and the per-tap weight sums S are built once per workgroup.
+//
+// Epilogue.  The recombined accumulators go through LDS once so that the rest runs row-major:
+// one lane owns 4 consecutive channels of one pixel (16-byte loads / stores of acc, scale, out),
+// rolled over the rows of the tile, and the next layer's plane words are assembled from 8 lanes'
+// nibbles with three DPP ORs.
 template <int WB, int AB, int TM, int TN, int KV, int VW>
 __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void
-bconv_tile_kernel(ConvParams p)
+bconv_tile_kernel(ConvTileParams p)
 {
-    using T = Tile<WB, AB, TM, TN, KV>;
-    __shared__ __attribute__((aligned(16))) uint32_t smem[2][T::STAGE_WORDS];
+    using T = Tile<WB, AB, TM, TN, KV, kConvKB>;
+    constexpr int UQ = T::UQ;
+    constexpr int BN = T::BN, BM = T::BM;
+    constexpr int EPI_STRIDE = BN + 16; // the 4 rows a wave writes at once land in 4 different bank groups
+    constexpr int EPI_WORDS = BM * EPI_STRIDE;
+    constexpr int STAGE_ALLOC = T::STAGE_WORDS > EPI_WORDS ? T::STAGE_WORDS : EPI_WORDS;
+    __shared__ __attribute__((aligned(16))) uint32_t smem[2][STAGE_ALLOC];
     __shared__ uint32_t tap_table[kMaxGroups];
+    extern __shared__ __attribute__((aligned(16))) int32_t S[]; // [taps][BN]
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
-    const int64_t tile = xcd_band_remap(blockIdx.x, p.nblocks);
-    const int64_t row0 = (tile / p.tiles_n) * T::BM;
-    const int64_t col0 = (tile % p.tiles_n) * T::BN;
+    const int col0 = ((int)blockIdx.x % p.tiles_n) * BN;
+    const int rt_first = (int)blockIdx.x / p.tiles_n;
     const bool wvec = p.wvec != 0;
     const int taps = p.kh * p.kw;
 
     // reduction word group -> (ky, kx, first channel word)
-    for (int64_t g = tid; g * VW < p.nw; g += kTileThreads) {
-        const int64_t kword = g * VW;
-        const int tap = (int)(kword / p.cw), ci = (int)(kword % p.cw);
+    for (int g = tid; g * VW < p.nw; g += kTileThreads) {
+        const int kword = g * VW;
+        const int tap = kword / p.cw, ci = kword % p.cw;
         tap_table[g] = ((uint32_t)(tap / p.kw) << 24) | ((uint32_t)(tap % p.kw) << 16) | (uint32_t)ci;
     }
-
-    // the output pixels this lane fetches for the workgroup (fixed for the whole reduction)
-    int hi0[T::A_PER_THREAD], wi0[T::A_PER_THREAD];
-    int64_t pbase[T::A_PER_THREAD];
-    bool rok[T::A_PER_THREAD];
-#pragma unroll
-    for (int u = 0; u < T::A_PER_THREAD; ++u) {
-        const int idx = tid + u * kTileThreads;
-        const int64_t m = row0 + (idx >> 2) % T::BM;
-        rok[u] = (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS) && m < p.M;
-        const int64_t mm = rok[u] ? m : 0;
-        const int64_t b = mm / (p.Ho * p.Wo), rem = mm % (p.Ho * p.Wo);
-        hi0[u] = (int)(rem / p.Wo) * p.stride - p.pad;
-        wi0[u] = (int)(rem % p.Wo) * p.stride - p.pad;
-        pbase[u] = b * p.H * p.W;
+    // S[t][c] = sum over channels of the weight levels of tap t, from the planes
+    for (int e = tid; e < BN * taps; e += kTileThreads) {
+        const int t = e / BN, cl = e % BN;
+        const int c = col0 + cl;
+        int32_t s = 0;
+        if (c < p.Cout) {
+            for (int i = 0; i < WB; ++i) {
+                const uint32_t *wp = p.w + ((int64_t)i * p.Cout + c) * p.nw + t * p.cw;
+                int32_t cnt = 0;
+                for (int k = 0; k < p.cw; ++k) cnt += __builtin_popcount(wp[k]);
+                s += (2 * cnt - p.Cin) << i;
+            }
+        }
+        S[e] = s;
     }
 
-    uint32_t P[TM][TN][T::S];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int n = 0; n < TN; ++n)
-#pragma unroll
-            for (int s = 0; s < T::S; ++s) P[i][n][s] = 0u;
-
-    uint4 ra[T::A_PER_THREAD], rw[T::W_PER_THREAD];
-    auto fetch = [&](int64_t k0) {
+    // coordinates of the output pixels this lane fetches for the workgroup
+    int hi0[T::A_PER_THREAD], wi0[T::A_PER_THREAD], pbase[T::A_PER_THREAD];
+    bool rok[T::A_PER_THREAD];
+    auto locate = [&](int row0) {
 #pragma unroll
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
-            const int plane = (idx >> 2) / T::BM;
-            ra[u] = gather4<VW>(p, p.a + (int64_t)plane * p.a_plane_stride, tap_table, rok[u], pbase[u],
-                                hi0[u], wi0[u], k0 + 4 * (idx & 3));
+            const int m = row0 + (idx / UQ) % BM;
+            rok[u] = (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS) && m < p.M;
+            const uint32_t mm = rok[u] ? (uint32_t)m : 0u;
+            const uint32_t b = fdiv(mm, p.div_howo), rem = mm - b * p.div_howo.d;
+            const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
+            hi0[u] = (int)ho * p.stride - p.pad;
+            wi0[u] = (int)wo * p.stride - p.pad;
+            pbase[u] = (int)b * p.HW;
+        }
+    };
+
+    uint4 ra[T::A_PER_THREAD], rw[T::W_PER_THREAD];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int u = 0; u < T::A_PER_THREAD; ++u) {
+            const int idx = tid + u * kTileThreads;
+            const int plane = (idx / UQ) / BM, q = idx % UQ;
+            ra[u] = gather4<VW>(p, p.a + (int64_t)plane * p.a_plane_stride, tap_table, rok[u] && 4 * q < p.kb,
+                                pbase[u], hi0[u], wi0[u], k0 + 4 * q);
         }
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
-            const int rp = idx >> 2;
+            const int rp = idx / UQ, q = idx % UQ;
             rw[u] = make_uint4(0u, 0u, 0u, 0u);
-            if (T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS)
-                rw[u] = load_rowmajor4(p.w, p.Cout, p.nw, rp / T::BN, col0 + rp % T::BN,
-                                       k0 + 4 * (idx & 3), wvec);
+            if ((T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS) && 4 * q < p.kb)
+                rw[u] = load_rowmajor4(p.w, p.Cout, p.nw, rp / BN, col0 + rp % BN, k0 + 4 * q, wvec);
         }
     };
     auto stash = [&](int buf) {
@@ -143,121 +205,143 @@ bconv_tile_kernel(ConvParams p)
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS)
-                *reinterpret_cast<uint4 *>(As + (idx >> 2) * kBKP + 4 * (idx & 3)) = ra[u];
+                *reinterpret_cast<uint4 *>(As + (idx / UQ) * T::BKP + 4 * (idx % UQ)) = ra[u];
         }
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS)
-                *reinterpret_cast<uint4 *>(Ws + (idx >> 2) * kBKP + 4 * (idx & 3)) = rw[u];
+                *reinterpret_cast<uint4 *>(Ws + (idx / UQ) * T::BKP + 4 * (idx % UQ)) = rw[u];
         }
     };
 
-    __syncthreads(); // tap_table
-    const int64_t nchunks = (p.nw + kBK - 1) / kBK;
+    // this lane's 4 channels in the row-major half of the epilogue
+    constexpr int LPR = BN / 4;            // lanes per pixel row
+    constexpr int RPP = kTileThreads / LPR; // pixel rows per pass
+    const int c4 = (tid % LPR) * 4;
+    const int cidx = col0 + c4;
+    const bool cols4 = cidx + 3 < p.Cout && (p.Cout & 3) == 0; // 16-byte accesses are whole and aligned
+    float sc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (p.scale) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (cidx + e < p.Cout) sc[e] = p.scale[cidx + e];
+    }
+
+    uint32_t P[TM][TN][T::S];
+    __syncthreads(); // tap_table and S are complete
+    int buf = 0;
+    locate(rt_first * BM);
     fetch(0);
     stash(0);
     __syncthreads();
-    for (int64_t c = 0; c < nchunks; ++c) {
-        const int buf = (int)(c & 1);
-        const bool more = c + 1 < nchunks;
-        if (more) fetch((c + 1) * kBK);
-        tile_mac<WB, AB, TM, TN, KV>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, P);
-        if (more) stash(buf ^ 1);
-        __syncthreads();
-    }
 
-    // ---- epilogue.  The staging buffers are free now and are reused for S and for codes. ----
-    // padded-tap mask of each of this lane's rows
-    uint64_t padmask[TM];
-    bool any_pad = false;
+    for (int rt = rt_first; rt < p.tiles_m; rt += p.row_tile_step) {
+        const int row0 = rt * BM;
+        const bool next_tile = rt + p.row_tile_step < p.tiles_m;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        padmask[i] = 0;
-        const int64_t m = row0 + ty + 16 * i;
-        if (m < p.M) {
-            const int64_t rem = m % (p.Ho * p.Wo);
-            const int h0 = (int)(rem / p.Wo) * p.stride - p.pad, w0 = (int)(rem % p.Wo) * p.stride - p.pad;
-            for (int t = 0; t < taps; ++t) {
-                const int hi = h0 + t / p.kw, wi = w0 + t % p.kw;
-                if (hi < 0 || hi >= p.H || wi < 0 || wi >= p.W) padmask[i] |= (uint64_t)1 << t;
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int n = 0; n < TN; ++n)
+#pragma unroll
+                for (int s = 0; s < T::S; ++s) P[i][n][s] = 0u;
+
+        for (int c = 0; c < p.nchunks; ++c) {
+            const bool more = c + 1 < p.nchunks;
+            if (more) {
+                fetch((c + 1) * p.kb);
+            } else if (next_tile) {
+                locate((rt + p.row_tile_step) * BM);
+                fetch(0);
             }
-            any_pad |= padmask[i] != 0;
+            const int left = p.nw - c * p.kb;
+            const int nkq = ((left < p.kb ? left : p.kb) + KV - 1) / KV;
+            tile_mac<WB, AB, TM, TN, KV, kConvKB>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P);
+            if (more || next_tile) stash(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
         }
-    }
-    int32_t *S = reinterpret_cast<int32_t *>(&smem[0][0]); // [BN][taps]
-    const bool block_pad = __syncthreads_or(any_pad ? 1 : 0) != 0;
-    if (block_pad) {
-        for (int e = tid; e < T::BN * taps; e += kTileThreads) {
-            const int cl = e / taps, t = e % taps;
-            const int64_t c = col0 + cl;
-            int32_t s = 0;
-            if (c < p.Cout) {
-                for (int i = 0; i < WB; ++i) {
-                    const uint32_t *wp = p.w + ((int64_t)i * p.Cout + c) * p.nw + (int64_t)t * p.cw;
-                    int32_t cnt = 0;
-                    for (int64_t k = 0; k < p.cw; ++k) cnt += __builtin_popcount(wp[k]);
-                    s += (2 * cnt - (int32_t)p.Cin) << i;
+        // stage `buf` now holds the next tile's first stage (if any); stage buf^1 is free
+
+        // ---- epilogue, first half: recombine and hand the tile over to a row-major layout ----
+        int32_t *V = reinterpret_cast<int32_t *>(&smem[buf ^ 1][0]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int n = 0; n < TN; ++n)
+                V[(ty + 16 * i) * EPI_STRIDE + tx + 16 * n] = recombine<T::S>(P[i][n], p.n_times_top);
+        __syncthreads();
+
+        // ---- second half: padding correction, stores, scale, quantize, plane split ----
+#pragma unroll 1
+        for (int pass = 0; pass < BM / RPP; ++pass) {
+            const int rl = pass * RPP + tid / LPR;
+            const int r = row0 + rl;
+            const bool rvalid = r < p.M;
+            const int4 vv = *reinterpret_cast<const int4 *>(V + rl * EPI_STRIDE + c4);
+            int32_t v[4] = {vv.x, vv.y, vv.z, vv.w};
+            // padded taps of this output pixel: tap (ky, kx) is padded iff its row or its column is
+            uint32_t ybad = 0, xbad = 0;
+            {
+                const uint32_t mm = rvalid ? (uint32_t)r : 0u;
+                const uint32_t b = fdiv(mm, p.div_howo), rem = mm - b * p.div_howo.d;
+                const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
+                const int h0 = (int)ho * p.stride - p.pad, w0 = (int)wo * p.stride - p.pad;
+                for (int ky = 0; ky < p.kh; ++ky)
+                    if ((unsigned)(h0 + ky) >= (unsigned)p.H) ybad |= 1u << ky;
+                for (int kx = 0; kx < p.kw; ++kx)
+                    if ((unsigned)(w0 + kx) >= (unsigned)p.W) xbad |= 1u << kx;
+            }
+            if (rvalid && (ybad | xbad) != 0) {
+                int32_t corr[4] = {0, 0, 0, 0};
+                for (int ky = 0; ky < p.kh; ++ky)
+                    for (int kx = 0; kx < p.kw; ++kx)
+                        if (((ybad >> ky) | (xbad >> kx)) & 1u) {
+                            const int4 s4 = *reinterpret_cast<const int4 *>(S + (ky * p.kw + kx) * BN + c4);
+                            corr[0] += s4.x, corr[1] += s4.y, corr[2] += s4.z, corr[3] += s4.w;
+                        }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] += p.top_a * corr[e];
+            }
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (float)v[e] * sc[e];
+            if (rvalid) {
+                const int64_t off = (int64_t)r * p.Cout + cidx;
+                if (cols4) {
+                    if (p.acc) *reinterpret_cast<int4 *>(p.acc + off) = make_int4(v[0], v[1], v[2], v[3]);
+                    if (p.out) *reinterpret_cast<float4 *>(p.out + off) = make_float4(o[0], o[1], o[2], o[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (cidx + e < p.Cout) {
+                            if (p.acc) p.acc[off + e] = v[e];
+                            if (p.out) p.out[off + e] = o[e];
+                        }
                 }
             }
-            S[e] = s;
-        }
-        __syncthreads();
-    }
-
-    uint8_t *codes = reinterpret_cast<uint8_t *>(&smem[1][0]); // [BM][BN]
+            if (p.next) {
+                // four byte codes in one register; channels past Cout give 0 bits (pad bits are 0)
+                uint32_t cw4 = 0;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int64_t r = row0 + ty + 16 * i;
-#pragma unroll
-        for (int n = 0; n < TN; ++n) {
-            const int cl = tx + 16 * n;
-            const int64_t cidx = col0 + cl;
-            const bool ok = r < p.M && cidx < p.Cout;
-            int32_t v = recombine<T::S>(P[i][n], p.n_times_top);
-            if (ok && padmask[i]) {
-                int32_t corr = 0;
-                for (uint64_t mbits = padmask[i]; mbits; mbits &= mbits - 1)
-                    corr += S[cl * taps + __builtin_ctzll(mbits)];
-                v += p.top_a * corr;
-            }
-            float o = 0.0f;
-            if (ok) {
-                if (p.acc) p.acc[r * p.Cout + cidx] = v;
-                if (p.scale) o = (float)v * p.scale[cidx];
-                if (p.out) p.out[r * p.Cout + cidx] = o;
-            }
-            if (p.next)
-                codes[(ty + 16 * i) * T::BN + cl] =
-                    ok ? (uint8_t)quantize_code(o, p.next_inv_clip, p.next_half_top, p.next_top) : (uint8_t)0;
-        }
-    }
-
-    if (p.next) {
-        // plane split of the staged codes: one lane builds one 32-channel word of every plane
-        static_assert(T::BN % 32 == 0, "the fused epilogue packs whole words");
-        constexpr int WPR = T::BN / 32;
-        __syncthreads();
-        for (int e = tid; e < T::BM * WPR; e += kTileThreads) {
-            const int rl = e / WPR, wc = e % WPR;
-            const int64_t r = row0 + rl;
-            const int64_t wword = col0 / 32 + wc;
-            if (r >= p.M || wword >= p.cwo) continue;
-            const uint32_t *src = reinterpret_cast<const uint32_t *>(codes + rl * T::BN + wc * 32);
-            uint32_t d[8];
-#pragma unroll
-            for (int q = 0; q < 8; ++q) d[q] = src[q];
-            for (int j = 0; j < p.next_bits; ++j) {
-                uint32_t word = 0;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    // bit j of four byte codes -> four adjacent bits
-                    const uint32_t x = (d[q] >> j) & 0x01010101u;
-                    word |= ((x * 0x00204081u >> 21) & 15u) << (4 * q);
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t code = cidx + e < p.Cout
+                                              ? (uint32_t)quantize_code(o[e], p.next_inv_clip, p.next_half_top, p.next_top)
+                                              : 0u;
+                    cw4 |= code << (8 * e);
                 }
-                p.next[((int64_t)j * p.M + r) * p.cwo + wword] = word;
+                const int wword = (col0 >> 5) + (tid % LPR) / 8;
+                const int shift = 4 * (tid & 7);
+                for (int j = 0; j < p.next_bits; ++j) {
+                    // bit j of the four codes -> a nibble -> this lane's place in the 32-channel word
+                    const uint32_t x = (cw4 >> j) & 0x01010101u;
+                    const uint32_t word = or_reduce8((((x * 0x00204081u) >> 21) & 15u) << shift);
+                    if ((tid & 7) == 0 && rvalid && wword < p.cwo)
+                        p.next[((int64_t)j * p.M + r) * p.cwo + wword] = word;
+                }
             }
         }
+        __syncthreads(); // V's stage is about to be refilled by the next tile's pipeline
     }
 }
 
@@ -297,32 +381,76 @@ __global__ __launch_bounds__(256) void bconv_plain_kernel(ConvParams p, int w_bi
     if (p.out) p.out[idx] = (float)v * p.scale[c];
 }
 
-template <int WB, int AB> static void launch_conv(ConvParams p, hipStream_t st)
+// Workgroups resident on the whole chip for one kernel (occupancy x CU count), cached per kernel.
+template <typename K> static int resident_workgroups(K kernel, size_t dyn_smem)
 {
-    using G = TilePick<WB, AB>;
-    // the fused epilogue packs whole 32-channel words, so the column tile is a multiple of 32
-    constexpr int TN = G::TN % 2 == 0 ? G::TN : G::TN + 1;
-    using T = Tile<WB, AB, G::TM, TN, G::KV>;
-    const int64_t tiles_m = ceil_div(p.M, T::BM);
-    p.tiles_n = ceil_div(p.Cout, T::BN);
-    p.nblocks = tiles_m * p.tiles_n;
-    const dim3 grid((unsigned)p.nblocks), block(kTileThreads);
-    if (p.cw % 4 == 0)
-        hipLaunchKernelGGL((bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, 4>), grid, block, 0, st, p);
-    else if (p.cw % 2 == 0)
-        hipLaunchKernelGGL((bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, 2>), grid, block, 0, st, p);
-    else
-        hipLaunchKernelGGL((bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, 1>), grid, block, 0, st, p);
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kTileThreads, dyn_smem) != hipSuccess)
+        return 0;
+    return cus * per_cu;
 }
 
-template <int WB> static bool conv_dispatch_a(int a_bits, const ConvParams &p, hipStream_t st)
+// Lane tile of the convolution kernel per (w_bits, a_bits).  The kernel carries more live state
+// than the GEMM (pixel coordinates, the prefetched chunk across the epilogue), so its tiles are
+// smaller; the column tile stays a multiple of 32 because the fused epilogue packs whole words.
+#ifdef QNN_CONV_TILE_OVERRIDE
+template <int WB, int AB> struct ConvPick {
+    static constexpr int TM = QNN_CONV_TM, TN = QNN_CONV_TN, KV = QNN_CONV_KV;
+};
+#else
+template <int WB, int AB> struct ConvPick {
+    static constexpr int TM = 4, TN = (WB + AB >= 7 ? 2 : 4), KV = (WB + AB >= 6 ? 2 : 4);
+};
+#endif
+
+template <int WB, int AB, int VW> static int launch_conv_vw(ConvTileParams p, hipStream_t st)
+{
+    using G = ConvPick<WB, AB>;
+    constexpr int TN = G::TN;
+    static_assert(TN % 2 == 0, "column tile must be a multiple of 32");
+    using T = Tile<WB, AB, G::TM, TN, G::KV, kConvKB>;
+    auto kernel = bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW>;
+    const size_t dyn = (size_t)T::BN * p.kh * p.kw * sizeof(int32_t);
+    p.tiles_m = (int)ceil_div(p.M, T::BM);
+    p.tiles_n = (int)ceil_div(p.Cout, T::BN);
+    // stage length: of the multiples of 4 up to the stage capacity, the one whose last stage is
+    // longest (the last stage of a tile hides the first fetch of the next tile); ties -> fewer stages
+    int best_kb = 4, best_last = 0;
+    for (int kb = 4; kb <= kConvKB; kb += 4) {
+        const int nch = (int)ceil_div(p.nw, kb);
+        const int last = p.nw - (nch - 1) * kb;
+        if (last >= best_last) best_last = last, best_kb = kb;
+    }
+    p.kb = best_kb;
+    p.nchunks = (int)ceil_div(p.nw, best_kb);
+    int slots = resident_workgroups(kernel, dyn);
+    if (slots <= 0) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: occupancy query failed");
+    // every workgroup owns one column tile; the row tiles are dealt round-robin to the
+    // slots / tiles_n workgroups of that column
+    int groups = slots / p.tiles_n;
+    if (groups < 1) groups = 1;
+    if (groups > p.tiles_m) groups = p.tiles_m;
+    p.row_tile_step = groups;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n)), dim3(kTileThreads), dyn, st, p);
+    return QNN_OK;
+}
+
+template <int WB, int AB> static int launch_conv(const ConvTileParams &p, hipStream_t st)
+{
+    if (p.cw % 4 == 0) return launch_conv_vw<WB, AB, 4>(p, st);
+    if (p.cw % 2 == 0) return launch_conv_vw<WB, AB, 2>(p, st);
+    return launch_conv_vw<WB, AB, 1>(p, st);
+}
+
+template <int WB> static int conv_dispatch_a(int a_bits, const ConvTileParams &p, hipStream_t st)
 {
     switch (a_bits) {
-    case 1: launch_conv<WB, 1>(p, st); return true;
-    case 2: launch_conv<WB, 2>(p, st); return true;
-    case 3: launch_conv<WB, 3>(p, st); return true;
-    case 4: launch_conv<WB, 4>(p, st); return true;
-    default: return false;
+    case 1: return launch_conv<WB, 1>(p, st);
+    case 2: return launch_conv<WB, 2>(p, st);
+    case 3: return launch_conv<WB, 3>(p, st);
+    default: return launch_conv<WB, 4>(p, st);
     }
 }
 
@@ -375,31 +503,42 @@ extern "C" int qnn_conv2d(const qnn_conv_desc *d, const uint32_t *a_planes, cons
     if (d->B > (INT64_MAX >> 24) / (p.Ho * p.Wo)) return fail(QNN_ERR_RANGE, "qnn_conv2d: too many output pixels");
     p.M = d->B * p.Ho * p.Wo;
     p.a_plane_stride = d->B * d->H * d->W * p.cw;
-    const int top_w = (1 << d->w_bits) - 1;
-    p.top_a = (1 << d->a_bits) - 1;
-    p.n_times_top = (uint32_t)(n * top_w * p.top_a);
     p.scale = scale;
     p.acc = acc;
     p.out = out;
-    p.next = next_planes;
-    p.next_bits = next_planes ? next_bits : 0;
-    p.next_top = next_planes ? (1 << next_bits) - 1 : 0;
-    p.next_inv_clip = next_planes ? 1.0f / next_clip : 0.0f;
-    p.next_half_top = (float)p.next_top * 0.5f;
-    p.cwo = ceil_div(d->Cout, 32);
-    p.wvec = (p.nw % 4 == 0) ? 1 : 0;
-    p.tiles_n = p.nblocks = 0;
+    const int64_t cwo = ceil_div(d->Cout, 32);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
+    // the register-blocked kernel indexes pixels and plane words with 32-bit integers
+    const bool small_index = p.M < (1LL << 29) && p.a_plane_stride < (1LL << 31) && p.M * cwo < (1LL << 31) &&
+                             p.Ho * p.Wo < (1LL << 31);
     bool done = false;
-    if (p.nw <= kMaxGroups && d->kh * d->kw <= kMaxTaps) {
+    if (p.nw <= kMaxGroups && d->kh * d->kw <= kMaxTaps && d->w_bits <= 4 && d->a_bits <= 4 && small_index) {
+        ConvTileParams t;
+        t.a = a_planes, t.w = w_planes, t.scale = scale, t.acc = acc, t.out = out, t.next = next_planes;
+        t.H = (int)d->H, t.W = (int)d->W, t.HW = (int)(d->H * d->W), t.Cin = (int)d->Cin, t.Cout = (int)d->Cout;
+        t.M = (int)p.M, t.cw = (int)p.cw, t.nw = (int)p.nw, t.cwo = (int)cwo;
+        t.kh = d->kh, t.kw = d->kw, t.stride = d->stride, t.pad = d->pad;
+        t.a_plane_stride = (int)p.a_plane_stride;
+        t.top_a = (1 << d->a_bits) - 1;
+        t.n_times_top = (uint32_t)(n * ((1 << d->w_bits) - 1) * t.top_a);
+        t.next_bits = next_planes ? next_bits : 0;
+        t.next_top = next_planes ? (1 << next_bits) - 1 : 0;
+        t.next_inv_clip = next_planes ? 1.0f / next_clip : 0.0f;
+        t.next_half_top = (float)t.next_top * 0.5f;
+        t.wvec = (p.nw % 4 == 0) ? 1 : 0;
+        t.div_howo = make_fastdiv((uint32_t)(p.Ho * p.Wo));
+        t.div_wo = make_fastdiv((uint32_t)p.Wo);
+        t.tiles_m = t.tiles_n = t.row_tile_step = t.kb = t.nchunks = 0;
+        int rc = QNN_OK;
         switch (d->w_bits) {
-        case 1: done = conv_dispatch_a<1>(d->a_bits, p, st); break;
-        case 2: done = conv_dispatch_a<2>(d->a_bits, p, st); break;
-        case 3: done = conv_dispatch_a<3>(d->a_bits, p, st); break;
-        case 4: done = conv_dispatch_a<4>(d->a_bits, p, st); break;
-        default: break;
+        case 1: rc = conv_dispatch_a<1>(d->a_bits, t, st); break;
+        case 2: rc = conv_dispatch_a<2>(d->a_bits, t, st); break;
+        case 3: rc = conv_dispatch_a<3>(d->a_bits, t, st); break;
+        default: rc = conv_dispatch_a<4>(d->a_bits, t, st); break;
         }
+        if (rc != QNN_OK) return rc;
+        done = true;
     }
     if (!done) {
         if (next_planes)

@@ -9,7 +9,8 @@ import os
 import torch  # loads the HIP runtime that libqnn.so binds to
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libqnn.so")
+# QNN_LIB_PATH selects another build of the same library (e.g. a tuning variant)
+LIB_PATH = os.environ.get("QNN_LIB_PATH") or os.path.join(_HERE, "libqnn.so")
 
 QNN_OK = 0
 QNN_ERR_INVALID_ARG = -1
