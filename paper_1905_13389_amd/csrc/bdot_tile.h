@@ -25,14 +25,16 @@ constexpr int kBK = 16; // default number of reduction words staged per step (64
 
 // KV = reduction words fetched from LDS per read (4: ds_read_b128, 2: ds_read_b64); the lane keeps
 // KV * (TM*AB + TN*WB) operand registers next to its TM*TN*(WB+AB-1) counters.
-// KB = reduction words an LDS stage can hold (a multiple of 4).  The LDS row stride BKP is the
-// next odd multiple of 4 words, which keeps rows 16-byte aligned and spreads the 16 rows a wave
-// reads at once over all banks.
+// KB = reduction words an LDS stage can hold (a multiple of 4).  The LDS row stride BKP (words) is
+// chosen so that the 16 rows a wave reads together fall into different banks (32 banks of 4
+// bytes, one pass serves 128 bytes): for 16-byte reads (KV = 4, 8 lanes per pass) an odd multiple
+// of 4 words; for 8-byte reads (KV = 2, 16 lanes per pass) twice an odd number, which leaves the
+// rows 8-byte aligned only, so stages are then written with 8-byte stores.
 template <int WB, int AB, int TM, int TN, int KV = 4, int KB = kBK> struct Tile {
     static_assert(KV == 2 || KV == 4, "KV is 2 or 4 words");
     static_assert(KB % 4 == 0, "stages are loaded in 16-byte units");
     static constexpr int UQ = KB / 4; // 16-byte units per row and plane
-    static constexpr int BKP = (UQ % 2 == 1) ? KB : KB + 4;
+    static constexpr int BKP = KV == 4 ? ((UQ % 2 == 1) ? KB : KB + 4) : KB + 2;
     static constexpr int BM = 16 * TM;
     static constexpr int BN = 16 * TN;
     static constexpr int S = WB + AB - 1;
@@ -94,9 +96,15 @@ __device__ __forceinline__ uint4 load_rowmajor4(const uint32_t *__restrict__ bas
 // All WB x AB plane pairs of one weight word column and one activation word column:
 // count[i + j] += bitcount(w[i] xor a[j]), exactly one v_xor_b32 and one v_bcnt_u32_b32 (whose
 // third operand is the running count) per pair.  One asm statement per call, so the compiler can
-// neither re-associate the count chains into extra adds, nor keep hundreds of xor results alive,
-// nor pad every pair with the wait state it conservatively puts between asm statements.
-#define QNN_XB(w, a, p) "v_xor_b32 %[t], %[" #w "], %[" #a "]\n\tv_bcnt_u32_b32 %[" #p "], %[t], %[" #p "]\n\t"
+// neither re-associate the count chains into extra adds nor keep hundreds of xor results alive.
+//
+// Issue order.  On gfx950 a wave64 v_xor_b32 occupies its SIMD for about 2.4 cycles and a
+// v_bcnt_u32_b32 for about 4.4 (measured with register-only loops, 2 or 4 waves per SIMD), but
+// only when something that is not a VALU instruction follows each xor/count pair: back-to-back
+// pairs cost about 10 cycles per pair instead of 6.7.  Hence the s_nop 0 after every pair (the
+// compiler puts one between asm statements on its own, which covers the single-pair cases).
+#define QNN_XB1(w, a, p) "v_xor_b32 %[t], %[" #w "], %[" #a "]\n\tv_bcnt_u32_b32 %[" #p "], %[t], %[" #p "]\n\t"
+#define QNN_XB(w, a, p) QNN_XB1(w, a, p) "s_nop 0\n\t"
 #define QNN_ROW1(w, p0) QNN_XB(w, a0, p0)
 #define QNN_ROW2(w, p0, p1) QNN_XB(w, a0, p0) QNN_XB(w, a1, p1)
 #define QNN_ROW3(w, p0, p1, p2) QNN_XB(w, a0, p0) QNN_XB(w, a1, p1) QNN_XB(w, a2, p2)
@@ -123,7 +131,7 @@ __device__ __forceinline__ void xor_bcnt_pairs(const uint32_t (&w)[WB], const ui
                                                uint32_t (&c)[WB + AB - 1])
 {
     uint32_t t;
-    if constexpr (WB == 1 && AB == 1) QNN_PAIRS(QNN_ROW1(w0, p0), QNN_P1, QNN_W1, QNN_A1);
+    if constexpr (WB == 1 && AB == 1) QNN_PAIRS(QNN_XB1(w0, a0, p0), QNN_P1, QNN_W1, QNN_A1);
     else if constexpr (WB == 1 && AB == 2) QNN_PAIRS(QNN_ROW2(w0, p0, p1), QNN_P2, QNN_W1, QNN_A2);
     else if constexpr (WB == 1 && AB == 3) QNN_PAIRS(QNN_ROW3(w0, p0, p1, p2), QNN_P3, QNN_W1, QNN_A3);
     else if constexpr (WB == 1 && AB == 4) QNN_PAIRS(QNN_ROW4(w0, p0, p1, p2, p3), QNN_P4, QNN_W1, QNN_A4);
@@ -161,7 +169,18 @@ __device__ __forceinline__ void xor_bcnt_pairs(const uint32_t (&w)[WB], const ui
     }
 }
 
-// The xor + bitcount block: one kBK-word stage out of LDS into the P_s accumulators.
+// Store one 4-word unit of a stage row (16-byte store when the row stride keeps that alignment).
+template <int KV> __device__ __forceinline__ void lds_write_unit(uint32_t *dst, const uint4 &v)
+{
+    if constexpr (KV == 4) {
+        *reinterpret_cast<uint4 *>(dst) = v;
+    } else {
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(v.x, v.y);
+        *reinterpret_cast<uint2 *>(dst + 2) = make_uint2(v.z, v.w);
+    }
+}
+
+// The xor + bitcount block: one stage out of LDS into the P_s accumulators.
 template <int KV> __device__ __forceinline__ void lds_read_words(const uint32_t *p, uint32_t (&dst)[KV])
 {
     if constexpr (KV == 4) {

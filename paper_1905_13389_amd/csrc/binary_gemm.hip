@@ -66,13 +66,13 @@ __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2,
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS)
-                *reinterpret_cast<uint4 *>(As + (idx >> 2) * T::BKP + 4 * (idx & 3)) = ra[u];
+                lds_write_unit<KV>(As + (idx >> 2) * T::BKP + 4 * (idx & 3), ra[u]);
         }
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS)
-                *reinterpret_cast<uint4 *>(Ws + (idx >> 2) * T::BKP + 4 * (idx & 3)) = rw[u];
+                lds_write_unit<KV>(Ws + (idx >> 2) * T::BKP + 4 * (idx & 3), rw[u]);
         }
     };
 

@@ -205,13 +205,13 @@ bconv_tile_kernel(ConvTileParams p)
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS)
-                *reinterpret_cast<uint4 *>(As + (idx / UQ) * T::BKP + 4 * (idx % UQ)) = ra[u];
+                lds_write_unit<KV>(As + (idx / UQ) * T::BKP + 4 * (idx % UQ), ra[u]);
         }
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS)
-                *reinterpret_cast<uint4 *>(Ws + (idx / UQ) * T::BKP + 4 * (idx % UQ)) = rw[u];
+                lds_write_unit<KV>(Ws + (idx / UQ) * T::BKP + 4 * (idx % UQ), rw[u]);
         }
     };
 
