@@ -19,11 +19,43 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz, one 32-bit VALU lane-op per lane and clock.
-# A plane pair costs one v_xor_b32 and one v_bcnt_u32_b32 per 32 bit-pairs, counted as 2 binary
-# operations per bit-pair (xnor and count, the 2*MAC convention): 32 * 2 / 2 = 32 per lane-op.
-VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
-PEAK_BINARY_TOPS = VALU_LANE_OPS_PER_S * 32 / 1e12
+# VALU roofline of the xor + bitcount pair on MI355X (256 CUs x 4 SIMDs, 2.4 GHz).
+# The published 157.3 TFLOP/s fp32 vector figure is 32 lanes per SIMD and clock (one FMA = 2 flops);
+# register-only loops (qnn_probe_valu, run below and reported as roofline.probe) show that a
+# wave64 v_xor_b32 indeed issues at that rate (about 2.4 cycles) while v_bcnt_u32_b32 runs at half
+# of it (16 lanes per clock, about 4.4 cycles).  One plane pair per 32 bit-pairs costs one of each
+# and counts as 2 binary operations per bit-pair (xnor and count, the 2*MAC convention):
+#   peak = 64 / (1 / 78.6e12 + 1 / 39.3e12) = 1677.7 binary TOP/s.
+# NOMINAL is the figure one gets by assuming 16 lanes per clock for both instructions.
+CLOCK_HZ = 2.4e9
+SIMDS = 256 * 4
+XOR_LANE_OPS_PER_S = SIMDS * 32 * CLOCK_HZ
+BCNT_LANE_OPS_PER_S = SIMDS * 16 * CLOCK_HZ
+PEAK_BINARY_TOPS = 64.0 / (1.0 / XOR_LANE_OPS_PER_S + 1.0 / BCNT_LANE_OPS_PER_S) / 1e12
+NOMINAL_BINARY_TOPS = SIMDS * 16 * CLOCK_HZ * 32 / 1e12
+
+# HBM bytes of one default-workload GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (profiles/bgemm_2x2_4096_hbm_counters.txt); only valid for size 4096, 2x2 bit
+GEMM_2X2_4096_TRAFFIC_BYTES = 183.9e6
+
+
+def valu_probe(qnn, torch):
+    """Cycles per wave64 VALU instruction and SIMD (at 2.4 GHz) of the register-only loops."""
+    wgs, iters = 512, 20000          # 2 waves per SIMD, 64 VALU instructions per iteration
+    buf = torch.empty(wgs * 256, dtype=torch.int32, device="cuda")
+    res = {}
+    for mode, name in ((0, "v_xor_b32"), (1, "v_bcnt_u32_b32"), (2, "xor_bcnt_pair")):
+        qnn.qnn_probe_valu(mode, wgs, iters // 10, buf)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        qnn.qnn_probe_valu(mode, wgs, iters, buf)
+        e1.record()
+        torch.cuda.synchronize()
+        instr_per_simd = 64.0 * iters * (wgs / 256)
+        res[name] = round(e0.elapsed_time(e1) * 1e-3 * CLOCK_HZ / instr_per_simd, 3)
+    res["unit"] = "cycles per wave64 instruction per SIMD at 2.4 GHz, 2 waves per SIMD"
+    res["pair_binary_tops"] = round(SIMDS * CLOCK_HZ / (2 * res["xor_bcnt_pair"]) * 64 * 64 / 1e12, 1)
+    return res
 
 
 def parse():
@@ -139,6 +171,7 @@ def conv_workload(args):
                    "step": "qnn_encode_pack + qnn_conv2d per layer (fused scale/quantize/pack epilogue)"},
         "roofline": {"bound": "alu", "achieved": round(tops, 2), "peak": round(PEAK_BINARY_TOPS, 1),
                      "unit": "binary TOP/s", "frac": round(tops / PEAK_BINARY_TOPS, 4), "traffic": None,
+                     "frac_of_16_lane_nominal": round(tops / NOMINAL_BINARY_TOPS, 4),
                      "note": "whole step (encode + all conv launches), not a single kernel"}}))
 
 
@@ -215,7 +248,12 @@ def main():
         "roofline": {"bound": "alu", "kernel": "bgemm_tile_kernel<%d,%d>" % (wb, ab),
                      "achieved": round(achieved, 2), "peak": round(PEAK_BINARY_TOPS, 1),
                      "unit": "binary TOP/s", "frac": round(achieved / PEAK_BINARY_TOPS, 4),
-                     "kernel_ms": round(gemm_ms, 4), "traffic": None},
+                     "kernel_ms": round(gemm_ms, 4),
+                     "traffic": GEMM_2X2_4096_TRAFFIC_BYTES if (size, wb, ab) == (4096, 2, 2) else None,
+                     "peak_note": "v_xor_b32 at 32 lanes/clk/SIMD + v_bcnt_u32_b32 at 16 lanes/clk/SIMD, "
+                                  "256 CUs x 4 SIMDs x 2.4 GHz",
+                     "frac_of_16_lane_nominal": round(achieved / NOMINAL_BINARY_TOPS, 4),
+                     "probe": valu_probe(qnn, torch)},
     }
 
     if args.sweep:

@@ -126,6 +126,16 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
                const float *scale, int32_t *acc, float *out, uint32_t *next_planes,
                float next_clip, int next_bits, void *stream);
 
+/*
+ * qnn_probe_valu -- measurement aid, not part of the hot path: launches `workgroups` workgroups
+ * of 256 lanes that each run `iters` iterations of a register-only loop of 64 VALU instructions
+ * per wave, so that the issue rate of the binary dot product's two instructions (the "xnor" and
+ * "bitcount" of the paper's abstract) can be timed on the device at hand.
+ *   mode 0: v_xor_b32 only; 1: v_bcnt_u32_b32 only; 2: xor/count pairs in the GEMM kernels' order
+ *   out  DEVICE, workgroups * 256 uint32 (receives the loops' results so they are not removed)
+ */
+int qnn_probe_valu(int mode, int workgroups, int iters, uint32_t *out, void *stream);
+
 /* Message for the last error returned on the calling thread ("" if none). Never NULL. */
 const char *qnn_last_error(void);
 

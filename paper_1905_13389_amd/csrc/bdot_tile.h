@@ -72,6 +72,22 @@ __device__ __forceinline__ int64_t xcd_band_remap(int64_t pid, int64_t nblocks)
     return tall * per + (xcd - tall) * (per - 1) + local;
 }
 
+// Linear tile id -> (tile row, tile column), walking kGroupRows tile rows down before moving one
+// tile column right.  The workgroups resident on an XCD at one time then cover a few tile rows
+// (their activation planes stay in that XCD's L2) and every weight tile they stream is shared by
+// kGroupRows workgroups instead of being fetched again for every tile row.
+constexpr int kGroupRows = 4;
+__device__ __forceinline__ void grouped_tile(int64_t tile, int64_t tiles_m, int64_t tiles_n, int64_t &tm,
+                                             int64_t &tn)
+{
+    const int64_t per_group = kGroupRows * tiles_n;
+    const int64_t group = tile / per_group, in_group = tile % per_group;
+    const int64_t first = group * kGroupRows;
+    const int64_t rows = tiles_m - first < kGroupRows ? tiles_m - first : kGroupRows;
+    tm = first + in_group % rows;
+    tn = in_group / rows;
+}
+
 // 4 reduction words of one row of a [plane][R][nw] row-major plane tensor; words past nw and
 // rows past R read as 0 (a zero word xors to the other operand's zero word: no contribution).
 __device__ __forceinline__ uint4 load_rowmajor4(const uint32_t *__restrict__ base, int64_t R,

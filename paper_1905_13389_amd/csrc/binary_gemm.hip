@@ -26,8 +26,10 @@ __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2,
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int64_t tile = xcd_band_remap(blockIdx.x, p.nblocks);
-    const int64_t row0 = (tile / p.tiles_n) * T::BM;
-    const int64_t col0 = (tile % p.tiles_n) * T::BN;
+    int64_t tm, tn;
+    grouped_tile(tile, p.nblocks / p.tiles_n, p.tiles_n, tm, tn);
+    const int64_t row0 = tm * T::BM;
+    const int64_t col0 = tn * T::BN;
     const bool vec = p.vec != 0;
 
     uint32_t P[TM][TN][T::S];

@@ -24,7 +24,7 @@ QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d",
-           "qnn_last_error", "qnn_version")
+           "qnn_probe_valu", "qnn_last_error", "qnn_version")
 
 
 class QnnError(RuntimeError):
@@ -61,6 +61,8 @@ def lib():
         L.qnn_dequant_scale.restype = i32
         L.qnn_conv2d.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_conv2d.restype = i32
+        L.qnn_probe_valu.argtypes = [i32, i32, i32, vp, vp]
+        L.qnn_probe_valu.restype = i32
         L.qnn_last_error.argtypes = []
         L.qnn_last_error.restype = ctypes.c_char_p
         L.qnn_version.argtypes = []
@@ -117,6 +119,12 @@ def qnn_binary_gemm(a_planes, w_planes, n, want_acc=True, scale=None, acc=None, 
     _check(lib().qnn_binary_gemm(_ptr(a_planes), a_bits, _ptr(w_planes), w_bits, rows, cols, n,
                                  _ptr(acc), _ptr(scale), _ptr(out), _stream()))
     return acc, out
+
+
+def qnn_probe_valu(mode, workgroups, iters, out):
+    """Launch the register-only issue-rate loop (see include/qnn.h); out: int32 [workgroups*256]."""
+    assert out.numel() >= workgroups * 256
+    _check(lib().qnn_probe_valu(int(mode), int(workgroups), int(iters), _ptr(out), _stream()))
 
 
 def qnn_dequant_scale(acc, scale, out=None):
