@@ -74,6 +74,85 @@ __global__ __launch_bounds__(256) void encode_pack_kernel(EncodeParams p)
     }
 }
 
+// Streaming variant for one long contiguous bit-vector (n a multiple of 32, 16-byte aligned
+// source): lane l of a wave loads elements 4l..4l+3 of a 256-element chunk with one vector load,
+// UNROLL chunks in flight per lane.  The 4 plane bits of a lane form a nibble; the 8 lanes that
+// share a 32-element word OR their shifted nibbles together with three DPP steps and lane 8k
+// stores word k.  The codes are the same quantize_code / level arithmetic as above.
+__device__ __forceinline__ uint32_t or_reduce8_lanes(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true); // row_half_mirror
+    return v;
+}
+
+template <typename T> struct Vec4;
+template <> struct Vec4<float> { using type = float4; };
+template <> struct Vec4<uint16_t> { using type = ushort4; };
+template <> struct Vec4<int8_t> { using type = char4; };
+
+template <typename T, int BITS, int UNROLL>
+__global__ __launch_bounds__(256) void encode_pack_stream_kernel(EncodeParams p)
+{
+    using V = typename Vec4<T>::type;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int64_t chunks = p.chunks_per_row; // 256-element chunks of the single row
+    const V *src = static_cast<const V *>(p.src);
+    const int shift = 4 * (lane & 7);
+
+    for (int64_t c0 = wave * UNROLL; c0 < chunks; c0 += nwaves * UNROLL) {
+        V v[UNROLL];
+        bool ok[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int64_t e = (c0 + u) * 256 + 4 * lane;
+            ok[u] = c0 + u < chunks && e < p.n;
+            if (ok[u]) v[u] = src[(c0 + u) * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            uint32_t cw4 = 0; // four byte codes; elements past the end give 0 bits
+            if (ok[u]) {
+                cw4 = (uint32_t)code_of<T>(v[u].x, p) | ((uint32_t)code_of<T>(v[u].y, p) << 8) |
+                      ((uint32_t)code_of<T>(v[u].z, p) << 16) | ((uint32_t)code_of<T>(v[u].w, p) << 24);
+            }
+            const int64_t k = (c0 + u) * 8 + (lane >> 3);
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) {
+                const uint32_t x = (cw4 >> j) & 0x01010101u;
+                const uint32_t word = or_reduce8_lanes((((x * 0x00204081u) >> 21) & 15u) << shift);
+                if ((lane & 7) == 0 && c0 + u < chunks && k < p.nw) p.planes[(int64_t)j * p.nw + k] = word;
+            }
+        }
+    }
+}
+
+template <typename T, int BITS> static void launch_stream(const EncodeParams &p, hipStream_t st)
+{
+    constexpr int UNROLL = 4;
+    const int64_t waves = ceil_div(p.chunks_per_row, UNROLL);
+    const int64_t blocks = ceil_div(waves, 4);
+    const unsigned grid = (unsigned)(blocks < 256 * 16 ? blocks : 256 * 16);
+    hipLaunchKernelGGL((encode_pack_stream_kernel<T, BITS, UNROLL>), dim3(grid), dim3(256), 0, st, p);
+}
+
+template <typename T> static void launch_stream_bits(const EncodeParams &p, int bits, hipStream_t st)
+{
+    switch (bits) {
+    case 1: launch_stream<T, 1>(p, st); break;
+    case 2: launch_stream<T, 2>(p, st); break;
+    case 3: launch_stream<T, 3>(p, st); break;
+    case 4: launch_stream<T, 4>(p, st); break;
+    case 5: launch_stream<T, 5>(p, st); break;
+    case 6: launch_stream<T, 6>(p, st); break;
+    case 7: launch_stream<T, 7>(p, st); break;
+    default: launch_stream<T, 8>(p, st); break;
+    }
+}
+
 template <typename T> static void launch_bits(const EncodeParams &p, int bits, unsigned grid, hipStream_t st)
 {
     switch (bits) {
@@ -118,10 +197,12 @@ extern "C" int qnn_encode_pack(const void *src, int dtype, int64_t rows, int64_t
     p.row_stride = row_stride_elems;
     // rows that are whole words long and contiguous form one long bit-vector per plane: treat
     // the tensor as a single row so that short rows (a pixel's channels) still fill whole waves
+    bool single_row = false;
     if (n % 32 == 0 && (rows == 1 || row_stride_elems == n)) {
         p.rows = 1;
         p.n = rows * n;
         p.row_stride = p.n;
+        single_row = true;
     }
     p.nw = ceil_div(p.n, 32);
     p.top = (1 << bits) - 1;
@@ -134,6 +215,14 @@ extern "C" int qnn_encode_pack(const void *src, int dtype, int64_t rows, int64_t
     const int64_t blocks = ceil_div(chunks, 4); // 4 waves per workgroup
     const unsigned grid = (unsigned)(blocks < 256 * 32 ? blocks : 256 * 32);
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (single_row && aligned16(src)) { // vector loads of 4 elements are whole and aligned
+        switch (dtype) {
+        case QNN_DTYPE_F32: launch_stream_bits<float>(p, bits, st); break;
+        case QNN_DTYPE_BF16: launch_stream_bits<uint16_t>(p, bits, st); break;
+        default: launch_stream_bits<int8_t>(p, bits, st); break;
+        }
+        return check_launch("qnn_encode_pack");
+    }
     switch (dtype) {
     case QNN_DTYPE_F32: launch_bits<float>(p, bits, grid, st); break;
     case QNN_DTYPE_BF16: launch_bits<uint16_t>(p, bits, grid, st); break;
