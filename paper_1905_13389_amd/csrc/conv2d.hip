@@ -16,7 +16,8 @@
 namespace qnn {
 
 constexpr int kMaxGroups = 1024; // reduction words (or word groups) addressable through the tap table
-constexpr int kMaxTaps = 49;
+constexpr int kMaxTaps = 32;      // tap sets are 32-bit masks
+constexpr int kMaxOutExtent = 2048; // Ho + Wo entries of the border-mask tables
 constexpr int kConvKB = 20; // an LDS stage holds up to 20 reduction words per row and plane
 
 // n / d for n < 2^31 and a divisor fixed per launch: q = (mulhi(n, mul) + n) >> shift.
@@ -55,7 +56,7 @@ struct ConvTileParams {
     int32_t *acc;
     float *out;
     uint32_t *next; // [next_bits][M][cwo]
-    int H, W, HW, Cin, Cout, M, cw, nw, cwo;
+    int H, W, HW, Cin, Cout, M, cw, nw, cwo, Ho, Wo;
     int kh, kw, stride, pad;
     int a_plane_stride;
     uint32_t n_times_top; // kh kw Cin (2^WB-1)(2^AB-1)
@@ -68,32 +69,29 @@ struct ConvTileParams {
     int kb, nchunks;                     // reduction words per LDS stage (multiple of 4), stages per tile
 };
 
-// gather 4 consecutive reduction words of one output pixel; VW = gcd(cw, 4) words share a tap
+// Gather 4 consecutive reduction words of one output pixel.  VW = gcd(cw, 4) words share a tap;
+// the table gives each word group its tap number and its word offset from the pixel's window
+// origin; `padded` has a bit set for every tap of this pixel that lies outside the image.
 template <int VW>
-__device__ __forceinline__ uint4 gather4(const ConvTileParams &p, const uint32_t *__restrict__ plane,
-                                         const uint32_t *tap_table, bool row_ok, int pix_base, int hi0,
-                                         int wi0, int kword)
+__device__ __forceinline__ uint4 gather4(const uint32_t *__restrict__ a, const uint32_t *tap_table, int nw,
+                                         uint32_t padded, int base, int kword)
 {
     uint32_t v[4] = {0u, 0u, 0u, 0u};
-    if (row_ok) {
 #pragma unroll
-        for (int g = 0; g < 4 / VW; ++g) {
-            const int kw0 = kword + g * VW;
-            if (kw0 < p.nw) {
-                const uint32_t e = tap_table[kw0 / VW];
-                const int ky = (int)(e >> 24), kx = (int)((e >> 16) & 255), ci = (int)(e & 0xffff);
-                const int hi = hi0 + ky, wi = wi0 + kx;
-                if ((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W) {
-                    const uint32_t *src = plane + (int64_t)(pix_base + hi * p.W + wi) * p.cw + ci;
-                    if constexpr (VW == 4) {
-                        const uint4 t = *reinterpret_cast<const uint4 *>(src);
-                        v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
-                    } else if constexpr (VW == 2) {
-                        const uint2 t = *reinterpret_cast<const uint2 *>(src);
-                        v[2 * g] = t.x, v[2 * g + 1] = t.y;
-                    } else {
-                        v[g] = *src;
-                    }
+    for (int g = 0; g < 4 / VW; ++g) {
+        const int kw0 = kword + g * VW;
+        if (kw0 < nw) {
+            const uint32_t e = tap_table[kw0 / VW];
+            if (!((padded >> (e >> 24)) & 1u)) {
+                const uint32_t *src = a + (base + (int)(e & 0xffffffu));
+                if constexpr (VW == 4) {
+                    const uint4 t = *reinterpret_cast<const uint4 *>(src);
+                    v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
+                } else if constexpr (VW == 2) {
+                    const uint2 t = *reinterpret_cast<const uint2 *>(src);
+                    v[2 * g] = t.x, v[2 * g + 1] = t.y;
+                } else {
+                    v[g] = *src;
                 }
             }
         }
@@ -132,7 +130,10 @@ bconv_tile_kernel(ConvTileParams p)
     constexpr int STAGE_ALLOC = T::STAGE_WORDS > EPI_WORDS ? T::STAGE_WORDS : EPI_WORDS;
     __shared__ __attribute__((aligned(16))) uint32_t smem[2][STAGE_ALLOC];
     __shared__ uint32_t tap_table[kMaxGroups];
-    extern __shared__ __attribute__((aligned(16))) int32_t S[]; // [taps][BN]
+    extern __shared__ __attribute__((aligned(16))) int32_t dyn_smem[];
+    int32_t *S = dyn_smem;                                                   // [taps][BN]
+    uint32_t *ymask = reinterpret_cast<uint32_t *>(dyn_smem) + BN * p.kh * p.kw; // [Ho] taps whose row is outside
+    uint32_t *xmask = ymask + p.Ho;                                          // [Wo] taps whose column is outside
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
@@ -141,11 +142,26 @@ bconv_tile_kernel(ConvTileParams p)
     const bool wvec = p.wvec != 0;
     const int taps = p.kh * p.kw;
 
-    // reduction word group -> (ky, kx, first channel word)
+    // reduction word group -> tap number and word offset from the window origin
     for (int g = tid; g * VW < p.nw; g += kTileThreads) {
         const int kword = g * VW;
         const int tap = kword / p.cw, ci = kword % p.cw;
-        tap_table[g] = ((uint32_t)(tap / p.kw) << 24) | ((uint32_t)(tap % p.kw) << 16) | (uint32_t)ci;
+        tap_table[g] = ((uint32_t)tap << 24) | (uint32_t)(((tap / p.kw) * p.W + tap % p.kw) * p.cw + ci);
+    }
+    // output row / column -> set of taps that fall outside the image
+    for (int o = tid; o < p.Ho + p.Wo; o += kTileThreads) {
+        uint32_t m = 0;
+        if (o < p.Ho) {
+            const int h0 = o * p.stride - p.pad;
+            for (int ky = 0; ky < p.kh; ++ky)
+                if ((unsigned)(h0 + ky) >= (unsigned)p.H) m |= ((1u << p.kw) - 1u) << (ky * p.kw);
+        } else {
+            const int w0 = (o - p.Ho) * p.stride - p.pad;
+            for (int kx = 0; kx < p.kw; ++kx)
+                if ((unsigned)(w0 + kx) >= (unsigned)p.W)
+                    for (int ky = 0; ky < p.kh; ++ky) m |= 1u << (ky * p.kw + kx);
+        }
+        ymask[o] = m; // xmask follows ymask
     }
     // S[t][c] = sum over channels of the weight levels of tap t, from the planes
     for (int e = tid; e < BN * taps; e += kTileThreads) {
@@ -163,21 +179,22 @@ bconv_tile_kernel(ConvTileParams p)
         S[e] = s;
     }
 
-    // coordinates of the output pixels this lane fetches for the workgroup
-    int hi0[T::A_PER_THREAD], wi0[T::A_PER_THREAD], pbase[T::A_PER_THREAD];
-    bool rok[T::A_PER_THREAD];
+    // where this lane's stage units start in the activation planes, and their padded taps
+    int abase[T::A_PER_THREAD];
+    uint32_t apad[T::A_PER_THREAD];
     auto locate = [&](int row0) {
 #pragma unroll
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
-            const int m = row0 + (idx / UQ) % BM;
-            rok[u] = (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS) && m < p.M;
-            const uint32_t mm = rok[u] ? (uint32_t)m : 0u;
+            const int rp = idx / UQ;
+            const int m = row0 + rp % BM;
+            const bool ok = (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS) && m < p.M;
+            const uint32_t mm = ok ? (uint32_t)m : 0u;
             const uint32_t b = fdiv(mm, p.div_howo), rem = mm - b * p.div_howo.d;
             const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
-            hi0[u] = (int)ho * p.stride - p.pad;
-            wi0[u] = (int)wo * p.stride - p.pad;
-            pbase[u] = (int)b * p.HW;
+            apad[u] = ok ? (ymask[ho] | xmask[wo]) : 0xffffffffu;
+            abase[u] = (rp / BM) * p.a_plane_stride +
+                       ((int)b * p.HW + ((int)ho * p.stride - p.pad) * p.W + (int)wo * p.stride - p.pad) * p.cw;
         }
     };
 
@@ -185,10 +202,8 @@ bconv_tile_kernel(ConvTileParams p)
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
-            const int idx = tid + u * kTileThreads;
-            const int plane = (idx / UQ) / BM, q = idx % UQ;
-            ra[u] = gather4<VW>(p, p.a + (int64_t)plane * p.a_plane_stride, tap_table, rok[u] && 4 * q < p.kb,
-                                pbase[u], hi0[u], wi0[u], k0 + 4 * q);
+            const int q = (tid + u * kTileThreads) % UQ;
+            ra[u] = gather4<VW>(p.a, tap_table, 4 * q < p.kb ? p.nw : 0, apad[u], abase[u], k0 + 4 * q);
         }
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
@@ -280,26 +295,19 @@ bconv_tile_kernel(ConvTileParams p)
             const bool rvalid = r < p.M;
             const int4 vv = *reinterpret_cast<const int4 *>(V + rl * EPI_STRIDE + c4);
             int32_t v[4] = {vv.x, vv.y, vv.z, vv.w};
-            // padded taps of this output pixel: tap (ky, kx) is padded iff its row or its column is
-            uint32_t ybad = 0, xbad = 0;
-            {
-                const uint32_t mm = rvalid ? (uint32_t)r : 0u;
-                const uint32_t b = fdiv(mm, p.div_howo), rem = mm - b * p.div_howo.d;
+            // padded taps of this output pixel
+            uint32_t padded = 0;
+            if (rvalid) {
+                const uint32_t b = fdiv((uint32_t)r, p.div_howo), rem = (uint32_t)r - b * p.div_howo.d;
                 const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
-                const int h0 = (int)ho * p.stride - p.pad, w0 = (int)wo * p.stride - p.pad;
-                for (int ky = 0; ky < p.kh; ++ky)
-                    if ((unsigned)(h0 + ky) >= (unsigned)p.H) ybad |= 1u << ky;
-                for (int kx = 0; kx < p.kw; ++kx)
-                    if ((unsigned)(w0 + kx) >= (unsigned)p.W) xbad |= 1u << kx;
+                padded = ymask[ho] | xmask[wo];
             }
-            if (rvalid && (ybad | xbad) != 0) {
+            if (padded) {
                 int32_t corr[4] = {0, 0, 0, 0};
-                for (int ky = 0; ky < p.kh; ++ky)
-                    for (int kx = 0; kx < p.kw; ++kx)
-                        if (((ybad >> ky) | (xbad >> kx)) & 1u) {
-                            const int4 s4 = *reinterpret_cast<const int4 *>(S + (ky * p.kw + kx) * BN + c4);
-                            corr[0] += s4.x, corr[1] += s4.y, corr[2] += s4.z, corr[3] += s4.w;
-                        }
+                for (uint32_t m = padded; m; m &= m - 1) {
+                    const int4 s4 = *reinterpret_cast<const int4 *>(S + __builtin_ctz(m) * BN + c4);
+                    corr[0] += s4.x, corr[1] += s4.y, corr[2] += s4.z, corr[3] += s4.w;
+                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] += p.top_a * corr[e];
             }
@@ -412,7 +420,7 @@ template <int WB, int AB, int VW> static int launch_conv_vw(ConvTileParams p, hi
     static_assert(TN % 2 == 0, "column tile must be a multiple of 32");
     using T = Tile<WB, AB, G::TM, TN, G::KV, kConvKB>;
     auto kernel = bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW>;
-    const size_t dyn = (size_t)T::BN * p.kh * p.kw * sizeof(int32_t);
+    const size_t dyn = ((size_t)T::BN * p.kh * p.kw + p.Ho + p.Wo) * sizeof(int32_t);
     p.tiles_m = (int)ceil_div(p.M, T::BM);
     p.tiles_n = (int)ceil_div(p.Cout, T::BN);
     // stage length: of the multiples of 4 up to the stage capacity, the one whose last stage is
@@ -510,14 +518,15 @@ extern "C" int qnn_conv2d(const qnn_conv_desc *d, const uint32_t *a_planes, cons
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     // the register-blocked kernel indexes pixels and plane words with 32-bit integers
-    const bool small_index = p.M < (1LL << 29) && p.a_plane_stride < (1LL << 31) && p.M * cwo < (1LL << 31) &&
-                             p.Ho * p.Wo < (1LL << 31);
+    const bool small_index = p.M < (1LL << 29) && p.a_plane_stride * d->a_bits < (1LL << 31) &&
+                             p.M * cwo < (1LL << 31) && p.Ho + p.Wo <= kMaxOutExtent &&
+                             ((int64_t)d->kh * d->W + d->kw) * p.cw < (1LL << 24);
     bool done = false;
     if (p.nw <= kMaxGroups && d->kh * d->kw <= kMaxTaps && d->w_bits <= 4 && d->a_bits <= 4 && small_index) {
         ConvTileParams t;
         t.a = a_planes, t.w = w_planes, t.scale = scale, t.acc = acc, t.out = out, t.next = next_planes;
         t.H = (int)d->H, t.W = (int)d->W, t.HW = (int)(d->H * d->W), t.Cin = (int)d->Cin, t.Cout = (int)d->Cout;
-        t.M = (int)p.M, t.cw = (int)p.cw, t.nw = (int)p.nw, t.cwo = (int)cwo;
+        t.M = (int)p.M, t.cw = (int)p.cw, t.nw = (int)p.nw, t.cwo = (int)cwo, t.Ho = (int)p.Ho, t.Wo = (int)p.Wo;
         t.kh = d->kh, t.kw = d->kw, t.stride = d->stride, t.pad = d->pad;
         t.a_plane_stride = (int)p.a_plane_stride;
         t.top_a = (1 << d->a_bits) - 1;
