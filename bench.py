@@ -256,6 +256,42 @@ def main():
                      "probe": valu_probe(qnn, torch)},
     }
 
+    # The bit-plane-sum variant on the matrix cores, same workload and outputs (comparison only:
+    # the headline value above is the xor + bitcount path).  Step = encode + plane sum of the
+    # activations + int8 MFMA GEMM with fused scale; the weights' levels are made once, offline.
+    if max(wb, ab) <= 7:
+        w_levels = qnn.qnn_plane_sum_i8(w_planes, size)
+        a_levels = torch.empty((size, qnn.qnn_level_row_bytes(size)), dtype=torch.int8, device="cuda")
+
+        def mfma_step():
+            qnn.qnn_encode_pack(d_x, clip, ab, planes=a_planes)
+            qnn.qnn_plane_sum_i8(a_planes, size, levels=a_levels)
+            qnn.qnn_level_gemm_i8(a_levels, w_levels, size, acc=acc, scale=d_scale, out=out)
+
+        for _ in range(args.warmup):
+            mfma_step()
+        evm = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            qnn.qnn_encode_pack(d_x, clip, ab, planes=a_planes)
+            qnn.qnn_plane_sum_i8(a_planes, size, levels=a_levels)
+            evm[i][0].record()
+            qnn.qnn_level_gemm_i8(a_levels, w_levels, size, acc=acc, scale=d_scale, out=out)
+            evm[i][1].record()
+        torch.cuda.synchronize()
+        m_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        m_gemm_ms = sum(a.elapsed_time(b) for a, b in evm) / args.steps
+        int8_tops = 2.0 * size ** 3 / (m_gemm_ms * 1e-3) / 1e12
+        result["mfma_variant"] = {
+            "step": "qnn_encode_pack + qnn_plane_sum_i8 + qnn_level_gemm_i8 (fused scale)",
+            "ms_per_step": round(m_ms, 4), "effective_binary_tops": round(ops / (m_ms * 1e-3) / 1e12, 1),
+            "speedup_vs_xor_bitcount_step": round(ms_per_step / m_ms, 2),
+            "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel", "achieved": round(int8_tops, 1),
+                         "peak": 5000.0, "unit": "int8 TOP/s", "frac": round(int8_tops / 5000.0, 4),
+                         "kernel_ms": round(m_gemm_ms, 4)}}
+
     if args.sweep:
         sweep = {}
         for w_b in range(1, 5):

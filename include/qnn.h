@@ -127,6 +127,25 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
                float next_clip, int next_bits, void *stream);
 
 /*
+ * Bit-plane-sum variant on the matrix cores (for comparison with qnn_binary_gemm; same integers).
+ * The M x K branch sum of Eq. 9 equals the integer dot product of the decoded levels (Eq. 7-10),
+ * so one can also sum the 2^j-weighted planes back into int8 levels and contract those with int8
+ * MFMA instructions.  Bit widths 1..7 (levels must fit int8).
+ *
+ * qnn_level_row_bytes(n): bytes per row of a level tensor = n rounded up to a multiple of 64.
+ * qnn_plane_sum_i8: planes DEVICE [bits][rows][ceil(n/32)] -> levels DEVICE int8
+ *     [rows][qnn_level_row_bytes(n)], level = sum_j 2^j (2 b_j - 1), bytes past n written as 0.
+ * qnn_level_gemm_i8: acc[r][c] = sum_k a[r][k] w[c][k] (int32, exact), optional
+ *     out[r][c] = (float)acc[r][c] * scale[c]; a_levels / w_levels as written by qnn_plane_sum_i8.
+ *     acc / out / scale as in qnn_binary_gemm.
+ */
+int64_t qnn_level_row_bytes(int64_t n);
+int qnn_plane_sum_i8(const uint32_t *planes, int bits, int64_t rows, int64_t n, int8_t *levels,
+                     void *stream);
+int qnn_level_gemm_i8(const int8_t *a_levels, const int8_t *w_levels, int64_t rows, int64_t cols,
+                      int64_t n, int32_t *acc, const float *scale, float *out, void *stream);
+
+/*
  * qnn_probe_valu -- measurement aid, not part of the hot path: launches `workgroups` workgroups
  * of 256 lanes that each run `iters` iterations of a register-only loop of 64 VALU instructions
  * per wave, so that the issue rate of the binary dot product's two instructions (the "xnor" and

@@ -24,7 +24,8 @@ QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d",
-           "qnn_probe_valu", "qnn_last_error", "qnn_version")
+           "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
+           "qnn_last_error", "qnn_version")
 
 
 class QnnError(RuntimeError):
@@ -63,6 +64,12 @@ def lib():
         L.qnn_conv2d.restype = i32
         L.qnn_probe_valu.argtypes = [i32, i32, i32, vp, vp]
         L.qnn_probe_valu.restype = i32
+        L.qnn_level_row_bytes.argtypes = [i64]
+        L.qnn_level_row_bytes.restype = i64
+        L.qnn_plane_sum_i8.argtypes = [vp, i32, i64, i64, vp, vp]
+        L.qnn_plane_sum_i8.restype = i32
+        L.qnn_level_gemm_i8.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp]
+        L.qnn_level_gemm_i8.restype = i32
         L.qnn_last_error.argtypes = []
         L.qnn_last_error.restype = ctypes.c_char_p
         L.qnn_version.argtypes = []
@@ -118,6 +125,34 @@ def qnn_binary_gemm(a_planes, w_planes, n, want_acc=True, scale=None, acc=None, 
         out = torch.empty((rows, cols), dtype=torch.float32, device=dev)
     _check(lib().qnn_binary_gemm(_ptr(a_planes), a_bits, _ptr(w_planes), w_bits, rows, cols, n,
                                  _ptr(acc), _ptr(scale), _ptr(out), _stream()))
+    return acc, out
+
+
+def qnn_level_row_bytes(n):
+    return lib().qnn_level_row_bytes(int(n))
+
+
+def qnn_plane_sum_i8(planes, n, levels=None):
+    """planes [bits][rows][nw] -> int8 levels [rows][qnn_level_row_bytes(n)] (bit-plane-sum variant)."""
+    bits, rows, nw = planes.shape
+    assert nw == (n + 31) // 32
+    if levels is None:
+        levels = torch.empty((rows, qnn_level_row_bytes(n)), dtype=torch.int8, device=planes.device)
+    _check(lib().qnn_plane_sum_i8(_ptr(planes), bits, rows, n, _ptr(levels), _stream()))
+    return levels
+
+
+def qnn_level_gemm_i8(a_levels, w_levels, n, want_acc=True, scale=None, acc=None, out=None):
+    """int8 MFMA GEMM on levels as written by qnn_plane_sum_i8 -> (acc int32 or None, out fp32 or None)."""
+    rows, cols = a_levels.shape[0], w_levels.shape[0]
+    assert a_levels.shape[1] == w_levels.shape[1] == qnn_level_row_bytes(n)
+    dev = a_levels.device
+    if want_acc and acc is None:
+        acc = torch.empty((rows, cols), dtype=torch.int32, device=dev)
+    if scale is not None and out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=dev)
+    _check(lib().qnn_level_gemm_i8(_ptr(a_levels), _ptr(w_levels), rows, cols, n, _ptr(acc), _ptr(scale),
+                                   _ptr(out), _stream()))
     return acc, out
 
 
