@@ -132,7 +132,7 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
  * so one can also sum the 2^j-weighted planes back into int8 levels and contract those with int8
  * MFMA instructions.  Bit widths 1..7 (levels must fit int8).
  *
- * qnn_level_row_bytes(n): bytes per row of a level tensor = n rounded up to a multiple of 64.
+ * qnn_level_row_bytes(n): bytes per row of a level tensor = n rounded up to a multiple of 128.
  * qnn_plane_sum_i8: planes DEVICE [bits][rows][ceil(n/32)] -> levels DEVICE int8
  *     [rows][qnn_level_row_bytes(n)], level = sum_j 2^j (2 b_j - 1), bytes past n written as 0.
  * qnn_level_gemm_i8: acc[r][c] = sum_k a[r][k] w[c][k] (int32, exact), optional

@@ -13,7 +13,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // ---------------------------------------------------------------------------------------------
-// planes [bits][rows][nw] -> int8 levels [rows][nk], nk a multiple of 64 bytes, zero padded.
+// planes [bits][rows][nw] -> int8 levels [rows][nk], nk a multiple of 128 bytes, zero padded.
 // One lane makes 16 levels (one 16-byte store) from 16 bits of every plane: a nibble of plane j
 // is spread to four 0/1 bytes with one multiply, shifted to bit j of the byte codes u, and
 // level = 2u - (2^bits - 1) is taken per byte as a carry-free byte-wise add of the negated top.
@@ -62,12 +62,20 @@ __global__ __launch_bounds__(256) void plane_sum_kernel(const uint32_t *__restri
 // ---------------------------------------------------------------------------------------------
 // int8 GEMM acc[r][c] = sum_k a[r][k] w[c][k] on v_mfma_i32_32x32x32_i8.
 // Workgroup: 256 lanes (4 waves as 2 x 2), block tile 256 x 256, each wave 128 x 128 = 4 x 4 MFMA
-// tiles (256 accumulator registers), reduction staged 64 bytes per row through LDS (row stride 80
-// bytes: conflict-free 16-byte reads), double buffered, one barrier per stage.
+// tiles (256 accumulator registers).  The reduction is staged 128 bytes per row (whole cache
+// lines) through two 64 KiB LDS stages filled by direct global -> LDS loads (no staging
+// registers): the loads of stage S+1 are issued right after the barrier that opens stage S and
+// have the 64 MFMAs of stage S to arrive.  Inside a stage the operands of the next 32-byte k step
+// are read from LDS while the MFMAs of the current step run.
+// LDS rows are 128 bytes apart with no padding; the 16-byte unit q of row r sits at position
+// q ^ (r & 7), so the operand reads of 8 consecutive rows hit all 32 banks.
 // The k order inside an MFMA operand does not matter for a dot product as long as both operands
-// use the same assignment, which they do by the symmetry of the instruction.
+// use the same assignment, which they do by the symmetry of the instruction.  Rows / columns past
+// the end are clamped to the last one (their outputs are never stored); bytes past n are 0.
 // ---------------------------------------------------------------------------------------------
-constexpr int kMB = 256, kNB = 256, kKB = 64, kRowBytes = 80;
+constexpr int kMB = 256, kNB = 256, kKB = 128;
+constexpr int kRing = 2, kStageBytes = (kMB + kNB) * kKB;
+constexpr int kLoadsPerStage = kStageBytes / (256 * 16); // direct loads per lane and stage
 
 struct LevelGemmParams {
     const int8_t *a, *w; // [rows][nk], [cols][nk]
@@ -78,9 +86,12 @@ struct LevelGemmParams {
     int64_t tiles_n, tiles_m;
 };
 
+// s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+#define QNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
 __global__ __launch_bounds__(256) void level_gemm_mfma_kernel(LevelGemmParams p)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t smem[2][(kMB + kNB) * kRowBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t smem[kRing][kStageBytes];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t row0 = ((int64_t)blockIdx.x / p.tiles_n) * kMB;
@@ -94,69 +105,88 @@ __global__ __launch_bounds__(256) void level_gemm_mfma_kernel(LevelGemmParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // stage units: 16 bytes; a stage has (256 + 256) rows x 4 units = 2048 units, 8 per lane
-    uint4 ra[4], rb[4];
-    auto fetch = [&](int64_t k0) {
+    // Direct load j of this wave fills the 1 KiB LDS chunk wave * 16 + j = stage rows chunk*8 .. +7
+    // (stage rows 0..255 are A, 256..511 are W); lane l delivers row l / 8, position l % 8.
+    const int8_t *src[kLoadsPerStage];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int idx = tid + u * 256;
-            const int r = idx >> 2, q = idx & 3;
-            const int64_t gr = row0 + r, gc = col0 + r;
-            ra[u] = gr < p.rows ? *reinterpret_cast<const uint4 *>(p.a + gr * p.nk + k0 + 16 * q)
-                                : make_uint4(0u, 0u, 0u, 0u);
-            rb[u] = gc < p.cols ? *reinterpret_cast<const uint4 *>(p.w + gc * p.nk + k0 + 16 * q)
-                                : make_uint4(0u, 0u, 0u, 0u);
+    for (int j = 0; j < kLoadsPerStage; ++j) {
+        const int row = (wave * kLoadsPerStage + j) * 8 + (lane >> 3);
+        const int q = (lane & 7) ^ (row & 7);
+        if (row < kMB) {
+            const int64_t g = row0 + row < p.rows ? row0 + row : p.rows - 1;
+            src[j] = p.a + g * p.nk + 16 * q;
+        } else {
+            const int64_t g = col0 + row - kMB < p.cols ? col0 + row - kMB : p.cols - 1;
+            src[j] = p.w + g * p.nk + 16 * q;
         }
-    };
-    auto stash = [&](int buf) {
+    }
+    auto issue = [&](int64_t stage) {
+        uint8_t *dst = smem[stage % kRing] + wave * (kLoadsPerStage * 1024);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int idx = tid + u * 256;
-            const int r = idx >> 2, q = idx & 3;
-            *reinterpret_cast<uint4 *>(&smem[buf][r * kRowBytes + 16 * q]) = ra[u];
-            *reinterpret_cast<uint4 *>(&smem[buf][(kMB + r) * kRowBytes + 16 * q]) = rb[u];
+        for (int j = 0; j < kLoadsPerStage; ++j)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(src[j] + stage * kKB),
+                (__attribute__((address_space(3))) void *)(dst + j * 1024), 16, 0, 0);
+    };
+
+    // operand reads at k step ks: row = tile row + lane % 32, unit 2 ks + lane / 32, swizzled
+    const int a_off = (wm * 128 + (lane & 31)) * kKB, b_off = (kMB + wn * 128 + (lane & 31)) * kKB;
+    const int hi = lane >> 5, swz = lane & 7;
+    auto read_step = [&](const uint8_t *st, int ks, v4i (&af)[4], v4i (&bf)[4]) {
+        const int u = 16 * ((2 * ks + hi) ^ swz);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            af[t] = *reinterpret_cast<const v4i *>(st + a_off + t * 32 * kKB + u);
+            bf[t] = *reinterpret_cast<const v4i *>(st + b_off + t * 32 * kKB + u);
         }
     };
 
+    // Pipeline.  Stage s is multiplied in four 32-byte k steps; the operands of step ks+1 are read
+    // while the MFMAs of step ks run.  The barrier that opens stage s+1 sits before the MFMAs of the
+    // last step of stage s: by then this wave has read all of stage s (its buffer may be refilled
+    // with stage s+2) and the first operands of stage s+1 are fetched under those last 16 MFMAs.
     const int64_t nstages = p.nk / kKB;
+    v4i af[2][4], bf[2][4];
+    // One k step: 16 MFMAs on operand set b.  The LDS reads of the following step (into the other
+    // operand set) are issued right after the first MFMA: the wait the compiler puts in front of
+    // that first MFMA then covers only this step's operands, and the reads fly under the other 15.
+    auto mfma_step = [&](int b, const uint8_t *next_stage, int next_ks) {
+        __builtin_amdgcn_sched_barrier(0);
+        acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][0], bf[b][0], acc[0][0], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_step(next_stage, next_ks, af[b ^ 1], bf[b ^ 1]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (i == 0 && j == 0) continue;
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][i], bf[b][j], acc[i][j], 0, 0, 0);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    };
     if (nstages > 0) {
-        fetch(0);
-        stash(0);
+        issue(0);
+        if (nstages > 1) issue(1);
+        if (nstages > 1) QNN_WAIT_VMCNT(kLoadsPerStage);
+        else QNN_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();
+        read_step(smem[0], 0, af[0], bf[0]);
     }
-    __syncthreads();
     for (int64_t s = 0; s < nstages; ++s) {
-        const int buf = (int)(s & 1);
-        const bool more = s + 1 < nstages;
-        if (more) fetch((s + 1) * kKB);
-        const uint8_t *As = smem[buf] + (wm * 128 + (lane & 31)) * kRowBytes + (lane >> 5) * 16;
-        const uint8_t *Bs = smem[buf] + (kMB + wn * 128 + (lane & 31)) * kRowBytes + (lane >> 5) * 16;
-        // Both 32-byte halves of the stage are read into separate registers, the second half while
-        // the first half's MFMAs run; the scheduling barriers keep the compiler from sinking the
-        // reads next to their uses (which would put an LDS round trip in front of every 4 MFMAs).
-        v4i af[2][4], bf[2][4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            af[0][t] = *reinterpret_cast<const v4i *>(As + t * 32 * kRowBytes);
-            bf[0][t] = *reinterpret_cast<const v4i *>(Bs + t * 32 * kRowBytes);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            af[1][t] = *reinterpret_cast<const v4i *>(As + t * 32 * kRowBytes + 32);
-            bf[1][t] = *reinterpret_cast<const v4i *>(Bs + t * 32 * kRowBytes + 32);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[ks][i], bf[ks][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (more) stash(buf ^ 1);
-        __syncthreads();
+        const uint8_t *st = smem[s % kRing];
+        mfma_step(0, st, 1);
+        mfma_step(1, st, 2);
+        mfma_step(0, st, 3);
+        // All of this lane's LDS reads of stage s have been issued and are waited for here; its loads
+        // of stage s+1 are complete.  After the barrier stage s's buffer may be refilled (stage s+2)
+        // and stage s+1 is visible.  After the last stage the same sequence runs once more on stale
+        // data that is never used, which keeps the loop free of branches around the LDS reads.
+        QNN_WAIT_VMCNT(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        if (s + 2 < nstages) issue(s + 2);
+        mfma_step(1, smem[(s + 1) % kRing], 0);
     }
 
     // D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) + r % 4
