@@ -61,21 +61,34 @@ __global__ __launch_bounds__(256) void plane_sum_kernel(const uint32_t *__restri
 
 // ---------------------------------------------------------------------------------------------
 // int8 GEMM acc[r][c] = sum_k a[r][k] w[c][k] on v_mfma_i32_32x32x32_i8.
-// Workgroup: 256 lanes (4 waves as 2 x 2), block tile 256 x 256, each wave 128 x 128 = 4 x 4 MFMA
-// tiles (256 accumulator registers).  The reduction is staged 128 bytes per row (whole cache
-// lines) through two 64 KiB LDS stages filled by direct global -> LDS loads (no staging
-// registers): the loads of stage S+1 are issued right after the barrier that opens stage S and
-// have the 64 MFMAs of stage S to arrive.  Inside a stage the operands of the next 32-byte k step
-// are read from LDS while the MFMAs of the current step run.
-// LDS rows are 128 bytes apart with no padding; the 16-byte unit q of row r sits at position
-// q ^ (r & 7), so the operand reads of 8 consecutive rows hit all 32 banks.
+// Workgroup: block tile 256 x 256, kWavesM x kWavesN waves, each wave kTM x kTN MFMA tiles of 32 x 32
+// (8 waves of 128 x 64: 128 accumulator registers, two waves per SIMD, so that one wave's MFMAs cover
+// the other's stalls at LDS and memory instructions).  The reduction is staged kKB bytes per row
+// through a ring of kRing LDS stages filled by direct global -> LDS loads (no staging registers); a
+// stage is requested kRing stages ahead of its use.  Inside a stage the operands of the next 32-byte
+// k step are read from LDS between the MFMAs of the current one.
+// LDS rows are kKB bytes apart with no padding; the 16-byte unit q of row r is stored at position
+// q ^ ((r / (8 / U)) mod U), U = kKB / 16 units per row, so that the operand reads of 8 consecutive
+// rows (one pass of a 16-byte LDS read) hit all 32 banks.
 // The k order inside an MFMA operand does not matter for a dot product as long as both operands
 // use the same assignment, which they do by the symmetry of the instruction.  Rows / columns past
 // the end are clamped to the last one (their outputs are never stored); bytes past n are 0.
 // ---------------------------------------------------------------------------------------------
-constexpr int kMB = 256, kNB = 256, kKB = 128;
-constexpr int kRing = 2, kStageBytes = (kMB + kNB) * kKB;
-constexpr int kLoadsPerStage = kStageBytes / (256 * 16); // direct loads per lane and stage
+constexpr int kMB = 256, kNB = 256;
+constexpr int kWavesM = 2, kWavesN = 4;
+constexpr int kThreads = 64 * kWavesM * kWavesN;
+constexpr int kTM = kMB / kWavesM / 32, kTN = kNB / kWavesN / 32; // MFMA tiles per wave
+constexpr int kKB = 128, kRing = 2;                       // stage depth in bytes of k, stages in LDS
+constexpr int kRowPad = 128;                              // level rows are padded to this many bytes
+constexpr int kSteps = kKB / 32;                          // 32-byte MFMA k steps per stage
+constexpr int kUnits = kKB / 16;                          // 16-byte units per LDS row
+constexpr int kStageBytes = (kMB + kNB) * kKB;
+constexpr int kLoadsPerStage = kStageBytes / (kThreads * 16); // direct loads per lane and stage
+constexpr int kRowsPerLoad = 1024 / kKB;                  // LDS rows one wave-wide 1 KiB load fills
+static_assert(kRowPad % kKB == 0 && kKB % 32 == 0 && kUnits <= 8 && kSteps >= 2, "stage shape");
+static_assert(kLoadsPerStage <= kTM * kTN && kTM + kTN <= kTM * kTN, "one read and one load per MFMA slot");
+static_assert(kRing * kStageBytes <= 160 * 1024, "LDS ring");
+static_assert((kRing - 1) * kLoadsPerStage < 64, "vmcnt range");
 
 struct LevelGemmParams {
     const int8_t *a, *w; // [rows][nk], [cols][nk]
@@ -89,29 +102,31 @@ struct LevelGemmParams {
 // s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 #define QNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-__global__ __launch_bounds__(256) void level_gemm_mfma_kernel(LevelGemmParams p)
+__device__ __forceinline__ int swizzle_of_row(int row) { return (row / (8 / kUnits)) & (kUnits - 1); }
+
+__global__ __launch_bounds__(kThreads) void level_gemm_mfma_kernel(LevelGemmParams p)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kRing][kStageBytes];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / kWavesN, wn = wave % kWavesN;
     const int64_t row0 = ((int64_t)blockIdx.x / p.tiles_n) * kMB;
     const int64_t col0 = ((int64_t)blockIdx.x % p.tiles_n) * kNB;
 
-    v16i acc[4][4];
+    v16i acc[kTM][kTN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kTM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < kTN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // Direct load j of this wave fills the 1 KiB LDS chunk wave * 16 + j = stage rows chunk*8 .. +7
-    // (stage rows 0..255 are A, 256..511 are W); lane l delivers row l / 8, position l % 8.
+    // Direct load j of this wave fills the 1 KiB LDS chunk wave * kLoadsPerStage + j = kRowsPerLoad
+    // stage rows (stage rows 0..255 are A, 256..511 are W); lane l delivers row l / U, position l % U.
     const int8_t *src[kLoadsPerStage];
 #pragma unroll
     for (int j = 0; j < kLoadsPerStage; ++j) {
-        const int row = (wave * kLoadsPerStage + j) * 8 + (lane >> 3);
-        const int q = (lane & 7) ^ (row & 7);
+        const int row = (wave * kLoadsPerStage + j) * kRowsPerLoad + lane / kUnits;
+        const int q = (lane % kUnits) ^ swizzle_of_row(row);
         if (row < kMB) {
             const int64_t g = row0 + row < p.rows ? row0 + row : p.rows - 1;
             src[j] = p.a + g * p.nk + 16 * q;
@@ -120,86 +135,94 @@ __global__ __launch_bounds__(256) void level_gemm_mfma_kernel(LevelGemmParams p)
             src[j] = p.w + g * p.nk + 16 * q;
         }
     }
-    auto issue = [&](int64_t stage) {
-        uint8_t *dst = smem[stage % kRing] + wave * (kLoadsPerStage * 1024);
-#pragma unroll
-        for (int j = 0; j < kLoadsPerStage; ++j)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(src[j] + stage * kKB),
-                (__attribute__((address_space(3))) void *)(dst + j * 1024), 16, 0, 0);
+    auto issue_one = [&](int64_t stage, int buf, int j) {
+        uint8_t *dst = smem[buf] + wave * (kLoadsPerStage * 1024);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + stage * kKB),
+                                         (__attribute__((address_space(3))) void *)(dst + j * 1024), 16, 0, 0);
     };
 
     // operand reads at k step ks: row = tile row + lane % 32, unit 2 ks + lane / 32, swizzled
-    const int a_off = (wm * 128 + (lane & 31)) * kKB, b_off = (kMB + wn * 128 + (lane & 31)) * kKB;
-    const int hi = lane >> 5, swz = lane & 7;
-    auto read_step = [&](const uint8_t *st, int ks, v4i (&af)[4], v4i (&bf)[4]) {
+    const int a_off = (wm * 32 * kTM + (lane & 31)) * kKB, b_off = (kMB + wn * 32 * kTN + (lane & 31)) * kKB;
+    const int hi = lane >> 5, swz = swizzle_of_row(lane & 31); // tile rows start at multiples of 32
+    v4i af[2][kTM], bf[2][kTN];
+    // operand read r of kTM + kTN of k step ks into operand set b, in the order the MFMAs first need
+    // them: A tile 0, W tiles 0.., A tiles 1..
+    auto read_one = [&](const uint8_t *st, int ks, int b, int r) {
         const int u = 16 * ((2 * ks + hi) ^ swz);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            af[t] = *reinterpret_cast<const v4i *>(st + a_off + t * 32 * kKB + u);
-            bf[t] = *reinterpret_cast<const v4i *>(st + b_off + t * 32 * kKB + u);
-        }
+        if (r == 0) af[b][0] = *reinterpret_cast<const v4i *>(st + a_off + u);
+        else if (r <= kTN) bf[b][r - 1] = *reinterpret_cast<const v4i *>(st + b_off + (r - 1) * 32 * kKB + u);
+        else af[b][r - kTN] = *reinterpret_cast<const v4i *>(st + a_off + (r - kTN) * 32 * kKB + u);
     };
 
-    // Pipeline.  Stage s is multiplied in four 32-byte k steps; the operands of step ks+1 are read
-    // while the MFMAs of step ks run.  The barrier that opens stage s+1 sits before the MFMAs of the
-    // last step of stage s: by then this wave has read all of stage s (its buffer may be refilled
-    // with stage s+2) and the first operands of stage s+1 are fetched under those last 16 MFMAs.
-    const int64_t nstages = p.nk / kKB;
-    v4i af[2][4], bf[2][4];
-    // One k step: 16 MFMAs on operand set b.  The LDS reads of the following step (into the other
-    // operand set) are issued right after the first MFMA: the wait the compiler puts in front of
-    // that first MFMA then covers only this step's operands, and the reads fly under the other 15.
-    auto mfma_step = [&](int b, const uint8_t *next_stage, int next_ks) {
-        __builtin_amdgcn_sched_barrier(0);
-        acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][0], bf[b][0], acc[0][0], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        read_step(next_stage, next_ks, af[b ^ 1], bf[b ^ 1]);
-        __builtin_amdgcn_sched_barrier(0);
+    // One k step: kTM * kTN MFMAs on operand set b.  The operand reads of the following k step (into
+    // the other operand set) and, in the last step of a stage, the direct loads of the stage kRing
+    // further on are spread one by one between the MFMAs, each behind an MFMA that keeps the matrix
+    // core busy while the wave sits at the LDS or memory instruction.  The first read follows the
+    // first MFMA, so the wait in front of that MFMA covers only this step's operands.
+    auto mfma_step = [&](int b, const uint8_t *next_stage, int next_ks, bool dma, int64_t dma_stage, int dma_buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (i == 0 && j == 0) continue;
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][i], bf[b][j], acc[i][j], 0, 0, 0);
-            }
+        for (int m = 0; m < kTM * kTN; ++m) {
+            __builtin_amdgcn_sched_barrier(0);
+            acc[m / kTN][m % kTN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][m / kTN], bf[b][m % kTN], acc[m / kTN][m % kTN], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (m < kTM + kTN) read_one(next_stage, next_ks, b ^ 1, m);
+            if (dma_buf >= 0 && m < kLoadsPerStage && dma) issue_one(dma_stage, dma_buf, m);
+        }
         __builtin_amdgcn_sched_barrier(0);
     };
-    if (nstages > 0) {
-        issue(0);
-        if (nstages > 1) issue(1);
-        if (nstages > 1) QNN_WAIT_VMCNT(kLoadsPerStage);
+
+    // wait until at most the loads of `stages` whole stages are outstanding (loads land in order)
+    auto wait_loads = [&](int64_t stages) {
+        static_assert(kRing <= 5, "extend the cases below");
+        constexpr int kL = kLoadsPerStage;
+        if (stages >= 4) QNN_WAIT_VMCNT(4 * kL < 63 ? 4 * kL : 63);
+        else if (stages == 3) QNN_WAIT_VMCNT(3 * kL < 63 ? 3 * kL : 63);
+        else if (stages == 2) QNN_WAIT_VMCNT(2 * kL < 63 ? 2 * kL : 63);
+        else if (stages == 1) QNN_WAIT_VMCNT(kLoadsPerStage);
         else QNN_WAIT_VMCNT(0);
+    };
+    const int64_t nstages = p.nk / kKB;
+    // prologue: request the first kRing stages, wait for stage 0, read its first operands
+    for (int t = 0; t < kRing; ++t)
+        if (t < nstages)
+#pragma unroll
+            for (int j = 0; j < kLoadsPerStage; ++j) issue_one(t, t, j);
+    if (nstages > 0) {
+        wait_loads(nstages - 1 < kRing - 1 ? nstages - 1 : kRing - 1);
         __builtin_amdgcn_s_barrier();
-        read_step(smem[0], 0, af[0], bf[0]);
+#pragma unroll
+        for (int r = 0; r < kTM + kTN; ++r) read_one(smem[0], 0, 0, r);
     }
+    // One stage per iteration, buffer cur = s mod kRing.  The barrier sits in front of the last k
+    // step: by then every wave has read all of stage s (its buffer may be refilled) and this wave's
+    // loads of stage s+1 have landed, so under the last step's MFMAs the first operands of stage s+1
+    // are read and stage s + kRing is requested into the buffer of stage s.
+    int cur = 0;
     for (int64_t s = 0; s < nstages; ++s) {
-        const uint8_t *st = smem[s % kRing];
-        mfma_step(0, st, 1);
-        mfma_step(1, st, 2);
-        mfma_step(0, st, 3);
-        // All of this lane's LDS reads of stage s have been issued and are waited for here; its loads
-        // of stage s+1 are complete.  After the barrier stage s's buffer may be refilled (stage s+2)
-        // and stage s+1 is visible.  After the last stage the same sequence runs once more on stale
-        // data that is never used, which keeps the loop free of branches around the LDS reads.
-        QNN_WAIT_VMCNT(0);
+        const uint8_t *st = smem[cur];
+        const int nxt = cur + 1 == kRing ? 0 : cur + 1;
+#pragma unroll
+        for (int ks = 0; ks + 1 < kSteps; ++ks) mfma_step(ks & 1, st, ks + 1, false, 0, -1);
+        // stages s+2 .. s+kRing-1 (as far as they exist) may still be in flight
+        wait_loads(nstages - (s + 2) < kRing - 2 ? nstages - (s + 2) : kRing - 2);
         __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        if (s + 2 < nstages) issue(s + 2);
-        mfma_step(1, smem[(s + 1) % kRing], 0);
+        // after the last stage this reads stale data that is never used (no branch around LDS reads)
+        mfma_step((kSteps - 1) & 1, smem[nxt], 0, s + kRing < nstages, s + kRing, cur);
+        cur = nxt;
     }
 
     // D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) + r % 4
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kTM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t c = col0 + wn * 128 + j * 32 + (lane & 31);
+        for (int j = 0; j < kTN; ++j) {
+            const int64_t c = col0 + (wn * kTN + j) * 32 + (lane & 31);
             if (c >= p.cols) continue;
             const float sc = p.out ? p.scale[c] : 0.0f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int64_t row = row0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int64_t row = row0 + (wm * kTM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (row >= p.rows) continue;
                 const int32_t v = acc[i][j][r];
                 if (p.acc) p.acc[row * p.cols + c] = v;
@@ -212,7 +235,7 @@ __global__ __launch_bounds__(256) void level_gemm_mfma_kernel(LevelGemmParams p)
 
 using namespace qnn;
 
-extern "C" int64_t qnn_level_row_bytes(int64_t n) { return n < 0 ? -1 : ceil_div(n, kKB) * kKB; }
+extern "C" int64_t qnn_level_row_bytes(int64_t n) { return n < 0 ? -1 : ceil_div(n, kRowPad) * kRowPad; }
 
 extern "C" int qnn_plane_sum_i8(const uint32_t *planes, int bits, int64_t rows, int64_t n, int8_t *levels,
                                 void *stream)
@@ -258,7 +281,7 @@ extern "C" int qnn_level_gemm_i8(const int8_t *a_levels, const int8_t *w_levels,
     p.acc = acc, p.scale = scale, p.out = out;
     p.tiles_m = ceil_div(rows, kMB), p.tiles_n = ceil_div(cols, kNB);
     if (p.tiles_m * p.tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_gemm_i8: too many tiles");
-    hipLaunchKernelGGL(level_gemm_mfma_kernel, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(256), 0,
+    hipLaunchKernelGGL(level_gemm_mfma_kernel, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), p);
     return check_launch("qnn_level_gemm_i8");
 }
