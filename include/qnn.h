@@ -146,6 +146,29 @@ int qnn_level_gemm_i8(const int8_t *a_levels, const int8_t *w_levels, int64_t ro
                       int64_t n, int32_t *acc, const float *scale, float *out, void *stream);
 
 /*
+ * Decoded-level convolution on the matrix cores (for comparison with qnn_conv2d; same integers).
+ * Section "Model Decomposition" reduces a convolution to the vector product of Eq. 7-10; here the
+ * levels stay decoded as int8 from layer to layer and the product is an implicit GEMM on int8 MFMA.
+ *
+ * qnn_encode_levels_i8: the quantizer of qnn_encode_pack (same fp32 steps, Table 1 HTanh, Eq. 15)
+ *     followed by level = 2u - (2^bits - 1) (Eq. 10), elementwise.
+ *     src DEVICE fp32 / bf16 [count] (QNN_DTYPE_F32 / QNN_DTYPE_BF16), levels DEVICE out int8 [count];
+ *     both 16-byte aligned; bits 1..7.
+ * qnn_level_conv2d_i8: as qnn_conv2d with int8 levels in place of planes.
+ *     a_levels DEVICE int8 [B][H][W][Cin], w_levels DEVICE int8 [Cout][kh][kw][Cin];
+ *     acc / out / scale as in qnn_conv2d; next_levels DEVICE out int8 [B][Ho][Wo][Cout], or NULL: the
+ *     fused epilogue out -> qnn_encode_levels_i8(out, clip = next_clip, bits = next_bits).
+ *     Taps outside the image contribute exactly 0.  desc->a_bits / w_bits (1..7) bound the levels for
+ *     the int32 range check only.  QNN_ERR_UNSUPPORTED unless Cin is a multiple of 16, kh * kw <= 31
+ *     and kh * kw * Cin <= 32768; QNN_ERR_RANGE when a tensor needs more than 32-bit byte offsets.
+ */
+int qnn_encode_levels_i8(const void *src, int dtype, int64_t count, float clip, int bits, int8_t *levels,
+                         void *stream);
+int qnn_level_conv2d_i8(const qnn_conv_desc *desc, const int8_t *a_levels, const int8_t *w_levels,
+                        const float *scale, int32_t *acc, float *out, int8_t *next_levels,
+                        float next_clip, int next_bits, void *stream);
+
+/*
  * qnn_probe_valu -- measurement aid, not part of the hot path: launches `workgroups` workgroups
  * of 256 lanes that each run `iters` iterations of a register-only loop of 64 VALU instructions
  * per wave, so that the issue rate of the binary dot product's two instructions (the "xnor" and

@@ -25,6 +25,7 @@ QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d",
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
+           "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_last_error", "qnn_version")
 
 
@@ -70,6 +71,10 @@ def lib():
         L.qnn_plane_sum_i8.restype = i32
         L.qnn_level_gemm_i8.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp]
         L.qnn_level_gemm_i8.restype = i32
+        L.qnn_encode_levels_i8.argtypes = [vp, i32, i64, f32, i32, vp, vp]
+        L.qnn_encode_levels_i8.restype = i32
+        L.qnn_level_conv2d_i8.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
+        L.qnn_level_conv2d_i8.restype = i32
         L.qnn_last_error.argtypes = []
         L.qnn_last_error.restype = ctypes.c_char_p
         L.qnn_version.argtypes = []
@@ -154,6 +159,41 @@ def qnn_level_gemm_i8(a_levels, w_levels, n, want_acc=True, scale=None, acc=None
     _check(lib().qnn_level_gemm_i8(_ptr(a_levels), _ptr(w_levels), rows, cols, n, _ptr(acc), _ptr(scale),
                                    _ptr(out), _stream()))
     return acc, out
+
+
+def qnn_encode_levels_i8(src, clip, bits, levels=None):
+    """src: CUDA fp32 / bf16 tensor, contiguous -> int8 levels of the same shape."""
+    assert src.is_cuda and src.is_contiguous() and src.dtype in (torch.float32, torch.bfloat16)
+    if levels is None:
+        levels = torch.empty(src.shape, dtype=torch.int8, device=src.device)
+    _check(lib().qnn_encode_levels_i8(_ptr(src), _DTYPES[src.dtype], src.numel(), float(clip), int(bits),
+                                      _ptr(levels), _stream()))
+    return levels
+
+
+def qnn_level_conv2d_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=None, want_acc=True,
+                        want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """a_levels int8 [B][H][W][Cin], w_levels int8 [Cout][kh][kw][Cin].  Returns (acc, out, next_levels);
+    entries not requested are None."""
+    B, H, W, cin = a_levels.shape
+    cout, kh, kw, cin2 = w_levels.shape
+    assert cin == cin2 and a_levels.dtype == torch.int8 and w_levels.dtype == torch.int8
+    assert a_levels.is_contiguous() and w_levels.is_contiguous()
+    ho = (H + 2 * pad - kh) // stride + 1
+    wo = (W + 2 * pad - kw) // stride + 1
+    dev = a_levels.device
+    d = qnn_conv_desc(B, H, W, cin, cout, kh, kw, stride, pad, a_bits, w_bits)
+    if want_acc and acc is None:
+        acc = torch.empty((B, ho, wo, cout), dtype=torch.int32, device=dev)
+    if want_out and out is None:
+        out = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=dev)
+    if next_clip is not None and next_levels is None:
+        next_levels = torch.empty((B, ho, wo, cout), dtype=torch.int8, device=dev)
+    _check(lib().qnn_level_conv2d_i8(ctypes.byref(d), _ptr(a_levels), _ptr(w_levels), _ptr(scale), _ptr(acc),
+                                     _ptr(out), _ptr(next_levels),
+                                     float(next_clip) if next_clip is not None else 0.0, int(next_bits),
+                                     _stream()))
+    return acc, out, next_levels
 
 
 def qnn_probe_valu(mode, workgroups, iters, out):

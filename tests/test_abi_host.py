@@ -116,3 +116,47 @@ def test_conv2d_argument_errors(qnn):
     assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 5, 5), scale=FAKE, nxt=FAKE, clip=1.0, nbits=2) \
         == qnn.QNN_ERR_UNSUPPORTED
     assert call(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
+
+
+def test_matrix_core_variant_argument_errors(qnn):
+    L = qnn.lib()
+    assert L.qnn_level_row_bytes(1) == 128 and L.qnn_level_row_bytes(128) == 128 and L.qnn_level_row_bytes(129) == 256
+    ps = L.qnn_plane_sum_i8
+    assert ps(FAKE, 8, 4, 64, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED       # 8-bit levels do not fit int8
+    assert ps(FAKE, 2, -1, 64, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert ps(None, 2, 4, 64, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert ps(FAKE, 2, 4, 64, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert ps(None, 2, 0, 64, None, None) == qnn.QNN_OK
+    g = L.qnn_level_gemm_i8
+    assert g(FAKE, FAKE, 4, 4, 64, None, None, None, None) == qnn.QNN_ERR_INVALID_ARG     # no output
+    assert g(FAKE, FAKE, 4, 4, 64, None, None, FAKE, None) == qnn.QNN_ERR_INVALID_ARG     # out, no scale
+    assert g(None, FAKE, 4, 4, 64, FAKE, None, None, None) == qnn.QNN_ERR_INVALID_ARG
+    assert g(FAKE, ODD, 4, 4, 64, FAKE, None, None, None) == qnn.QNN_ERR_ALIGNMENT
+    assert g(FAKE, FAKE, 4, 4, 1 << 20, FAKE, None, None, None) == qnn.QNN_ERR_RANGE      # 127^2 n >= 2^31
+    assert g(None, None, 0, 4, 64, FAKE, None, None, None) == qnn.QNN_OK
+    e = L.qnn_encode_levels_i8
+    assert e(FAKE, 2, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED    # int8 input has no quantizer
+    assert e(FAKE, 0, 64, 1.0, 8, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert e(FAKE, 0, -1, 1.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert e(FAKE, 0, 64, 0.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert e(None, 0, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert e(ODD, 0, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_ALIGNMENT
+    assert e(None, 0, 0, 1.0, 2, None, None) == qnn.QNN_OK
+
+    def conv(desc, a=FAKE, w=FAKE, scale=None, acc=FAKE, out=None, nxt=None, clip=0.0, nbits=0):
+        return L.qnn_level_conv2d_i8(ctypes.byref(desc) if desc is not None else None, a, w, scale, acc, out,
+                                     nxt, clip, nbits, None)
+
+    D = qnn.qnn_conv_desc
+    ok = D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)
+    assert conv(None) == qnn.QNN_ERR_INVALID_ARG
+    assert conv(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 8, 2)) == qnn.QNN_ERR_INVALID_ARG   # 8-bit levels
+    assert conv(D(1, 8, 8, 24, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED   # Cin % 16
+    assert conv(D(1, 8, 8, 64, 64, 7, 7, 1, 3, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED   # 49 taps
+    assert conv(D(1, 8, 8, 4096, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED  # reduction > 32 KiB
+    assert conv(D(1 << 20, 64, 64, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_RANGE  # 32-bit offsets
+    assert conv(ok, acc=None) == qnn.QNN_ERR_INVALID_ARG
+    assert conv(ok, scale=FAKE, nxt=FAKE, clip=1.0, nbits=8) == qnn.QNN_ERR_INVALID_ARG
+    assert conv(ok, a=None) == qnn.QNN_ERR_INVALID_ARG
+    assert conv(ok, w=ODD) == qnn.QNN_ERR_ALIGNMENT
+    assert conv(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
