@@ -80,7 +80,7 @@ template <bool BF16> __global__ __launch_bounds__(256) void encode_levels_kernel
 // ---------------------------------------------------------------------------------------------
 // Implicit-GEMM convolution.  Rows = output pixels (b, oy, ox flattened, NHWC), columns = output
 // channels, reduction axis = (ky, kx, ci) in bytes, nk = kh kw Cin, cut into stages of kKB = 128
-// bytes.  A workgroup (8 waves as WM x WN, two per SIMD) owns an MB x NB block; stages go through a
+// bytes.  A workgroup (WM x WN waves) owns an MB x NB block; stages go through a
 // ring of two LDS buffers filled by direct global -> LDS loads of 16 bytes per lane.  A lane's 16
 // bytes never straddle a tap because Cin is a multiple of 16: the lane looks up (tap, byte offset
 // relative to the pixel's first tap) of its unit in a table built once per workgroup, tests the tap
@@ -94,7 +94,6 @@ template <bool BF16> __global__ __launch_bounds__(256) void encode_levels_kernel
 // levels (scale, quantize, 2u - top) are transposed through LDS and stored 16 channels per lane.
 // ---------------------------------------------------------------------------------------------
 constexpr int kKB = 128, kRing = 2, kSteps = kKB / 32, kUnits = kKB / 16;
-constexpr int kConvThreads = 512, kConvWaves = 8;
 constexpr int kMaxUnits = 2048; // table entries: reduction axis up to 32 KiB (e.g. 5 x 5 x 1024)
 constexpr int kMaxMfmaTaps = 31; // tap 31 marks units past the end of the reduction axis
 
@@ -119,14 +118,14 @@ struct LevelConvParams {
 #define QNN_CONV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
 template <int MB, int NB, int WM, int WN>
-__global__ __launch_bounds__(kConvThreads) void level_conv_mfma_kernel(LevelConvParams p)
+__global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConvParams p)
 {
-    static_assert(WM * WN == kConvWaves, "8 waves");
+    constexpr int kWaves = WM * WN, kConvThreads = 64 * kWaves;
     constexpr int TM = MB / WM / 32, TN = NB / WN / 32;  // MFMA tiles per wave
     constexpr int NM = TM * TN, NR = TM + TN;             // MFMAs and operand reads per k step
-    constexpr int LA = MB / 64, LW = NB / 64, L = LA + LW; // direct loads per lane and stage
+    constexpr int LA = MB / (8 * kWaves), LW = NB / (8 * kWaves), L = LA + LW; // direct loads per lane and stage
     constexpr int kStageBytes = (MB + NB) * kKB;
-    static_assert(MB % 64 == 0 && NB % 64 == 0 && TM >= 1 && TN >= 1, "tile shape");
+    static_assert(MB % (8 * kWaves) == 0 && NB % (8 * kWaves) == 0 && TM >= 1 && TN >= 1, "tile shape");
     static_assert(kRing * kStageBytes + kMaxUnits * 4 <= 160 * 1024, "LDS");
     static_assert(MB * NB <= kRing * kStageBytes, "level transpose fits the ring");
 
@@ -156,7 +155,7 @@ __global__ __launch_bounds__(kConvThreads) void level_conv_mfma_kernel(LevelConv
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // Direct load j of this wave fills the 1 KiB LDS chunk j * 8 + wave = 8 stage rows (stage rows
+    // Direct load j of this wave fills the 1 KiB LDS chunk j * kWaves + wave = 8 stage rows (stage rows
     // 0..MB-1 are pixels, MB.. are output channels): loads j < LA gather activations, the others
     // read weights.  Lane l delivers row l / 8, position l % 8, i.e. the unit q = (l % 8) ^ (l / 8) of
     // the stage (chunks start at multiples of 8 rows), the same q for every load of the lane.
@@ -166,7 +165,7 @@ __global__ __launch_bounds__(kConvThreads) void level_conv_mfma_kernel(LevelConv
     int w_off[LW];      // byte offset of the output channel's weights
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
-        const int row = (j * 8 + wave) * 8 + (lane >> 3);
+        const int row = (j * kWaves + wave) * 8 + (lane >> 3);
         const int m = row0 + row < p.pixels ? row0 + row : p.pixels - 1;
         const int ox = m % p.Wo, t = m / p.Wo, oy = t % p.Ho, b = t / p.Ho;
         const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
@@ -180,7 +179,7 @@ __global__ __launch_bounds__(kConvThreads) void level_conv_mfma_kernel(LevelConv
     }
 #pragma unroll
     for (int j = 0; j < LW; ++j) {
-        const int col = ((LA + j) * 8 + wave) * 8 + (lane >> 3) - MB;
+        const int col = ((LA + j) * kWaves + wave) * 8 + (lane >> 3) - MB;
         w_off[j] = (col0 + col < p.Cout ? col0 + col : p.Cout - 1) * p.nk;
     }
     const uint8_t *zero = g_zero_units + 16 * (lane & 7);
@@ -196,7 +195,7 @@ __global__ __launch_bounds__(kConvThreads) void level_conv_mfma_kernel(LevelConv
             src = u < p.units ? reinterpret_cast<const uint8_t *>(p.w) + (w_off[j >= LA ? j - LA : 0] + 16 * u) : zero;
         }
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(smem[buf] + (j * 8 + wave) * 1024), 16,
+                                         (__attribute__((address_space(3))) void *)(smem[buf] + (j * kWaves + wave) * 1024), 16,
                                          0, 0);
     };
 
@@ -326,7 +325,7 @@ template <int MB, int NB, int WM, int WN> int launch_level_conv(LevelConvParams 
     const int64_t tiles_m = ceil_div(p.pixels, MB), tiles_n = ceil_div(p.Cout, NB);
     if (tiles_m * tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_conv2d_i8: too many tiles");
     p.tiles_n = (int)tiles_n;
-    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kConvThreads),
+    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN),
                        0, st, p);
     return check_launch("qnn_level_conv2d_i8");
 }
@@ -415,7 +414,19 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
     p.next_half_top = (float)p.next_top * 0.5f;
     p.next_inv_clip = next_levels ? 1.0f / next_clip : 0.0f;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (d->Cout > 128) return launch_level_conv<256, 256, 2, 4>(p, st);
-    if (d->Cout > 64) return launch_level_conv<256, 128, 4, 2>(p, st);
-    return launch_level_conv<512, 64, 8, 1>(p, st);
+#ifdef QNN_MFMA_CONV_FORCE_TILE
+    return launch_level_conv<QNN_MFMA_CONV_FORCE_TILE>(p, st);
+#endif
+    // Block shape (measured per layer shape of the two stacks): 512 x 64 for up to 64 output channels;
+    // 256 x 256 (one workgroup per CU) when its workgroups fill at least three quarters of the CU
+    // rounds they take; otherwise 128 x 128 with four waves, two workgroups per CU.
+    if (d->Cout <= 64) return launch_level_conv<512, 64, 8, 1>(p, st);
+    if (d->Cout > 128) {
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (cus < 1) cus = 256;
+        const int64_t tiles = ceil_div(p.pixels, 256) * ceil_div(d->Cout, 256);
+        if (4 * tiles >= 3 * ceil_div(tiles, cus) * cus) return launch_level_conv<256, 256, 2, 4>(p, st);
+    }
+    return launch_level_conv<128, 128, 2, 2>(p, st);
 }
