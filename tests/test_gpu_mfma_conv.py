@@ -160,3 +160,27 @@ def test_level_conv_argument_errors():
     with pytest.raises(qnn.QnnError) as e:
         qnn.qnn_level_conv2d_i8(a, w, 1, 3, 2, 2)
     assert e.value.code == -2          # 49 taps
+
+
+def test_config4_full_batch_levels_sampled_images():
+    # batch 256 as bench.py times the matrix-core route; the oracle chain on three of the
+    # (independent) images gives their exact levels after every layer
+    c = wl.resnet18_stack()
+    images = [0, 131, 255]
+    trace = _run_stack_levels(c["x"], c["layers"], keep_acc=False)
+    want = oracle.conv_stack(c["x"][images], c["layers"])
+    for li, (g, o) in enumerate(zip(trace, want)):
+        assert np.array_equal(g["levels"][images].cpu().numpy(), _lv(o["levels"])), li
+    np.testing.assert_allclose(trace[-1]["out"][images].cpu().numpy(), want[-1]["out"], rtol=RTOL, atol=0)
+
+
+def test_config5_full_batch_levels_sampled_images():
+    images = [0, 31]
+    for g in wl.vgg_ssd_stack():
+        trace = _run_stack_levels(g["x"], g["layers"], keep_acc=False)
+        want = oracle.conv_stack(g["x"][images], g["layers"])
+        for li, (t, o) in enumerate(zip(trace, want)):
+            assert np.array_equal(t["levels"][images].cpu().numpy(), _lv(o["levels"])), li
+        np.testing.assert_allclose(trace[-1]["out"][images].cpu().numpy(), want[-1]["out"], rtol=RTOL, atol=0)
+        del trace
+        torch.cuda.empty_cache()
