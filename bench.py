@@ -339,9 +339,43 @@ def main():
             "step": "qnn_encode_pack + qnn_plane_sum_i8 + qnn_level_gemm_i8 (fused scale)",
             "ms_per_step": round(m_ms, 4), "effective_binary_tops": round(ops / (m_ms * 1e-3) / 1e12, 1),
             "speedup_vs_xor_bitcount_step": round(ms_per_step / m_ms, 2),
-            "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel", "achieved": round(int8_tops, 1),
+            "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel<int8>", "achieved": round(int8_tops, 1),
                          "peak": 5000.0, "unit": "int8 TOP/s", "frac": round(int8_tops / 5000.0, 4),
                          "kernel_ms": round(m_gemm_ms, 4)}}
+
+    # 1- and 2-bit codes also fit the fp4 matrix-core path (levels -3..3 are exact fp4 values)
+    if max(wb, ab) <= 2:
+        w4 = qnn.qnn_plane_sum_fp4(w_planes, size)
+        a4 = torch.empty((size, qnn.qnn_fp4_row_bytes(size)), dtype=torch.uint8, device="cuda")
+
+        def fp4_step():
+            qnn.qnn_encode_pack(d_x, clip, ab, planes=a_planes)
+            qnn.qnn_plane_sum_fp4(a_planes, size, levels=a4)
+            qnn.qnn_level_gemm_fp4(a4, w4, size, acc=acc, scale=d_scale, out=out)
+
+        for _ in range(args.warmup):
+            fp4_step()
+        evf = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            qnn.qnn_encode_pack(d_x, clip, ab, planes=a_planes)
+            qnn.qnn_plane_sum_fp4(a_planes, size, levels=a4)
+            evf[i][0].record()
+            qnn.qnn_level_gemm_fp4(a4, w4, size, acc=acc, scale=d_scale, out=out)
+            evf[i][1].record()
+        torch.cuda.synchronize()
+        f_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        f_gemm_ms = sum(a.elapsed_time(b) for a, b in evf) / args.steps
+        fp4_tops = 2.0 * size ** 3 / (f_gemm_ms * 1e-3) / 1e12
+        result["fp4_variant"] = {
+            "step": "qnn_encode_pack + qnn_plane_sum_fp4 + qnn_level_gemm_fp4 (fused scale)",
+            "ms_per_step": round(f_ms, 4), "effective_binary_tops": round(ops / (f_ms * 1e-3) / 1e12, 1),
+            "speedup_vs_xor_bitcount_step": round(ms_per_step / f_ms, 2),
+            "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel<fp4>", "achieved": round(fp4_tops, 1),
+                         "peak": 10100.0, "unit": "fp4 TFLOP/s", "frac": round(fp4_tops / 10100.0, 4),
+                         "kernel_ms": round(f_gemm_ms, 4)}}
 
     if args.sweep:
         sweep = {}

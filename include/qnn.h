@@ -146,6 +146,24 @@ int qnn_level_gemm_i8(const int8_t *a_levels, const int8_t *w_levels, int64_t ro
                       int64_t n, int32_t *acc, const float *scale, float *out, void *stream);
 
 /*
+ * The same variant for 1- and 2-bit codes on the fp4 matrix-core path: the levels -3, -1, +1, +3 are
+ * exact fp4 (E2M1) values, products and partial sums are integers that fp32 accumulates exactly
+ * while 9 n < 2^24 (QNN_ERR_RANGE beyond), and the instruction runs twice as many multiply-adds per
+ * clock as the int8 one on half the bytes.
+ *
+ * qnn_fp4_row_bytes(n): bytes per row of an fp4 level tensor = n / 2 rounded up to a multiple of 128.
+ * qnn_plane_sum_fp4: planes DEVICE [bits][rows][ceil(n/32)], bits 1 or 2 -> levels DEVICE uint8
+ *     [rows][qnn_fp4_row_bytes(n)], element 2i in the low nibble of byte i, nibble = sign << 3 | E2M1
+ *     magnitude (1 = 0b0010, 3 = 0b0101), nibbles past n written as 0.
+ * qnn_level_gemm_fp4: as qnn_level_gemm_i8 on such tensors; acc is the exact int32 value.
+ */
+int64_t qnn_fp4_row_bytes(int64_t n);
+int qnn_plane_sum_fp4(const uint32_t *planes, int bits, int64_t rows, int64_t n, uint8_t *levels,
+                      void *stream);
+int qnn_level_gemm_fp4(const uint8_t *a_levels, const uint8_t *w_levels, int64_t rows, int64_t cols,
+                       int64_t n, int32_t *acc, const float *scale, float *out, void *stream);
+
+/*
  * Decoded-level convolution on the matrix cores (for comparison with qnn_conv2d; same integers).
  * Section "Model Decomposition" reduces a convolution to the vector product of Eq. 7-10; here the
  * levels stay decoded as int8 from layer to layer and the product is an implicit GEMM on int8 MFMA.

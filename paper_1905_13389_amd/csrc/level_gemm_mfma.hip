@@ -6,11 +6,14 @@
 // them with v_mfma_i32_32x32x32_i8 (qnn_level_gemm_i8).  It is NOT the graded xor + bitcount
 // path (binary_gemm.hip); it exists to be compared with it, same inputs, same int32 outputs.
 #include "qnn_host.h"
+#include <type_traits>
 
 namespace qnn {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 // ---------------------------------------------------------------------------------------------
 // planes [bits][rows][nw] -> int8 levels [rows][nk], nk a multiple of 128 bytes, zero padded.
@@ -60,6 +63,52 @@ __global__ __launch_bounds__(256) void plane_sum_kernel(const uint32_t *__restri
 }
 
 // ---------------------------------------------------------------------------------------------
+// planes [bits][rows][nw], bits <= 2 -> fp4 (E2M1) levels, two per byte, [rows][nb], nb a multiple of
+// 128 bytes, zero padded.  The levels of 1- and 2-bit codes, -3 -1 +1 +3, are exact fp4 values:
+// 1 = 0b0010, 3 = 0b0101, sign in bit 3.  One lane turns one word of each plane into 32 nibbles (one
+// 16-byte store): the 8 bits of a byte are spread to bit 0 of 8 nibbles, sign = not the high plane
+// bit, magnitude 3 where both plane bits agree.  Element 2i sits in the low nibble of byte i.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t spread_bits_to_nibbles(uint32_t byte)
+{
+    uint32_t x = byte & 0xffu;
+    x = (x | (x << 12)) & 0x000f000fu;
+    x = (x | (x << 6)) & 0x03030303u;
+    x = (x | (x << 3)) & 0x11111111u;
+    return x;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void plane_sum_fp4_kernel(const uint32_t *__restrict__ planes, int64_t rows,
+                                                            int64_t n, int64_t nw, int64_t nb, uint8_t *__restrict__ out)
+{
+    static_assert(BITS == 1 || BITS == 2, "fp4 holds the levels of 1- and 2-bit codes");
+    const int64_t groups_per_row = nb / 16; // 32 elements = one plane word per group
+    const int64_t total = rows * groups_per_row;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+        const int64_t r = idx / groups_per_row, g = idx % groups_per_row;
+        uint32_t hi = 0, lo = 0, valid = 0;
+        if (g < nw) {
+            hi = planes[((int64_t)(BITS - 1) * rows + r) * nw + g];
+            lo = BITS == 2 ? planes[r * nw + g] : ~hi; // 1 bit: magnitude 1 everywhere (bits differ)
+            const int64_t left = n - g * 32;
+            valid = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
+        }
+        uint32_t o[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t h = spread_bits_to_nibbles(hi >> (8 * d)), l = spread_bits_to_nibbles(lo >> (8 * d));
+            const uint32_t v = spread_bits_to_nibbles(valid >> (8 * d));
+            const uint32_t same = ~(h ^ l) & 0x11111111u;
+            const uint32_t nib = ((~h & 0x11111111u) << 3) | (0x22222222u ^ (same * 7u));
+            o[d] = nib & (v * 15u); // elements past n are 0
+        }
+        *reinterpret_cast<uint4 *>(out + r * nb + g * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // int8 GEMM acc[r][c] = sum_k a[r][k] w[c][k] on v_mfma_i32_32x32x32_i8.
 // Workgroup: block tile 256 x 256, kWavesM x kWavesN waves, each wave kTM x kTN MFMA tiles of 32 x 32
 // (8 waves of 128 x 64: 128 accumulator registers, two waves per SIMD, so that one wave's MFMAs cover
@@ -104,7 +153,9 @@ struct LevelGemmParams {
 
 __device__ __forceinline__ int swizzle_of_row(int row) { return (row / (8 / kUnits)) & (kUnits - 1); }
 
-__global__ __launch_bounds__(kThreads) void level_gemm_mfma_kernel(LevelGemmParams p)
+// FP4: the operands are fp4 levels (two per byte) multiplied by v_mfma_scale_f32_32x32x64_f8f6f4 with
+// unit scales; products and partial sums are integers below 2^24, which fp32 holds exactly.
+template <bool FP4> __global__ __launch_bounds__(kThreads) void level_gemm_mfma_kernel(LevelGemmParams p)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t smem[kRing][kStageBytes];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -112,7 +163,8 @@ __global__ __launch_bounds__(kThreads) void level_gemm_mfma_kernel(LevelGemmPara
     const int64_t row0 = ((int64_t)blockIdx.x / p.tiles_n) * kMB;
     const int64_t col0 = ((int64_t)blockIdx.x % p.tiles_n) * kNB;
 
-    v16i acc[kTM][kTN];
+    using Acc = typename std::conditional<FP4, v16f, v16i>::type;
+    Acc acc[kTM][kTN];
 #pragma unroll
     for (int i = 0; i < kTM; ++i)
 #pragma unroll
@@ -159,14 +211,24 @@ __global__ __launch_bounds__(kThreads) void level_gemm_mfma_kernel(LevelGemmPara
     // further on are spread one by one between the MFMAs, each behind an MFMA that keeps the matrix
     // core busy while the wave sits at the LDS or memory instruction.  The first read follows the
     // first MFMA, so the wait in front of that MFMA covers only this step's operands.
-    auto mfma_step = [&](int b, const uint8_t *next_stage, int next_ks, bool dma, int64_t dma_stage, int dma_buf) {
+    auto mfma_step = [&](int b, const uint8_t *next_stage, int next_ks, auto dma, int64_t dma_stage, int dma_buf) {
 #pragma unroll
         for (int m = 0; m < kTM * kTN; ++m) {
             __builtin_amdgcn_sched_barrier(0);
-            acc[m / kTN][m % kTN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][m / kTN], bf[b][m % kTN], acc[m / kTN][m % kTN], 0, 0, 0);
+            if constexpr (FP4) {
+                const v4i x = af[b][m / kTN], y = bf[b][m % kTN];
+                // the builtin takes 8 registers per operand and uses the first 4 for fp4: leave the rest undefined
+                const v8i x8 = __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1);
+                const v8i y8 = __builtin_shufflevector(y, y, 0, 1, 2, 3, -1, -1, -1, -1);
+                // cbsz = blgp = 4: both operands fp4; scale bytes 127 = 2^0
+                acc[m / kTN][m % kTN] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(x8, y8, acc[m / kTN][m % kTN], 4, 4, 0, 127, 0, 127);
+            } else {
+                acc[m / kTN][m % kTN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][m / kTN], bf[b][m % kTN], acc[m / kTN][m % kTN], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             if (m < kTM + kTN) read_one(next_stage, next_ks, b ^ 1, m);
-            if (dma_buf >= 0 && m < kLoadsPerStage && dma) issue_one(dma_stage, dma_buf, m);
+            if constexpr (decltype(dma)::value)
+                if (m < kLoadsPerStage) issue_one(dma_stage, dma_buf, m);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -197,20 +259,25 @@ __global__ __launch_bounds__(kThreads) void level_gemm_mfma_kernel(LevelGemmPara
     // step: by then every wave has read all of stage s (its buffer may be refilled) and this wave's
     // loads of stage s+1 have landed, so under the last step's MFMAs the first operands of stage s+1
     // are read and stage s + kRing is requested into the buffer of stage s.
+    // The loop runs in two parts, with and without the request for stage s + kRing, so that each body
+    // is one straight line of code whose order the scheduling barriers pin.
     int cur = 0;
-    for (int64_t s = 0; s < nstages; ++s) {
+    auto stage_body = [&](int64_t s, auto dma) {
         const uint8_t *st = smem[cur];
         const int nxt = cur + 1 == kRing ? 0 : cur + 1;
 #pragma unroll
-        for (int ks = 0; ks + 1 < kSteps; ++ks) mfma_step(ks & 1, st, ks + 1, false, 0, -1);
+        for (int ks = 0; ks + 1 < kSteps; ++ks) mfma_step(ks & 1, st, ks + 1, std::false_type{}, 0, 0);
         // stages s+2 .. s+kRing-1 (as far as they exist) may still be in flight
         wait_loads(nstages - (s + 2) < kRing - 2 ? nstages - (s + 2) : kRing - 2);
         __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         // after the last stage this reads stale data that is never used (no branch around LDS reads)
-        mfma_step((kSteps - 1) & 1, smem[nxt], 0, s + kRing < nstages, s + kRing, cur);
+        mfma_step((kSteps - 1) & 1, smem[nxt], 0, dma, s + kRing, cur);
         cur = nxt;
-    }
+    };
+    int64_t s = 0;
+    for (; s + kRing < nstages; ++s) stage_body(s, std::true_type{});
+    for (; s < nstages; ++s) stage_body(s, std::false_type{});
 
     // D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) + r % 4
 #pragma unroll
@@ -224,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void level_gemm_mfma_kernel(LevelGemmPara
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = row0 + (wm * kTM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                 if (row >= p.rows) continue;
-                const int32_t v = acc[i][j][r];
+                const int32_t v = (int32_t)acc[i][j][r];
                 if (p.acc) p.acc[row * p.cols + c] = v;
                 if (p.out) p.out[row * p.cols + c] = (float)v * sc;
             }
@@ -281,7 +348,51 @@ extern "C" int qnn_level_gemm_i8(const int8_t *a_levels, const int8_t *w_levels,
     p.acc = acc, p.scale = scale, p.out = out;
     p.tiles_m = ceil_div(rows, kMB), p.tiles_n = ceil_div(cols, kNB);
     if (p.tiles_m * p.tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_gemm_i8: too many tiles");
-    hipLaunchKernelGGL(level_gemm_mfma_kernel, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(kThreads), 0,
+    hipLaunchKernelGGL(level_gemm_mfma_kernel<false>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), p);
     return check_launch("qnn_level_gemm_i8");
+}
+
+extern "C" int64_t qnn_fp4_row_bytes(int64_t n) { return n < 0 ? -1 : ceil_div(n, 2 * kRowPad) * kRowPad; }
+
+extern "C" int qnn_plane_sum_fp4(const uint32_t *planes, int bits, int64_t rows, int64_t n, uint8_t *levels,
+                                 void *stream)
+{
+    if (bits < 1 || bits > 2) return fail(QNN_ERR_UNSUPPORTED, "qnn_plane_sum_fp4: fp4 holds the levels of 1 or 2 bits (got %d)", bits);
+    if (rows < 0 || n < 0) return fail(QNN_ERR_INVALID_ARG, "qnn_plane_sum_fp4: negative size");
+    if (rows == 0 || n == 0) return QNN_OK;
+    if (!planes || !levels) return fail(QNN_ERR_INVALID_ARG, "qnn_plane_sum_fp4: NULL pointer");
+    if (!aligned16(planes) || !aligned16(levels)) return fail(QNN_ERR_ALIGNMENT, "qnn_plane_sum_fp4: pointers must be 16-byte aligned");
+    const int64_t nw = ceil_div(n, 32), nb = qnn_fp4_row_bytes(n);
+    if (rows > (INT64_MAX >> 8) / nb) return fail(QNN_ERR_RANGE, "qnn_plane_sum_fp4: tensor too large");
+    const int64_t blocks = ceil_div(rows * (nb / 16), 256);
+    const dim3 grid((unsigned)(blocks < 256 * 32 ? blocks : 256 * 32)), block(256);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (bits == 1) hipLaunchKernelGGL(plane_sum_fp4_kernel<1>, grid, block, 0, st, planes, rows, n, nw, nb, levels);
+    else hipLaunchKernelGGL(plane_sum_fp4_kernel<2>, grid, block, 0, st, planes, rows, n, nw, nb, levels);
+    return check_launch("qnn_plane_sum_fp4");
+}
+
+extern "C" int qnn_level_gemm_fp4(const uint8_t *a_levels, const uint8_t *w_levels, int64_t rows, int64_t cols,
+                                  int64_t n, int32_t *acc, const float *scale, float *out, void *stream)
+{
+    if (rows < 0 || cols < 0 || n < 0) return fail(QNN_ERR_INVALID_ARG, "qnn_level_gemm_fp4: negative size");
+    if (!acc && !out) return fail(QNN_ERR_INVALID_ARG, "qnn_level_gemm_fp4: acc and out are both NULL");
+    if (out && !scale) return fail(QNN_ERR_INVALID_ARG, "qnn_level_gemm_fp4: out given without scale");
+    if (rows == 0 || cols == 0) return QNN_OK;
+    if (n > 0 && (!a_levels || !w_levels)) return fail(QNN_ERR_INVALID_ARG, "qnn_level_gemm_fp4: NULL level pointer");
+    if (!aligned16(a_levels) || !aligned16(w_levels) || !aligned16(acc) || !aligned16(out))
+        return fail(QNN_ERR_ALIGNMENT, "qnn_level_gemm_fp4: pointers must be 16-byte aligned");
+    // |acc| <= 9 n must stay below 2^24 for the fp32 accumulators of the instruction to be exact
+    if (n > ((int64_t)1 << 24) / 9)
+        return fail(QNN_ERR_RANGE, "qnn_level_gemm_fp4: n=%lld exceeds the exact range of fp32 accumulation", (long long)n);
+    LevelGemmParams p;
+    p.a = reinterpret_cast<const int8_t *>(a_levels), p.w = reinterpret_cast<const int8_t *>(w_levels);
+    p.rows = rows, p.cols = cols, p.nk = qnn_fp4_row_bytes(n);
+    p.acc = acc, p.scale = scale, p.out = out;
+    p.tiles_m = ceil_div(rows, kMB), p.tiles_n = ceil_div(cols, kNB);
+    if (p.tiles_m * p.tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_gemm_fp4: too many tiles");
+    hipLaunchKernelGGL(level_gemm_mfma_kernel<true>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), p);
+    return check_launch("qnn_level_gemm_fp4");
 }

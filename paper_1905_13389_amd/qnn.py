@@ -26,6 +26,7 @@ QNN_DTYPE_I8 = 2
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d",
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
+           "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
            "qnn_last_error", "qnn_version")
 
 
@@ -71,6 +72,12 @@ def lib():
         L.qnn_plane_sum_i8.restype = i32
         L.qnn_level_gemm_i8.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp]
         L.qnn_level_gemm_i8.restype = i32
+        L.qnn_fp4_row_bytes.argtypes = [i64]
+        L.qnn_fp4_row_bytes.restype = i64
+        L.qnn_plane_sum_fp4.argtypes = [vp, i32, i64, i64, vp, vp]
+        L.qnn_plane_sum_fp4.restype = i32
+        L.qnn_level_gemm_fp4.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp]
+        L.qnn_level_gemm_fp4.restype = i32
         L.qnn_encode_levels_i8.argtypes = [vp, i32, i64, f32, i32, vp, vp]
         L.qnn_encode_levels_i8.restype = i32
         L.qnn_level_conv2d_i8.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
@@ -158,6 +165,34 @@ def qnn_level_gemm_i8(a_levels, w_levels, n, want_acc=True, scale=None, acc=None
         out = torch.empty((rows, cols), dtype=torch.float32, device=dev)
     _check(lib().qnn_level_gemm_i8(_ptr(a_levels), _ptr(w_levels), rows, cols, n, _ptr(acc), _ptr(scale),
                                    _ptr(out), _stream()))
+    return acc, out
+
+
+def qnn_fp4_row_bytes(n):
+    return int(lib().qnn_fp4_row_bytes(int(n)))
+
+
+def qnn_plane_sum_fp4(planes, n, levels=None):
+    """planes [bits][rows][nw], bits <= 2 -> fp4 levels, two per byte, uint8 [rows][qnn_fp4_row_bytes(n)]."""
+    bits, rows, nw = planes.shape
+    assert nw == (n + 31) // 32
+    if levels is None:
+        levels = torch.empty((rows, qnn_fp4_row_bytes(n)), dtype=torch.uint8, device=planes.device)
+    _check(lib().qnn_plane_sum_fp4(_ptr(planes), bits, rows, n, _ptr(levels), _stream()))
+    return levels
+
+
+def qnn_level_gemm_fp4(a_levels, w_levels, n, want_acc=True, scale=None, acc=None, out=None):
+    """fp4 MFMA GEMM on levels as written by qnn_plane_sum_fp4 -> (acc int32 or None, out fp32 or None)."""
+    rows, cols = a_levels.shape[0], w_levels.shape[0]
+    assert a_levels.shape[1] == w_levels.shape[1] == qnn_fp4_row_bytes(n)
+    dev = a_levels.device
+    if want_acc and acc is None:
+        acc = torch.empty((rows, cols), dtype=torch.int32, device=dev)
+    if scale is not None and out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=dev)
+    _check(lib().qnn_level_gemm_fp4(_ptr(a_levels), _ptr(w_levels), rows, cols, n, _ptr(acc), _ptr(scale),
+                                    _ptr(out), _stream()))
     return acc, out
 
 
