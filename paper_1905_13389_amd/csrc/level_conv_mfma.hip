@@ -8,6 +8,7 @@
 // be compared with it.
 #include "qnn_host.h"
 #include "quantize.h"
+#include <type_traits>
 
 namespace qnn {
 
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     };
     // One k step: NM MFMAs on operand set b; the operand reads of the following step and (dma) the
     // direct loads of a later stage are issued one by one between them.
-    auto mfma_step = [&](int b, const uint8_t *next_stage, int next_ks, bool dma, int dma_stage, int dma_buf, uint32_t entry) {
+    auto mfma_step = [&](int b, const uint8_t *next_stage, int next_ks, auto dma, int dma_stage, int dma_buf, uint32_t entry) {
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             __builtin_amdgcn_sched_barrier(0);
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = m; r < NR; r += NM) read_one(next_stage, next_ks, b ^ 1, r);
-            if (dma_buf >= 0 && dma) {
+            if constexpr (decltype(dma)::value) {
 #pragma unroll
                 for (int j = m; j < L; j += NM) issue_one(dma_stage, dma_buf, j, entry);
             }
@@ -247,20 +248,25 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     // of stage s+1 have landed, so under the last step's MFMAs the first operands of stage s+1 are
     // read and stage s+2 is requested into the buffer of stage s.
     static_assert(kRing == 2, "the waits below assume two buffers");
+    // The loop runs in two parts, with and without the request for stage s+2, so that each body is
+    // one straight line of code whose order the scheduling barriers pin.
     int cur = 0;
-    for (int s = 0; s < p.nstages; ++s) {
+    auto stage_body = [&](int s, auto dma) {
         const uint8_t *st = smem[cur];
-        const bool more = s + kRing < p.nstages;
 #pragma unroll
-        for (int ks = 0; ks + 1 < kSteps; ++ks) mfma_step(ks & 1, st, ks + 1, false, 0, -1, 0u);
-        const uint32_t entry = more ? tap_table[(s + kRing) * kUnits + q] : 0u;
+        for (int ks = 0; ks + 1 < kSteps; ++ks) mfma_step(ks & 1, st, ks + 1, std::false_type{}, 0, 0, 0u);
+        uint32_t entry = 0u;
+        if constexpr (decltype(dma)::value) entry = tap_table[(s + kRing) * kUnits + q];
         QNN_CONV_WAIT_VMCNT(0);
         __builtin_amdgcn_s_waitcnt(0xC07F); // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         // after the last stage this reads stale data that is never used (no branch around LDS reads)
-        mfma_step((kSteps - 1) & 1, smem[cur ^ 1], 0, more, s + kRing, cur, entry);
+        mfma_step((kSteps - 1) & 1, smem[cur ^ 1], 0, dma, s + kRing, cur, entry);
         cur ^= 1;
-    }
+    };
+    int s = 0;
+    for (; s + kRing < p.nstages; ++s) stage_body(s, std::true_type{});
+    for (; s < p.nstages; ++s) stage_body(s, std::false_type{});
 
     // D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) + r % 4
     if (p.acc || p.out) {
