@@ -2,9 +2,11 @@
 //
 // The M x K binary branches of the paper (Eq. 9 with the {-1,+1} code of Eq. 10) recombine to the
 // integer dot product of the decoded levels.  This file takes the other road to the same
-// integers: sum the 2^j-weighted planes back into int8 levels (qnn_plane_sum_i8) and contract
-// them with v_mfma_i32_32x32x32_i8 (qnn_level_gemm_i8).  It is NOT the graded xor + bitcount
-// path (binary_gemm.hip); it exists to be compared with it, same inputs, same int32 outputs.
+// integers: sum the 2^j-weighted planes back into levels -- int8 (qnn_plane_sum_i8, up to 7 bits)
+// or fp4 (qnn_plane_sum_fp4, 1 and 2 bits) -- and contract them with v_mfma_i32_32x32x32_i8
+// (qnn_level_gemm_i8) or v_mfma_scale_f32_32x32x64_f8f6f4 (qnn_level_gemm_fp4).  It is NOT the
+// graded xor + bitcount path (binary_gemm.hip); it exists to be compared with it, same inputs,
+// same int32 outputs.
 #include "qnn_host.h"
 #include <type_traits>
 
