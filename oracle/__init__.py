@@ -188,3 +188,47 @@ def conv_stack(x, layers):
         trace.append({"levels": lv, "acc": acc, "out": out})
         cur = out
     return trace
+
+
+def pool_out_size(size, k, stride, pad, ceil_mode):
+    """Output extent of a pooling window sweep: floor or ceil of (size + 2 pad - k) / stride, plus 1;
+    in ceil mode a last window that would start beyond the image and its left padding is dropped."""
+    span = size + 2 * pad - k
+    if span < 0:
+        raise ValueError("pooling window larger than the padded image")
+    if ceil_mode:
+        out = -(-span // stride) + 1
+        if (out - 1) * stride >= size + pad:
+            out -= 1
+    else:
+        out = span // stride + 1
+    return out
+
+
+def maxpool(levels, k, stride, pad=0, ceil_mode=False):
+    """Max-pooling of a quantized activation tensor, taken on the decoded levels.
+
+    The linear quantizer (Eq. 15 after the range limit of Table 1) is monotone non-decreasing, so the
+    maximum over a window of the quantized values is the quantized maximum: pooling the levels (or,
+    equally, the codes) is exact.  levels: integer [B][H][W][C].  Window elements outside the image
+    (padding, ceil-mode overhang) are ignored.  Plain definition: for every window offset, an
+    elementwise maximum of the shifted view.
+    """
+    a = np.asarray(levels)
+    B, H, W, C = a.shape
+    if pad * 2 > k:
+        raise ValueError("pad must be at most half the window")
+    ho = pool_out_size(H, k, stride, pad, ceil_mode)
+    wo = pool_out_size(W, k, stride, pad, ceil_mode)
+    lowest = np.iinfo(np.int32).min
+    out = np.full((B, ho, wo, C), lowest, dtype=np.int32)
+    for oy in range(ho):
+        for ox in range(wo):
+            for ky in range(k):
+                for kx in range(k):
+                    y, x = oy * stride - pad + ky, ox * stride - pad + kx
+                    if 0 <= y < H and 0 <= x < W:
+                        out[:, oy, ox, :] = np.maximum(out[:, oy, ox, :], a[:, y, x, :])
+    if (out == lowest).any():
+        raise ValueError("a pooling window holds no image element")
+    return out.astype(a.dtype)
