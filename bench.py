@@ -69,7 +69,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "conv3", "stack4", "stack5"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "conv3", "stack4", "stack5", "pool"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -226,12 +226,49 @@ def conv_workload(args):
                                       "note": "whole step, not a single kernel"}}}))
 
 
+def pool_workload(args):
+    """2x2 stride-2 max-pooling on the 4-bit planes of the detection stack's first resolution change
+    (batch 32, 300x300x64 -> 150x150x64): a streaming kernel, bound by HBM."""
+    import torch
+    from paper_1905_13389_amd import qnn
+
+    B, H, C, bits = args.batch or 32, 300, 64, 4
+    cw = C // 32
+    gen = torch.Generator(device="cuda").manual_seed(190513389)
+    planes = torch.randint(-2 ** 31, 2 ** 31 - 1, (bits, B * H * H, cw), dtype=torch.int32, device="cuda",
+                           generator=gen)
+    ho = qnn.qnn_pool_out_size(H, 2, 2)
+    out = torch.empty((bits, B * ho * ho, cw), dtype=torch.int32, device="cuda")
+    for _ in range(args.warmup):
+        qnn.qnn_maxpool_planes(planes, (B, H, H), C, 2, 2, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        qnn.qnn_maxpool_planes(planes, (B, H, H), C, 2, 2, out=out)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    nbytes = 4.0 * (planes.numel() + out.numel())
+    tbs = nbytes / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "max-pooling on bit-planes, HBM bytes per second", "value": round(tbs, 3), "unit": "TB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 bit-planes",
+        "data": "synthetic",
+        "config": {"workload": "2x2 stride-2 max-pool, batch %d, 300x300x64, 4-bit planes" % B,
+                   "step": "qnn_maxpool_planes"},
+        "roofline": {"bound": "hbm", "kernel": "maxpool_planes_kernel<4>", "achieved": round(tbs * 1e3, 1),
+                     "peak": 8000.0, "unit": "GB/s", "frac": round(tbs / 8.0, 4), "traffic": None,
+                     "algorithmic_bytes": nbytes}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by output rows with no "
               "exchange; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "pool":
+        return pool_workload(args)
     if args.workload != "gemm":
         return conv_workload(args)
 

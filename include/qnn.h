@@ -127,6 +127,23 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
                float next_clip, int next_bits, void *stream);
 
 /*
+ * qnn_maxpool_planes / qnn_maxpool_levels_i8 -- max-pooling between quantized layers, taken on the
+ * codes.  The linear quantizer (Table 1 range limit, Eq. 15) is monotone non-decreasing, so the
+ * maximum of quantized values over a window equals the quantized maximum: pooling planes is exact.
+ * Window k x k (k <= 7), `stride`, `pad` (2 pad <= k); window elements outside the image are ignored.
+ *   Ho = qnn_pool_out_size(H, k, stride, pad, ceil_mode): floor((H + 2 pad - k) / stride) + 1, or with
+ *   ceil_mode != 0 the ceiling of the quotient, less one if the last window would start past H + pad;
+ *   -1 for an invalid geometry.
+ *   planes     DEVICE [bits][B][H][W][ceil(C/32)]  ->  out_planes DEVICE [bits][B][Ho][Wo][ceil(C/32)]
+ *   levels     DEVICE int8 [B][H][W][C]            ->  out_levels DEVICE int8 [B][Ho][Wo][C]
+ */
+int64_t qnn_pool_out_size(int64_t size, int k, int stride, int pad, int ceil_mode);
+int qnn_maxpool_planes(const uint32_t *planes, int bits, int64_t B, int64_t H, int64_t W, int64_t C, int k,
+                       int stride, int pad, int ceil_mode, uint32_t *out_planes, void *stream);
+int qnn_maxpool_levels_i8(const int8_t *levels, int64_t B, int64_t H, int64_t W, int64_t C, int k, int stride,
+                          int pad, int ceil_mode, int8_t *out_levels, void *stream);
+
+/*
  * Bit-plane-sum variant on the matrix cores (for comparison with qnn_binary_gemm; same integers).
  * The M x K branch sum of Eq. 9 equals the integer dot product of the decoded levels (Eq. 7-10),
  * so one can also sum the 2^j-weighted planes back into int8 levels and contract those with int8

@@ -27,6 +27,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
+           "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
            "qnn_last_error", "qnn_version")
 
 
@@ -72,6 +73,12 @@ def lib():
         L.qnn_plane_sum_i8.restype = i32
         L.qnn_level_gemm_i8.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp]
         L.qnn_level_gemm_i8.restype = i32
+        L.qnn_pool_out_size.argtypes = [i64, i32, i32, i32, i32]
+        L.qnn_pool_out_size.restype = i64
+        L.qnn_maxpool_planes.argtypes = [vp, i32, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
+        L.qnn_maxpool_planes.restype = i32
+        L.qnn_maxpool_levels_i8.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
+        L.qnn_maxpool_levels_i8.restype = i32
         L.qnn_fp4_row_bytes.argtypes = [i64]
         L.qnn_fp4_row_bytes.restype = i64
         L.qnn_plane_sum_fp4.argtypes = [vp, i32, i64, i64, vp, vp]
@@ -166,6 +173,34 @@ def qnn_level_gemm_i8(a_levels, w_levels, n, want_acc=True, scale=None, acc=None
     _check(lib().qnn_level_gemm_i8(_ptr(a_levels), _ptr(w_levels), rows, cols, n, _ptr(acc), _ptr(scale),
                                    _ptr(out), _stream()))
     return acc, out
+
+
+def qnn_pool_out_size(size, k, stride, pad=0, ceil_mode=False):
+    return int(lib().qnn_pool_out_size(int(size), int(k), int(stride), int(pad), int(bool(ceil_mode))))
+
+
+def qnn_maxpool_planes(planes, shape, channels, k, stride, pad=0, ceil_mode=False, out=None):
+    """planes [bits][B*H*W][cw] of an NHWC tensor of shape=(B, H, W) -> planes [bits][B*Ho*Wo][cw]."""
+    B, H, W = shape
+    bits, rows, cw = planes.shape
+    assert rows == B * H * W and cw == (channels + 31) // 32
+    ho, wo = qnn_pool_out_size(H, k, stride, pad, ceil_mode), qnn_pool_out_size(W, k, stride, pad, ceil_mode)
+    if out is None:
+        out = torch.empty((bits, B * max(ho, 0) * max(wo, 0), cw), dtype=torch.int32, device=planes.device)
+    _check(lib().qnn_maxpool_planes(_ptr(planes), bits, B, H, W, channels, int(k), int(stride), int(pad),
+                                    int(bool(ceil_mode)), _ptr(out), _stream()))
+    return out
+
+
+def qnn_maxpool_levels_i8(levels, k, stride, pad=0, ceil_mode=False, out=None):
+    """int8 levels [B][H][W][C] -> [B][Ho][Wo][C]."""
+    B, H, W, C = levels.shape
+    ho, wo = qnn_pool_out_size(H, k, stride, pad, ceil_mode), qnn_pool_out_size(W, k, stride, pad, ceil_mode)
+    if out is None:
+        out = torch.empty((B, max(ho, 0), max(wo, 0), C), dtype=torch.int8, device=levels.device)
+    _check(lib().qnn_maxpool_levels_i8(_ptr(levels), B, H, W, C, int(k), int(stride), int(pad),
+                                       int(bool(ceil_mode)), _ptr(out), _stream()))
+    return out
 
 
 def qnn_fp4_row_bytes(n):

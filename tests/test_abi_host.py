@@ -160,3 +160,26 @@ def test_matrix_core_variant_argument_errors(qnn):
     assert conv(ok, a=None) == qnn.QNN_ERR_INVALID_ARG
     assert conv(ok, w=ODD) == qnn.QNN_ERR_ALIGNMENT
     assert conv(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
+
+
+def test_pool_argument_errors_and_out_size(qnn):
+    L = qnn.lib()
+    assert L.qnn_pool_out_size(8, 2, 2, 0, 0) == 4
+    assert L.qnn_pool_out_size(75, 2, 2, 0, 0) == 37 and L.qnn_pool_out_size(75, 2, 2, 0, 1) == 38
+    assert L.qnn_pool_out_size(112, 3, 2, 1, 0) == 56
+    assert L.qnn_pool_out_size(4, 3, 2, 1, 1) == 3
+    assert L.qnn_pool_out_size(5, 2, 2, 1, 1) == 3          # a fourth window would start in the right padding
+    assert L.qnn_pool_out_size(3, 5, 1, 0, 0) == -1 and L.qnn_pool_out_size(8, 2, 2, 2, 0) == -1
+    mp = L.qnn_maxpool_planes
+    assert mp(FAKE, 0, 1, 8, 8, 32, 2, 2, 0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert mp(FAKE, 2, 1, 8, 8, 32, 2, 0, 0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert mp(FAKE, 2, 1, 8, 8, 32, 2, 2, 2, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert mp(FAKE, 2, 1, 8, 8, 32, 9, 1, 0, 0, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED
+    assert mp(FAKE, 2, 1, 2, 2, 32, 3, 1, 0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert mp(None, 2, 1, 8, 8, 32, 2, 2, 0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert mp(FAKE, 2, 1, 8, 8, 32, 2, 2, 0, 0, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert mp(None, 2, 0, 8, 8, 32, 2, 2, 0, 0, None, None) == qnn.QNN_OK
+    ml = L.qnn_maxpool_levels_i8
+    assert ml(FAKE, 1, 8, 8, 0, 2, 2, 0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert ml(ODD, 1, 8, 8, 16, 2, 2, 0, 0, FAKE, None) == qnn.QNN_ERR_ALIGNMENT
+    assert ml(None, 0, 8, 8, 16, 2, 2, 0, 0, None, None) == qnn.QNN_OK

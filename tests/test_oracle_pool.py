@@ -16,6 +16,7 @@ GEOMS = [
     (9, 9, 3, 1, 1, False),     # 3x3 stride 1 pad 1 (keeps the size)
     (10, 7, 3, 3, 1, True),
     (5, 5, 5, 1, 2, False),
+    (5, 5, 2, 2, 1, True),      # the window that would start in the right padding is dropped
 ]
 
 
