@@ -83,3 +83,14 @@ def test_dequant_scale(shape):
     s = gen.uniform(0.01, 0.1, size=shape[1]).astype(np.float32)
     got = qnn.qnn_dequant_scale(dev(acc), dev(s)).cpu().numpy()
     assert np.array_equal(got, oracle.scale(acc, s))
+
+
+@pytest.mark.parametrize("bits", [1, 2, 4])
+def test_encode_hrelu_limited_values(bits):
+    # HReLU-limited activations ([0, 1], Table 1) through the same encoder: upper levels only
+    gen = np.random.default_rng(40 + bits)
+    h = np.clip(gen.normal(0, 1, size=(33, 100)), 0.0, 1.0).astype(np.float32)
+    got = qnn.qnn_encode_pack(dev(h), 1.0, bits)
+    lv, _ = oracle.quantize(h, 1.0, bits)
+    assert lv.min() >= 1
+    assert np.array_equal(planes_to_numpy(got), oracle.pack_planes(lv.reshape(33, 100), bits))

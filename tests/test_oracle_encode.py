@@ -171,3 +171,24 @@ def test_pack_rejects_even_or_out_of_range_levels():
         oracle.pack_planes(np.array([[0]], dtype=np.int16), 2)
     with pytest.raises(ValueError):
         oracle.pack_planes(np.array([[5]], dtype=np.int16), 2)
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 8])
+def test_hrelu_limited_values_use_the_upper_levels(bits):
+    # Table 1's HReLU limits the data to [0, 1]; the encoder of Eq. 15 is then applied to that value as
+    # it is, so only the non-negative half of the levels occurs, and with one bit every activation is
+    # +1 (the special case noted in the experiments section, which is why 1-bit uses HTanh)
+    gen = np.random.default_rng(bits)
+    x = gen.normal(0, 1, size=20000).astype(np.float32)
+    h = np.clip(x, 0.0, 1.0)
+    lv, code = oracle.quantize(h, 1.0, bits)
+    top = (1 << bits) - 1
+    assert lv.min() == 1 and lv.max() == top
+    if bits == 1:
+        assert np.all(lv == 1)
+    else:
+        assert len(np.unique(lv)) == (top + 1) // 2
+    # Eq. 15 in float64 on the limited value, away from the rounding thresholds
+    u = (top * (h.astype(np.float64) + 1.0) / 2.0)
+    far = np.abs(u - np.floor(u) - 0.5) > 1e-4
+    assert np.array_equal(code[far], np.floor(u[far] + 0.5).astype(code.dtype))
