@@ -5,7 +5,9 @@ tests/, the smoke check and the benchmark's cpu_baseline leg may import this pac
 the GPU library never does and shares no code with it.
 
 Every function cites the passage of the paper it follows; the C file's header lists
-what pins each of them.
+what pins each of them.  maxpool / pool_out_size are plain numpy here; their pins (the library
+pooling routine on the same integers, commutation with the quantizer, brute force) are in
+tests/test_oracle_pool.py.
 """
 import ctypes
 import os
