@@ -137,3 +137,43 @@ def vgg_ssd_stack(batch=32, bits=4, config_index=4, plan=VGG_SSD_PLAN):
             t += 1
         groups.append({"x": x, "layers": layers})
     return groups
+
+
+# --------------------------------------------------------------------------- whole network
+CIFAR_VGG_PLAN = (
+    # The CIFAR-10 network of the paper's Table 3 (the BinaryConnect / BNN architecture it cites:
+    # 2x128C3 - MP2 - 2x256C3 - MP2 - 2x512C3 - MP2 - 2x1024FC - 10), from its second layer on: the
+    # first convolution reads the real-valued image and is not part of the quantized path.
+    ("conv", 128, 128), ("pool",),
+    ("conv", 128, 256), ("conv", 256, 256), ("pool",),
+    ("conv", 256, 512), ("conv", 512, 512), ("pool",),
+    ("fc", 4 * 4 * 512, 1024), ("fc", 1024, 1024), ("fc", 1024, 10),
+)
+
+
+def cifar_vgg_network(batch=8, bits=2, config_index=5, plan=CIFAR_VGG_PLAN):
+    """Input at the first layer's output shape [batch][32][32][128] ~ N(0,1), clip = 3 sigma; every
+    later quantizer clips at 3.0.  Ops: dicts with kind conv (as _stack_layer), pool (2x2 stride 2)
+    or fc (w int8 levels [cout][n], scale fp32 [cout], clip of its input quantizer)."""
+    x = rng(config_index, 0).standard_normal((batch, 32, 32, plan[0][1]), dtype=np.float32)
+    clip0 = float(np.float32(3.0 * np.std(x.astype(np.float64))))
+    ops, t, first = [], 0, True
+    for op in plan:
+        if op[0] == "pool":
+            ops.append({"kind": "pool", "k": 2, "stride": 2})
+            continue
+        gw, gs = rng(config_index, 10 + 2 * t), rng(config_index, 11 + 2 * t)
+        t += 1
+        clip = clip0 if first else 3.0
+        first = False
+        if op[0] == "conv":
+            L = _stack_layer(gw, gs, op[1], op[2], bits, 1, clip)
+            L["kind"] = "conv"
+        else:
+            n, cout = op[1], op[2]
+            g = gs.uniform(0.5, 1.5, size=cout)
+            s = g / np.sqrt(n * _uniform_level_variance(bits) * _gaussian_level_variance(bits))
+            L = {"kind": "fc", "w": odd_levels(gw, (cout, n), bits), "scale": s.astype(np.float32),
+                 "clip": float(clip), "a_bits": bits, "w_bits": bits, "n": n, "cout": cout}
+        ops.append(L)
+    return {"x": x, "ops": ops}
