@@ -15,6 +15,12 @@ struct GemmParams {
     float *out;           // or nullptr
     int vec;              // nw % 4 == 0: 16-byte loads of the planes are aligned
     int64_t tiles_n, nblocks;
+    // Bit widths above 4 run as up to four launches over chunks of at most 4 planes per operand:
+    // Eq. 9's double sum splits into chunk pairs, each an ordinary (<= 4) x (<= 4) product whose
+    // result enters with the weight 2^shift of its lowest planes.
+    int shift;                  // weight of this chunk pair
+    const int32_t *partial_in;  // sum of the chunk pairs done so far, or nullptr
+    int32_t *partial_out;       // where to leave the running sum (not the last chunk pair), or nullptr
 };
 
 template <int WB, int AB, int TM, int TN, int KV>
@@ -101,33 +107,18 @@ __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2,
         for (int n = 0; n < TN; ++n) {
             const int64_t cidx = col0 + tx + 16 * n;
             if (cidx >= p.cols) continue;
-            const int32_t v = recombine<T::S>(P[i][n], p.n_times_top);
-            if (p.acc) p.acc[r * p.cols + cidx] = v;
-            if (p.out) p.out[r * p.cols + cidx] = (float)v * p.scale[cidx];
+            int32_t v = recombine<T::S>(P[i][n], p.n_times_top);
+            const int64_t o = r * p.cols + cidx;
+            v = (int32_t)((uint32_t)v << p.shift);
+            if (p.partial_in) v += p.partial_in[o];
+            if (p.partial_out) {
+                p.partial_out[o] = v;
+                continue;
+            }
+            if (p.acc) p.acc[o] = v;
+            if (p.out) p.out[o] = (float)v * p.scale[cidx];
         }
     }
-}
-
-// Any bit widths 1..8: one lane per output, plane pairs looped at run time.  Slow and plain; it
-// serves the widths the register-blocked kernels are not instantiated for.
-__global__ __launch_bounds__(256) void bgemm_plain_kernel(GemmParams p, int w_bits, int a_bits)
-{
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= p.rows * p.cols) return;
-    const int64_t r = idx / p.cols, c = idx % p.cols;
-    uint32_t sum = 0;
-    for (int i = 0; i < w_bits; ++i) {
-        const uint32_t *wp = p.w + ((int64_t)i * p.cols + c) * p.nw;
-        for (int j = 0; j < a_bits; ++j) {
-            const uint32_t *ap = p.a + ((int64_t)j * p.rows + r) * p.nw;
-            uint32_t cnt = 0;
-            for (int64_t k = 0; k < p.nw; ++k) cnt += __builtin_popcount(wp[k] ^ ap[k]);
-            sum += cnt << (i + j);
-        }
-    }
-    const int32_t v = (int32_t)(p.n_times_top - 2u * sum);
-    if (p.acc) p.acc[idx] = v;
-    if (p.out) p.out[idx] = (float)v * p.scale[c];
 }
 
 template <int WB, int AB, int TM, int TN, int KV> static void launch_tile(GemmParams p, hipStream_t st)
@@ -190,7 +181,6 @@ extern "C" int qnn_binary_gemm(const uint32_t *a_planes, int a_bits, const uint3
     p.rows = rows;
     p.cols = cols;
     p.nw = ceil_div(n, 32);
-    p.n_times_top = (uint32_t)(n * ((1 << w_bits) - 1) * ((1 << a_bits) - 1));
     p.acc = acc;
     p.scale = scale;
     p.out = out;
@@ -198,20 +188,32 @@ extern "C" int qnn_binary_gemm(const uint32_t *a_planes, int a_bits, const uint3
     p.tiles_n = p.nblocks = 0;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    bool done = false;
-    switch (w_bits) {
-    case 1: done = dispatch_a<1>(a_bits, p, st); break;
-    case 2: done = dispatch_a<2>(a_bits, p, st); break;
-    case 3: done = dispatch_a<3>(a_bits, p, st); break;
-    case 4: done = dispatch_a<4>(a_bits, p, st); break;
-    default: break;
-    }
-    if (!done) {
-        const int64_t total = rows * cols;
-        if (ceil_div(total, 256) > 0x7fffffffLL)
-            return fail(QNN_ERR_UNSUPPORTED, "qnn_binary_gemm: output too large for the wide-bit kernel");
-        hipLaunchKernelGGL(bgemm_plain_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, st, p,
-                           w_bits, a_bits);
-    }
-    return check_launch("qnn_binary_gemm");
+    // chunk pairs of at most 4 x 4 planes; the running int32 sum lives in acc, or (bit for bit) in
+    // the memory of out when no acc was asked for -- the last launch turns it into the results
+    int32_t *running = acc ? acc : reinterpret_cast<int32_t *>(out);
+    const int w_chunks = (w_bits + 3) / 4, a_chunks = (a_bits + 3) / 4;
+    int launch = 0;
+    for (int cw = 0; cw < w_chunks; ++cw)
+        for (int ca = 0; ca < a_chunks; ++ca, ++launch) {
+            const int wb = w_bits - 4 * cw < 4 ? w_bits - 4 * cw : 4;
+            const int ab = a_bits - 4 * ca < 4 ? a_bits - 4 * ca : 4;
+            GemmParams q = p;
+            q.w = w_planes + (int64_t)4 * cw * cols * p.nw;
+            q.a = a_planes + (int64_t)4 * ca * rows * p.nw;
+            q.n_times_top = (uint32_t)(n * ((1 << wb) - 1) * ((1 << ab) - 1));
+            q.shift = 4 * (cw + ca);
+            q.partial_in = launch > 0 ? running : nullptr;
+            q.partial_out = launch + 1 < w_chunks * a_chunks ? running : nullptr;
+            bool done = false;
+            switch (wb) {
+            case 1: done = dispatch_a<1>(ab, q, st); break;
+            case 2: done = dispatch_a<2>(ab, q, st); break;
+            case 3: done = dispatch_a<3>(ab, q, st); break;
+            default: done = dispatch_a<4>(ab, q, st); break;
+            }
+            if (!done) return fail(QNN_ERR_UNSUPPORTED, "qnn_binary_gemm: no kernel for %d x %d planes", wb, ab);
+            const int rc = check_launch("qnn_binary_gemm");
+            if (rc != QNN_OK) return rc;
+        }
+    return QNN_OK;
 }

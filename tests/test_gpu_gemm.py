@@ -44,19 +44,50 @@ def test_tiled_kernels_ragged(w_bits, a_bits, shape):
     np.testing.assert_allclose(out, oracle.scale(want, s), rtol=RTOL, atol=0)
 
 
-@pytest.mark.parametrize("bits", [(5, 5), (8, 2), (3, 7), (1, 6)])
-def test_wide_bit_kernel(bits):
+def _wide_levels(gen, shape, bits):
+    top = (1 << bits) - 1
+    return (2 * gen.integers(0, top + 1, size=shape) - top).astype(np.int16)
+
+
+WIDE_BITS = [(5, 5), (8, 2), (3, 7), (1, 6), (8, 8), (6, 5), (7, 8), (4, 5), (5, 4)]
+
+
+@pytest.mark.parametrize("bits", WIDE_BITS)
+@pytest.mark.parametrize("shape", [(37, 19, 200), (130, 70, 1000), (257, 129, 33)])
+def test_wide_bits_run_as_plane_chunks(bits, shape):
+    # widths above 4 are split into chunks of at most 4 planes; the chunk pairs' results are summed
+    # with their 2^shift weights in the int32 accumulator, also when only the scaled output is asked for
     w_bits, a_bits = bits
-    gen = np.random.default_rng(w_bits * 10 + a_bits)
-    rows, cols, n = 37, 19, 200
-    top_a, top_w = (1 << a_bits) - 1, (1 << w_bits) - 1
-    a = (2 * gen.integers(0, top_a + 1, size=(rows, n)) - top_a).astype(np.int16)
-    w = (2 * gen.integers(0, top_w + 1, size=(cols, n)) - top_w).astype(np.int16)
+    rows, cols, n = shape
+    gen = np.random.default_rng(w_bits * 10 + a_bits + rows)
+    a, w = _wide_levels(gen, (rows, n), a_bits), _wide_levels(gen, (cols, n), w_bits)
+    s = gen.uniform(0.01, 0.1, size=cols).astype(np.float32)
     ap = dev(oracle.pack_planes(a, a_bits).view(np.int32))   # 8-bit levels do not fit the int8 input path
     wp = dev(oracle.pack_planes(w, w_bits).view(np.int32))
-    acc, _ = qnn.qnn_binary_gemm(ap, wp, n)
+    acc, out = qnn.qnn_binary_gemm(ap, wp, n, scale=dev(s))
+    _, out_only = qnn.qnn_binary_gemm(ap, wp, n, want_acc=False, scale=dev(s))
+    acc_only, _ = qnn.qnn_binary_gemm(ap, wp, n)
     torch.cuda.synchronize()
-    assert np.array_equal(acc.cpu().numpy(), oracle.gemm(a, w))
+    want = oracle.gemm(a, w)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    assert np.array_equal(acc_only.cpu().numpy(), want)
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s), rtol=RTOL, atol=0)
+    assert torch.equal(out, out_only)
+
+
+def test_wide_bits_extreme_levels():
+    # 8 x 8 bit at the largest n the int32 accumulator allows: |acc| = n 255^2
+    n = 33025
+    a = np.full((3, n), 255, np.int16)
+    w = np.stack([np.full(n, 255, np.int16), np.full(n, -255, np.int16)])
+    a[2, ::2] = -255
+    acc, _ = qnn.qnn_binary_gemm(dev(oracle.pack_planes(a, 8).view(np.int32)),
+                                 dev(oracle.pack_planes(w, 8).view(np.int32)), n)
+    torch.cuda.synchronize()
+    want = a.astype(np.int64) @ w.astype(np.int64).T
+    assert want[0, 0] == n * 255 * 255 < 2 ** 31
+    assert np.array_equal(acc.cpu().numpy(), want)
+    assert np.array_equal(oracle.gemm(a, w), want)
 
 
 def test_extreme_levels_hit_the_bound():
