@@ -416,23 +416,23 @@ def main():
 
     if args.sweep:
         sweep = {}
-        for w_b in range(1, 5):
-            for a_b in range(1, 5):
-                c2 = wl.gemm_square(w_b, a_b, size)
-                wp = qnn.qnn_encode_pack(torch.from_numpy(c2["w"]).cuda(), 1.0, w_b)
-                apl = qnn.qnn_encode_pack(torch.from_numpy(c2["a"]).cuda(), 1.0, a_b)
-                for _ in range(3):
-                    qnn.qnn_binary_gemm(apl, wp, size, acc=acc)
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(10):
-                    qnn.qnn_binary_gemm(apl, wp, size, acc=acc)
-                e1.record()
-                torch.cuda.synchronize()
-                ms = e0.elapsed_time(e1) / 10
-                tops = 2.0 * size ** 3 * w_b * a_b / (ms * 1e-3) / 1e12
-                sweep["%dx%d" % (w_b, a_b)] = {"ms": round(ms, 4), "binary_tops": round(tops, 1),
-                                               "frac": round(tops / PEAK_BINARY_TOPS, 4)}
+        combos = [(w_b, a_b) for w_b in range(1, 5) for a_b in range(1, 5)] + [(5, 5), (6, 6), (7, 7)]
+        for w_b, a_b in combos:
+            c2 = wl.gemm_square(w_b, a_b, size)
+            wp = qnn.qnn_encode_pack(torch.from_numpy(c2["w"]).cuda(), 1.0, w_b)
+            apl = qnn.qnn_encode_pack(torch.from_numpy(c2["a"]).cuda(), 1.0, a_b)
+            for _ in range(3):
+                qnn.qnn_binary_gemm(apl, wp, size, acc=acc)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                qnn.qnn_binary_gemm(apl, wp, size, acc=acc)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            tops = 2.0 * size ** 3 * w_b * a_b / (ms * 1e-3) / 1e12
+            sweep["%dx%d" % (w_b, a_b)] = {"ms": round(ms, 4), "binary_tops": round(tops, 1),
+                                           "frac": round(tops / PEAK_BINARY_TOPS, 4)}
         result["sweep"] = sweep
 
     if not args.no_cpu_baseline:

@@ -82,7 +82,9 @@ int qnn_encode_pack(const void *src, int dtype, int64_t rows, int64_t n,
  *   acc      DEVICE out int32 [rows][cols], or NULL
  *   scale    DEVICE fp32 [cols]; required iff out != NULL
  *   out      DEVICE out fp32 [rows][cols], or NULL         (acc and out not both NULL)
- * Bit widths 1..4 x 1..4 run register-blocked kernels; wider ones a plain kernel.
+ * Bit widths above 4 run as up to four launches over chunks of at most 4 planes per operand (the
+ * double sum of Eq. 9 splits into chunk pairs); the running int32 sum is kept in acc, or in the
+ * memory of out when acc is NULL, until the last launch writes the results.
  */
 int qnn_binary_gemm(const uint32_t *a_planes, int a_bits, const uint32_t *w_planes, int w_bits,
                     int64_t rows, int64_t cols, int64_t n, int32_t *acc, const float *scale,
@@ -114,7 +116,9 @@ int qnn_dequant_scale(const int32_t *acc, const float *scale, int64_t rows, int6
  *   next_planes DEVICE out [next_bits][B][Ho][Wo][ceil(Cout/32)], or NULL: the fused epilogue
  *            out -> qnn_encode_pack(out, clip = next_clip, bits = next_bits), so the next
  *            layer's planes are produced without the accumulator leaving the chip.
- * At least one of acc / out / next_planes must be given.  kh, kw in [1,7].
+ * At least one of acc / out / next_planes must be given.  kh, kw in [1,7].  Bit widths above 4 run as
+ * plane chunks like qnn_binary_gemm and need acc or out for the running sum (QNN_ERR_UNSUPPORTED with
+ * next_planes alone).
  */
 typedef struct qnn_conv_desc {
     int64_t B, H, W, Cin, Cout;

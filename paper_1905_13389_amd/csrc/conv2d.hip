@@ -67,6 +67,12 @@ struct ConvTileParams {
     FastDiv div_howo, div_wo;
     int tiles_m, tiles_n, row_tile_step; // persistent schedule: see bconv_tile_kernel
     int kb, nchunks;                     // reduction words per LDS stage (multiple of 4), stages per tile
+    // Bit widths above 4 run as up to four launches over chunks of at most 4 planes per operand (the
+    // double sum of Eq. 9 splits into chunk pairs); `shift` is the weight 2^shift of this pair,
+    // `partial` the running int32 sum: read when bit 0 of partial_mode is set, written instead of the
+    // outputs when bit 1 is set.
+    int shift, partial_mode;
+    int32_t *partial;
 };
 
 // Gather 4 consecutive reduction words of one output pixel.  VW = gcd(cw, 4) words share a tap;
@@ -311,6 +317,20 @@ bconv_tile_kernel(ConvTileParams p)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] += p.top_a * corr[e];
             }
+            if (p.partial_mode | p.shift) {
+                const int64_t off = (int64_t)r * p.Cout + cidx;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = (int32_t)((uint32_t)v[e] << p.shift);
+                    if ((p.partial_mode & 1) && rvalid && cidx + e < p.Cout) v[e] += p.partial[off + e];
+                }
+                if (p.partial_mode & 2) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (rvalid && cidx + e < p.Cout) p.partial[off + e] = v[e];
+                    continue;
+                }
+            }
             float o[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[e] = (float)v[e] * sc[e];
@@ -522,15 +542,16 @@ extern "C" int qnn_conv2d(const qnn_conv_desc *d, const uint32_t *a_planes, cons
                              p.M * cwo < (1LL << 31) && p.Ho + p.Wo <= kMaxOutExtent &&
                              ((int64_t)d->kh * d->W + d->kw) * p.cw < (1LL << 24);
     bool done = false;
-    if (p.nw <= kMaxGroups && d->kh * d->kw <= kMaxTaps && d->w_bits <= 4 && d->a_bits <= 4 && small_index) {
+    const bool wide = d->w_bits > 4 || d->a_bits > 4;
+    if (p.nw <= kMaxGroups && d->kh * d->kw <= kMaxTaps && small_index && (!wide || acc || out)) {
         ConvTileParams t;
         t.a = a_planes, t.w = w_planes, t.scale = scale, t.acc = acc, t.out = out, t.next = next_planes;
         t.H = (int)d->H, t.W = (int)d->W, t.HW = (int)(d->H * d->W), t.Cin = (int)d->Cin, t.Cout = (int)d->Cout;
         t.M = (int)p.M, t.cw = (int)p.cw, t.nw = (int)p.nw, t.cwo = (int)cwo, t.Ho = (int)p.Ho, t.Wo = (int)p.Wo;
         t.kh = d->kh, t.kw = d->kw, t.stride = d->stride, t.pad = d->pad;
         t.a_plane_stride = (int)p.a_plane_stride;
-        t.top_a = (1 << d->a_bits) - 1;
-        t.n_times_top = (uint32_t)(n * ((1 << d->w_bits) - 1) * t.top_a);
+        t.top_a = t.shift = t.partial_mode = 0;
+        t.n_times_top = 0;
         t.next_bits = next_planes ? next_bits : 0;
         t.next_top = next_planes ? (1 << next_bits) - 1 : 0;
         t.next_inv_clip = next_planes ? 1.0f / next_clip : 0.0f;
@@ -539,21 +560,42 @@ extern "C" int qnn_conv2d(const qnn_conv_desc *d, const uint32_t *a_planes, cons
         t.div_howo = make_fastdiv((uint32_t)(p.Ho * p.Wo));
         t.div_wo = make_fastdiv((uint32_t)p.Wo);
         t.tiles_m = t.tiles_n = t.row_tile_step = t.kb = t.nchunks = 0;
-        int rc = QNN_OK;
-        switch (d->w_bits) {
-        case 1: rc = conv_dispatch_a<1>(d->a_bits, t, st); break;
-        case 2: rc = conv_dispatch_a<2>(d->a_bits, t, st); break;
-        case 3: rc = conv_dispatch_a<3>(d->a_bits, t, st); break;
-        default: rc = conv_dispatch_a<4>(d->a_bits, t, st); break;
-        }
-        if (rc != QNN_OK) return rc;
+        // chunk pairs of at most 4 x 4 planes; the running sum lives in acc, or (bit for bit) in the
+        // memory of out; only the last launch writes the outputs and the next layer's planes
+        t.partial = acc ? acc : reinterpret_cast<int32_t *>(out);
+        const int w_chunks = (d->w_bits + 3) / 4, a_chunks = (d->a_bits + 3) / 4;
+        const int64_t w_plane_words = (int64_t)d->Cout * p.nw;
+        int launch = 0;
+        for (int cw = 0; cw < w_chunks; ++cw)
+            for (int ca = 0; ca < a_chunks; ++ca, ++launch) {
+                const int wb = d->w_bits - 4 * cw < 4 ? d->w_bits - 4 * cw : 4;
+                const int ab = d->a_bits - 4 * ca < 4 ? d->a_bits - 4 * ca : 4;
+                ConvTileParams q = t;
+                q.w = w_planes + 4 * cw * w_plane_words;
+                q.a = a_planes + 4 * ca * p.a_plane_stride;
+                q.top_a = (1 << ab) - 1;
+                q.n_times_top = (uint32_t)(n * ((1 << wb) - 1) * q.top_a);
+                q.shift = 4 * (cw + ca);
+                q.partial_mode = (launch > 0 ? 1 : 0) | (launch + 1 < w_chunks * a_chunks ? 2 : 0);
+                int rc = QNN_OK;
+                switch (wb) {
+                case 1: rc = conv_dispatch_a<1>(ab, q, st); break;
+                case 2: rc = conv_dispatch_a<2>(ab, q, st); break;
+                case 3: rc = conv_dispatch_a<3>(ab, q, st); break;
+                default: rc = conv_dispatch_a<4>(ab, q, st); break;
+                }
+                if (rc != QNN_OK) return rc;
+                rc = check_launch("qnn_conv2d");
+                if (rc != QNN_OK) return rc;
+            }
         done = true;
     }
     if (!done) {
         if (next_planes)
             return fail(QNN_ERR_UNSUPPORTED,
-                        "qnn_conv2d: the fused next-layer epilogue needs bits <= 4 and <= %d reduction words",
-                        kMaxGroups);
+                        "qnn_conv2d: the fused next-layer epilogue needs <= %d reduction words and <= %d taps, and "
+                        "above 4 bits an acc or out buffer for the running sum",
+                        kMaxGroups, kMaxTaps);
         const int64_t total = p.M * p.Cout;
         if (ceil_div(total, 256) > 0x7fffffffLL) return fail(QNN_ERR_UNSUPPORTED, "qnn_conv2d: output too large");
         hipLaunchKernelGGL(bconv_plain_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, st, p,

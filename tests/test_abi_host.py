@@ -112,8 +112,8 @@ def test_conv2d_argument_errors(qnn):
     assert call(ok, w=ODD) == qnn.QNN_ERR_ALIGNMENT
     # 8x8 bits with 3x3x4096 channels overflows int32
     assert call(D(1, 8, 8, 4096, 64, 3, 3, 1, 1, 8, 8)) == qnn.QNN_ERR_RANGE
-    # wide bits cannot use the fused epilogue
-    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 5, 5), scale=FAKE, nxt=FAKE, clip=1.0, nbits=2) \
+    # above 4 bits the fused epilogue needs an acc or out buffer for the running sum of the plane chunks
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 5, 5), scale=FAKE, acc=None, nxt=FAKE, clip=1.0, nbits=2) \
         == qnn.QNN_ERR_UNSUPPORTED
     assert call(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
 

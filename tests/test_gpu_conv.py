@@ -57,24 +57,64 @@ def test_conv_acc_and_out(geom, bits):
     np.testing.assert_allclose(out, oracle.scale(want, s), rtol=RTOL, atol=0)
 
 
-@pytest.mark.parametrize("bits", [(5, 5), (8, 8), (6, 2)])
-def test_conv_wide_bits(bits):
+def _wide(gen, shape, bits):
+    top = (1 << bits) - 1
+    return (2 * gen.integers(0, top + 1, size=shape) - top).astype(np.int16)
+
+
+def _zero_padded_im2col_gemm(a, w, k, stride, pad):
+    # oracle GEMM on an explicit zero-padded im2col: the pad = 0 / 1x1 identities pinned for the
+    # oracle's convolution, usable for 8-bit levels that do not fit its int8 input
+    B, H, W, Cin = a.shape
+    Cout = w.shape[0]
+    ap = np.zeros((B, H + 2 * pad, W + 2 * pad, Cin), np.int16)
+    ap[:, pad:pad + H, pad:pad + W] = a
+    ho, wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    cols = np.stack([ap[b, y * stride:y * stride + k, x * stride:x * stride + k].reshape(-1)
+                     for b in range(B) for y in range(ho) for x in range(wo)])
+    return oracle.gemm(cols, w.reshape(Cout, -1)).reshape(B, ho, wo, Cout)
+
+
+@pytest.mark.parametrize("bits", [(5, 5), (8, 8), (6, 2), (3, 7), (4, 5)])
+@pytest.mark.parametrize("geom", [(1, 6, 6, 40, 9, 3, 1, 1), (2, 9, 10, 64, 70, 3, 2, 1), (1, 7, 7, 32, 33, 5, 1, 2)])
+def test_conv_wide_bits(bits, geom):
+    # widths above 4 run as chunk pairs of at most 4 x 4 planes with a shifted running sum, including
+    # the zero-padding correction of every chunk pair
     w_bits, a_bits = bits
-    gen = np.random.default_rng(w_bits + a_bits)
-    B, H, W, Cin, Cout = 1, 6, 6, 40, 9
-    ta, tw = (1 << a_bits) - 1, (1 << w_bits) - 1
-    a = (2 * gen.integers(0, ta + 1, size=(B, H, W, Cin)) - ta).astype(np.int16)
-    w = (2 * gen.integers(0, tw + 1, size=(Cout, 3, 3, Cin)) - tw).astype(np.int16)
+    B, H, W, Cin, Cout, k, stride, pad = geom
+    gen = np.random.default_rng(w_bits + a_bits + sum(geom))
+    a, w = _wide(gen, (B, H, W, Cin), a_bits), _wide(gen, (Cout, k, k, Cin), w_bits)
+    s = gen.uniform(0.01, 0.1, size=Cout).astype(np.float32)
     ap = dev(oracle.pack_planes(a.reshape(-1, Cin), a_bits).view(np.int32))
-    wp = dev(oracle.pack_planes(w.reshape(-1, Cin), w_bits).view(np.int32)).view(w_bits, Cout, 3, 3, -1)
-    acc, _, _ = qnn.qnn_conv2d(ap, wp, (B, H, W), Cin, 1, 1)
+    wp = dev(oracle.pack_planes(w.reshape(-1, Cin), w_bits).view(np.int32)).view(w_bits, Cout, k, k, -1)
+    acc, out, _ = qnn.qnn_conv2d(ap, wp, (B, H, W), Cin, stride, pad, scale=dev(s), want_out=True)
+    _, out_only, _ = qnn.qnn_conv2d(ap, wp, (B, H, W), Cin, stride, pad, scale=dev(s), want_acc=False, want_out=True)
     torch.cuda.synchronize()
-    # oracle conv on int16 levels via torch float64 is a test pin, not the oracle: use the oracle's
-    # GEMM on an explicit zero-padded im2col instead
-    apad = np.zeros((B, H + 2, W + 2, Cin), np.int16)
-    apad[:, 1:-1, 1:-1] = a
-    cols = np.stack([apad[0, y:y + 3, x:x + 3].reshape(-1) for y in range(H) for x in range(W)])
-    assert np.array_equal(acc.cpu().numpy().reshape(-1, Cout), oracle.gemm(cols, w.reshape(Cout, -1)))
+    want = _zero_padded_im2col_gemm(a, w, k, stride, pad)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s), rtol=RTOL, atol=0)
+    assert torch.equal(out, out_only)
+
+
+def test_conv_wide_bits_fused_next_planes():
+    # 6-bit layer feeding a 5-bit one: the last chunk pair's epilogue quantizes the complete sum
+    gen = np.random.default_rng(65)
+    B, H, W, Cin, Cout = 2, 8, 8, 64, 64
+    a, w = _wide(gen, (B, H, W, Cin), 6), _wide(gen, (Cout, 3, 3, Cin), 6)
+    var = (4.0 ** 6 - 1) / 3
+    s = (gen.uniform(0.5, 1.5, size=Cout) / np.sqrt(9 * Cin * var * var)).astype(np.float32)
+    ap = dev(oracle.pack_planes(a.reshape(-1, Cin), 6).view(np.int32))
+    wp = dev(oracle.pack_planes(w.reshape(-1, Cin), 6).view(np.int32)).view(6, Cout, 3, 3, -1)
+    acc, _, nxt = qnn.qnn_conv2d(ap, wp, (B, H, W), Cin, 1, 1, scale=dev(s), next_clip=2.5, next_bits=5)
+    torch.cuda.synchronize()
+    want = _zero_padded_im2col_gemm(a, w, 3, 1, 1)
+    lv, _ = oracle.quantize(oracle.scale(want, s), 2.5, 5)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    assert np.array_equal(planes_to_numpy(nxt), oracle.pack_planes(lv.reshape(-1, Cout), 5))
+    assert len(np.unique(lv)) == 32
+    with pytest.raises(qnn.QnnError) as e:       # planes only: nowhere to keep the running sum
+        qnn.qnn_conv2d(ap, wp, (B, H, W), Cin, 1, 1, scale=dev(s), want_acc=False, next_clip=2.5, next_bits=5)
+    assert e.value.code == -2
 
 
 @pytest.mark.parametrize("geom", [(2, 9, 9, 64, 64, 3, 1, 1), (1, 10, 10, 32, 100, 3, 2, 1),
