@@ -133,3 +133,22 @@ def test_config2_full_size_sampled(w_bits, a_bits):
     assert np.abs(acc).max() <= size * top
     np.testing.assert_allclose(out[rsel], oracle.scale(acc[rsel], c["scale"]), rtol=RTOL, atol=0)
     assert np.array_equal(out, acc.astype(np.float32) * c["scale"][None, :])
+
+
+@pytest.mark.parametrize("bits", [(5, 5), (7, 6)])
+def test_full_size_wide_bits_sampled(bits):
+    # 4096^3 above 4 bits (four chunk-pair launches), checked like the sweep configurations
+    w_bits, a_bits = bits
+    size = 4096
+    c = wl.gemm_square(w_bits, a_bits, size)
+    a, w = c["a"], c["w"]
+    acc, out = qnn.qnn_binary_gemm(pack_levels(a, a_bits), pack_levels(w, w_bits), size, scale=dev(c["scale"]))
+    torch.cuda.synchronize()
+    acc = acc.cpu().numpy()
+    gen = np.random.default_rng(w_bits * 10 + a_bits)
+    rsel = np.concatenate([[0, size - 1], gen.integers(0, size, 4)])
+    csel = np.concatenate([[0, size - 1], gen.integers(0, size, 4)])
+    assert np.array_equal(acc[rsel], oracle.gemm(a[rsel], w))
+    assert np.array_equal(acc[:, csel], oracle.gemm(a, w[csel]))
+    assert np.all((acc & 1) == 0)
+    assert np.array_equal(out.cpu().numpy(), acc.astype(np.float32) * c["scale"][None, :])
