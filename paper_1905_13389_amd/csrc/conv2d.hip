@@ -423,15 +423,9 @@ template <typename K> static int resident_workgroups(K kernel, size_t dyn_smem)
 // Lane tile of the convolution kernel per (w_bits, a_bits).  The kernel carries more live state
 // than the GEMM (pixel coordinates, the prefetched chunk across the epilogue), so its tiles are
 // smaller; the column tile stays a multiple of 32 because the fused epilogue packs whole words.
-#ifdef QNN_CONV_TILE_OVERRIDE
-template <int WB, int AB> struct ConvPick {
-    static constexpr int TM = QNN_CONV_TM, TN = QNN_CONV_TN, KV = QNN_CONV_KV;
-};
-#else
 template <int WB, int AB> struct ConvPick {
     static constexpr int TM = 4, TN = (WB + AB >= 7 ? 2 : 4), KV = (WB + AB >= 6 ? 2 : 4);
 };
-#endif
 
 template <int WB, int AB, int VW> static int launch_conv_vw(ConvTileParams p, hipStream_t st)
 {

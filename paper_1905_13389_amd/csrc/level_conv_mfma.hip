@@ -420,9 +420,6 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
     p.next_half_top = (float)p.next_top * 0.5f;
     p.next_inv_clip = next_levels ? 1.0f / next_clip : 0.0f;
     hipStream_t st = static_cast<hipStream_t>(stream);
-#ifdef QNN_MFMA_CONV_FORCE_TILE
-    return launch_level_conv<QNN_MFMA_CONV_FORCE_TILE>(p, st);
-#endif
     // Block shape (measured per layer shape of the two stacks): 512 x 64 for up to 64 output channels;
     // 256 x 256 (one workgroup per CU) when its workgroups fill at least three quarters of the CU
     // rounds they take; otherwise 128 x 128 with four waves, two workgroups per CU.
