@@ -199,7 +199,7 @@ int qnn_level_gemm_fp4(const uint8_t *a_levels, const uint8_t *w_levels, int64_t
  *     fused epilogue out -> qnn_encode_levels_i8(out, clip = next_clip, bits = next_bits).
  *     Taps outside the image contribute exactly 0.  desc->a_bits / w_bits (1..7) bound the levels for
  *     the int32 range check only.  QNN_ERR_UNSUPPORTED unless Cin is a multiple of 16, kh * kw <= 31
- *     and kh * kw * Cin <= 32768; QNN_ERR_RANGE when a tensor needs more than 32-bit byte offsets.
+ *     and kh * kw * Cin <= 16384; QNN_ERR_RANGE when a tensor needs more than 32-bit byte offsets.
  */
 int qnn_encode_levels_i8(const void *src, int dtype, int64_t count, float clip, int bits, int8_t *levels,
                          void *stream);

@@ -80,7 +80,7 @@ template <bool BF16> __global__ __launch_bounds__(256) void encode_levels_kernel
 
 // ---------------------------------------------------------------------------------------------
 // Implicit-GEMM convolution.  Rows = output pixels (b, oy, ox flattened, NHWC), columns = output
-// channels, reduction axis = (ky, kx, ci) in bytes, nk = kh kw Cin, cut into stages of kKB = 128
+// channels, reduction axis = (ky, kx, ci) in bytes, nk = kh kw Cin, cut into stages of 128 (or 64)
 // bytes.  A workgroup (WM x WN waves) owns an MB x NB block; stages go through a
 // ring of two LDS buffers filled by direct global -> LDS loads of 16 bytes per lane.  A lane's 16
 // bytes never straddle a tap because Cin is a multiple of 16: the lane looks up (tap, byte offset
@@ -88,14 +88,14 @@ template <bool BF16> __global__ __launch_bounds__(256) void encode_levels_kernel
 // against the pixel's bit mask of taps that fall outside the image, and loads either the 16 levels
 // or 16 zero bytes: a level of 0 contributes exactly 0, which is the zero padding of the decoded
 // integers.  Units past the end of the reduction axis are zero the same way, in both operands.
-// LDS rows are 128 bytes apart, the 16-byte unit q of row r is stored at position q ^ (r mod 8), so
-// the operand reads of 8 consecutive rows hit all 32 banks.  The k order inside an MFMA operand is
+// LDS rows are one stage length apart (U = 8 or 4 units of 16 bytes), the unit q of row r is stored at
+// position q ^ ((r / (8 / U)) mod U), so the operand reads of 8 consecutive rows hit all 32 banks.  The k order inside an MFMA operand is
 // the same for both operands, which is all a dot product needs.
 // Epilogue: int32 acc and / or fp32 acc * scale[c] stored from the MFMA layout; the next layer's
 // levels (scale, quantize, 2u - top) are transposed through LDS and stored 16 channels per lane.
 // ---------------------------------------------------------------------------------------------
-constexpr int kKB = 128, kRing = 2, kSteps = kKB / 32, kUnits = kKB / 16;
-constexpr int kMaxUnits = 2048; // table entries: reduction axis up to 32 KiB (e.g. 5 x 5 x 1024)
+constexpr int kRing = 2;
+constexpr int kMaxUnits = 1024; // table entries: reduction axis up to 16 KiB (e.g. 3 x 3 x 1024, 5 x 5 x 512)
 constexpr int kMaxMfmaTaps = 31; // tap 31 marks units past the end of the reduction axis
 
 __device__ __attribute__((aligned(256))) uint8_t g_zero_units[256]; // zero-initialised, read only
@@ -118,15 +118,20 @@ struct LevelConvParams {
 
 #define QNN_CONV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
 
-template <int MB, int NB, int WM, int WN>
+// KB: stage length in bytes of the reduction axis, 128 or 64 (short reductions: more, smaller
+// workgroups per CU, no half-empty last stage at kh kw Cin = 576)
+template <int MB, int NB, int WM, int WN, int KB>
 __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConvParams p)
 {
+    constexpr int kKB = KB, kSteps = KB / 32, kUnits = KB / 16; // k steps of 32 bytes, 16-byte units per row
+    constexpr int kRowsPerLoad = 1024 / KB;                      // LDS rows one wave-wide 1 KiB load fills
+    static_assert(KB == 128 || KB == 64, "stage length");
     constexpr int kWaves = WM * WN, kConvThreads = 64 * kWaves;
     constexpr int TM = MB / WM / 32, TN = NB / WN / 32;  // MFMA tiles per wave
     constexpr int NM = TM * TN, NR = TM + TN;             // MFMAs and operand reads per k step
-    constexpr int LA = MB / (8 * kWaves), LW = NB / (8 * kWaves), L = LA + LW; // direct loads per lane and stage
+    constexpr int LA = MB / (kRowsPerLoad * kWaves), LW = NB / (kRowsPerLoad * kWaves), L = LA + LW; // direct loads per lane and stage
     constexpr int kStageBytes = (MB + NB) * kKB;
-    static_assert(MB % (8 * kWaves) == 0 && NB % (8 * kWaves) == 0 && TM >= 1 && TN >= 1, "tile shape");
+    static_assert(MB % (kRowsPerLoad * kWaves) == 0 && NB % (kRowsPerLoad * kWaves) == 0 && TM >= 1 && TN >= 1, "tile shape");
     static_assert(kRing * kStageBytes + kMaxUnits * 4 <= 160 * 1024, "LDS");
     static_assert(MB * NB <= kRing * kStageBytes, "level transpose fits the ring");
 
@@ -156,17 +161,19 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // Direct load j of this wave fills the 1 KiB LDS chunk j * kWaves + wave = 8 stage rows (stage rows
-    // 0..MB-1 are pixels, MB.. are output channels): loads j < LA gather activations, the others
-    // read weights.  Lane l delivers row l / 8, position l % 8, i.e. the unit q = (l % 8) ^ (l / 8) of
-    // the stage (chunks start at multiples of 8 rows), the same q for every load of the lane.
-    const int q = (lane & 7) ^ (lane >> 3);
+    // Direct load j of this wave fills the 1 KiB LDS chunk j * kWaves + wave = kRowsPerLoad stage rows
+    // (stage rows 0..MB-1 are pixels, MB.. are output channels): loads j < LA gather activations, the
+    // others read weights.  Lane l delivers row l / U, position l % U (U = kUnits), i.e. the unit
+    // q = (l % U) ^ swizzle(row) of the stage; chunks start at multiples of 8 rows, so the swizzle and
+    // with it q are the same for every load of the lane.
+    const int lrow = lane / kUnits;                                  // row inside the chunk
+    const int q = (lane % kUnits) ^ ((lrow / (8 / kUnits)) & (kUnits - 1));
     int a_off[LA];      // byte offset of the pixel's tap (0, 0) in the activation tensor (may be < 0)
     uint32_t a_mask[LA]; // bit t: tap t falls outside the image for this pixel; bit 31 always
     int w_off[LW];      // byte offset of the output channel's weights
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
-        const int row = (j * kWaves + wave) * 8 + (lane >> 3);
+        const int row = (j * kWaves + wave) * kRowsPerLoad + lrow;
         const int m = row0 + row < p.pixels ? row0 + row : p.pixels - 1;
         const int ox = m % p.Wo, t = m / p.Wo, oy = t % p.Ho, b = t / p.Ho;
         const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
@@ -180,10 +187,10 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     }
 #pragma unroll
     for (int j = 0; j < LW; ++j) {
-        const int col = ((LA + j) * kWaves + wave) * 8 + (lane >> 3) - MB;
+        const int col = ((LA + j) * kWaves + wave) * kRowsPerLoad + lrow - MB;
         w_off[j] = (col0 + col < p.Cout ? col0 + col : p.Cout - 1) * p.nk;
     }
-    const uint8_t *zero = g_zero_units + 16 * (lane & 7);
+    const uint8_t *zero = g_zero_units + 16 * (lane % kUnits);
 
     // load j of stage `stage` into ring buffer `buf`; `entry` = tap_table[8 stage + q]
     auto issue_one = [&](int stage, int buf, int j, uint32_t entry) {
@@ -202,7 +209,7 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
 
     // operand reads at k step ks: row = tile row + lane % 32, unit 2 ks + lane / 32, swizzled
     const int a_rd = (wm * 32 * TM + (lane & 31)) * kKB, b_rd = (MB + wn * 32 * TN + (lane & 31)) * kKB;
-    const int hi = lane >> 5, swz = lane & 7; // tile rows start at multiples of 32
+    const int hi = lane >> 5, swz = ((lane & 31) / (8 / kUnits)) & (kUnits - 1); // tile rows start at multiples of 32
     v4i af[2][TM], bf[2][TN];
     // operand read r of NR of k step ks into operand set b, in the order the MFMAs first need them
     auto read_one = [&](const uint8_t *st, int ks, int b, int r) {
@@ -326,12 +333,13 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     }
 }
 
-template <int MB, int NB, int WM, int WN> int launch_level_conv(LevelConvParams &p, hipStream_t st)
+template <int MB, int NB, int WM, int WN, int KB> int launch_level_conv(LevelConvParams &p, hipStream_t st)
 {
+    p.nstages = (int)ceil_div(p.nk, KB);
     const int64_t tiles_m = ceil_div(p.pixels, MB), tiles_n = ceil_div(p.Cout, NB);
     if (tiles_m * tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_conv2d_i8: too many tiles");
     p.tiles_n = (int)tiles_n;
-    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN),
+    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN, KB>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN),
                        0, st, p);
     return check_launch("qnn_level_conv2d_i8");
 }
@@ -391,7 +399,7 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
     if ((int64_t)d->kh * d->kw > kMaxMfmaTaps)
         return fail(QNN_ERR_UNSUPPORTED, "qnn_level_conv2d_i8: more than %d taps", kMaxMfmaTaps);
     const int64_t nk = (int64_t)d->kh * d->kw * d->Cin;
-    if (ceil_div(nk, kKB) * kUnits > kMaxUnits)
+    if (ceil_div(nk, 128) * 8 > kMaxUnits)
         return fail(QNN_ERR_UNSUPPORTED, "qnn_level_conv2d_i8: reduction axis of %lld bytes (limit %d)", (long long)nk,
                     kMaxUnits * 16);
     if (!acc_fits_int32(nk, d->w_bits, d->a_bits))
@@ -414,22 +422,23 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
     p.H = (int)d->H, p.W = (int)d->W, p.Cin = (int)d->Cin, p.Cout = (int)d->Cout, p.Ho = (int)Ho, p.Wo = (int)Wo;
     p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad;
     p.pixels = (int)(d->B * Ho * Wo);
-    p.nk = (int)nk, p.units = (int)(nk / 16), p.nstages = (int)ceil_div(nk, kKB);
+    p.nk = (int)nk, p.units = (int)(nk / 16), p.nstages = 0;
     p.tiles_n = 0;
     p.next_top = next_levels ? (1 << next_bits) - 1 : 0;
     p.next_half_top = (float)p.next_top * 0.5f;
     p.next_inv_clip = next_levels ? 1.0f / next_clip : 0.0f;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // Block shape (measured per layer shape of the two stacks): 512 x 64 for up to 64 output channels;
-    // 256 x 256 (one workgroup per CU) when its workgroups fill at least three quarters of the CU
-    // rounds they take; otherwise 128 x 128 with four waves, two workgroups per CU.
-    if (d->Cout <= 64) return launch_level_conv<512, 64, 8, 1>(p, st);
-    if (d->Cout > 128) {
-        int dev = 0, cus = 256;
-        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (cus < 1) cus = 256;
-        const int64_t tiles = ceil_div(p.pixels, 256) * ceil_div(d->Cout, 256);
-        if (4 * tiles >= 3 * ceil_div(tiles, cus) * cus) return launch_level_conv<256, 256, 2, 4>(p, st);
-    }
-    return launch_level_conv<128, 128, 2, 2>(p, st);
+    // Block shape and stage length, measured per layer shape of the two stacks: up to 128 output
+    // channels the reduction is short (576 .. 1152 bytes), so 64-byte stages with several small
+    // workgroups per CU hide each other's prologue and epilogue; above that 256 x 256 with 128-byte
+    // stages (one workgroup per CU) when its workgroups fill at least three quarters of the CU rounds
+    // they take, otherwise 128 x 128 with four waves, two workgroups per CU.
+    if (d->Cout <= 64) return launch_level_conv<256, 64, 4, 1, 64>(p, st);
+    if (d->Cout <= 128) return launch_level_conv<256, 128, 4, 2, 64>(p, st);
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus < 1) cus = 256;
+    const int64_t tiles = ceil_div(p.pixels, 256) * ceil_div(d->Cout, 256);
+    if (4 * tiles >= 3 * ceil_div(tiles, cus) * cus) return launch_level_conv<256, 256, 2, 4, 128>(p, st);
+    return launch_level_conv<128, 128, 2, 2, 128>(p, st);
 }

@@ -153,7 +153,7 @@ def test_matrix_core_variant_argument_errors(qnn):
     assert conv(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 8, 2)) == qnn.QNN_ERR_INVALID_ARG   # 8-bit levels
     assert conv(D(1, 8, 8, 24, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED   # Cin % 16
     assert conv(D(1, 8, 8, 64, 64, 7, 7, 1, 3, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED   # 49 taps
-    assert conv(D(1, 8, 8, 4096, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED  # reduction > 32 KiB
+    assert conv(D(1, 8, 8, 4096, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED  # reduction > 16 KiB
     assert conv(D(1 << 20, 64, 64, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_RANGE  # 32-bit offsets
     assert conv(ok, acc=None) == qnn.QNN_ERR_INVALID_ARG
     assert conv(ok, scale=FAKE, nxt=FAKE, clip=1.0, nbits=8) == qnn.QNN_ERR_INVALID_ARG
