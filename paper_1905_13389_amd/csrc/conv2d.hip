@@ -12,6 +12,7 @@
 #include "bdot_tile.h"
 #include "qnn_host.h"
 #include "quantize.h"
+#include "fastdiv.h"
 
 namespace qnn {
 
@@ -19,22 +20,6 @@ constexpr int kMaxGroups = 1024; // reduction words (or word groups) addressable
 constexpr int kMaxTaps = 32;      // tap sets are 32-bit masks
 constexpr int kMaxOutExtent = 2048; // Ho + Wo entries of the border-mask tables
 constexpr int kConvKB = 20; // an LDS stage holds up to 20 reduction words per row and plane
-
-// n / d for n < 2^31 and a divisor fixed per launch: q = (mulhi(n, mul) + n) >> shift.
-struct FastDiv {
-    uint32_t mul, shift, d;
-};
-static FastDiv make_fastdiv(uint32_t d)
-{
-    uint32_t l = 0;
-    while (((uint64_t)1 << l) < d) ++l;
-    FastDiv f;
-    f.shift = l;
-    f.mul = (uint32_t)(((((uint64_t)1) << 32) * ((((uint64_t)1) << l) - d)) / d + 1);
-    f.d = d;
-    return f;
-}
-__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) { return (__umulhi(n, f.mul) + n) >> f.shift; }
 
 // Everything the plain kernel needs (64-bit sizes).
 struct ConvParams {

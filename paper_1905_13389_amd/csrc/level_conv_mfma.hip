@@ -8,6 +8,7 @@
 // be compared with it.
 #include "qnn_host.h"
 #include "quantize.h"
+#include "fastdiv.h"
 #include <type_traits>
 
 namespace qnn {
@@ -112,6 +113,8 @@ struct LevelConvParams {
     int units;   // nk / 16
     int nstages; // ceil(nk / 128)
     int tiles_n;
+    FastDiv div_howo, div_wo, div_cin, div_kw; // pixel -> (b, oy, ox); byte of the reduction axis -> (tap, c) -> (ky, kx)
+    uint32_t row_taps, col_taps;               // bit masks of the taps of kernel row 0 / kernel column 0
     float next_inv_clip, next_half_top;
     int next_top;
 };
@@ -146,8 +149,8 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     for (int u = tid; u < p.nstages * kUnits; u += kConvThreads) {
         uint32_t e = (uint32_t)kMaxMfmaTaps << 24;
         if (u < p.units) {
-            const int kb = 16 * u, tap = kb / p.Cin, c = kb - tap * p.Cin;
-            const int ky = tap / p.kw, kx = tap - ky * p.kw;
+            const int kb = 16 * u, tap = (int)fdiv((uint32_t)kb, p.div_cin), c = kb - tap * p.Cin;
+            const int ky = (int)fdiv((uint32_t)tap, p.div_kw), kx = tap - ky * p.kw;
             e = ((uint32_t)tap << 24) | (uint32_t)((ky * p.W + kx) * p.Cin + c);
         }
         tap_table[u] = e;
@@ -175,14 +178,16 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     for (int j = 0; j < LA; ++j) {
         const int row = (j * kWaves + wave) * kRowsPerLoad + lrow;
         const int m = row0 + row < p.pixels ? row0 + row : p.pixels - 1;
-        const int ox = m % p.Wo, t = m / p.Wo, oy = t % p.Ho, b = t / p.Ho;
+        const int b = (int)fdiv((uint32_t)m, p.div_howo), rem = m - b * (int)p.div_howo.d;
+        const int oy = (int)fdiv((uint32_t)rem, p.div_wo), ox = rem - oy * p.Wo;
         const int iy0 = oy * p.stride - p.pad, ix0 = ox * p.stride - p.pad;
         a_off[j] = ((b * p.H + iy0) * p.W + ix0) * p.Cin;
+        // whole kernel rows / columns that fall outside the image
         uint32_t mask = 1u << kMaxMfmaTaps;
         for (int ky = 0; ky < p.kh; ++ky)
-            for (int kx = 0; kx < p.kw; ++kx)
-                if ((unsigned)(iy0 + ky) >= (unsigned)p.H || (unsigned)(ix0 + kx) >= (unsigned)p.W)
-                    mask |= 1u << (ky * p.kw + kx);
+            if ((unsigned)(iy0 + ky) >= (unsigned)p.H) mask |= p.row_taps << (ky * p.kw);
+        for (int kx = 0; kx < p.kw; ++kx)
+            if ((unsigned)(ix0 + kx) >= (unsigned)p.W) mask |= p.col_taps << kx;
         a_mask[j] = mask;
     }
 #pragma unroll
@@ -424,6 +429,11 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
     p.pixels = (int)(d->B * Ho * Wo);
     p.nk = (int)nk, p.units = (int)(nk / 16), p.nstages = 0;
     p.tiles_n = 0;
+    p.div_howo = make_fastdiv((uint32_t)(Ho * Wo)), p.div_wo = make_fastdiv((uint32_t)Wo);
+    p.div_cin = make_fastdiv((uint32_t)d->Cin), p.div_kw = make_fastdiv((uint32_t)d->kw);
+    p.row_taps = (1u << d->kw) - 1u;
+    p.col_taps = 0;
+    for (int ky = 0; ky < d->kh; ++ky) p.col_taps |= 1u << (ky * d->kw);
     p.next_top = next_levels ? (1 << next_bits) - 1 : 0;
     p.next_half_top = (float)p.next_top * 0.5f;
     p.next_inv_clip = next_levels ? 1.0f / next_clip : 0.0f;
