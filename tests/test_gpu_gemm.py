@@ -152,3 +152,27 @@ def test_full_size_wide_bits_sampled(bits):
     assert np.array_equal(acc[:, csel], oracle.gemm(a, w[csel]))
     assert np.all((acc & 1) == 0)
     assert np.array_equal(out.cpu().numpy(), acc.astype(np.float32) * c["scale"][None, :])
+
+
+@pytest.mark.parametrize("case", [(1, 1, (1 << 24) + 37), (2, 2, (1 << 22) + 5), (4, 4, 9544371)])
+def test_longest_reductions(case):
+    # reduction lengths near the int32 limit of each width (4 x 4 bit: n 225 < 2^31 -> n <= 9544371),
+    # ragged against the 32-bit words; a few rows and columns only
+    w_bits, a_bits, n = case
+    gen = np.random.default_rng(n % 1000)
+    a, w = levels(gen, (3, n), a_bits), levels(gen, (5, n), w_bits)
+    a[0] = (1 << a_bits) - 1                      # a row at the positive extreme
+    w[0] = (1 << w_bits) - 1
+    w[1] = -((1 << w_bits) - 1)
+    ap, wp = pack_levels(a, a_bits), pack_levels(w, w_bits)
+    acc, _ = qnn.qnn_binary_gemm(ap, wp, n)
+    torch.cuda.synchronize()
+    want = oracle.gemm(a, w)
+    top = ((1 << a_bits) - 1) * ((1 << w_bits) - 1)
+    assert want[0, 0] == n * top and want[0, 1] == -n * top
+    assert np.array_equal(acc.cpu().numpy(), want)
+    if w_bits == 4:
+        assert (n + 1 + 31) // 32 == (n + 31) // 32       # same planes, one element more than int32 allows
+        with pytest.raises(qnn.QnnError) as e:
+            qnn.qnn_binary_gemm(ap, wp, n + 1)
+        assert e.value.code == -4

@@ -132,3 +132,18 @@ def test_fp4_full_size_matches_int8_route():
     assert torch.equal(acc4, acc8) and torch.equal(out4, out8)
     rows = [0, 1, 2047, 4095]
     assert np.array_equal(acc4[rows].cpu().numpy(), oracle.gemm(c["a"][rows], c["w"]))
+
+
+def test_level_gemm_i8_longest_reduction():
+    # 7-bit levels at the largest n the int32 accumulator allows: 127^2 n < 2^31
+    n = (2 ** 31 - 1) // (127 * 127)
+    gen = np.random.default_rng(1)
+    a, w = levels(gen, (3, n), 7), levels(gen, (4, n), 7)
+    a[0], w[0], w[1] = 127, 127, -127
+    a8 = qnn.qnn_plane_sum_i8(pack_levels(a, 7), n)
+    w8 = qnn.qnn_plane_sum_i8(pack_levels(w, 7), n)
+    acc, _ = qnn.qnn_level_gemm_i8(a8, w8, n)
+    torch.cuda.synchronize()
+    want = oracle.gemm(a, w)
+    assert want[0, 0] == n * 127 * 127 and want[0, 1] == -n * 127 * 127
+    assert np.array_equal(acc.cpu().numpy(), want)
