@@ -69,7 +69,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "conv3", "stack4", "stack5", "pool"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "pool"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -226,6 +226,48 @@ def conv_workload(args):
                                       "note": "whole step, not a single kernel"}}}))
 
 
+def fc_workload(args):
+    """Config 1: one FC layer, 2 x 2 bit, A [64][512] x W [256][512]: 6.7e7 binary operations, far too
+    little to load the chip -- the figure of interest is the latency of the two launches."""
+    import torch
+    import qnn_workloads as wl
+    from paper_1905_13389_amd import qnn
+
+    c = wl.fc_2x2()
+    d_a = torch.from_numpy(c["a"]).cuda()
+    w_planes = qnn.qnn_encode_pack(torch.from_numpy(c["w"]).cuda(), 1.0, 2)
+    d_scale = torch.from_numpy(c["scale"]).cuda()
+    a_planes = torch.empty((2, 64, 16), dtype=torch.int32, device="cuda")
+    acc = torch.empty((64, 256), dtype=torch.int32, device="cuda")
+    out = torch.empty((64, 256), dtype=torch.float32, device="cuda")
+
+    def step():
+        qnn.qnn_encode_pack(d_a, 1.0, 2, planes=a_planes)
+        qnn.qnn_binary_gemm(a_planes, w_planes, 512, acc=acc, scale=d_scale, out=out)
+
+    steps = max(args.steps, 200)
+    for _ in range(max(args.warmup, 20)):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    ops = 2.0 * 64 * 256 * 512 * 4
+    tops = ops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "effective binary TOPS (xnor+popcount), 1 MI355X", "value": round(tops, 4), "unit": "binary TOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 20), "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+        "config": {"workload": "FC 64x512 -> 256, w_bits=2 a_bits=2, int8 levels packed on device",
+                   "step": "qnn_encode_pack + qnn_binary_gemm (fused scale)"},
+        "roofline": {"bound": "alu", "achieved": round(tops, 4), "peak": round(PEAK_BINARY_TOPS, 1),
+                     "unit": "binary TOP/s", "frac": round(tops / PEAK_BINARY_TOPS, 6), "traffic": None,
+                     "note": "launch / latency bound: 0.04 us of VALU work per step"}}))
+
+
 def pool_workload(args):
     """2x2 stride-2 max-pooling on the 4-bit planes of the detection stack's first resolution change
     (batch 32, 300x300x64 -> 150x150x64): a streaming kernel, bound by HBM."""
@@ -269,6 +311,8 @@ def main():
         sys.exit(2)
     if args.workload == "pool":
         return pool_workload(args)
+    if args.workload == "fc1":
+        return fc_workload(args)
     if args.workload != "gemm":
         return conv_workload(args)
 
