@@ -99,24 +99,72 @@ __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2,
         __syncthreads();
     }
 
+    // Epilogue.  The recombined accumulators go through LDS once so that the stores run row-major:
+    // a lane owns 4 consecutive columns of one row (16-byte acc / out stores, 16 B x BN / 4 lanes =
+    // whole 256- or 512-byte row pieces per wave) instead of 64-byte pieces of 4 rows.  The stage
+    // buffers are free (the loop ends with a barrier); when they cannot hold the whole block the rows
+    // go through in rounds of 16 IPR.
+    constexpr int EPI_STRIDE = T::BN + 16;
+    constexpr int IPR = (2 * T::STAGE_WORDS) / (16 * EPI_STRIDE) < TM ? (2 * T::STAGE_WORDS) / (16 * EPI_STRIDE) : TM;
+    static_assert(IPR >= 1, "the stage buffers hold at least 16 rows of the block");
+    constexpr int LPR = T::BN / 4;            // lanes per row
+    constexpr int RPP = kTileThreads / LPR;   // rows per pass
+    static_assert((16 * IPR) % RPP == 0 || RPP > 16 * IPR, "passes cover whole rounds");
+    int32_t *V = reinterpret_cast<int32_t *>(&smem[0][0]);
+    const int c4 = (tid % LPR) * 4;
+    const int64_t cidx = col0 + c4;
+    const bool cols4 = cidx + 3 < p.cols && (p.cols & 3) == 0; // 16-byte accesses are whole and aligned
+    float sc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (p.out && !p.partial_out) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int64_t r = row0 + ty + 16 * i;
-        if (r >= p.rows) continue;
+        for (int e = 0; e < 4; ++e)
+            if (cidx + e < p.cols) sc[e] = p.scale[cidx + e];
+    }
 #pragma unroll
-        for (int n = 0; n < TN; ++n) {
-            const int64_t cidx = col0 + tx + 16 * n;
-            if (cidx >= p.cols) continue;
-            int32_t v = recombine<T::S>(P[i][n], p.n_times_top);
+    for (int i0 = 0; i0 < TM; i0 += IPR) {
+        if (i0 > 0) __syncthreads(); // the previous round's rows have been read
+#pragma unroll
+        for (int i = i0; i < i0 + IPR && i < TM; ++i)
+#pragma unroll
+            for (int n = 0; n < TN; ++n)
+                V[((i - i0) * 16 + ty) * EPI_STRIDE + tx + 16 * n] = recombine<T::S>(P[i][n], p.n_times_top);
+        __syncthreads();
+        constexpr int kRoundRows = 16 * IPR;
+#pragma unroll 1
+        for (int rl = tid / LPR; rl < kRoundRows && i0 + rl / 16 < TM; rl += RPP) {
+            const int64_t r = row0 + (rl % 16) + 16 * (i0 + rl / 16);
+            if (r >= p.rows || cidx >= p.cols) continue;
+            const int4 vv = *reinterpret_cast<const int4 *>(V + rl * EPI_STRIDE + c4);
+            int32_t v[4] = {vv.x, vv.y, vv.z, vv.w};
             const int64_t o = r * p.cols + cidx;
-            v = (int32_t)((uint32_t)v << p.shift);
-            if (p.partial_in) v += p.partial_in[o];
-            if (p.partial_out) {
-                p.partial_out[o] = v;
-                continue;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (int32_t)((uint32_t)v[e] << p.shift);
+            if (cols4) {
+                if (p.partial_in) {
+                    const int4 q = *reinterpret_cast<const int4 *>(p.partial_in + o);
+                    v[0] += q.x, v[1] += q.y, v[2] += q.z, v[3] += q.w;
+                }
+                if (p.partial_out) {
+                    *reinterpret_cast<int4 *>(p.partial_out + o) = make_int4(v[0], v[1], v[2], v[3]);
+                    continue;
+                }
+                if (p.acc) *reinterpret_cast<int4 *>(p.acc + o) = make_int4(v[0], v[1], v[2], v[3]);
+                if (p.out)
+                    *reinterpret_cast<float4 *>(p.out + o) =
+                        make_float4((float)v[0] * sc[0], (float)v[1] * sc[1], (float)v[2] * sc[2], (float)v[3] * sc[3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (cidx + e >= p.cols) continue;
+                    if (p.partial_in) v[e] += p.partial_in[o + e];
+                    if (p.partial_out) {
+                        p.partial_out[o + e] = v[e];
+                        continue;
+                    }
+                    if (p.acc) p.acc[o + e] = v[e];
+                    if (p.out) p.out[o + e] = (float)v[e] * sc[e];
+                }
             }
-            if (p.acc) p.acc[o] = v;
-            if (p.out) p.out[o] = (float)v * p.scale[cidx];
         }
     }
 }
