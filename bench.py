@@ -36,7 +36,7 @@ NOMINAL_BINARY_TOPS = SIMDS * 16 * CLOCK_HZ * 32 / 1e12
 
 # HBM bytes of one default-workload GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/bgemm_2x2_4096_hbm_counters.txt); only valid for size 4096, 2x2 bit
-GEMM_2X2_4096_TRAFFIC_BYTES = 183.8e6
+GEMM_2X2_4096_TRAFFIC_BYTES = 182.7e6
 
 
 def valu_probe(qnn, torch):
