@@ -109,7 +109,9 @@ __device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
 // one lane owns 4 consecutive channels of one pixel (16-byte loads / stores of acc, scale, out),
 // rolled over the rows of the tile, and the next layer's plane words are assembled from 8 lanes'
 // nibbles with three DPP ORs.
-template <int WB, int AB, int TM, int TN, int KV, int VW>
+// KEEPW: the reduction fits one stage (nchunks == 1) and the weight stage is written to LDS once per
+// workgroup instead of once per row tile; the two stage buffers then hold activations only.
+template <int WB, int AB, int TM, int TN, int KV, int VW, bool KEEPW>
 __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 bconv_tile_kernel(ConvTileParams p)
 {
@@ -118,8 +120,12 @@ bconv_tile_kernel(ConvTileParams p)
     constexpr int BN = T::BN, BM = T::BM;
     constexpr int EPI_STRIDE = BN + 16; // the 4 rows a wave writes at once land in 4 different bank groups
     constexpr int EPI_WORDS = BM * EPI_STRIDE;
-    constexpr int STAGE_ALLOC = T::STAGE_WORDS > EPI_WORDS ? T::STAGE_WORDS : EPI_WORDS;
+    // with the weights resident elsewhere a stage buffer holds activations only
+    constexpr int STAGE_NEED = KEEPW ? T::A_WORDS : T::STAGE_WORDS;
+    constexpr int STAGE_ALLOC = STAGE_NEED > EPI_WORDS ? STAGE_NEED : EPI_WORDS;
     __shared__ __attribute__((aligned(16))) uint32_t smem[2][STAGE_ALLOC];
+    constexpr int W_WORDS = T::STAGE_WORDS - T::A_WORDS;
+    __shared__ __attribute__((aligned(16))) uint32_t w_resident[KEEPW ? W_WORDS : 4];
     __shared__ uint32_t tap_table[kMaxGroups];
     extern __shared__ __attribute__((aligned(16))) int32_t dyn_smem[];
     int32_t *S = dyn_smem;                                                   // [taps][BN]
@@ -190,12 +196,15 @@ bconv_tile_kernel(ConvTileParams p)
     };
 
     uint4 ra[T::A_PER_THREAD], rw[T::W_PER_THREAD];
+    constexpr bool keep_w = KEEPW;
+    bool w_staged = false;
     auto fetch = [&](int k0) {
 #pragma unroll
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int q = (tid + u * kTileThreads) % UQ;
             ra[u] = gather4<VW>(p.a, tap_table, 4 * q < p.kb ? p.nw : 0, apad[u], abase[u], k0 + 4 * q);
         }
+        if (w_staged) return;
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
@@ -206,13 +215,15 @@ bconv_tile_kernel(ConvTileParams p)
         }
     };
     auto stash = [&](int buf) {
-        uint32_t *As = smem[buf], *Ws = smem[buf] + T::A_WORDS;
+        uint32_t *As = smem[buf], *Ws = keep_w ? w_resident : smem[buf] + T::A_WORDS;
 #pragma unroll
         for (int u = 0; u < T::A_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
             if (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS)
                 lds_write_unit<KV>(As + (idx / UQ) * T::BKP + 4 * (idx % UQ), ra[u]);
         }
+        if (w_staged) return;
+        w_staged = keep_w;
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
             const int idx = tid + u * kTileThreads;
@@ -262,7 +273,7 @@ bconv_tile_kernel(ConvTileParams p)
             }
             const int left = p.nw - c * p.kb;
             const int nkq = ((left < p.kb ? left : p.kb) + KV - 1) / KV;
-            tile_mac<WB, AB, TM, TN, KV, kConvKB>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P);
+            tile_mac<WB, AB, TM, TN, KV, kConvKB>(smem[buf], keep_w ? w_resident : smem[buf] + T::A_WORDS, ty, tx, nkq, P);
             if (more || next_tile) stash(buf ^ 1);
             __syncthreads();
             buf ^= 1;
@@ -418,7 +429,6 @@ template <int WB, int AB, int VW> static int launch_conv_vw(ConvTileParams p, hi
     constexpr int TN = G::TN;
     static_assert(TN % 2 == 0, "column tile must be a multiple of 32");
     using T = Tile<WB, AB, G::TM, TN, G::KV, kConvKB>;
-    auto kernel = bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW>;
     const size_t dyn = ((size_t)T::BN * p.kh * p.kw + p.Ho + p.Wo) * sizeof(int32_t);
     p.tiles_m = (int)ceil_div(p.M, T::BM);
     p.tiles_n = (int)ceil_div(p.Cout, T::BN);
@@ -432,16 +442,20 @@ template <int WB, int AB, int VW> static int launch_conv_vw(ConvTileParams p, hi
     }
     p.kb = best_kb;
     p.nchunks = (int)ceil_div(p.nw, best_kb);
-    int slots = resident_workgroups(kernel, dyn);
-    if (slots <= 0) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: occupancy query failed");
-    // every workgroup owns one column tile; the row tiles are dealt round-robin to the
-    // slots / tiles_n workgroups of that column
-    int groups = slots / p.tiles_n;
-    if (groups < 1) groups = 1;
-    if (groups > p.tiles_m) groups = p.tiles_m;
-    p.row_tile_step = groups;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n)), dim3(kTileThreads), dyn, st, p);
-    return QNN_OK;
+    auto launch = [&](auto kernel) {
+        int slots = resident_workgroups(kernel, dyn);
+        if (slots <= 0) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: occupancy query failed");
+        // every workgroup owns one column tile; the row tiles are dealt round-robin to the
+        // slots / tiles_n workgroups of that column
+        int groups = slots / p.tiles_n;
+        if (groups < 1) groups = 1;
+        if (groups > p.tiles_m) groups = p.tiles_m;
+        p.row_tile_step = groups;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n)), dim3(kTileThreads), dyn, st, p);
+        return (int)QNN_OK;
+    };
+    if (p.nchunks == 1) return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, true>);
+    return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, false>);
 }
 
 template <int WB, int AB> static int launch_conv(const ConvTileParams &p, hipStream_t st)
