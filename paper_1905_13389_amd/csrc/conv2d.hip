@@ -405,7 +405,8 @@ __global__ __launch_bounds__(256) void bconv_plain_kernel(ConvParams p, int w_bi
     if (p.out) p.out[idx] = (float)v * p.scale[c];
 }
 
-// Workgroups resident on the whole chip for one kernel (occupancy x CU count), cached per kernel.
+// Workgroups resident on the whole chip for one kernel (occupancy x CU count); two host-side queries
+// per launch, negligible against the launch itself.
 template <typename K> static int resident_workgroups(K kernel, size_t dyn_smem)
 {
     int dev = 0, cus = 0, per_cu = 0;
