@@ -89,9 +89,10 @@ template <bool BF16> __global__ __launch_bounds__(256) void encode_levels_kernel
 // against the pixel's bit mask of taps that fall outside the image, and loads either the 16 levels
 // or 16 zero bytes: a level of 0 contributes exactly 0, which is the zero padding of the decoded
 // integers.  Units past the end of the reduction axis are zero the same way, in both operands.
-// LDS rows are one stage length apart (U = 8 or 4 units of 16 bytes), the unit q of row r is stored at
-// position q ^ ((r / (8 / U)) mod U), so the operand reads of 8 consecutive rows hit all 32 banks.  The k order inside an MFMA operand is
-// the same for both operands, which is all a dot product needs.
+// LDS rows are one stage length apart (U = 8 or 4 units of 16 bytes), the unit q of row r is stored
+// at position q ^ ((r / (8 / U)) mod U), so the operand reads of 8 consecutive rows hit all 32
+// banks.  The k order inside an MFMA operand is the same for both operands, which is all a dot
+// product needs.
 // Epilogue: int32 acc and / or fp32 acc * scale[c] stored from the MFMA layout; the next layer's
 // levels (scale, quantize, 2u - top) are transposed through LDS and stored 16 channels per lane.
 // ---------------------------------------------------------------------------------------------
@@ -111,7 +112,7 @@ struct LevelConvParams {
     int pixels;  // B Ho Wo
     int nk;      // kh kw Cin
     int units;   // nk / 16
-    int nstages; // ceil(nk / 128)
+    int nstages; // ceil(nk / stage length)
     int tiles_n;
     FastDiv div_howo, div_wo, div_cin, div_kw; // pixel -> (b, oy, ox); byte of the reduction axis -> (tap, c) -> (ky, kx)
     uint32_t row_taps, col_taps;               // bit masks of the taps of kernel row 0 / kernel column 0
