@@ -7,7 +7,9 @@ the GPU library never does and shares no code with it.
 Every function cites the passage of the paper it follows; the C file's header lists
 what pins each of them.  maxpool / pool_out_size are plain numpy here; their pins (the library
 pooling routine on the same integers, commutation with the quantizer, brute force) are in
-tests/test_oracle_pool.py.
+tests/test_oracle_pool.py.  block_epilogue / residual_trunk are numpy float32 here; their pins (the same
+sums in float64, the library's batch normalisation, Table 2's real values as the shortcut, the library's
+float64 convolution block by block) are in tests/test_oracle_block.py.
 """
 import ctypes
 import os
@@ -189,6 +191,68 @@ def conv_stack(x, layers):
         out = scale(acc, L["scale"])
         trace.append({"levels": lv, "acc": acc, "out": out})
         cur = out
+    return trace
+
+
+def block_epilogue(acc, scale_vec, bias=None, res_levels=None, res_scale=None, res_f32=None):
+    """What a residual block adds between the decoder's scale factor and the next quantizer (the
+    ResNet-18 of the experiments section has shortcuts and batch normalisation; the derivation itself
+    leaves the bias out): a per-channel shift -- a folded batch-norm -- and the shortcut term, either
+    quantized levels times one real factor or an fp32 tensor.  fp32 throughout, one rounding per step,
+    in this order:
+        y = (float)acc * scale[c];  y = y + bias[c];  y = y + ((float)res_level * res_scale);
+        y = y + res_f32.
+    numpy float32 array arithmetic is one IEEE single-precision operation per element per operator.
+    """
+    y = scale(acc, scale_vec)
+    if bias is not None:
+        b = np.ascontiguousarray(bias, dtype=np.float32)
+        assert b.shape == (y.shape[-1],)
+        y = y + b
+    if res_levels is not None:
+        lv = np.asarray(res_levels)
+        assert lv.shape == y.shape
+        y = y + lv.astype(np.float32) * np.float32(res_scale)
+    if res_f32 is not None:
+        r = np.asarray(res_f32)
+        assert r.dtype == np.float32 and r.shape == y.shape
+        y = y + r
+    assert y.dtype == np.float32
+    return y
+
+
+def residual_trunk(x, blocks):
+    """Chain of two-convolution residual blocks (the ResNet-18 shape of the experiments section) on
+    quantized layers.  x: float32 [B][H][W][C].  Each block: dict with conv1, conv2 and down (None or
+    a 1x1 convolution), every convolution a dict with w (int8 levels), scale, bias (float32 [Cout]),
+    stride, pad, clip (of the quantizer in front of it), a_bits.
+
+        a  = quantize(x, conv1.clip)                      block input, shared by conv1 and the shortcut
+        h  = epilogue(conv(a, conv1))                     scale + bias
+        hq = quantize(h, conv2.clip)
+        y  = epilogue(conv(hq, conv2), shortcut)          shortcut: a's levels times res_scale (identity
+                                                          block) or the fp32 output of down(a)
+    and y is the next block's x.  Returns per block {a, acc1, hq, acc2, accd, shortcut, y}.
+    """
+    trace = []
+    cur = np.ascontiguousarray(x, dtype=np.float32)
+    for blk in blocks:
+        c1, c2, dn = blk["conv1"], blk["conv2"], blk["down"]
+        assert 1 <= c1["a_bits"] <= 7 and 1 <= c2["a_bits"] <= 7
+        a, _ = quantize(cur, c1["clip"], c1["a_bits"])
+        acc1 = conv2d(a.astype(np.int8), c1["w"], c1["stride"], c1["pad"])
+        h = block_epilogue(acc1, c1["scale"], c1["bias"])
+        hq, _ = quantize(h, c2["clip"], c2["a_bits"])
+        acc2 = conv2d(hq.astype(np.int8), c2["w"], c2["stride"], c2["pad"])
+        if dn is None:
+            accd, shortcut = None, None
+            y = block_epilogue(acc2, c2["scale"], c2["bias"], res_levels=a, res_scale=blk["res_scale"])
+        else:
+            accd = conv2d(a.astype(np.int8), dn["w"], dn["stride"], dn["pad"])
+            shortcut = block_epilogue(accd, dn["scale"], dn["bias"])
+            y = block_epilogue(acc2, c2["scale"], c2["bias"], res_f32=shortcut)
+        trace.append({"a": a, "acc1": acc1, "hq": hq, "acc2": acc2, "accd": accd, "shortcut": shortcut, "y": y})
+        cur = y
     return trace
 
 

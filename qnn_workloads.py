@@ -177,3 +177,42 @@ def cifar_vgg_network(batch=8, bits=2, config_index=5, plan=CIFAR_VGG_PLAN):
                  "clip": float(clip), "a_bits": bits, "w_bits": bits, "n": n, "cout": cout}
         ops.append(L)
     return {"x": x, "ops": ops}
+
+
+# --------------------------------------------------------------------------- residual trunk
+RESNET18_BLOCKS = (
+    # (cin, cout, stride of the block's first convolution); a block whose shape changes takes its
+    # shortcut through a 1x1 convolution of the same stride, the others add their own input
+    (64, 64, 1), (64, 64, 1), (64, 128, 2), (128, 128, 1),
+    (128, 256, 2), (256, 256, 1), (256, 512, 2), (512, 512, 1),
+)
+
+
+def _block_conv(ci, t, cin, cout, k, bits, stride, clip, gain):
+    L = _stack_layer(rng(ci, 10 + 3 * t), rng(ci, 11 + 3 * t), cin, cout, bits, stride, clip)
+    if k == 1:
+        L["w"] = odd_levels(rng(ci, 10 + 3 * t), (cout, 1, 1, cin), bits)
+        L["scale"] = (L["scale"] * 3.0).astype(np.float32)      # a ninth of the taps
+        L["pad"] = 0
+    L["scale"] = (L["scale"] * np.float32(gain)).astype(np.float32)
+    L["bias"] = rng(ci, 12 + 3 * t).uniform(-0.2, 0.2, size=cout).astype(np.float32)
+    return L
+
+
+def resnet18_trunk(batch=256, hw=56, bits=3, config_index=6, plan=RESNET18_BLOCKS):
+    """The residual trunk of ResNet-18 (8 two-convolution blocks, 16 3x3 convolutions and 3 1x1
+    shortcut convolutions) on quantized layers, input at the stem's output shape.  Every convolution
+    has a per-channel scale and shift (a folded batch-norm); the second convolution of a block and
+    the shortcut each carry a gain of 0.7 so that their sum keeps unit variance block after block."""
+    x = rng(config_index, 0).standard_normal((batch, hw, hw, plan[0][0]), dtype=np.float32)
+    top = (1 << bits) - 1
+    blocks, t = [], 0
+    for cin, cout, stride in plan:
+        blk = {"conv1": _block_conv(config_index, t, cin, cout, 3, bits, stride, 3.0, 1.0),
+               "conv2": _block_conv(config_index, t + 1, cout, cout, 3, bits, 1, 3.0, 0.7),
+               "down": None, "res_scale": float(np.float32(0.7 * 3.0 / top))}
+        if stride != 1 or cin != cout:
+            blk["down"] = _block_conv(config_index, t + 2, cin, cout, 1, bits, stride, 3.0, 0.7)
+        t += 3
+        blocks.append(blk)
+    return {"x": x, "blocks": blocks}
