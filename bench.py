@@ -72,7 +72,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "pool"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "trunk", "pool"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -229,6 +229,112 @@ def conv_workload(args):
                                       "note": "whole step, not a single kernel"}}}))
 
 
+def trunk_workload(args):
+    """The residual trunk of ResNet-18 (8 blocks: 16 3x3 convolutions, 3 1x1 shortcut convolutions, bias
+    and shortcut terms fused into the epilogues), 3x3 bit, on both machine routes.  Between layers only
+    planes (or int8 levels) exist; the three 1x1 shortcuts are handed over in fp32."""
+    import torch
+    import qnn_workloads as wl
+    from paper_1905_13389_amd import qnn
+
+    bits = 3
+    net = wl.resnet18_trunk(batch=args.batch or 256, bits=bits)
+    x, blocks = net["x"], net["blocks"]
+    B, H0, W0, C0 = x.shape
+    d_x = torch.from_numpy(x).cuda()
+    up = lambda a: torch.from_numpy(a).cuda()
+    macs = 0
+
+    def build(route):
+        nonlocal macs
+        macs = 0
+        H, W, C = H0, W0, C0
+        if route == "planes":
+            new = lambda h, w, c: torch.empty((bits, B * h * w, (c + 31) // 32), dtype=torch.int32, device="cuda")
+            wt = lambda L, k: qnn.qnn_encode_pack(up(L["w"]), 1.0, bits).view(bits, L["cout"], k, k, -1)
+        else:
+            new = lambda h, w, c: torch.empty((B, h, w, c), dtype=torch.int8, device="cuda")
+            wt = lambda L, k: up(L["w"])
+        first = a = new(H, W, C)
+        calls = []
+        for bi, blk in enumerate(blocks):
+            c1, c2, dn = blk["conv1"], blk["conv2"], blk["down"]
+            st, cout = c1["stride"], c1["cout"]
+            Ho, Wo = (H + 2 - 3) // st + 1, (W + 2 - 3) // st + 1
+            last = bi + 1 == len(blocks)
+            hq = new(Ho, Wo, cout)
+            nxt = None if last else new(Ho, Wo, cout)
+            y = torch.empty((B, Ho, Wo, cout), dtype=torch.float32, device="cuda") if last else None
+            short = torch.empty((B, Ho, Wo, cout), dtype=torch.float32, device="cuda") if dn is not None else None
+            nclip = None if last else blocks[bi + 1]["conv1"]["clip"]
+            common = {"want_acc": False}
+            calls.append((a, wt(c1, 3), (B, H, W), C, st, 1, up(c1["scale"]),
+                          dict(common, bias=up(c1["bias"]), next_clip=c2["clip"], next_bits=bits), hq, None))
+            macs += B * Ho * Wo * cout * 9 * C
+            if dn is not None:
+                calls.append((a, wt(dn, 1), (B, H, W), C, st, 0, up(dn["scale"]),
+                              dict(common, bias=up(dn["bias"]), want_out=True), None, short))
+                macs += B * Ho * Wo * cout * C
+                res = {"res_f32": short}
+            elif route == "planes":
+                res = {"res_planes": a, "res_scale": blk["res_scale"]}
+            else:
+                res = {"res_levels": a, "res_bits": bits, "res_scale": blk["res_scale"]}
+            calls.append((hq, wt(c2, 3), (B, Ho, Wo), cout, 1, 1, up(c2["scale"]),
+                          dict(common, bias=up(c2["bias"]), want_out=last, next_clip=nclip,
+                               next_bits=0 if last else bits, **res), nxt, y))
+            macs += B * Ho * Wo * cout * 9 * cout
+            a, H, W, C = nxt, Ho, Wo, cout
+        return first, calls
+
+    p_first, p_calls = build("planes")
+    l_first, l_calls = build("levels")
+    clip0 = blocks[0]["conv1"]["clip"]
+
+    def step():
+        qnn.qnn_encode_pack(d_x, clip0, bits, planes=p_first)
+        for a, w, shape, cin, st, pad, sc, kw, nxt, out in p_calls:
+            qnn.qnn_conv2d_block(a, w, shape, cin, st, pad, sc, next_planes=nxt, out=out, **kw)
+
+    def mfma_step():
+        qnn.qnn_encode_levels_i8(d_x, clip0, bits, levels=l_first)
+        for a, w, shape, cin, st, pad, sc, kw, nxt, out in l_calls:
+            qnn.qnn_level_conv2d_block_i8(a, w, st, pad, bits, bits, sc, next_levels=nxt, out=out, **kw)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps * 1e3
+
+    ms, m_ms = timed(step), timed(mfma_step)
+    binops = 2.0 * macs * bits * bits
+    tops = binops / (ms * 1e-3) / 1e12
+    int8_tops = 2.0 * macs / (m_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "effective binary TOPS (xnor+popcount) and % of VALU/HBM roofline, 1 MI355X", "value": round(tops, 2),
+        "unit": "binary TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+        "config": {"workload": "residual trunk of ResNet-18 (16 3x3 + 3 1x1 convolutions, shortcuts and folded "
+                               "batch-norm shifts in the epilogues), batch %d, 3x3 bit" % B, "macs": macs,
+                   "step": "qnn_encode_pack + qnn_conv2d_block per convolution"},
+        "roofline": {"bound": "alu", "achieved": round(tops, 2), "peak": round(PEAK_BINARY_TOPS, 1),
+                     "unit": "binary TOP/s", "frac": round(tops / PEAK_BINARY_TOPS, 4), "traffic": None,
+                     "frac_of_16_lane_nominal": round(tops / NOMINAL_BINARY_TOPS, 4),
+                     "note": "whole step (encode + all conv launches), not a single kernel"},
+        "mfma_variant": {"step": "qnn_encode_levels_i8 + qnn_level_conv2d_block_i8 per convolution",
+                         "ms_per_step": round(m_ms, 4), "effective_binary_tops": round(binops / (m_ms * 1e-3) / 1e12, 1),
+                         "speedup_vs_xor_bitcount_step": round(ms / m_ms, 2),
+                         "roofline": {"bound": "mfma", "achieved": round(int8_tops, 1), "peak": 5000.0,
+                                      "unit": "int8 TOP/s", "frac": round(int8_tops / 5000.0, 4),
+                                      "note": "whole step, not a single kernel"}}}))
+
+
 def fc_workload(args):
     """Config 1: one FC layer, 2 x 2 bit, A [64][512] x W [256][512]: 6.7e7 binary operations, far too
     little to load the chip -- the figure of interest is the latency of the two launches."""
@@ -312,6 +418,8 @@ def main():
         print("bench.py: this build runs on one GPU only (the path shards by output rows with no "
               "exchange; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "trunk":
+        return trunk_workload(args)
     if args.workload == "pool":
         return pool_workload(args)
     if args.workload == "fc1":

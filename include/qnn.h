@@ -131,6 +131,36 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
                float next_clip, int next_bits, void *stream);
 
 /*
+ * qnn_conv2d_block -- qnn_conv2d with the terms a residual block puts between the scale factor and
+ * the next quantizer (the experiments section's ResNet-18 has shortcuts and batch normalisation; the
+ * derivation itself leaves the bias out).  With epi == NULL it is qnn_conv2d.  Otherwise, per output
+ * element, in fp32 with one rounding per step and in this order:
+ *     y = (float)acc * scale[c]
+ *     y = y + bias[c]                               if bias     (a folded batch-norm shift)
+ *     y = y + ((float)res_level * res_scale)        if res_q    (shortcut held as quantized codes)
+ *     y = y + res_f32[...]                          if res_f32  (shortcut held in fp32)
+ * `out` receives y and next_planes its codes; `acc` stays the integer product.
+ *   bias     DEVICE fp32 [Cout], or NULL
+ *   res_q    DEVICE bit-planes [res_bits][B][Ho][Wo][ceil(Cout/32)] (as qnn_encode_pack or a fused
+ *            epilogue writes them for a tensor of the output's shape), or NULL; level = 2 u - (2^res_bits - 1)
+ *            (Eq. 10); res_bits in [1,8]; res_scale finite: the real value of one level step, e.g.
+ *            clip / (2^res_bits - 1) for codes made with that clip
+ *   res_f32  DEVICE fp32 [B][Ho][Wo][Cout], or NULL
+ * All three 16-byte aligned; scale is required when epi is given.
+ */
+typedef struct qnn_block_epilogue {
+    const float *bias;
+    const void *res_q;
+    int32_t res_bits;
+    float res_scale;
+    const float *res_f32;
+} qnn_block_epilogue;
+
+int qnn_conv2d_block(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32_t *w_planes,
+                     const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                     uint32_t *next_planes, float next_clip, int next_bits, void *stream);
+
+/*
  * qnn_maxpool_planes / qnn_maxpool_levels_i8 -- max-pooling between quantized layers, taken on the
  * codes.  The linear quantizer (Table 1 range limit, Eq. 15) is monotone non-decreasing, so the
  * maximum of quantized values over a window equals the quantized maximum: pooling planes is exact.
@@ -206,6 +236,15 @@ int qnn_encode_levels_i8(const void *src, int dtype, int64_t count, float clip, 
 int qnn_level_conv2d_i8(const qnn_conv_desc *desc, const int8_t *a_levels, const int8_t *w_levels,
                         const float *scale, int32_t *acc, float *out, int8_t *next_levels,
                         float next_clip, int next_bits, void *stream);
+
+/*
+ * qnn_level_conv2d_block_i8 -- qnn_level_conv2d_i8 with the residual-block terms of qnn_conv2d_block
+ * (same steps, same order); here epi->res_q is DEVICE int8 levels [B][Ho][Wo][Cout] and res_bits only
+ * bounds them (1..7).
+ */
+int qnn_level_conv2d_block_i8(const qnn_conv_desc *desc, const int8_t *a_levels, const int8_t *w_levels,
+                              const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                              int8_t *next_levels, float next_clip, int next_bits, void *stream);
 
 /*
  * qnn_probe_valu -- measurement aid, not part of the hot path: launches `workgroups` workgroups

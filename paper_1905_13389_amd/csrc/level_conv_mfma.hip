@@ -9,6 +9,7 @@
 #include "qnn_host.h"
 #include "quantize.h"
 #include "fastdiv.h"
+#include "block_terms.h"
 #include <type_traits>
 
 namespace qnn {
@@ -118,6 +119,7 @@ struct LevelConvParams {
     uint32_t row_taps, col_taps;               // bit masks of the taps of kernel row 0 / kernel column 0
     float next_inv_clip, next_half_top;
     int next_top;
+    BlockTerms blk; // res_q: int8 levels [pixels][Cout]
 };
 
 #define QNN_CONV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
@@ -281,6 +283,18 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     for (; s + kRing < p.nstages; ++s) stage_body(s, std::true_type{});
     for (; s < p.nstages; ++s) stage_body(s, std::false_type{});
 
+    // scale, then the residual-block terms in their documented order (one fp32 rounding each)
+    auto block_y = [&](int32_t v, float sc, float bi, int64_t o) -> float {
+        float y = (float)v * sc;
+        if (p.blk.bias) y = y + bi;
+        if (p.blk.res_q) {
+            const float term = (float)(int)static_cast<const int8_t *>(p.blk.res_q)[o] * p.blk.res_scale;
+            y = y + term;
+        }
+        if (p.blk.res_f32) y = y + p.blk.res_f32[o];
+        return y;
+    };
+
     // D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) + r % 4
     if (p.acc || p.out) {
 #pragma unroll
@@ -290,6 +304,7 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
                 const int c = col0 + (wn * TN + j) * 32 + (lane & 31);
                 if (c >= p.Cout) continue;
                 const float sc = p.out ? p.scale[c] : 0.0f;
+                const float bi = p.out && p.blk.bias ? p.blk.bias[c] : 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = row0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -297,7 +312,7 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
                     const int32_t v = acc[i][j][r];
                     const int64_t o = (int64_t)row * p.Cout + c;
                     if (p.acc) p.acc[o] = v;
-                    if (p.out) p.out[o] = (float)v * sc;
+                    if (p.out) p.out[o] = block_y(v, sc, bi, o);
                 }
             }
     }
@@ -313,10 +328,13 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
                 const int cl = (wn * TN + j) * 32 + (lane & 31);
                 const int c = col0 + cl < p.Cout ? col0 + cl : p.Cout - 1;
                 const float sc = p.scale[c];
+                const float bi = p.blk.bias ? p.blk.bias[c] : 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rl = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    const float o = (float)acc[i][j][r] * sc;
+                    // rows past the last pixel and columns past Cout are never stored: any in-range address does
+                    const int row = row0 + rl < p.pixels ? row0 + rl : p.pixels - 1;
+                    const float o = block_y(acc[i][j][r], sc, bi, (int64_t)row * p.Cout + c);
                     const int level = 2 * quantize_code(o, p.next_inv_clip, p.next_half_top, p.next_top) - p.next_top;
                     lv[rl * NB + cl] = (uint8_t)level;
                 }
@@ -384,7 +402,18 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
                                    const float *scale, int32_t *acc, float *out, int8_t *next_levels,
                                    float next_clip, int next_bits, void *stream)
 {
+    return qnn_level_conv2d_block_i8(d, a_levels, w_levels, scale, nullptr, acc, out, next_levels, next_clip, next_bits,
+                                     stream);
+}
+
+extern "C" int qnn_level_conv2d_block_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
+                                         const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                                         int8_t *next_levels, float next_clip, int next_bits, void *stream)
+{
     if (!d) return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: NULL descriptor");
+    BlockTerms blk;
+    const int brc = block_terms("qnn_level_conv2d_block_i8", epi, scale, 7, blk);
+    if (brc != QNN_OK) return brc;
     if (d->a_bits < 1 || d->a_bits > 7 || d->w_bits < 1 || d->w_bits > 7)
         return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: bits must be in [1,7] (int8 levels)");
     if (d->B < 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0)
@@ -425,6 +454,7 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
 
     LevelConvParams p;
     p.a = a_levels, p.w = w_levels, p.scale = scale, p.acc = acc, p.out = out, p.next = next_levels;
+    p.blk = blk;
     p.H = (int)d->H, p.W = (int)d->W, p.Cin = (int)d->Cin, p.Cout = (int)d->Cout, p.Ho = (int)Ho, p.Wo = (int)Wo;
     p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad;
     p.pixels = (int)(d->B * Ho * Wo);

@@ -23,7 +23,8 @@ QNN_DTYPE_F32 = 0
 QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
-EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d",
+EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d", "qnn_conv2d_block",
+           "qnn_level_conv2d_block_i8",
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
@@ -42,6 +43,11 @@ class qnn_conv_desc(ctypes.Structure):
                 ("Cin", ctypes.c_int64), ("Cout", ctypes.c_int64),
                 ("kh", ctypes.c_int32), ("kw", ctypes.c_int32), ("stride", ctypes.c_int32),
                 ("pad", ctypes.c_int32), ("a_bits", ctypes.c_int32), ("w_bits", ctypes.c_int32)]
+
+
+class qnn_block_epilogue(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("res_q", ctypes.c_void_p), ("res_bits", ctypes.c_int32),
+                ("res_scale", ctypes.c_float), ("res_f32", ctypes.c_void_p)]
 
 
 _lib = None
@@ -65,6 +71,11 @@ def lib():
         L.qnn_dequant_scale.restype = i32
         L.qnn_conv2d.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_conv2d.restype = i32
+        L.qnn_conv2d_block.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, ctypes.POINTER(qnn_block_epilogue),
+                                       vp, vp, vp, f32, i32, vp]
+        L.qnn_conv2d_block.restype = i32
+        L.qnn_level_conv2d_block_i8.argtypes = L.qnn_conv2d_block.argtypes
+        L.qnn_level_conv2d_block_i8.restype = i32
         L.qnn_probe_valu.argtypes = [i32, i32, i32, vp, vp]
         L.qnn_probe_valu.restype = i32
         L.qnn_level_row_bytes.argtypes = [i64]
@@ -241,10 +252,12 @@ def qnn_encode_levels_i8(src, clip, bits, levels=None):
     return levels
 
 
-def qnn_level_conv2d_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=None, want_acc=True,
-                        want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
-    """a_levels int8 [B][H][W][Cin], w_levels int8 [Cout][kh][kw][Cin].  Returns (acc, out, next_levels);
-    entries not requested are None."""
+def _block_epilogue(bias, res_q, res_bits, res_scale, res_f32):
+    return qnn_block_epilogue(_ptr(bias), _ptr(res_q), int(res_bits), float(res_scale), _ptr(res_f32))
+
+
+def _level_conv(entry, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale, want_acc, want_out, next_clip,
+                next_bits, acc, out, next_levels):
     B, H, W, cin = a_levels.shape
     cout, kh, kw, cin2 = w_levels.shape
     assert cin == cin2 and a_levels.dtype == torch.int8 and w_levels.dtype == torch.int8
@@ -259,11 +272,29 @@ def qnn_level_conv2d_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=N
         out = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=dev)
     if next_clip is not None and next_levels is None:
         next_levels = torch.empty((B, ho, wo, cout), dtype=torch.int8, device=dev)
-    _check(lib().qnn_level_conv2d_i8(ctypes.byref(d), _ptr(a_levels), _ptr(w_levels), _ptr(scale), _ptr(acc),
-                                     _ptr(out), _ptr(next_levels),
-                                     float(next_clip) if next_clip is not None else 0.0, int(next_bits),
-                                     _stream()))
+    head = (ctypes.byref(d), _ptr(a_levels), _ptr(w_levels), _ptr(scale))
+    tail = (_ptr(acc), _ptr(out), _ptr(next_levels), float(next_clip) if next_clip is not None else 0.0,
+            int(next_bits), _stream())
+    _check(entry(*head, *tail) if epi is None else entry(*head, ctypes.byref(epi), *tail))
     return acc, out, next_levels
+
+
+def qnn_level_conv2d_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=None, want_acc=True,
+                        want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """a_levels int8 [B][H][W][Cin], w_levels int8 [Cout][kh][kw][Cin].  Returns (acc, out, next_levels);
+    entries not requested are None."""
+    return _level_conv(lib().qnn_level_conv2d_i8, None, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
+                       want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
+
+
+def qnn_level_conv2d_block_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale, bias=None, res_levels=None,
+                              res_bits=0, res_scale=0.0, res_f32=None, want_acc=True, want_out=False,
+                              next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """qnn_level_conv2d_i8 with the residual-block terms: bias fp32 [Cout], res_levels int8 [B][Ho][Wo][Cout]
+    with its factor res_scale, res_f32 fp32 [B][Ho][Wo][Cout]."""
+    epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32)
+    return _level_conv(lib().qnn_level_conv2d_block_i8, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
+                       want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
 
 
 def qnn_probe_valu(mode, workgroups, iters, out):
@@ -280,10 +311,8 @@ def qnn_dequant_scale(acc, scale, out=None):
     return out
 
 
-def qnn_conv2d(a_planes, w_planes, shape, cin, stride, pad, scale=None, want_acc=True, want_out=False,
-               next_clip=None, next_bits=0, acc=None, out=None, next_planes=None):
-    """a_planes [a_bits][B*H*W][cw] for an NHWC tensor of shape=(B, H, W); w_planes
-    [w_bits][Cout][kh][kw][cw].  Returns (acc, out, next_planes); entries not requested are None."""
+def _conv(entry, epi, a_planes, w_planes, shape, cin, stride, pad, scale, want_acc, want_out, next_clip, next_bits,
+          acc, out, next_planes):
     B, H, W = shape
     a_bits = a_planes.shape[0]
     w_bits, cout, kh, kw, cw = w_planes.shape
@@ -298,7 +327,27 @@ def qnn_conv2d(a_planes, w_planes, shape, cin, stride, pad, scale=None, want_acc
         out = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=dev)
     if next_clip is not None and next_planes is None:
         next_planes = torch.empty((next_bits, B * ho * wo, (cout + 31) // 32), dtype=torch.int32, device=dev)
-    _check(lib().qnn_conv2d(ctypes.byref(d), _ptr(a_planes), _ptr(w_planes), _ptr(scale), _ptr(acc),
-                            _ptr(out), _ptr(next_planes),
-                            float(next_clip) if next_clip is not None else 0.0, int(next_bits), _stream()))
+    head = (ctypes.byref(d), _ptr(a_planes), _ptr(w_planes), _ptr(scale))
+    tail = (_ptr(acc), _ptr(out), _ptr(next_planes), float(next_clip) if next_clip is not None else 0.0,
+            int(next_bits), _stream())
+    _check(entry(*head, *tail) if epi is None else entry(*head, ctypes.byref(epi), *tail))
     return acc, out, next_planes
+
+
+def qnn_conv2d(a_planes, w_planes, shape, cin, stride, pad, scale=None, want_acc=True, want_out=False,
+               next_clip=None, next_bits=0, acc=None, out=None, next_planes=None):
+    """a_planes [a_bits][B*H*W][cw] for an NHWC tensor of shape=(B, H, W); w_planes
+    [w_bits][Cout][kh][kw][cw].  Returns (acc, out, next_planes); entries not requested are None."""
+    return _conv(lib().qnn_conv2d, None, a_planes, w_planes, shape, cin, stride, pad, scale, want_acc, want_out,
+                 next_clip, next_bits, acc, out, next_planes)
+
+
+def qnn_conv2d_block(a_planes, w_planes, shape, cin, stride, pad, scale, bias=None, res_planes=None, res_scale=0.0,
+                     res_f32=None, want_acc=True, want_out=False, next_clip=None, next_bits=0, acc=None, out=None,
+                     next_planes=None):
+    """qnn_conv2d with the residual-block terms: bias fp32 [Cout], res_planes [res_bits][B*Ho*Wo][ceil(Cout/32)]
+    with its factor res_scale, res_f32 fp32 [B][Ho][Wo][Cout]."""
+    res_bits = res_planes.shape[0] if res_planes is not None else 0
+    epi = _block_epilogue(bias, res_planes, res_bits, res_scale, res_f32)
+    return _conv(lib().qnn_conv2d_block, epi, a_planes, w_planes, shape, cin, stride, pad, scale, want_acc, want_out,
+                 next_clip, next_bits, acc, out, next_planes)

@@ -118,6 +118,34 @@ def test_conv2d_argument_errors(qnn):
     assert call(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
 
 
+def test_block_epilogue_argument_errors(qnn):
+    L = qnn.lib()
+    D, E = qnn.qnn_conv_desc, qnn.qnn_block_epilogue
+    # pointer, pointer, int32, float, pointer
+    assert ctypes.sizeof(E) == 32 and E.res_bits.offset == 16 and E.res_scale.offset == 20 and E.res_f32.offset == 24
+    ok = D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)
+    F, O = FAKE.value, ODD.value
+
+    def call(entry, epi, scale=FAKE, desc=ok):
+        return entry(ctypes.byref(desc), FAKE, FAKE, scale, ctypes.byref(epi) if epi is not None else None,
+                     FAKE, None, None, 0.0, 0, None)
+
+    for entry, max_bits in ((L.qnn_conv2d_block, 8), (L.qnn_level_conv2d_block_i8, 7)):
+        assert call(entry, E(F, None, 0, 0.0, None), scale=None) == qnn.QNN_ERR_INVALID_ARG   # terms without scale
+        assert call(entry, E(None, F, 0, 1.0, None)) == qnn.QNN_ERR_INVALID_ARG               # res_bits too small
+        assert call(entry, E(None, F, max_bits + 1, 1.0, None)) == qnn.QNN_ERR_INVALID_ARG
+        assert call(entry, E(None, F, 2, float("nan"), None)) == qnn.QNN_ERR_INVALID_ARG
+        assert call(entry, E(None, F, 2, float("inf"), None)) == qnn.QNN_ERR_INVALID_ARG
+        assert b"res_scale" in L.qnn_last_error()
+        assert call(entry, E(O, None, 0, 0.0, None)) == qnn.QNN_ERR_ALIGNMENT
+        assert call(entry, E(None, O, 2, 1.0, None)) == qnn.QNN_ERR_ALIGNMENT
+        assert call(entry, E(None, None, 0, 0.0, O)) == qnn.QNN_ERR_ALIGNMENT
+        # a valid epilogue does not mask the convolution's own checks; an empty batch returns before any launch
+        assert call(entry, E(F, F, 2, 1.0, F), desc=D(1, 8, 8, 64, 64, 3, 3, 0, 1, 2, 2)) == qnn.QNN_ERR_INVALID_ARG
+        assert call(entry, E(F, F, 2, 1.0, F), desc=D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
+        assert call(entry, None, desc=D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
+
+
 def test_matrix_core_variant_argument_errors(qnn):
     L = qnn.lib()
     assert L.qnn_level_row_bytes(1) == 128 and L.qnn_level_row_bytes(128) == 128 and L.qnn_level_row_bytes(129) == 256
