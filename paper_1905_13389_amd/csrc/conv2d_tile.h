@@ -112,6 +112,7 @@ bconv_tile_kernel(ConvTileParams p)
     constexpr int W_WORDS = T::STAGE_WORDS - T::A_WORDS;
     __shared__ __attribute__((aligned(16))) uint32_t w_resident[KEEPW ? W_WORDS : 4];
     __shared__ uint32_t tap_table[kMaxGroups];
+    __shared__ __attribute__((aligned(16))) float bias_lds[BLK ? BN : 4]; // the column tile's shifts (0 without)
     extern __shared__ __attribute__((aligned(16))) int32_t dyn_smem[];
     int32_t *S = dyn_smem;                                                   // [taps][BN]
     uint32_t *ymask = reinterpret_cast<uint32_t *>(dyn_smem) + BN * p.kh * p.kw; // [Ho] taps whose row is outside
@@ -124,6 +125,10 @@ bconv_tile_kernel(ConvTileParams p)
     const bool wvec = p.wvec != 0;
     const int taps = p.kh * p.kw;
 
+    if constexpr (BLK) {
+        for (int e = tid; e < BN; e += kTileThreads)
+            bias_lds[e] = p.blk.bias && col0 + e < p.Cout ? p.blk.bias[col0 + e] : 0.0f;
+    }
     // reduction word group -> tap number and word offset from the window origin
     for (int g = tid; g * VW < p.nw; g += kTileThreads) {
         const int kword = g * VW;
@@ -272,11 +277,45 @@ bconv_tile_kernel(ConvTileParams p)
 #pragma unroll
             for (int n = 0; n < TN; ++n)
                 V[(ty + 16 * i) * EPI_STRIDE + tx + 16 * n] = recombine<T::S>(P[i][n], p.n_times_top);
+        // this lane's nibble of the 32-channel plane word its 4 channels belong to
+        const int wword = (col0 >> 5) + (tid % LPR) / 8;
+        const int nib_shift = 4 * (tid & 7);
+        // The shortcut operands of all passes are requested here, in one go, now that the partial sums
+        // no longer occupy registers: one memory latency per tile, hidden behind the barrier, the
+        // LDS reads and the other resident workgroup, instead of one per pass.
+        constexpr int NPASS = BM / RPP;
+        uint32_t rq_pre[BLK ? NPASS : 1][8];
+        float4 rf_pre[BLK ? NPASS : 1];
+        if constexpr (BLK) {
+            const uint32_t *rq = static_cast<const uint32_t *>(p.blk.res_q);
+#pragma unroll
+            for (int ps = 0; ps < NPASS; ++ps) {
+                const int r = row0 + ps * RPP + tid / LPR;
+                const bool rvalid = r < p.M;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    rq_pre[ps][j] = 0u;
+                    if (rq && rvalid && wword < p.cwo && j < p.blk.res_bits)
+                        rq_pre[ps][j] = rq[((int64_t)j * p.M + r) * p.cwo + wword];
+                }
+                rf_pre[ps] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (p.blk.res_f32 && rvalid) {
+                    const float *src = p.blk.res_f32 + ((int64_t)r * p.Cout + cidx);
+                    if (cols4) {
+                        rf_pre[ps] = *reinterpret_cast<const float4 *>(src);
+                    } else {
+                        if (cidx + 0 < p.Cout) rf_pre[ps].x = src[0];
+                        if (cidx + 1 < p.Cout) rf_pre[ps].y = src[1];
+                        if (cidx + 2 < p.Cout) rf_pre[ps].z = src[2];
+                        if (cidx + 3 < p.Cout) rf_pre[ps].w = src[3];
+                    }
+                }
+            }
+        }
         __syncthreads();
 
         // ---- second half: padding correction, stores, scale, quantize, plane split ----
-#pragma unroll 1
-        for (int pass = 0; pass < BM / RPP; ++pass) {
+        auto do_pass = [&](const int pass, const uint32_t (&rqw)[8], const float4 rf) {
             const int rl = pass * RPP + tid / LPR;
             const int r = row0 + rl;
             const bool rvalid = r < p.M;
@@ -309,46 +348,35 @@ bconv_tile_kernel(ConvTileParams p)
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (rvalid && cidx + e < p.Cout) p.partial[off + e] = v[e];
-                    continue;
+                    return;
                 }
             }
             float o[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[e] = (float)v[e] * sc[e];
-            // this lane's nibble of the 32-channel plane word its 4 channels belong to
-            const int wword = (col0 >> 5) + (tid % LPR) / 8;
-            const int nib_shift = 4 * (tid & 7);
-            // residual-block terms, in the documented order (one fp32 rounding each); nothing of them
-            // is kept in registers across the reduction loop
-            if (BLK && p.blk.bias) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (cidx + e < p.Cout) o[e] = o[e] + p.blk.bias[cidx + e];
-            }
-            if (BLK && p.blk.res_q && rvalid && wword < p.cwo) {
-                const uint32_t *rq = static_cast<const uint32_t *>(p.blk.res_q);
-                uint32_t code[4] = {0u, 0u, 0u, 0u};
-                for (int j = 0; j < p.blk.res_bits; ++j) {
-                    const uint32_t nib = rq[((int64_t)j * p.M + r) * p.cwo + wword] >> nib_shift;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) code[e] |= ((nib >> e) & 1u) << j;
+            // residual-block terms, in the documented order (one fp32 rounding each)
+            if constexpr (BLK) {
+                if (p.blk.bias) {
+                    const float4 bi = *reinterpret_cast<const float4 *>(bias_lds + c4);
+                    o[0] = o[0] + bi.x, o[1] = o[1] + bi.y, o[2] = o[2] + bi.z, o[3] = o[3] + bi.w;
                 }
+                if (p.blk.res_q) {
+                    uint32_t code[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float term = (float)(2 * (int)code[e] - p.blk.res_top) * p.blk.res_scale;
-                    o[e] = o[e] + term;
-                }
-            }
-            if (BLK && p.blk.res_f32 && rvalid) {
-                const int64_t off = (int64_t)r * p.Cout + cidx;
-                if (cols4) {
-                    const float4 rr = *reinterpret_cast<const float4 *>(p.blk.res_f32 + off);
-                    o[0] = o[0] + rr.x, o[1] = o[1] + rr.y, o[2] = o[2] + rr.z, o[3] = o[3] + rr.w;
-                } else {
+                    for (int j = 0; j < 8; ++j) {
+                        if (j < p.blk.res_bits) {
+                            const uint32_t nib = rqw[j] >> nib_shift;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (cidx + e < p.Cout) o[e] = o[e] + p.blk.res_f32[off + e];
+                            for (int e = 0; e < 4; ++e) code[e] |= ((nib >> e) & 1u) << j;
+                        }
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float term = (float)(2 * (int)code[e] - p.blk.res_top) * p.blk.res_scale;
+                        o[e] = o[e] + term;
+                    }
                 }
+                if (p.blk.res_f32) o[0] = o[0] + rf.x, o[1] = o[1] + rf.y, o[2] = o[2] + rf.z, o[3] = o[3] + rf.w;
             }
             if (rvalid) {
                 const int64_t off = (int64_t)r * p.Cout + cidx;
@@ -382,6 +410,13 @@ bconv_tile_kernel(ConvTileParams p)
                         p.next[((int64_t)j * p.M + r) * p.cwo + wword] = word;
                 }
             }
+        };
+        if constexpr (BLK) {
+#pragma unroll
+            for (int pass = 0; pass < NPASS; ++pass) do_pass(pass, rq_pre[pass], rf_pre[pass]);
+        } else {
+#pragma unroll 1
+            for (int pass = 0; pass < NPASS; ++pass) do_pass(pass, rq_pre[0], rf_pre[0]);
         }
         __syncthreads(); // V's stage is about to be refilled by the next tile's pipeline
     }

@@ -126,8 +126,11 @@ struct LevelConvParams {
 
 // KB: stage length in bytes of the reduction axis, 128 or 64 (short reductions: more, smaller
 // workgroups per CU, no half-empty last stage at kh kw Cin = 576)
+// The 256 x 64 block runs three workgroups per CU (one wave each per SIMD): its register budget is
+// held to a third of the file.
 template <int MB, int NB, int WM, int WN, int KB>
-__global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConvParams p)
+__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(MB * NB == 256 * 64 ? 3 : 1))) void
+level_conv_mfma_kernel(LevelConvParams p)
 {
     constexpr int kKB = KB, kSteps = KB / 32, kUnits = KB / 16; // k steps of 32 bytes, 16-byte units per row
     constexpr int kRowsPerLoad = 1024 / KB;                      // LDS rows one wave-wide 1 KiB load fills
@@ -283,12 +286,39 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
     for (; s + kRing < p.nstages; ++s) stage_body(s, std::true_type{});
     for (; s < p.nstages; ++s) stage_body(s, std::false_type{});
 
-    // scale, then the residual-block terms in their documented order (one fp32 rounding each)
-    auto block_y = [&](int32_t v, float sc, float bi, int64_t o) -> float {
+    // ---- epilogue ----
+    // The quantized shortcut tile (int8 [MB][NB]) is fetched into LDS with 16-byte loads and read back
+    // bytewise; a lane later writes its level to the very byte it read, so the same region serves as
+    // the level tile that leaves with 16-byte stores.
+    const int8_t *resq = static_cast<const int8_t *>(p.blk.res_q);
+    uint8_t *lv = &smem[0][0]; // [MB][NB] bytes
+    constexpr int kVecPerRow = NB / 16;
+    if (resq || p.next) {
+        // every wave is past its last LDS read (the loop's final reads are waited for here)
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __syncthreads();
+    }
+    if (resq) {
+        for (int v = tid; v < MB * kVecPerRow; v += kConvThreads) {
+            const int rl = v / kVecPerRow, cv = (v % kVecPerRow) * 16;
+            const int row = row0 + rl, c = col0 + cv;
+            if (row >= p.pixels || c >= p.Cout) continue;
+            const int8_t *src = resq + (int64_t)row * p.Cout + c;
+            if (c + 16 <= p.Cout && (p.Cout & 15) == 0) {
+                *reinterpret_cast<uint4 *>(lv + rl * NB + cv) = *reinterpret_cast<const uint4 *>(src);
+            } else {
+                for (int e = 0; e < 16 && c + e < p.Cout; ++e) lv[rl * NB + cv + e] = (uint8_t)src[e];
+            }
+        }
+        __syncthreads();
+    }
+    // scale, then the residual-block terms in their documented order (one fp32 rounding each);
+    // `at`: this output's byte in the LDS tile, `o`: its element offset in the global tensors
+    auto block_y = [&](int32_t v, float sc, float bi, int at, int64_t o) -> float {
         float y = (float)v * sc;
         if (p.blk.bias) y = y + bi;
-        if (p.blk.res_q) {
-            const float term = (float)(int)static_cast<const int8_t *>(p.blk.res_q)[o] * p.blk.res_scale;
+        if (resq) {
+            const float term = (float)(int)(int8_t)lv[at] * p.blk.res_scale;
             y = y + term;
         }
         if (p.blk.res_f32) y = y + p.blk.res_f32[o];
@@ -301,26 +331,23 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int c = col0 + (wn * TN + j) * 32 + (lane & 31);
+                const int cl = (wn * TN + j) * 32 + (lane & 31);
+                const int c = col0 + cl;
                 if (c >= p.Cout) continue;
                 const float sc = p.out ? p.scale[c] : 0.0f;
                 const float bi = p.out && p.blk.bias ? p.blk.bias[c] : 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = row0 + (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    if (row >= p.pixels) continue;
+                    const int rl = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    if (row0 + rl >= p.pixels) continue;
                     const int32_t v = acc[i][j][r];
-                    const int64_t o = (int64_t)row * p.Cout + c;
+                    const int64_t o = (int64_t)(row0 + rl) * p.Cout + c;
                     if (p.acc) p.acc[o] = v;
-                    if (p.out) p.out[o] = block_y(v, sc, bi, o);
+                    if (p.out) p.out[o] = block_y(v, sc, bi, rl * NB + cl, o);
                 }
             }
     }
     if (p.next) {
-        // every wave is past its last LDS read (the loop's final reads are waited for here)
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        __syncthreads();
-        uint8_t *lv = &smem[0][0]; // [MB][NB] bytes
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -334,13 +361,14 @@ __global__ __launch_bounds__(64 * WM * WN) void level_conv_mfma_kernel(LevelConv
                     const int rl = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     // rows past the last pixel and columns past Cout are never stored: any in-range address does
                     const int row = row0 + rl < p.pixels ? row0 + rl : p.pixels - 1;
-                    const float o = block_y(acc[i][j][r], sc, bi, (int64_t)row * p.Cout + c);
-                    const int level = 2 * quantize_code(o, p.next_inv_clip, p.next_half_top, p.next_top) - p.next_top;
-                    lv[rl * NB + cl] = (uint8_t)level;
+                    const float y = block_y(acc[i][j][r], sc, bi, rl * NB + cl, (int64_t)row * p.Cout + c);
+                    lv[rl * NB + cl] =
+                        (uint8_t)(2 * quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) - p.next_top);
                 }
             }
+    }
+    if (p.next) {
         __syncthreads();
-        constexpr int kVecPerRow = NB / 16;
         for (int v = tid; v < MB * kVecPerRow; v += kConvThreads) {
             const int rl = v / kVecPerRow, cv = (v % kVecPerRow) * 16;
             const int row = row0 + rl, c = col0 + cv;
