@@ -9,7 +9,9 @@ what pins each of them.  maxpool / pool_out_size are plain numpy here; their pin
 pooling routine on the same integers, commutation with the quantizer, brute force) are in
 tests/test_oracle_pool.py.  block_epilogue / residual_trunk are numpy float32 here; their pins (the same
 sums in float64, the library's batch normalisation, Table 2's real values as the shortcut, the library's
-float64 convolution block by block) are in tests/test_oracle_block.py.
+float64 convolution block by block) are in tests/test_oracle_block.py.  quantize_ste_backward /
+encoder_backward are numpy float64; their pins (Eq. 12-13's printed values, finite differences of the sines,
+the sines' signs against the quantizer's planes) are in tests/test_oracle_training.py.
 """
 import ctypes
 import os
@@ -254,6 +256,41 @@ def residual_trunk(x, blocks):
         trace.append({"a": a, "acc1": acc1, "hq": hq, "acc2": acc2, "accd": accd, "shortcut": shortcut, "y": y})
         cur = y
     return trace
+
+
+def _range_limited(x, clip):
+    """t = x * (1 / clip) in fp32, as the quantizer forms it, and the mask of -1 <= t <= 1."""
+    inv = np.float32(1.0) / np.float32(clip)
+    t = np.ascontiguousarray(x, dtype=np.float32) * inv
+    return t.astype(np.float64), (t >= -1.0) & (t <= 1.0), np.float64(inv)
+
+
+def quantize_ste_backward(x, grad_q, clip):
+    """Straight-through gradient of the hard ladder q_k behind the range limit (Section "Quantized
+    Networks Training"; Table 1 HTanh): q_k(HTanh(x / clip)) is differentiated as if q_k were the
+    identity, so the gradient passes with slope 1 / clip where -1 <= x / clip <= 1 and is 0 outside.
+    With clip = 1 this is also the gradient of Binarize(x) = sign(HTanh(x)) (Eq. 14).  float64 out."""
+    _, inside, inv = _range_limited(x, clip)
+    g = np.asarray(grad_q, dtype=np.float64)
+    return np.where(inside, g * inv, 0.0)
+
+
+def encoder_backward(x, grad_planes, clip, bits):
+    """Surrogate gradient of the M-bit encoder (Eq. 12-13 for M = 2).  Plane m of M (m = 1 lowest) is
+    the sign of a sine: +sin(pi K t / 2^M) for m = M and -sin(pi K t / 2^m) below, K = 2^M - 1,
+    t = HTanh(x / clip); its derivative is taken as that of the sine inside [-1, 1] and 0 outside:
+        d plane_M / dt = +(pi K / 2^M) cos(pi K t / 2^M),  d plane_m / dt = -(pi K / 2^m) cos(pi K t / 2^m).
+    grad_planes: [bits][...] gradients w.r.t. each plane (index m - 1).  Returns d loss / d x, float64."""
+    t, inside, inv = _range_limited(x, clip)
+    g = np.asarray(grad_planes, dtype=np.float64)
+    assert g.shape == (bits,) + t.shape
+    K = float((1 << bits) - 1)
+    total = np.zeros(t.shape, dtype=np.float64)
+    for m in range(1, bits + 1):
+        coef = np.pi * K / float(1 << m)
+        sign = 1.0 if m == bits else -1.0
+        total += g[m - 1] * (sign * coef * np.cos(coef * t))
+    return np.where(inside, total * inv, 0.0)
 
 
 def pool_out_size(size, k, stride, pad, ceil_mode):
