@@ -72,7 +72,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "trunk", "pool"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "trunk", "pool", "grad"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -412,6 +412,44 @@ def pool_workload(args):
                      "algorithmic_bytes": nbytes}}))
 
 
+def grad_workload(args):
+    """The training-side gradients on config 3's activation tensor (batch 64, 56x56x64 fp32): the
+    straight-through gradient of the ladder and the 2-bit encoder's surrogate gradient; streaming, HBM bound."""
+    import torch
+    from paper_1905_13389_amd import qnn
+
+    n = (args.batch or 64) * 56 * 56 * 64
+    gen = torch.Generator(device="cuda").manual_seed(190513389)
+    x = torch.randn(n, device="cuda", generator=gen)
+    g = torch.randn((2, n), device="cuda", generator=gen)
+    gx = torch.empty_like(x)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps * 1e3
+
+    ms_ste = timed(lambda: qnn.qnn_quantize_ste_backward(x, g[0], 3.0, grad_x=gx))
+    ms_enc = timed(lambda: qnn.qnn_encoder_backward(x, g, 3.0, grad_x=gx))
+    b_ste, b_enc = 12.0 * n, 16.0 * n          # x + gradient(s) read, grad_x written
+    tbs = b_enc / (ms_enc * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "encoder surrogate gradient, HBM bytes per second", "value": round(tbs, 3), "unit": "TB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_enc, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%d fp32 activations, 2-bit encoder" % n, "step": "qnn_encoder_backward"},
+        "roofline": {"bound": "hbm", "kernel": "encoder_backward_kernel<2, 4>", "achieved": round(tbs * 1e3, 1),
+                     "peak": 8000.0, "unit": "GB/s", "frac": round(tbs / 8.0, 4), "traffic": None,
+                     "algorithmic_bytes": b_enc},
+        "quantize_ste_backward": {"ms": round(ms_ste, 5), "GB/s": round(b_ste / (ms_ste * 1e-3) / 1e9, 1),
+                                  "frac": round(b_ste / (ms_ste * 1e-3) / 8e12, 4), "algorithmic_bytes": b_ste}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -422,6 +460,8 @@ def main():
         return trunk_workload(args)
     if args.workload == "pool":
         return pool_workload(args)
+    if args.workload == "grad":
+        return grad_workload(args)
     if args.workload == "fc1":
         return fc_workload(args)
     if args.workload != "gemm":

@@ -178,6 +178,29 @@ int qnn_maxpool_levels_i8(const int8_t *levels, int64_t B, int64_t H, int64_t W,
                           int pad, int ceil_mode, int8_t *out_levels, void *stream);
 
 /*
+ * Training-side gradients (sections "Multi-Branch Binary Networks Training" and "Quantized Networks
+ * Training"), elementwise; x, the gradients and grad_x are DEVICE fp32, 16-byte aligned, count elements.
+ *
+ * qnn_quantize_ste_backward: the straight-through gradient of the hard ladder q_k (Eq. 15) behind the
+ *     range limit HTanh (Table 1): with t = x * (1 / clip) in fp32,
+ *         grad_x = grad_q * (1 / clip)  where -1 <= t <= 1,  0 elsewhere.
+ *     grad_q is the gradient w.r.t. q_k(HTanh(x / clip)) in [-1, 1] (= level / (2^k - 1)).  With clip = 1
+ *     it is also the gradient of Binarize(x) = sign(HTanh(x)) (Eq. 14), whose forward is
+ *     qnn_encode_pack with bits = 1.
+ * qnn_encoder_backward: the surrogate gradient of the M-bit encoder (Eq. 12-13 for M = 2).  Plane m
+ *     (m = 1 lowest; grad_planes DEVICE fp32 [bits][count], index m - 1) is the sign of +sin(pi K t / 2^M)
+ *     for m = M and of -sin(pi K t / 2^m) below, K = 2^M - 1; its derivative is the sine's on [-1, 1]:
+ *         grad_x = (1 / clip) * sum_m grad_planes[m] * (+-)(pi K / 2^m) cos(pi K t / 2^m),  0 outside.
+ *     fp32 arithmetic; the cosine's argument t K / 2^m carries one rounding and is reduced exactly
+ *     (cospi), so with s_m = pi K / 2^m the result is within
+ *     (1 / clip) sum_m |grad_planes[m]| s_m (s_m + 4) 2^-24 of the value in real arithmetic.
+ */
+int qnn_quantize_ste_backward(const float *x, const float *grad_q, int64_t count, float clip, float *grad_x,
+                              void *stream);
+int qnn_encoder_backward(const float *x, const float *grad_planes, int64_t count, float clip, int bits,
+                         float *grad_x, void *stream);
+
+/*
  * Bit-plane-sum variant on the matrix cores (for comparison with qnn_binary_gemm; same integers).
  * The M x K branch sum of Eq. 9 equals the integer dot product of the decoded levels (Eq. 7-10),
  * so one can also sum the 2^j-weighted planes back into int8 levels and contract those with int8

@@ -129,7 +129,7 @@ struct LevelConvParams {
 // The 256 x 64 block runs three workgroups per CU (one wave each per SIMD): its register budget is
 // held to a third of the file.
 template <int MB, int NB, int WM, int WN, int KB>
-__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(MB * NB == 256 * 64 ? 3 : 1))) void
+__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(MB == 256 && NB == 64 ? 3 : 1))) void
 level_conv_mfma_kernel(LevelConvParams p)
 {
     constexpr int kKB = KB, kSteps = KB / 32, kUnits = KB / 16; // k steps of 32 bytes, 16-byte units per row

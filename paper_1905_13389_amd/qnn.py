@@ -24,7 +24,7 @@ QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d", "qnn_conv2d_block",
-           "qnn_level_conv2d_block_i8",
+           "qnn_level_conv2d_block_i8", "qnn_quantize_ste_backward", "qnn_encoder_backward",
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
@@ -100,6 +100,10 @@ def lib():
         L.qnn_encode_levels_i8.restype = i32
         L.qnn_level_conv2d_i8.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_level_conv2d_i8.restype = i32
+        L.qnn_quantize_ste_backward.argtypes = [vp, vp, i64, f32, vp, vp]
+        L.qnn_quantize_ste_backward.restype = i32
+        L.qnn_encoder_backward.argtypes = [vp, vp, i64, f32, i32, vp, vp]
+        L.qnn_encoder_backward.restype = i32
         L.qnn_last_error.argtypes = []
         L.qnn_last_error.restype = ctypes.c_char_p
         L.qnn_version.argtypes = []
@@ -295,6 +299,26 @@ def qnn_level_conv2d_block_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, s
     epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32)
     return _level_conv(lib().qnn_level_conv2d_block_i8, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
                        want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
+
+
+def qnn_quantize_ste_backward(x, grad_q, clip, grad_x=None):
+    """x, grad_q fp32 of one shape -> grad_x fp32 (straight-through gradient of the ladder behind the range limit)."""
+    assert x.dtype == torch.float32 and grad_q.dtype == torch.float32 and x.shape == grad_q.shape
+    if grad_x is None:
+        grad_x = torch.empty_like(x)
+    _check(lib().qnn_quantize_ste_backward(_ptr(x), _ptr(grad_q), x.numel(), float(clip), _ptr(grad_x), _stream()))
+    return grad_x
+
+
+def qnn_encoder_backward(x, grad_planes, clip, grad_x=None):
+    """x fp32 [...], grad_planes fp32 [bits][...] -> grad_x fp32 (surrogate gradient of the encoder)."""
+    bits = grad_planes.shape[0]
+    assert x.dtype == torch.float32 and grad_planes.dtype == torch.float32 and grad_planes.shape[1:] == x.shape
+    assert grad_planes.is_contiguous() and x.is_contiguous()
+    if grad_x is None:
+        grad_x = torch.empty_like(x)
+    _check(lib().qnn_encoder_backward(_ptr(x), _ptr(grad_planes), x.numel(), float(clip), bits, _ptr(grad_x), _stream()))
+    return grad_x
 
 
 def qnn_probe_valu(mode, workgroups, iters, out):

@@ -146,6 +146,20 @@ def test_block_epilogue_argument_errors(qnn):
         assert call(entry, None, desc=D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
 
 
+def test_training_gradient_argument_errors(qnn):
+    L = qnn.lib()
+    assert L.qnn_quantize_ste_backward(FAKE, FAKE, -1, 1.0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_quantize_ste_backward(FAKE, FAKE, 8, 0.0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_quantize_ste_backward(FAKE, None, 8, 1.0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_quantize_ste_backward(FAKE, FAKE, 8, 1.0, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert L.qnn_quantize_ste_backward(None, None, 0, 1.0, None, None) == qnn.QNN_OK
+    assert L.qnn_encoder_backward(FAKE, FAKE, 8, 1.0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encoder_backward(FAKE, FAKE, 8, 1.0, 9, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encoder_backward(FAKE, FAKE, 8, float("nan"), 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encoder_backward(ODD, FAKE, 8, 1.0, 2, FAKE, None) == qnn.QNN_ERR_ALIGNMENT
+    assert L.qnn_encoder_backward(None, None, 0, 1.0, 2, None, None) == qnn.QNN_OK
+
+
 def test_matrix_core_variant_argument_errors(qnn):
     L = qnn.lib()
     assert L.qnn_level_row_bytes(1) == 128 and L.qnn_level_row_bytes(128) == 128 and L.qnn_level_row_bytes(129) == 256
