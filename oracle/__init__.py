@@ -9,7 +9,9 @@ what pins each of them.  maxpool / pool_out_size are plain numpy here; their pin
 pooling routine on the same integers, commutation with the quantizer, brute force) are in
 tests/test_oracle_pool.py.  block_epilogue / residual_trunk are numpy float32 here; their pins (the same
 sums in float64, the library's batch normalisation, Table 2's real values as the shortcut, the library's
-float64 convolution block by block) are in tests/test_oracle_block.py.  quantize_ste_backward /
+float64 convolution block by block) are in tests/test_oracle_block.py.  deconv2d is plain numpy; its pins
+(the library's transposed convolution in float64, the adjoint identity with conv2d, brute force) are in
+tests/test_oracle_deconv.py.  quantize_ste_backward /
 encoder_backward are numpy float64; their pins (Eq. 12-13's printed values, finite differences of the sines,
 the sines' signs against the quantizer's planes) are in tests/test_oracle_training.py.
 """
@@ -194,6 +196,29 @@ def conv_stack(x, layers):
         trace.append({"levels": lv, "acc": acc, "out": out})
         cur = out
     return trace
+
+
+def deconv2d(a_levels, w_levels, stride, pad):
+    """Transposed convolution ("deconvolution", Section "Model Decomposition": deconvolution layers
+    reduce to the same vector products) on decoded levels, written as its definition: every input
+    pixel (i, j) adds a[b][i][j][:] . w[co][ky][kx][:] to output pixel (i stride + ky - pad,
+    j stride + kx - pad); contributions that fall outside the output are dropped.
+    a: [B][H][W][Cin], w: [Cout][kh][kw][Cin] -> int32 [B][Ho][Wo][Cout], Ho = (H - 1) stride - 2 pad + kh."""
+    a = np.ascontiguousarray(a_levels).astype(np.int64)
+    w = np.ascontiguousarray(w_levels).astype(np.int64)
+    B, H, W, Cin = a.shape
+    Cout, kh, kw, Cin2 = w.shape
+    assert Cin == Cin2
+    Ho, Wo = (H - 1) * stride - 2 * pad + kh, (W - 1) * stride - 2 * pad + kw
+    assert Ho >= 1 and Wo >= 1
+    full = np.zeros((B, (H - 1) * stride + kh, (W - 1) * stride + kw, Cout), dtype=np.int64)
+    for ky in range(kh):
+        for kx in range(kw):
+            contrib = a @ w[:, ky, kx, :].T                       # [B][H][W][Cout]
+            full[:, ky:ky + (H - 1) * stride + 1:stride, kx:kx + (W - 1) * stride + 1:stride, :] += contrib
+    out = full[:, pad:pad + Ho, pad:pad + Wo, :]
+    assert np.abs(out).max() < 2 ** 31
+    return np.ascontiguousarray(out.astype(np.int32))
 
 
 def block_epilogue(acc, scale_vec, bias=None, res_levels=None, res_scale=None, res_f32=None):
