@@ -72,7 +72,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "trunk", "pool", "grad"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "trunk", "pool", "grad", "deconv"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -412,6 +412,49 @@ def pool_workload(args):
                      "algorithmic_bytes": nbytes}}))
 
 
+def deconv_workload(args):
+    """A 2x upsampling transposed convolution (4x4 kernel, stride 2, pad 1) of decoder shape: batch 64,
+    28x28x128 -> 56x56x64, 2x2 bit, fused next-layer planes; four phase launches of the conv kernel."""
+    import torch
+    import qnn_workloads as wl
+    from paper_1905_13389_amd import qnn
+
+    B, H, cin, cout, k, s, pad, bits = args.batch or 64, 28, 128, 64, 4, 2, 1, 2
+    x = torch.from_numpy(wl.rng(7, 0).standard_normal((B * H * H, cin), dtype="float32")).cuda()
+    w = torch.from_numpy(wl.odd_levels(wl.rng(7, 1), (cout, k, k, cin), bits)).cuda()
+    sc = torch.from_numpy(wl.channel_scales(wl.rng(7, 2), cout)).cuda()
+    ph = qnn.qnn_deconv_pack_weights(qnn.qnn_encode_pack(w, 1.0, bits).view(bits, cout, k, k, -1), cin, s)
+    planes = qnn.qnn_encode_pack(x, 3.0, bits)
+    ho = (H - 1) * s - 2 * pad + k
+    nxt = torch.empty((bits, B * ho * ho, (cout + 31) // 32), dtype=torch.int32, device="cuda")
+
+    def step():
+        qnn.qnn_deconv2d(planes, ph, (B, H, H), cin, cout, k, k, s, pad, bits, scale=sc, want_acc=False,
+                         next_clip=3.0, next_bits=bits, next_planes=nxt)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    macs = B * H * H * k * k * cin * cout
+    tops = 2.0 * macs * bits * bits / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "effective binary TOPS (xnor+popcount) and % of VALU/HBM roofline, 1 MI355X", "value": round(tops, 2),
+        "unit": "binary TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 bit-planes, int32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "transposed conv 4x4 stride 2, batch %d, 28x28x128 -> 56x56x64, 2x2 bit" % B, "macs": macs,
+                   "step": "qnn_deconv2d (4 phase launches, fused scale/quantize/pack epilogue)"},
+        "roofline": {"bound": "alu", "achieved": round(tops, 2), "peak": round(PEAK_BINARY_TOPS, 1),
+                     "unit": "binary TOP/s", "frac": round(tops / PEAK_BINARY_TOPS, 4), "traffic": None,
+                     "frac_of_16_lane_nominal": round(tops / NOMINAL_BINARY_TOPS, 4),
+                     "note": "whole step (4 launches), not a single kernel"}}))
+
+
 def grad_workload(args):
     """The training-side gradients on config 3's activation tensor (batch 64, 56x56x64 fp32): the
     straight-through gradient of the ladder and the 2-bit encoder's surrogate gradient; streaming, HBM bound."""
@@ -462,6 +505,8 @@ def main():
         return pool_workload(args)
     if args.workload == "grad":
         return grad_workload(args)
+    if args.workload == "deconv":
+        return deconv_workload(args)
     if args.workload == "fc1":
         return fc_workload(args)
     if args.workload != "gemm":

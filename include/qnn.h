@@ -161,6 +161,33 @@ int qnn_conv2d_block(const qnn_conv_desc *desc, const uint32_t *a_planes, const 
                      uint32_t *next_planes, float next_clip, int next_bits, void *stream);
 
 /*
+ * qnn_deconv2d -- transposed convolution ("deconvolution"; section "Model Decomposition": deconvolution
+ * layers reduce to the same vector products) on bit-planes:
+ *     acc[b][y][x][co] = sum over (i, ky), (j, kx) with i stride + ky - pad = y, j stride + kx - pad = x
+ *                        of a[b][i][j][:] . w[co][ky][kx][:],    Ho = (H - 1) stride - 2 pad + kh, Wo likewise.
+ * For one output row only every stride-th kernel row takes part, so the stride x stride phases of the
+ * output are ordinary stride-1 convolutions with the (flipped) sub-kernels, run as that many launches of
+ * qnn_conv2d's kernel, each writing every stride-th output pixel per axis.
+ *
+ * qnn_deconv_phase_words: uint32 words of the phase-ordered weight planes (-1 for a bad geometry).
+ * qnn_deconv_pack_weights: w_planes DEVICE [w_bits][Cout][kh][kw][ceil(Cin/32)] (as for qnn_conv2d) ->
+ *     phase_planes DEVICE, qnn_deconv_phase_words(...) words: for fy, fx in 0..stride-1 (fy outer), the
+ *     planes [w_bits][Cout][Ty][Tx][ceil(Cin/32)] of the taps ky = fy + t stride, kx = fx + t' stride in
+ *     flipped order, each phase starting at a multiple of 4 words.  Done once per layer.
+ * qnn_deconv2d: desc->H, W, Cin describe the input, Cout / kh / kw / stride / pad the transposed
+ *     convolution; a_planes DEVICE [a_bits][B][H][W][ceil(Cin/32)]; scale, acc, out, next_planes,
+ *     next_clip, next_bits as in qnn_conv2d on the [B][Ho][Wo][Cout] output; bias DEVICE fp32 [Cout] or
+ *     NULL, added after the scale as in qnn_conv2d_block.  QNN_ERR_UNSUPPORTED for bit widths above 4,
+ *     kh or kw below stride (output pixels that no tap reaches) or above 16, stride above 8.
+ */
+int64_t qnn_deconv_phase_words(int w_bits, int64_t Cout, int kh, int kw, int64_t Cin, int stride);
+int qnn_deconv_pack_weights(const uint32_t *w_planes, int w_bits, int64_t Cout, int kh, int kw, int64_t Cin,
+                            int stride, uint32_t *phase_planes, void *stream);
+int qnn_deconv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32_t *phase_planes,
+                 const float *scale, const float *bias, int32_t *acc, float *out, uint32_t *next_planes,
+                 float next_clip, int next_bits, void *stream);
+
+/*
  * qnn_maxpool_planes / qnn_maxpool_levels_i8 -- max-pooling between quantized layers, taken on the
  * codes.  The linear quantizer (Table 1 range limit, Eq. 15) is monotone non-decreasing, so the
  * maximum of quantized values over a window equals the quantized maximum: pooling planes is exact.

@@ -170,6 +170,8 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
         // chunk pairs of at most 4 x 4 planes; the running sum lives in acc, or (bit for bit) in the
         // memory of out; only the last launch writes the outputs and the next layer's planes
         t.blk = blk;
+        t.pad_y = t.pad_x = d->pad;
+        t.scatter = 0, t.os = 1, t.oy0 = t.ox0 = 0, t.HO = (int)p.Ho, t.WO = (int)p.Wo, t.M_out = (int)p.M;
         const bool has_terms = blk.bias || blk.res_q || blk.res_f32;
         t.partial = acc ? acc : reinterpret_cast<int32_t *>(out);
         const int w_chunks = (d->w_bits + 3) / 4, a_chunks = (d->a_bits + 3) / 4;

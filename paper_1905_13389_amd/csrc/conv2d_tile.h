@@ -42,6 +42,12 @@ struct ConvTileParams {
     int shift, partial_mode;
     int32_t *partial;
     BlockTerms blk;
+    // BLK kernels only.  Window origin per axis: (ho stride - pad_y, wo stride - pad_x), pads may be
+    // negative.  With scatter != 0 the output pixel (b, ho, wo) of this launch is pixel
+    // (b, ho os + oy0, wo os + ox0) of a [B][HO][WO] tensor of M_out pixels: the phases of a
+    // transposed convolution interleave that way.
+    int pad_y, pad_x;
+    int scatter, os, oy0, ox0, HO, WO, M_out;
 };
 
 // Gather 4 consecutive reduction words of one output pixel.  VW = gcd(cw, 4) words share a tap;
@@ -124,6 +130,7 @@ bconv_tile_kernel(ConvTileParams p)
     const int rt_first = (int)blockIdx.x / p.tiles_n;
     const bool wvec = p.wvec != 0;
     const int taps = p.kh * p.kw;
+    const int pad_y = BLK ? p.pad_y : p.pad, pad_x = BLK ? p.pad_x : p.pad;
 
     if constexpr (BLK) {
         for (int e = tid; e < BN; e += kTileThreads)
@@ -139,11 +146,11 @@ bconv_tile_kernel(ConvTileParams p)
     for (int o = tid; o < p.Ho + p.Wo; o += kTileThreads) {
         uint32_t m = 0;
         if (o < p.Ho) {
-            const int h0 = o * p.stride - p.pad;
+            const int h0 = o * p.stride - pad_y;
             for (int ky = 0; ky < p.kh; ++ky)
                 if ((unsigned)(h0 + ky) >= (unsigned)p.H) m |= ((1u << p.kw) - 1u) << (ky * p.kw);
         } else {
-            const int w0 = (o - p.Ho) * p.stride - p.pad;
+            const int w0 = (o - p.Ho) * p.stride - pad_x;
             for (int kx = 0; kx < p.kw; ++kx)
                 if ((unsigned)(w0 + kx) >= (unsigned)p.W)
                     for (int ky = 0; ky < p.kh; ++ky) m |= 1u << (ky * p.kw + kx);
@@ -181,7 +188,7 @@ bconv_tile_kernel(ConvTileParams p)
             const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
             apad[u] = ok ? (ymask[ho] | xmask[wo]) : 0xffffffffu;
             abase[u] = (rp / BM) * p.a_plane_stride +
-                       ((int)b * p.HW + ((int)ho * p.stride - p.pad) * p.W + (int)wo * p.stride - p.pad) * p.cw;
+                       ((int)b * p.HW + ((int)ho * p.stride - pad_y) * p.W + (int)wo * p.stride - pad_x) * p.cw;
         }
     };
 
@@ -323,10 +330,17 @@ bconv_tile_kernel(ConvTileParams p)
             int32_t v[4] = {vv.x, vv.y, vv.z, vv.w};
             // padded taps of this output pixel
             uint32_t padded = 0;
+            int64_t ro = r, Mo = p.M; // pixel index in the output tensors, their pixel count
             if (rvalid) {
                 const uint32_t b = fdiv((uint32_t)r, p.div_howo), rem = (uint32_t)r - b * p.div_howo.d;
                 const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
                 padded = ymask[ho] | xmask[wo];
+                if constexpr (BLK) {
+                    if (p.scatter) {
+                        ro = ((int64_t)b * p.HO + (ho * p.os + p.oy0)) * p.WO + (wo * p.os + p.ox0);
+                        Mo = p.M_out;
+                    }
+                }
             }
             if (padded) {
                 int32_t corr[4] = {0, 0, 0, 0};
@@ -338,7 +352,7 @@ bconv_tile_kernel(ConvTileParams p)
                 for (int e = 0; e < 4; ++e) v[e] += p.top_a * corr[e];
             }
             if (p.partial_mode | p.shift) {
-                const int64_t off = (int64_t)r * p.Cout + cidx;
+                const int64_t off = ro * p.Cout + cidx;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     v[e] = (int32_t)((uint32_t)v[e] << p.shift);
@@ -379,7 +393,7 @@ bconv_tile_kernel(ConvTileParams p)
                 if (p.blk.res_f32) o[0] = o[0] + rf.x, o[1] = o[1] + rf.y, o[2] = o[2] + rf.z, o[3] = o[3] + rf.w;
             }
             if (rvalid) {
-                const int64_t off = (int64_t)r * p.Cout + cidx;
+                const int64_t off = ro * p.Cout + cidx;
                 if (cols4) {
                     if (p.acc) *reinterpret_cast<int4 *>(p.acc + off) = make_int4(v[0], v[1], v[2], v[3]);
                     if (p.out) *reinterpret_cast<float4 *>(p.out + off) = make_float4(o[0], o[1], o[2], o[3]);
@@ -407,7 +421,7 @@ bconv_tile_kernel(ConvTileParams p)
                     const uint32_t x = (cw4 >> j) & 0x01010101u;
                     const uint32_t word = or_reduce8((((x * 0x00204081u) >> 21) & 15u) << nib_shift);
                     if ((tid & 7) == 0 && rvalid && wword < p.cwo)
-                        p.next[((int64_t)j * p.M + r) * p.cwo + wword] = word;
+                        p.next[((int64_t)j * Mo + ro) * p.cwo + wword] = word;
                 }
             }
         };

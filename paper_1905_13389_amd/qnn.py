@@ -24,7 +24,8 @@ QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d", "qnn_conv2d_block",
-           "qnn_level_conv2d_block_i8", "qnn_quantize_ste_backward", "qnn_encoder_backward",
+           "qnn_level_conv2d_block_i8", "qnn_deconv_phase_words", "qnn_deconv_pack_weights", "qnn_deconv2d",
+           "qnn_quantize_ste_backward", "qnn_encoder_backward",
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
@@ -100,6 +101,12 @@ def lib():
         L.qnn_encode_levels_i8.restype = i32
         L.qnn_level_conv2d_i8.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_level_conv2d_i8.restype = i32
+        L.qnn_deconv_phase_words.argtypes = [i32, i64, i32, i32, i64, i32]
+        L.qnn_deconv_phase_words.restype = i64
+        L.qnn_deconv_pack_weights.argtypes = [vp, i32, i64, i32, i32, i64, i32, vp, vp]
+        L.qnn_deconv_pack_weights.restype = i32
+        L.qnn_deconv2d.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, vp, f32, i32, vp]
+        L.qnn_deconv2d.restype = i32
         L.qnn_quantize_ste_backward.argtypes = [vp, vp, i64, f32, vp, vp]
         L.qnn_quantize_ste_backward.restype = i32
         L.qnn_encoder_backward.argtypes = [vp, vp, i64, f32, i32, vp, vp]
@@ -299,6 +306,41 @@ def qnn_level_conv2d_block_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, s
     epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32)
     return _level_conv(lib().qnn_level_conv2d_block_i8, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
                        want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
+
+
+def qnn_deconv_pack_weights(w_planes, cin, stride, phase_planes=None):
+    """w_planes [w_bits][Cout][kh][kw][cw] -> the phase-ordered sub-kernel planes qnn_deconv2d reads (1-D int32)."""
+    w_bits, cout, kh, kw, cw = w_planes.shape
+    assert cw == (cin + 31) // 32 and w_planes.is_contiguous()
+    words = lib().qnn_deconv_phase_words(w_bits, cout, kh, kw, cin, stride)
+    if words < 0:
+        raise QnnError(QNN_ERR_INVALID_ARG, "qnn_deconv_phase_words: bad geometry")
+    if phase_planes is None:
+        phase_planes = torch.zeros((words,), dtype=torch.int32, device=w_planes.device)
+    assert phase_planes.numel() >= words
+    _check(lib().qnn_deconv_pack_weights(_ptr(w_planes), w_bits, cout, kh, kw, cin, stride, _ptr(phase_planes), _stream()))
+    return phase_planes
+
+
+def qnn_deconv2d(a_planes, phase_planes, shape, cin, cout, kh, kw, stride, pad, w_bits, scale=None, bias=None,
+                 want_acc=True, want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_planes=None):
+    """Transposed convolution of a_planes [a_bits][B*H*W][cw], shape = (B, H, W), with weights from
+    qnn_deconv_pack_weights.  Returns (acc, out, next_planes) on the [B][Ho][Wo][Cout] output."""
+    B, H, W = shape
+    a_bits = a_planes.shape[0]
+    ho, wo = (H - 1) * stride - 2 * pad + kh, (W - 1) * stride - 2 * pad + kw
+    dev = a_planes.device
+    d = qnn_conv_desc(B, H, W, cin, cout, kh, kw, stride, pad, a_bits, w_bits)
+    if want_acc and acc is None:
+        acc = torch.empty((B, ho, wo, cout), dtype=torch.int32, device=dev)
+    if want_out and out is None:
+        out = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=dev)
+    if next_clip is not None and next_planes is None:
+        next_planes = torch.empty((next_bits, B * ho * wo, (cout + 31) // 32), dtype=torch.int32, device=dev)
+    _check(lib().qnn_deconv2d(ctypes.byref(d), _ptr(a_planes), _ptr(phase_planes), _ptr(scale), _ptr(bias), _ptr(acc),
+                              _ptr(out), _ptr(next_planes), float(next_clip) if next_clip is not None else 0.0,
+                              int(next_bits), _stream()))
+    return acc, out, next_planes
 
 
 def qnn_quantize_ste_backward(x, grad_q, clip, grad_x=None):

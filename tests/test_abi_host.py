@@ -146,6 +146,40 @@ def test_block_epilogue_argument_errors(qnn):
         assert call(entry, None, desc=D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
 
 
+def test_deconv_argument_errors_and_phase_words(qnn):
+    L = qnn.lib()
+    D = qnn.qnn_conv_desc
+    # 4x4 kernel, stride 2, 64 -> 32 channels, 2 bits: 4 phases of 2x2 taps, 2*32*4*2 words each
+    assert L.qnn_deconv_phase_words(2, 32, 4, 4, 64, 2) == 4 * 2 * 32 * 4 * 2
+    # 3x3 kernel, stride 2, one word per tap: phases of 4, 2, 2, 1 taps; 3 channels -> 3, 6, 6, 12 words, each rounded up to 4
+    assert L.qnn_deconv_phase_words(1, 3, 3, 3, 5, 2) == 12 + 8 + 8 + 4
+    assert L.qnn_deconv_phase_words(0, 3, 3, 3, 5, 2) == -1
+    assert L.qnn_deconv_phase_words(1, 3, 3, 3, 5, 0) == -1
+    assert L.qnn_deconv_pack_weights(FAKE, 9, 8, 3, 3, 32, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_deconv_pack_weights(FAKE, 2, 8, 3, 3, 32, 2, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert L.qnn_deconv_pack_weights(None, 2, 8, 3, 3, 32, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_deconv_pack_weights(FAKE, 2, 8, 17, 3, 32, 2, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED
+
+    def call(desc, a=FAKE, w=FAKE, scale=None, bias=None, acc=FAKE, out=None, nxt=None, clip=0.0, nbits=0):
+        return L.qnn_deconv2d(ctypes.byref(desc) if desc is not None else None, a, w, scale, bias, acc, out, nxt,
+                              clip, nbits, None)
+
+    ok = D(1, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)
+    assert call(None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(D(1, 8, 8, 64, 32, 4, 4, 2, 1, 0, 2)) == qnn.QNN_ERR_INVALID_ARG
+    assert call(D(1, 8, 8, 64, 32, 4, 4, 2, 1, 5, 2)) == qnn.QNN_ERR_UNSUPPORTED       # more than 4 bits
+    assert call(D(1, 8, 8, 64, 32, 1, 1, 2, 0, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED       # kernel below stride
+    assert call(D(1, 1, 1, 64, 32, 2, 2, 2, 1, 2, 2)) == qnn.QNN_ERR_INVALID_ARG       # pad eats the whole output
+    assert call(ok, acc=None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(ok, out=FAKE) == qnn.QNN_ERR_INVALID_ARG                               # out without scale
+    assert call(ok, bias=FAKE) == qnn.QNN_ERR_INVALID_ARG                              # bias without scale
+    assert call(ok, scale=FAKE, nxt=FAKE, clip=1.0, nbits=9) == qnn.QNN_ERR_INVALID_ARG
+    assert call(ok, a=None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(ok, w=ODD) == qnn.QNN_ERR_ALIGNMENT
+    assert call(ok, scale=FAKE, bias=ODD) == qnn.QNN_ERR_ALIGNMENT
+    assert call(D(0, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)) == qnn.QNN_OK
+
+
 def test_training_gradient_argument_errors(qnn):
     L = qnn.lib()
     assert L.qnn_quantize_ste_backward(FAKE, FAKE, -1, 1.0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
