@@ -87,3 +87,39 @@ def test_deconv_then_conv_chain():
     assert np.array_equal(planes_to_numpy(mid), oracle.pack_planes(lv2.reshape(-1, 32), 2))
     assert np.array_equal(acc.cpu().numpy(), want)
     np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s2), rtol=RTOL, atol=0)
+
+
+def _random_geoms(seed, count):
+    gen = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        stride = int(gen.integers(1, 5))
+        kh, kw = int(gen.integers(stride, 8)), int(gen.integers(stride, 8))
+        pad = int(gen.integers(0, 4))
+        H, W = int(gen.integers(1, 9)), int(gen.integers(1, 9))
+        if (H - 1) * stride - 2 * pad + kh < 1 or (W - 1) * stride - 2 * pad + kw < 1:
+            continue
+        if -(-kh // stride) * -(-kw // stride) > 32:
+            continue
+        out.append((int(gen.integers(1, 4)), H, W, int(gen.choice([1, 31, 32, 33, 64, 100, 128])),
+                    int(gen.choice([1, 3, 32, 33, 65, 130])), kh, kw, stride, pad, int(gen.integers(1, 5)),
+                    int(gen.integers(1, 5))))
+    return out
+
+
+@pytest.mark.parametrize("geom", _random_geoms(19051, 40))
+def test_deconv_random_geometry(geom):
+    # rectangular kernels, strides up to 4, pads that crop whole phases, single-pixel images
+    B, H, W, Cin, Cout, kh, kw, stride, pad, w_bits, a_bits = geom
+    gen = np.random.default_rng(sum(x * (i + 1) for i, x in enumerate(geom)))
+    a, w = levels(gen, (B, H, W, Cin), a_bits), levels(gen, (Cout, kh, kw, Cin), w_bits)
+    s = gen.uniform(0.001, 0.01, size=Cout).astype(np.float32)
+    ph = qnn.qnn_deconv_pack_weights(pack_levels(w, w_bits).view(w_bits, Cout, kh, kw, -1), Cin, stride)
+    acc, out, nxt = qnn.qnn_deconv2d(pack_levels(a, a_bits), ph, (B, H, W), Cin, Cout, kh, kw, stride, pad, w_bits,
+                                     scale=dev(s), want_out=True, next_clip=1.0, next_bits=2)
+    torch.cuda.synchronize()
+    want = oracle.deconv2d(a, w, stride, pad)
+    assert np.array_equal(acc.cpu().numpy(), want), geom
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s), rtol=RTOL, atol=0)
+    lv, _ = oracle.quantize(oracle.scale(want, s), 1.0, 2)
+    assert np.array_equal(planes_to_numpy(nxt), oracle.pack_planes(lv.reshape(-1, Cout), 2)), geom

@@ -73,3 +73,19 @@ def test_stride_one_is_a_convolution_with_the_flipped_kernel():
     a, w = _rand((2, 5, 4, 6, 3, 3, 1, 1), 5)
     flipped = np.ascontiguousarray(w[:, ::-1, ::-1, :])
     assert np.array_equal(oracle.deconv2d(a, w, 1, 1), oracle.conv2d(a, flipped, 1, 3 - 1 - 1))
+
+
+def test_random_rectangular_geometries_against_library():
+    gen = np.random.default_rng(7)
+    for _ in range(40):
+        s = int(gen.integers(1, 5))
+        kh, kw, p = int(gen.integers(s, 8)), int(gen.integers(s, 8)), int(gen.integers(0, 4))
+        B, H, W, Cin, Cout = (int(gen.integers(1, 4)), int(gen.integers(1, 9)), int(gen.integers(1, 9)),
+                              int(gen.integers(1, 9)), int(gen.integers(1, 6)))
+        if (H - 1) * s - 2 * p + kh < 1 or (W - 1) * s - 2 * p + kw < 1:
+            continue
+        a, w = wl.odd_levels(gen, (B, H, W, Cin), 2), wl.odd_levels(gen, (Cout, kh, kw, Cin), 3)
+        x = torch.from_numpy(a.astype(np.float64)).permute(0, 3, 1, 2)
+        k = torch.from_numpy(w.astype(np.float64)).permute(3, 0, 1, 2)
+        want = torch.nn.functional.conv_transpose2d(x, k, stride=s, padding=p).permute(0, 2, 3, 1).numpy()
+        assert np.array_equal(oracle.deconv2d(a, w, s, p), want.astype(np.int64)), (B, H, W, Cin, Cout, kh, kw, s, p)
