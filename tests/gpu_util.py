@@ -1,7 +1,12 @@
 """Helpers for the GPU parity tests: numpy <-> device tensors and level packing through the
 library's own qnn_encode_pack (int8 level path)."""
+import functools
+
 import numpy as np
 import torch
+
+import oracle
+import qnn_workloads as wl
 
 from paper_1905_13389_amd import qnn
 
@@ -23,3 +28,17 @@ def pack_levels(levels_np, bits):
 def levels(gen, shape, bits):
     top = (1 << bits) - 1
     return (2 * gen.integers(0, top + 1, size=shape) - top).astype(np.int8)
+
+
+@functools.lru_cache(maxsize=None)
+def oracle_full_batch(config):
+    """The oracle's chain over the whole batch of configuration 4 ('stack4') or 5 ('stack5'), computed once
+    per test session: per resolution group, the int8 levels entering every layer and the last layer's fp32
+    output.  (The workload generators are seeded, so the tests rebuild the same inputs themselves.)"""
+    groups = [wl.resnet18_stack()] if config == "stack4" else wl.vgg_ssd_stack()
+    res = []
+    for g in groups:
+        trace = oracle.conv_stack(g["x"], g["layers"])
+        res.append(([t["levels"].astype(np.int8) for t in trace], trace[-1]["out"]))
+        del trace
+    return res

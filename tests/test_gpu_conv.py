@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import qnn_workloads as wl
-from gpu_util import dev, pack_levels, planes_to_numpy, levels
+from gpu_util import dev, pack_levels, planes_to_numpy, levels, oracle_full_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -206,37 +206,23 @@ def test_config5_vgg_ssd_stack_small_batch():
             assert np.array_equal(t["acc"].cpu().numpy(), o["acc"]), li
 
 
-def _sampled_image_rows(planes_np, images, hw):
-    # planes [bits][B*H*W][cw] -> the rows of the sampled images
-    return np.concatenate([planes_np[:, i * hw:(i + 1) * hw] for i in images], axis=1)
-
-
-def test_config4_full_batch_sampled_images():
-    # batch 256 as bench.py times it (fused epilogues only, no accumulator leaves the chip); images are
-    # independent, so the oracle chain on three of them gives their exact planes and outputs
+def test_config4_full_batch_every_image():
+    # batch 256 as bench.py times it (fused epilogues only, no accumulator leaves the chip), against the
+    # oracle's chain over the whole batch: the planes entering every layer and the final output
     c = wl.resnet18_stack()
-    images = [0, 131, 255]
     trace = _run_stack_gpu(c["x"], c["layers"], keep_acc=False)
-    want = oracle.conv_stack(c["x"][images], c["layers"])
-    H = 56
-    for li, (g, o) in enumerate(zip(trace, want)):
-        L = c["layers"][li]
-        got = _sampled_image_rows(planes_to_numpy(g["planes"]), images, H * H)
-        assert np.array_equal(got, oracle.pack_planes(o["levels"].reshape(-1, L["cin"]), 3)), li
-        H = (H + 2 * L["pad"] - 3) // L["stride"] + 1
-    np.testing.assert_allclose(trace[-1]["out"].cpu().numpy()[images], want[-1]["out"], rtol=RTOL, atol=0)
+    (want_levels, want_out), = oracle_full_batch("stack4")
+    for li, (g, lv) in enumerate(zip(trace, want_levels)):
+        assert np.array_equal(planes_to_numpy(g["planes"]), oracle.pack_planes(lv.reshape(-1, lv.shape[-1]), 3)), li
+    np.testing.assert_allclose(trace[-1]["out"].cpu().numpy(), want_out, rtol=RTOL, atol=0)
 
 
-def test_config5_full_batch_sampled_images():
+def test_config5_full_batch_every_image():
     groups = wl.vgg_ssd_stack()     # batch 32
-    images = [0, 31]
-    for g in groups:
+    for g, (want_levels, want_out) in zip(groups, oracle_full_batch("stack5")):
         trace = _run_stack_gpu(g["x"], g["layers"], keep_acc=False)
-        want = oracle.conv_stack(g["x"][images], g["layers"])
-        hw = g["x"].shape[1] * g["x"].shape[2]
-        for li, (t, o) in enumerate(zip(trace, want)):
-            got = _sampled_image_rows(planes_to_numpy(t["planes"]), images, hw)
-            assert np.array_equal(got, oracle.pack_planes(o["levels"].reshape(-1, g["layers"][li]["cin"]), 4)), li
-        np.testing.assert_allclose(trace[-1]["out"].cpu().numpy()[images], want[-1]["out"], rtol=RTOL, atol=0)
+        for li, (t, lv) in enumerate(zip(trace, want_levels)):
+            assert np.array_equal(planes_to_numpy(t["planes"]), oracle.pack_planes(lv.reshape(-1, lv.shape[-1]), 4)), li
+        np.testing.assert_allclose(trace[-1]["out"].cpu().numpy(), want_out, rtol=RTOL, atol=0)
         del trace
         torch.cuda.empty_cache()

@@ -110,9 +110,8 @@ def test_only_out_requested():
 
 @pytest.mark.parametrize("w_bits", [1, 2, 3, 4])
 @pytest.mark.parametrize("a_bits", [1, 2, 3, 4])
-def test_config2_full_size_sampled(w_bits, a_bits):
-    # 4096^3 in the launch configuration the benchmark times; oracle on 6 full rows, 6 full
-    # columns and 512 scattered outputs, plus invariants that hold for every output
+def test_config2_full_size_every_output(w_bits, a_bits):
+    # 4096^3 in the launch configuration the benchmark times, against the oracle's whole product
     size = 4096
     c = wl.gemm_square(w_bits, a_bits, size)
     a, w = c["a"], c["w"]
@@ -121,18 +120,16 @@ def test_config2_full_size_sampled(w_bits, a_bits):
     torch.cuda.synchronize()
     acc = acc.cpu().numpy()
     out = out.cpu().numpy()
+    want = oracle.gemm(a, w)
+    assert np.array_equal(acc, want)
+    # single outputs through the oracle's scalar routine, and invariants that hold for every output
     gen = np.random.default_rng(w_bits * 10 + a_bits)
-    rsel = np.concatenate([[0, size - 1], gen.integers(0, size, 4)])
-    csel = np.concatenate([[0, size - 1], gen.integers(0, size, 4)])
-    assert np.array_equal(acc[rsel], oracle.gemm(a[rsel], w))
-    assert np.array_equal(acc[:, csel], oracle.gemm(a, w[csel]))
-    for r, col in zip(gen.integers(0, size, 512), gen.integers(0, size, 512)):
+    for r, col in zip(gen.integers(0, size, 64), gen.integers(0, size, 64)):
         assert acc[r, col] == oracle.gemm_one(a[r], w[col])
     top = ((1 << w_bits) - 1) * ((1 << a_bits) - 1)
     assert np.all((acc & 1) == 0)                      # n even -> sum of n odd products is even
     assert np.abs(acc).max() <= size * top
-    np.testing.assert_allclose(out[rsel], oracle.scale(acc[rsel], c["scale"]), rtol=RTOL, atol=0)
-    assert np.array_equal(out, acc.astype(np.float32) * c["scale"][None, :])
+    np.testing.assert_allclose(out, oracle.scale(want, c["scale"]), rtol=RTOL, atol=0)
 
 
 @pytest.mark.parametrize("bits", [(5, 5), (7, 6)])

@@ -7,7 +7,7 @@ import torch
 
 import oracle
 import qnn_workloads as wl
-from gpu_util import dev, levels
+from gpu_util import dev, levels, oracle_full_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -162,25 +162,21 @@ def test_level_conv_argument_errors():
     assert e.value.code == -2          # 49 taps
 
 
-def test_config4_full_batch_levels_sampled_images():
-    # batch 256 as bench.py times the matrix-core route; the oracle chain on three of the
-    # (independent) images gives their exact levels after every layer
+def test_config4_full_batch_levels_every_image():
+    # batch 256 as bench.py times the matrix-core route, against the oracle's chain over the whole batch
     c = wl.resnet18_stack()
-    images = [0, 131, 255]
     trace = _run_stack_levels(c["x"], c["layers"], keep_acc=False)
-    want = oracle.conv_stack(c["x"][images], c["layers"])
-    for li, (g, o) in enumerate(zip(trace, want)):
-        assert np.array_equal(g["levels"][images].cpu().numpy(), _lv(o["levels"])), li
-    np.testing.assert_allclose(trace[-1]["out"][images].cpu().numpy(), want[-1]["out"], rtol=RTOL, atol=0)
+    (want_levels, want_out), = oracle_full_batch("stack4")
+    for li, (g, lv) in enumerate(zip(trace, want_levels)):
+        assert np.array_equal(g["levels"].cpu().numpy(), lv), li
+    np.testing.assert_allclose(trace[-1]["out"].cpu().numpy(), want_out, rtol=RTOL, atol=0)
 
 
-def test_config5_full_batch_levels_sampled_images():
-    images = [0, 31]
-    for g in wl.vgg_ssd_stack():
+def test_config5_full_batch_levels_every_image():
+    for g, (want_levels, want_out) in zip(wl.vgg_ssd_stack(), oracle_full_batch("stack5")):
         trace = _run_stack_levels(g["x"], g["layers"], keep_acc=False)
-        want = oracle.conv_stack(g["x"][images], g["layers"])
-        for li, (t, o) in enumerate(zip(trace, want)):
-            assert np.array_equal(t["levels"][images].cpu().numpy(), _lv(o["levels"])), li
-        np.testing.assert_allclose(trace[-1]["out"][images].cpu().numpy(), want[-1]["out"], rtol=RTOL, atol=0)
+        for li, (t, lv) in enumerate(zip(trace, want_levels)):
+            assert np.array_equal(t["levels"].cpu().numpy(), lv), li
+        np.testing.assert_allclose(trace[-1]["out"].cpu().numpy(), want_out, rtol=RTOL, atol=0)
         del trace
         torch.cuda.empty_cache()
