@@ -151,7 +151,7 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
     bool done = false;
     const bool wide = d->w_bits > 4 || d->a_bits > 4;
     if (p.nw <= kMaxGroups && d->kh * d->kw <= kMaxTaps && small_index && (!wide || acc || out)) {
-        ConvTileParams t;
+        ConvTileParams t = {};
         t.a = a_planes, t.w = w_planes, t.scale = scale, t.acc = acc, t.out = out, t.next = next_planes;
         t.H = (int)d->H, t.W = (int)d->W, t.HW = (int)(d->H * d->W), t.Cin = (int)d->Cin, t.Cout = (int)d->Cout;
         t.M = (int)p.M, t.cw = (int)p.cw, t.nw = (int)p.nw, t.cwo = (int)cwo, t.Ho = (int)p.Ho, t.Wo = (int)p.Wo;
@@ -171,6 +171,7 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
         // memory of out; only the last launch writes the outputs and the next layer's planes
         t.blk = blk;
         t.pad_y = t.pad_x = d->pad;
+        t.nphase = 1, t.wgs_per_phase = 0, t.phase_words = 0;
         t.scatter = 0, t.os = 1, t.oy0 = t.ox0 = 0, t.HO = (int)p.Ho, t.WO = (int)p.Wo, t.M_out = (int)p.M;
         const bool has_terms = blk.bias || blk.res_q || blk.res_f32;
         t.partial = acc ? acc : reinterpret_cast<int32_t *>(out);

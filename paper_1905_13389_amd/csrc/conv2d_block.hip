@@ -166,6 +166,31 @@ extern "C" int qnn_deconv2d(const qnn_conv_desc *d, const uint32_t *a_planes, co
     t.next_half_top = (float)t.next_top * 0.5f;
     t.blk.bias = bias;
     t.scatter = 1, t.os = s, t.HO = (int)HO, t.WO = (int)WO, t.M_out = (int)(d->B * HO * WO);
+    t.nphase = 1;
+    // Phases of one shape (kernel extents and output extents multiples of the stride: the usual
+    // upsampling layers) run as one launch, the resident workgroups divided among them.
+    if (s > 1 && d->kh % s == 0 && d->kw % s == 0 && HO % s == 0 && WO % s == 0) {
+        const PhaseAxis ay0 = phase_axis(0, d->kh, s, d->pad, HO), ax0 = phase_axis(0, d->kw, s, d->pad, WO);
+        const int64_t words = phase_words(d->w_bits, d->Cout, ay0.taps, ax0.taps, (int)cw);
+        if (words * s * s < (1LL << 31)) {
+            ConvTileParams q = t;
+            q.w = phase_planes;
+            q.nphase = s * s, q.phase_words = (int)words;
+            for (int f = 0; f < s; ++f) {
+                const PhaseAxis ay = phase_axis(f, d->kh, s, d->pad, HO), ax = phase_axis(f, d->kw, s, d->pad, WO);
+                q.ph_pad_y[f] = ay.pad, q.ph_first_y[f] = ay.first, q.ph_pad_x[f] = ax.pad, q.ph_first_x[f] = ax.first;
+            }
+            q.kh = ay0.taps, q.kw = ax0.taps;
+            q.nw = (int)(ay0.taps * ax0.taps * cw);
+            q.wvec = q.nw % 4 == 0 ? 1 : 0;
+            q.Ho = ay0.count, q.Wo = ax0.count, q.M = (int)(d->B * ay0.count * ax0.count);
+            q.n_times_top = (uint32_t)((int64_t)ay0.taps * ax0.taps * d->Cin * ((1 << d->w_bits) - 1) * q.top_a);
+            q.div_howo = make_fastdiv((uint32_t)(ay0.count * ax0.count));
+            q.div_wo = make_fastdiv((uint32_t)ax0.count);
+            const int rc = conv_dispatch<true>(d->w_bits, d->a_bits, q, st);
+            return rc != QNN_OK ? rc : check_launch("qnn_deconv2d");
+        }
+    }
     int64_t w_off = 0;
     for (int fy = 0; fy < s; ++fy)
         for (int fx = 0; fx < s; ++fx) {

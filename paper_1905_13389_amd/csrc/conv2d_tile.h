@@ -48,6 +48,12 @@ struct ConvTileParams {
     // transposed convolution interleave that way.
     int pad_y, pad_x;
     int scatter, os, oy0, ox0, HO, WO, M_out;
+    // nphase > 1: one launch runs all os x os phases of a transposed convolution whose phases have the
+    // same shape; workgroup b belongs to phase b / wgs_per_phase = fy os + fx, whose weights start
+    // phase_words further on and whose window origin and first output coordinate per axis come
+    // from the tables (pad_y, pad_x, oy0, ox0 above are then unused).
+    int nphase, wgs_per_phase, phase_words;
+    int ph_pad_y[8], ph_pad_x[8], ph_first_y[8], ph_first_x[8];
 };
 
 // Gather 4 consecutive reduction words of one output pixel.  VW = gcd(cw, 4) words share a tap;
@@ -126,11 +132,22 @@ bconv_tile_kernel(ConvTileParams p)
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
-    const int col0 = ((int)blockIdx.x % p.tiles_n) * BN;
-    const int rt_first = (int)blockIdx.x / p.tiles_n;
+    int bid = (int)blockIdx.x;
+    const uint32_t *wbase = p.w;
+    int pad_y = BLK ? p.pad_y : p.pad, pad_x = BLK ? p.pad_x : p.pad, oy0 = 0, ox0 = 0;
+    if constexpr (BLK) {
+        oy0 = p.oy0, ox0 = p.ox0;
+        if (p.nphase > 1) {
+            const int ph = bid / p.wgs_per_phase, fy = ph / p.os, fx = ph - fy * p.os;
+            bid -= ph * p.wgs_per_phase;
+            wbase += (int64_t)ph * p.phase_words;
+            pad_y = p.ph_pad_y[fy], pad_x = p.ph_pad_x[fx], oy0 = p.ph_first_y[fy], ox0 = p.ph_first_x[fx];
+        }
+    }
+    const int col0 = (bid % p.tiles_n) * BN;
+    const int rt_first = bid / p.tiles_n;
     const bool wvec = p.wvec != 0;
     const int taps = p.kh * p.kw;
-    const int pad_y = BLK ? p.pad_y : p.pad, pad_x = BLK ? p.pad_x : p.pad;
 
     if constexpr (BLK) {
         for (int e = tid; e < BN; e += kTileThreads)
@@ -164,7 +181,7 @@ bconv_tile_kernel(ConvTileParams p)
         int32_t s = 0;
         if (c < p.Cout) {
             for (int i = 0; i < WB; ++i) {
-                const uint32_t *wp = p.w + ((int64_t)i * p.Cout + c) * p.nw + t * p.cw;
+                const uint32_t *wp = wbase + ((int64_t)i * p.Cout + c) * p.nw + t * p.cw;
                 int32_t cnt = 0;
                 for (int k = 0; k < p.cw; ++k) cnt += __builtin_popcount(wp[k]);
                 s += (2 * cnt - p.Cin) << i;
@@ -208,7 +225,7 @@ bconv_tile_kernel(ConvTileParams p)
             const int rp = idx / UQ, q = idx % UQ;
             rw[u] = make_uint4(0u, 0u, 0u, 0u);
             if ((T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS) && 4 * q < p.kb)
-                rw[u] = load_rowmajor4(p.w, p.Cout, p.nw, rp / BN, col0 + rp % BN, k0 + 4 * q, wvec);
+                rw[u] = load_rowmajor4(wbase, p.Cout, p.nw, rp / BN, col0 + rp % BN, k0 + 4 * q, wvec);
         }
     };
     auto stash = [&](int buf) {
@@ -337,7 +354,7 @@ bconv_tile_kernel(ConvTileParams p)
                 padded = ymask[ho] | xmask[wo];
                 if constexpr (BLK) {
                     if (p.scatter) {
-                        ro = ((int64_t)b * p.HO + (ho * p.os + p.oy0)) * p.WO + (wo * p.os + p.ox0);
+                        ro = ((int64_t)b * p.HO + (ho * p.os + oy0)) * p.WO + (wo * p.os + ox0);
                         Mo = p.M_out;
                     }
                 }
@@ -479,11 +496,13 @@ template <int WB, int AB, int VW, bool BLK> static int launch_conv_vw(ConvTilePa
         if (slots <= 0) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: occupancy query failed");
         // every workgroup owns one column tile; the row tiles are dealt round-robin to the
         // slots / tiles_n workgroups of that column
-        int groups = slots / p.tiles_n;
+        const int phases = BLK && p.nphase > 1 ? p.nphase : 1; // phases of one launch share the slots
+        int groups = slots / (p.tiles_n * phases);
         if (groups < 1) groups = 1;
         if (groups > p.tiles_m) groups = p.tiles_m;
         p.row_tile_step = groups;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n)), dim3(kTileThreads), dyn, st, p);
+        p.wgs_per_phase = groups * p.tiles_n;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n * phases)), dim3(kTileThreads), dyn, st, p);
         return (int)QNN_OK;
     };
     if (p.nchunks == 1) return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, true, BLK>);
