@@ -210,11 +210,56 @@ def conv_workload(args):
     m_ms = (time.perf_counter() - t0) / args.steps * 1e3
     int8_tops = 2.0 * macs / (m_ms * 1e-3) / 1e12
 
+    # 1- and 2-bit chains also run on the fp4 matrix-core path: two levels per byte, twice the products per clock
+    fp4 = None
+    if all(L["a_bits"] <= 2 and L["w_bits"] <= 2 for g in groups for L in g["layers"]):
+        fplans = []
+        for g in groups:
+            B, H, W, C = g["x"].shape
+            d_x = torch.from_numpy(g["x"]).cuda()
+            lv = torch.empty((B, H, W, C // 2), dtype=torch.uint8, device="cuda")
+            first, fsteps = lv, []
+            for li, L in enumerate(g["layers"]):
+                ho = (H + 2 * L["pad"] - 3) // L["stride"] + 1
+                wo = (W + 2 * L["pad"] - 3) // L["stride"] + 1
+                last = li + 1 == len(g["layers"])
+                nxt = None if last else torch.empty((B, ho, wo, L["cout"] // 2), dtype=torch.uint8, device="cuda")
+                out = torch.empty((B, ho, wo, L["cout"]), dtype=torch.float32, device="cuda") if last else None
+                fsteps.append((lv, qnn.qnn_levels_to_fp4(torch.from_numpy(L["w"]).cuda()), L,
+                               torch.from_numpy(L["scale"]).cuda(), out, nxt, None if last else g["layers"][li + 1]))
+                lv, H, W = nxt, ho, wo
+            fplans.append((d_x, g["layers"][0], first, fsteps))
+
+        def fp4_step():
+            for d_x, L0, first, fsteps in fplans:
+                qnn.qnn_encode_levels_fp4(d_x, L0["clip"], L0["a_bits"], levels=first)
+                for lv, w, L, sc, out, nxt, Ln in fsteps:
+                    qnn.qnn_level_conv2d_fp4(lv, w, L["stride"], L["pad"], L["a_bits"], L["w_bits"], scale=sc,
+                                             want_acc=False, want_out=out is not None, out=out,
+                                             next_clip=None if Ln is None else Ln["clip"],
+                                             next_bits=0 if Ln is None else Ln["a_bits"], next_levels=nxt)
+
+        for _ in range(args.warmup):
+            fp4_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fp4_step()
+        torch.cuda.synchronize()
+        f_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        fp4_tops = 2.0 * macs / (f_ms * 1e-3) / 1e12
+        fp4 = {"step": "qnn_encode_levels_fp4 + qnn_level_conv2d_fp4 per layer (fused scale/quantize epilogue)",
+               "ms_per_step": round(f_ms, 4), "effective_binary_tops": round(binops / (f_ms * 1e-3) / 1e12, 1),
+               "speedup_vs_xor_bitcount_step": round(ms / f_ms, 2),
+               "roofline": {"bound": "mfma", "achieved": round(fp4_tops, 1), "peak": 10100.0, "unit": "fp4 TFLOP/s",
+                            "frac": round(fp4_tops / 10100.0, 4), "note": "whole step, not a single kernel"}}
+
     print(json.dumps({
         "metric": "effective binary TOPS (xnor+popcount) and % of VALU/HBM roofline, 1 MI355X", "value": round(tops, 2),
         "unit": "binary TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+        "fp4_variant": fp4,
         "config": {"workload": name, "macs": macs,
                    "step": "qnn_encode_pack + qnn_conv2d per layer (fused scale/quantize/pack epilogue)"},
         "roofline": {"bound": "alu", "achieved": round(tops, 2), "peak": round(PEAK_BINARY_TOPS, 1),

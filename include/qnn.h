@@ -297,6 +297,27 @@ int qnn_level_conv2d_block_i8(const qnn_conv_desc *desc, const int8_t *a_levels,
                               int8_t *next_levels, float next_clip, int next_bits, void *stream);
 
 /*
+ * The decoded-level convolution for 1- and 2-bit codes on the fp4 matrix-core path (as
+ * qnn_level_gemm_fp4: the levels -3, -1, +1, +3 are exact fp4 values, fp32 accumulates their products
+ * exactly while 9 kh kw Cin < 2^24).  Level tensors hold two channels per byte, channel 2i in the low
+ * nibble of byte i, nibble = sign << 3 | E2M1 magnitude (1 = 0b0010, 3 = 0b0101).
+ *
+ * qnn_encode_levels_fp4: as qnn_encode_levels_i8 (bits 1 or 2, count even) -> DEVICE uint8 [count / 2].
+ * qnn_levels_to_fp4: int8 levels (odd, |level| <= 3) DEVICE [count], count even -> DEVICE uint8 [count / 2]
+ *     (weights, once per layer).
+ * qnn_level_conv2d_fp4: as qnn_level_conv2d_i8 with a_levels DEVICE uint8 [B][H][W][Cin / 2], w_levels
+ *     DEVICE uint8 [Cout][kh][kw][Cin / 2], next_levels DEVICE out uint8 [B][Ho][Wo][Cout / 2]; acc is the
+ *     exact int32 value.  QNN_ERR_UNSUPPORTED unless a_bits, w_bits <= 2, Cin is a multiple of 32 and (with
+ *     next_levels) Cout is even; QNN_ERR_RANGE beyond the exact range of fp32 accumulation.
+ */
+int qnn_encode_levels_fp4(const void *src, int dtype, int64_t count, float clip, int bits, uint8_t *levels,
+                          void *stream);
+int qnn_levels_to_fp4(const int8_t *levels, int64_t count, uint8_t *fp4, void *stream);
+int qnn_level_conv2d_fp4(const qnn_conv_desc *desc, const uint8_t *a_levels, const uint8_t *w_levels,
+                         const float *scale, int32_t *acc, float *out, uint8_t *next_levels,
+                         float next_clip, int next_bits, void *stream);
+
+/*
  * qnn_probe_valu -- measurement aid, not part of the hot path: launches `workgroups` workgroups
  * of 256 lanes that each run `iters` iterations of a register-only loop of 64 VALU instructions
  * per wave, so that the issue rate of the binary dot product's two instructions (the "xnor" and

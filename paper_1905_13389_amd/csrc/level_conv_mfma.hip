@@ -15,7 +15,17 @@
 namespace qnn {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// A level of a 1- or 2-bit code (-3, -1, +1, +3) as an fp4 (E2M1) nibble: sign << 3 | magnitude code
+// (1 = 0b0010, 3 = 0b0101); these values are exact in fp4.
+__device__ __forceinline__ uint32_t fp4_nibble(int level)
+{
+    const int mag = level < 0 ? -level : level;
+    return (level < 0 ? 8u : 0u) | (mag == 3 ? 5u : 2u);
+}
 
 // ---------------------------------------------------------------------------------------------
 // fp32 / bf16 values -> int8 levels, elementwise: level = 2u - (2^bits - 1) with the code u of the
@@ -27,12 +37,12 @@ struct EncodeLevelParams {
     int64_t count;
     float inv_clip, half_top;
     int top;
-    int8_t *levels;
+    int8_t *levels; // int8 per element, or (FP4) one nibble per element, element 2i in the low nibble of byte i
 };
 
 __device__ __forceinline__ float widen_bf16(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
 
-template <bool BF16> __global__ __launch_bounds__(256) void encode_levels_kernel(EncodeLevelParams p)
+template <bool BF16, bool FP4> __global__ __launch_bounds__(256) void encode_levels_kernel(EncodeLevelParams p)
 {
     const int64_t groups = (p.count + 15) / 16;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -70,12 +80,43 @@ template <bool BF16> __global__ __launch_bounds__(256) void encode_levels_kernel
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int lv = 2 * quantize_code(x[i], p.inv_clip, p.half_top, p.top) - p.top;
-            o[i >> 2] |= ((uint32_t)lv & 0xffu) << (8 * (i & 3));
+            if (FP4) o[i >> 3] |= fp4_nibble(lv) << (4 * (i & 7));
+            else o[i >> 2] |= ((uint32_t)lv & 0xffu) << (8 * (i & 3));
         }
-        if (e0 + 16 <= p.count) {
+        if constexpr (FP4) {
+            // count is even (checked on the host): whole bytes
+            uint8_t *dst = reinterpret_cast<uint8_t *>(p.levels) + e0 / 2;
+            if (e0 + 16 <= p.count) {
+                *reinterpret_cast<uint2 *>(dst) = make_uint2(o[0], o[1]);
+            } else {
+                for (int i = 0; i < 8 && e0 + 2 * i < p.count; ++i) dst[i] = (uint8_t)(o[i >> 2] >> (8 * (i & 3)));
+            }
+        } else if (e0 + 16 <= p.count) {
             *reinterpret_cast<uint4 *>(p.levels + e0) = make_uint4(o[0], o[1], o[2], o[3]);
         } else {
             for (int i = 0; i < 16 && e0 + i < p.count; ++i) p.levels[e0 + i] = (int8_t)(o[i >> 2] >> (8 * (i & 3)));
+        }
+    }
+}
+
+// int8 levels of 1- or 2-bit codes -> fp4 nibbles, 16 elements per lane (weights, once per layer)
+__global__ __launch_bounds__(256) void levels_to_fp4_kernel(const int8_t *__restrict__ src, int64_t count,
+                                                            uint8_t *__restrict__ dst)
+{
+    const int64_t groups = (count + 15) / 16, stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += stride) {
+        const int64_t e0 = g * 16;
+        if (e0 + 16 <= count) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(src + e0);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            uint32_t o[2] = {0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                o[i >> 3] |= fp4_nibble((int)(int8_t)(w[i >> 2] >> (8 * (i & 3)))) << (4 * (i & 7));
+            *reinterpret_cast<uint2 *>(dst + e0 / 2) = make_uint2(o[0], o[1]);
+        } else {
+            for (int64_t e = e0; e < count; e += 2) // count is even
+                dst[e / 2] = (uint8_t)(fp4_nibble(src[e]) | (fp4_nibble(src[e + 1]) << 4));
         }
     }
 }
@@ -128,7 +169,11 @@ struct LevelConvParams {
 // workgroups per CU, no half-empty last stage at kh kw Cin = 576)
 // The 256 x 64 block runs three workgroups per CU (one wave each per SIMD): its register budget is
 // held to a third of the file.
-template <int MB, int NB, int WM, int WN, int KB>
+// FP4: both operands hold fp4 levels, two per byte (1- and 2-bit codes); the byte-level addressing is
+// the same with Cin / 2 bytes per pixel, the product is v_mfma_scale_f32_32x32x64_f8f6f4 with unit
+// scales (64 values per 32-byte k step), accumulated in fp32 -- exact, the host bounds the sums by
+// 2^24 -- and the next layer's levels leave as nibbles.
+template <int MB, int NB, int WM, int WN, int KB, bool FP4>
 __global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(MB == 256 && NB == 64 ? 3 : 1))) void
 level_conv_mfma_kernel(LevelConvParams p)
 {
@@ -162,7 +207,8 @@ level_conv_mfma_kernel(LevelConvParams p)
         tap_table[u] = e;
     }
 
-    v16i acc[TM][TN];
+    using Acc = typename std::conditional<FP4, v16f, v16i>::type;
+    Acc acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -235,7 +281,16 @@ level_conv_mfma_kernel(LevelConvParams p)
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
             __builtin_amdgcn_sched_barrier(0);
-            acc[m / TN][m % TN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][m / TN], bf[b][m % TN], acc[m / TN][m % TN], 0, 0, 0);
+            if constexpr (FP4) {
+                // the builtin takes 8 registers per operand and uses the first 4 for fp4: the rest stay undefined;
+                // cbsz = blgp = 4: both operands fp4; scale bytes 127 = 2^0
+                const v4i x = af[b][m / TN], y = bf[b][m % TN];
+                const v8i x8 = __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1);
+                const v8i y8 = __builtin_shufflevector(y, y, 0, 1, 2, 3, -1, -1, -1, -1);
+                acc[m / TN][m % TN] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(x8, y8, acc[m / TN][m % TN], 4, 4, 0, 127, 0, 127);
+            } else {
+                acc[m / TN][m % TN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[b][m / TN], bf[b][m % TN], acc[m / TN][m % TN], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = m; r < NR; r += NM) read_one(next_stage, next_ks, b ^ 1, r);
@@ -340,7 +395,7 @@ level_conv_mfma_kernel(LevelConvParams p)
                 for (int r = 0; r < 16; ++r) {
                     const int rl = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     if (row0 + rl >= p.pixels) continue;
-                    const int32_t v = acc[i][j][r];
+                    const int32_t v = (int32_t)acc[i][j][r]; // fp4: an integer-valued float
                     const int64_t o = (int64_t)(row0 + rl) * p.Cout + c;
                     if (p.acc) p.acc[o] = v;
                     if (p.out) p.out[o] = block_y(v, sc, bi, rl * NB + cl, o);
@@ -361,7 +416,7 @@ level_conv_mfma_kernel(LevelConvParams p)
                     const int rl = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     // rows past the last pixel and columns past Cout are never stored: any in-range address does
                     const int row = row0 + rl < p.pixels ? row0 + rl : p.pixels - 1;
-                    const float y = block_y(acc[i][j][r], sc, bi, rl * NB + cl, (int64_t)row * p.Cout + c);
+                    const float y = block_y((int32_t)acc[i][j][r], sc, bi, rl * NB + cl, (int64_t)row * p.Cout + c);
                     lv[rl * NB + cl] =
                         (uint8_t)(2 * quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) - p.next_top);
                 }
@@ -374,24 +429,38 @@ level_conv_mfma_kernel(LevelConvParams p)
             const int row = row0 + rl, c = col0 + cv;
             if (row >= p.pixels || c >= p.Cout) continue;
             const uint4 val = *reinterpret_cast<const uint4 *>(lv + rl * NB + cv);
+            const uint32_t w4[4] = {val.x, val.y, val.z, val.w};
+            if constexpr (FP4) {
+                // 16 levels -> 16 nibbles = 8 bytes; Cout is even (checked on the host)
+                uint32_t o[2] = {0u, 0u};
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    o[e >> 3] |= fp4_nibble((int)(int8_t)(w4[e >> 2] >> (8 * (e & 3)))) << (4 * (e & 7));
+                uint8_t *dst = reinterpret_cast<uint8_t *>(p.next) + ((int64_t)row * p.Cout + c) / 2;
+                if (c + 16 <= p.Cout && (p.Cout & 15) == 0) {
+                    *reinterpret_cast<uint2 *>(dst) = make_uint2(o[0], o[1]);
+                } else {
+                    for (int e = 0; e < 8 && c + 2 * e < p.Cout; ++e) dst[e] = (uint8_t)(o[e >> 2] >> (8 * (e & 3)));
+                }
+                continue;
+            }
             int8_t *dst = p.next + (int64_t)row * p.Cout + c;
             if (c + 16 <= p.Cout && (p.Cout & 15) == 0) {
                 *reinterpret_cast<uint4 *>(dst) = val;
             } else {
-                const uint32_t w4[4] = {val.x, val.y, val.z, val.w};
                 for (int e = 0; e < 16 && c + e < p.Cout; ++e) dst[e] = (int8_t)(w4[e >> 2] >> (8 * (e & 3)));
             }
         }
     }
 }
 
-template <int MB, int NB, int WM, int WN, int KB> int launch_level_conv(LevelConvParams &p, hipStream_t st)
+template <int MB, int NB, int WM, int WN, int KB, bool FP4 = false> int launch_level_conv(LevelConvParams &p, hipStream_t st)
 {
     p.nstages = (int)ceil_div(p.nk, KB);
     const int64_t tiles_m = ceil_div(p.pixels, MB), tiles_n = ceil_div(p.Cout, NB);
     if (tiles_m * tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_conv2d_i8: too many tiles");
     p.tiles_n = (int)tiles_n;
-    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN, KB>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN),
+    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN, KB, FP4>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN),
                        0, st, p);
     return check_launch("qnn_level_conv2d_i8");
 }
@@ -400,96 +469,116 @@ template <int MB, int NB, int WM, int WN, int KB> int launch_level_conv(LevelCon
 
 using namespace qnn;
 
-extern "C" int qnn_encode_levels_i8(const void *src, int dtype, int64_t count, float clip, int bits, int8_t *levels,
-                                    void *stream)
+static int encode_levels_run(const char *who, bool fp4, const void *src, int dtype, int64_t count, float clip, int bits,
+                             void *levels, void *stream)
 {
+    const int max_bits = fp4 ? 2 : 7;
     if (dtype != QNN_DTYPE_F32 && dtype != QNN_DTYPE_BF16)
-        return fail(QNN_ERR_UNSUPPORTED, "qnn_encode_levels_i8: dtype %d (fp32 or bf16 only)", dtype);
-    if (bits < 1 || bits > 7) return fail(QNN_ERR_INVALID_ARG, "qnn_encode_levels_i8: bits=%d outside [1,7]", bits);
-    if (count < 0) return fail(QNN_ERR_INVALID_ARG, "qnn_encode_levels_i8: negative size");
-    if (!(clip > 0.0f && clip <= 3.0e38f))
-        return fail(QNN_ERR_INVALID_ARG, "qnn_encode_levels_i8: clip must be positive and finite");
+        return fail(QNN_ERR_UNSUPPORTED, "%s: dtype %d (fp32 or bf16 only)", who, dtype);
+    if (bits < 1 || bits > max_bits) return fail(QNN_ERR_INVALID_ARG, "%s: bits=%d outside [1,%d]", who, bits, max_bits);
+    if (count < 0 || (fp4 && count % 2 != 0)) return fail(QNN_ERR_INVALID_ARG, "%s: bad size", who);
+    if (!(clip > 0.0f && clip <= 3.0e38f)) return fail(QNN_ERR_INVALID_ARG, "%s: clip must be positive and finite", who);
     if (count == 0) return QNN_OK;
-    if (!src || !levels) return fail(QNN_ERR_INVALID_ARG, "qnn_encode_levels_i8: NULL pointer");
-    if (!aligned16(src) || !aligned16(levels))
-        return fail(QNN_ERR_ALIGNMENT, "qnn_encode_levels_i8: pointers must be 16-byte aligned");
+    if (!src || !levels) return fail(QNN_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    if (!aligned16(src) || !aligned16(levels)) return fail(QNN_ERR_ALIGNMENT, "%s: pointers must be 16-byte aligned", who);
     EncodeLevelParams p;
-    p.src = src, p.count = count, p.levels = levels;
+    p.src = src, p.count = count, p.levels = static_cast<int8_t *>(levels);
     p.top = (1 << bits) - 1;
     p.half_top = (float)p.top * 0.5f;
     p.inv_clip = 1.0f / clip;
     const int64_t blocks = ceil_div(ceil_div(count, 16), 256);
     const dim3 grid((unsigned)(blocks < 256 * 64 ? blocks : 256 * 64)), block(256);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dtype == QNN_DTYPE_BF16) hipLaunchKernelGGL(encode_levels_kernel<true>, grid, block, 0, st, p);
-    else hipLaunchKernelGGL(encode_levels_kernel<false>, grid, block, 0, st, p);
-    return check_launch("qnn_encode_levels_i8");
+    const bool bf16 = dtype == QNN_DTYPE_BF16;
+    if (fp4 && bf16) hipLaunchKernelGGL((encode_levels_kernel<true, true>), grid, block, 0, st, p);
+    else if (fp4) hipLaunchKernelGGL((encode_levels_kernel<false, true>), grid, block, 0, st, p);
+    else if (bf16) hipLaunchKernelGGL((encode_levels_kernel<true, false>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((encode_levels_kernel<false, false>), grid, block, 0, st, p);
+    return check_launch(who);
 }
 
-extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
-                                   const float *scale, int32_t *acc, float *out, int8_t *next_levels,
-                                   float next_clip, int next_bits, void *stream)
+extern "C" int qnn_encode_levels_i8(const void *src, int dtype, int64_t count, float clip, int bits, int8_t *levels,
+                                    void *stream)
 {
-    return qnn_level_conv2d_block_i8(d, a_levels, w_levels, scale, nullptr, acc, out, next_levels, next_clip, next_bits,
-                                     stream);
+    return encode_levels_run("qnn_encode_levels_i8", false, src, dtype, count, clip, bits, levels, stream);
 }
 
-extern "C" int qnn_level_conv2d_block_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
-                                         const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
-                                         int8_t *next_levels, float next_clip, int next_bits, void *stream)
+extern "C" int qnn_encode_levels_fp4(const void *src, int dtype, int64_t count, float clip, int bits, uint8_t *levels,
+                                     void *stream)
 {
-    if (!d) return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: NULL descriptor");
+    return encode_levels_run("qnn_encode_levels_fp4", true, src, dtype, count, clip, bits, levels, stream);
+}
+
+// fp4: the operands and next_levels hold two levels per byte (1- and 2-bit codes); the kernel then sees
+// Cin / 2 bytes per pixel
+static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
+                          const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                          int8_t *next_levels, float next_clip, int next_bits, void *stream)
+{
+    const int max_bits = fp4 ? 2 : 7;
+    if (!d) return fail(QNN_ERR_INVALID_ARG, "%s: NULL descriptor", who);
     BlockTerms blk;
-    const int brc = block_terms("qnn_level_conv2d_block_i8", epi, scale, 7, blk);
+    const int brc = block_terms(who, epi, scale, 7, blk);
     if (brc != QNN_OK) return brc;
-    if (d->a_bits < 1 || d->a_bits > 7 || d->w_bits < 1 || d->w_bits > 7)
-        return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: bits must be in [1,7] (int8 levels)");
+    const int hard_bits = fp4 ? 8 : 7; // int8 levels hold 7 bits; wider fp4 requests are valid codes that fp4 cannot hold
+    if (d->a_bits < 1 || d->a_bits > hard_bits || d->w_bits < 1 || d->w_bits > hard_bits)
+        return fail(QNN_ERR_INVALID_ARG, "%s: bits must be in [1,%d]", who, hard_bits);
+    if (d->a_bits > max_bits || d->w_bits > max_bits)
+        return fail(QNN_ERR_UNSUPPORTED, "%s: more than %d bits (%s levels)", who, max_bits, fp4 ? "fp4" : "int8");
+    if (fp4 && (blk.bias || blk.res_q || blk.res_f32))
+        return fail(QNN_ERR_UNSUPPORTED, "%s: residual-block terms are not built for fp4 levels", who);
     if (d->B < 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0)
-        return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: bad tensor size");
+        return fail(QNN_ERR_INVALID_ARG, "%s: bad tensor size", who);
     if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
-        return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: bad kernel geometry");
+        return fail(QNN_ERR_INVALID_ARG, "%s: bad kernel geometry", who);
     if (d->H + 2 * (int64_t)d->pad < d->kh || d->W + 2 * (int64_t)d->pad < d->kw)
-        return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: kernel larger than the padded image");
-    if (!acc && !out && !next_levels) return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: no output requested");
+        return fail(QNN_ERR_INVALID_ARG, "%s: kernel larger than the padded image", who);
+    if (!acc && !out && !next_levels) return fail(QNN_ERR_INVALID_ARG, "%s: no output requested", who);
     if ((out || next_levels) && !scale)
-        return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: out / next_levels given without scale");
-    if (next_levels && (next_bits < 1 || next_bits > 7))
-        return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: next_bits=%d outside [1,7]", next_bits);
+        return fail(QNN_ERR_INVALID_ARG, "%s: out / next_levels given without scale", who);
+    if (next_levels && (next_bits < 1 || next_bits > max_bits))
+        return fail(QNN_ERR_INVALID_ARG, "%s: next_bits=%d outside [1,%d]", who, next_bits, max_bits);
     if (next_levels && !(next_clip > 0.0f && next_clip <= 3.0e38f))
-        return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: next_clip must be positive and finite");
-    if (d->Cin % 16 != 0)
-        return fail(QNN_ERR_UNSUPPORTED, "qnn_level_conv2d_i8: Cin=%lld is not a multiple of 16", (long long)d->Cin);
+        return fail(QNN_ERR_INVALID_ARG, "%s: next_clip must be positive and finite", who);
+    if (d->Cin % (fp4 ? 32 : 16) != 0)
+        return fail(QNN_ERR_UNSUPPORTED, "%s: Cin=%lld is not a multiple of %d", who, (long long)d->Cin, fp4 ? 32 : 16);
+    if (fp4 && next_levels && d->Cout % 2 != 0)
+        return fail(QNN_ERR_UNSUPPORTED, "%s: fp4 next_levels need an even Cout", who);
+    const int64_t cinb = fp4 ? d->Cin / 2 : d->Cin; // bytes per pixel
     if ((int64_t)d->kh * d->kw > kMaxMfmaTaps)
-        return fail(QNN_ERR_UNSUPPORTED, "qnn_level_conv2d_i8: more than %d taps", kMaxMfmaTaps);
-    const int64_t nk = (int64_t)d->kh * d->kw * d->Cin;
+        return fail(QNN_ERR_UNSUPPORTED, "%s: more than %d taps", who, kMaxMfmaTaps);
+    const int64_t nk = (int64_t)d->kh * d->kw * cinb; // bytes of the reduction axis
     if (ceil_div(nk, 128) * 8 > kMaxUnits)
-        return fail(QNN_ERR_UNSUPPORTED, "qnn_level_conv2d_i8: reduction axis of %lld bytes (limit %d)", (long long)nk,
+        return fail(QNN_ERR_UNSUPPORTED, "%s: reduction axis of %lld bytes (limit %d)", who, (long long)nk,
                     kMaxUnits * 16);
-    if (!acc_fits_int32(nk, d->w_bits, d->a_bits))
-        return fail(QNN_ERR_RANGE, "qnn_level_conv2d_i8: reduction length %lld with %dx%d bits overflows int32",
-                    (long long)nk, d->w_bits, d->a_bits);
+    const int64_t n = (int64_t)d->kh * d->kw * d->Cin;
+    if (!acc_fits_int32(n, d->w_bits, d->a_bits))
+        return fail(QNN_ERR_RANGE, "%s: reduction length %lld with %dx%d bits overflows int32", who, (long long)n,
+                    d->w_bits, d->a_bits);
+    if (fp4 && n * ((1 << d->w_bits) - 1) * ((1 << d->a_bits) - 1) >= (1LL << 24))
+        return fail(QNN_ERR_RANGE, "%s: reduction length %lld exceeds the exact range of fp32 accumulation", who, (long long)n);
     const int64_t Ho = (d->H + 2 * (int64_t)d->pad - d->kh) / d->stride + 1;
     const int64_t Wo = (d->W + 2 * (int64_t)d->pad - d->kw) / d->stride + 1;
     // the kernel indexes both tensors and the output pixels with 32-bit integers
-    if (d->H > (1 << 20) || d->W > (1 << 20) || d->B > (1LL << 31) / (d->H * d->W * d->Cin) - 1 ||
+    if (d->H > (1 << 20) || d->W > (1 << 20) || d->B > (1LL << 31) / (d->H * d->W * cinb) - 1 ||
         d->B * Ho * Wo >= (1LL << 31) - 1024 || d->Cout * nk >= (1LL << 31) ||
-        ((int64_t)d->kh * d->W + d->kw) * d->Cin >= (1LL << 24))
-        return fail(QNN_ERR_RANGE, "qnn_level_conv2d_i8: tensor too large for 32-bit indexing");
+        ((int64_t)d->kh * d->W + d->kw) * cinb >= (1LL << 24))
+        return fail(QNN_ERR_RANGE, "%s: tensor too large for 32-bit indexing", who);
     if (d->B == 0) return QNN_OK;
-    if (!a_levels || !w_levels) return fail(QNN_ERR_INVALID_ARG, "qnn_level_conv2d_i8: NULL level pointer");
+    if (!a_levels || !w_levels) return fail(QNN_ERR_INVALID_ARG, "%s: NULL level pointer", who);
     if (!aligned16(a_levels) || !aligned16(w_levels) || !aligned16(acc) || !aligned16(out) || !aligned16(next_levels))
-        return fail(QNN_ERR_ALIGNMENT, "qnn_level_conv2d_i8: pointers must be 16-byte aligned");
+        return fail(QNN_ERR_ALIGNMENT, "%s: pointers must be 16-byte aligned", who);
 
     LevelConvParams p;
     p.a = a_levels, p.w = w_levels, p.scale = scale, p.acc = acc, p.out = out, p.next = next_levels;
     p.blk = blk;
-    p.H = (int)d->H, p.W = (int)d->W, p.Cin = (int)d->Cin, p.Cout = (int)d->Cout, p.Ho = (int)Ho, p.Wo = (int)Wo;
+    p.H = (int)d->H, p.W = (int)d->W, p.Cin = (int)cinb, p.Cout = (int)d->Cout, p.Ho = (int)Ho, p.Wo = (int)Wo;
     p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad;
     p.pixels = (int)(d->B * Ho * Wo);
     p.nk = (int)nk, p.units = (int)(nk / 16), p.nstages = 0;
     p.tiles_n = 0;
     p.div_howo = make_fastdiv((uint32_t)(Ho * Wo)), p.div_wo = make_fastdiv((uint32_t)Wo);
-    p.div_cin = make_fastdiv((uint32_t)d->Cin), p.div_kw = make_fastdiv((uint32_t)d->kw);
+    p.div_cin = make_fastdiv((uint32_t)cinb), p.div_kw = make_fastdiv((uint32_t)d->kw);
     p.row_taps = (1u << d->kw) - 1u;
     p.col_taps = 0;
     for (int ky = 0; ky < d->kh; ++ky) p.col_taps |= 1u << (ky * d->kw);
@@ -502,12 +591,50 @@ extern "C" int qnn_level_conv2d_block_i8(const qnn_conv_desc *d, const int8_t *a
     // workgroups per CU hide each other's prologue and epilogue; above that 256 x 256 with 128-byte
     // stages (one workgroup per CU) when its workgroups fill at least three quarters of the CU rounds
     // they take, otherwise 128 x 128 with four waves, two workgroups per CU.
-    if (d->Cout <= 64) return launch_level_conv<256, 64, 4, 1, 64>(p, st);
-    if (d->Cout <= 128) return launch_level_conv<256, 128, 4, 2, 64>(p, st);
+    if (d->Cout <= 64) return fp4 ? launch_level_conv<256, 64, 4, 1, 64, true>(p, st) : launch_level_conv<256, 64, 4, 1, 64>(p, st);
+    if (d->Cout <= 128) return fp4 ? launch_level_conv<256, 128, 4, 2, 64, true>(p, st) : launch_level_conv<256, 128, 4, 2, 64>(p, st);
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus < 1) cus = 256;
     const int64_t tiles = ceil_div(p.pixels, 256) * ceil_div(d->Cout, 256);
-    if (4 * tiles >= 3 * ceil_div(tiles, cus) * cus) return launch_level_conv<256, 256, 2, 4, 128>(p, st);
-    return launch_level_conv<128, 128, 2, 2, 128>(p, st);
+    if (4 * tiles >= 3 * ceil_div(tiles, cus) * cus)
+        return fp4 ? launch_level_conv<256, 256, 2, 4, 128, true>(p, st) : launch_level_conv<256, 256, 2, 4, 128>(p, st);
+    return fp4 ? launch_level_conv<128, 128, 2, 2, 128, true>(p, st) : launch_level_conv<128, 128, 2, 2, 128>(p, st);
+}
+
+extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
+                                   const float *scale, int32_t *acc, float *out, int8_t *next_levels,
+                                   float next_clip, int next_bits, void *stream)
+{
+    return level_conv_run("qnn_level_conv2d_i8", false, d, a_levels, w_levels, scale, nullptr, acc, out, next_levels,
+                          next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_level_conv2d_block_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
+                                         const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                                         int8_t *next_levels, float next_clip, int next_bits, void *stream)
+{
+    return level_conv_run("qnn_level_conv2d_block_i8", false, d, a_levels, w_levels, scale, epi, acc, out, next_levels,
+                          next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_level_conv2d_fp4(const qnn_conv_desc *d, const uint8_t *a_levels, const uint8_t *w_levels,
+                                    const float *scale, int32_t *acc, float *out, uint8_t *next_levels,
+                                    float next_clip, int next_bits, void *stream)
+{
+    return level_conv_run("qnn_level_conv2d_fp4", true, d, reinterpret_cast<const int8_t *>(a_levels),
+                          reinterpret_cast<const int8_t *>(w_levels), scale, nullptr, acc, out,
+                          reinterpret_cast<int8_t *>(next_levels), next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_levels_to_fp4(const int8_t *levels, int64_t count, uint8_t *fp4, void *stream)
+{
+    if (count < 0 || count % 2 != 0) return fail(QNN_ERR_INVALID_ARG, "qnn_levels_to_fp4: count must be even and >= 0");
+    if (count == 0) return QNN_OK;
+    if (!levels || !fp4) return fail(QNN_ERR_INVALID_ARG, "qnn_levels_to_fp4: NULL pointer");
+    if (!aligned16(levels) || !aligned16(fp4)) return fail(QNN_ERR_ALIGNMENT, "qnn_levels_to_fp4: pointers must be 16-byte aligned");
+    const int64_t blocks = ceil_div(ceil_div(count, 16), 256);
+    hipLaunchKernelGGL(levels_to_fp4_kernel, dim3((unsigned)(blocks < 256 * 64 ? blocks : 256 * 64)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), levels, count, fp4);
+    return check_launch("qnn_levels_to_fp4");
 }

@@ -29,6 +29,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
+           "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4",
            "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
            "qnn_last_error", "qnn_version")
 
@@ -111,6 +112,12 @@ def lib():
         L.qnn_quantize_ste_backward.restype = i32
         L.qnn_encoder_backward.argtypes = [vp, vp, i64, f32, i32, vp, vp]
         L.qnn_encoder_backward.restype = i32
+        L.qnn_encode_levels_fp4.argtypes = [vp, i32, i64, f32, i32, vp, vp]
+        L.qnn_encode_levels_fp4.restype = i32
+        L.qnn_levels_to_fp4.argtypes = [vp, i64, vp, vp]
+        L.qnn_levels_to_fp4.restype = i32
+        L.qnn_level_conv2d_fp4.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
+        L.qnn_level_conv2d_fp4.restype = i32
         L.qnn_last_error.argtypes = []
         L.qnn_last_error.restype = ctypes.c_char_p
         L.qnn_version.argtypes = []
@@ -361,6 +368,49 @@ def qnn_encoder_backward(x, grad_planes, clip, grad_x=None):
         grad_x = torch.empty_like(x)
     _check(lib().qnn_encoder_backward(_ptr(x), _ptr(grad_planes), x.numel(), float(clip), bits, _ptr(grad_x), _stream()))
     return grad_x
+
+
+def qnn_encode_levels_fp4(src, clip, bits, levels=None):
+    """fp32 / bf16 [..., C] (C even) -> fp4 levels uint8 [..., C / 2], two channels per byte."""
+    dtype = {torch.float32: QNN_DTYPE_F32, torch.bfloat16: QNN_DTYPE_BF16}[src.dtype]
+    assert src.is_contiguous() and src.shape[-1] % 2 == 0
+    if levels is None:
+        levels = torch.empty(src.shape[:-1] + (src.shape[-1] // 2,), dtype=torch.uint8, device=src.device)
+    _check(lib().qnn_encode_levels_fp4(_ptr(src), dtype, src.numel(), float(clip), int(bits), _ptr(levels), _stream()))
+    return levels
+
+
+def qnn_levels_to_fp4(levels, out=None):
+    """int8 levels [..., C] (C even, |level| <= 3) -> fp4 levels uint8 [..., C / 2]."""
+    assert levels.dtype == torch.int8 and levels.is_contiguous() and levels.shape[-1] % 2 == 0
+    if out is None:
+        out = torch.empty(levels.shape[:-1] + (levels.shape[-1] // 2,), dtype=torch.uint8, device=levels.device)
+    _check(lib().qnn_levels_to_fp4(_ptr(levels), levels.numel(), _ptr(out), _stream()))
+    return out
+
+
+def qnn_level_conv2d_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=None, want_acc=True, want_out=False,
+                         next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """a_levels uint8 [B][H][W][Cin/2], w_levels uint8 [Cout][kh][kw][Cin/2] (fp4, two channels per byte).
+    Returns (acc, out, next_levels [B][Ho][Wo][Cout/2]); entries not requested are None."""
+    B, H, W, cinb = a_levels.shape
+    cout, kh, kw, cinb2 = w_levels.shape
+    assert cinb == cinb2 and a_levels.dtype == torch.uint8 and w_levels.dtype == torch.uint8
+    assert a_levels.is_contiguous() and w_levels.is_contiguous()
+    ho = (H + 2 * pad - kh) // stride + 1
+    wo = (W + 2 * pad - kw) // stride + 1
+    dev = a_levels.device
+    d = qnn_conv_desc(B, H, W, 2 * cinb, cout, kh, kw, stride, pad, a_bits, w_bits)
+    if want_acc and acc is None:
+        acc = torch.empty((B, ho, wo, cout), dtype=torch.int32, device=dev)
+    if want_out and out is None:
+        out = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=dev)
+    if next_clip is not None and next_levels is None:
+        next_levels = torch.empty((B, ho, wo, cout // 2), dtype=torch.uint8, device=dev)
+    _check(lib().qnn_level_conv2d_fp4(ctypes.byref(d), _ptr(a_levels), _ptr(w_levels), _ptr(scale), _ptr(acc), _ptr(out),
+                                      _ptr(next_levels), float(next_clip) if next_clip is not None else 0.0,
+                                      int(next_bits), _stream()))
+    return acc, out, next_levels
 
 
 def qnn_probe_valu(mode, workgroups, iters, out):

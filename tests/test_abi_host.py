@@ -180,6 +180,30 @@ def test_deconv_argument_errors_and_phase_words(qnn):
     assert call(D(0, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)) == qnn.QNN_OK
 
 
+def test_fp4_convolution_argument_errors(qnn):
+    L = qnn.lib()
+    D = qnn.qnn_conv_desc
+
+    def call(desc, a=FAKE, w=FAKE, scale=None, acc=FAKE, out=None, nxt=None, clip=0.0, nbits=0):
+        return L.qnn_level_conv2d_fp4(ctypes.byref(desc), a, w, scale, acc, out, nxt, clip, nbits, None)
+
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 3, 2)) == qnn.QNN_ERR_UNSUPPORTED        # 3-bit codes are not fp4 values
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 9, 2)) == qnn.QNN_ERR_INVALID_ARG
+    assert call(D(1, 8, 8, 48, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED        # Cin not a multiple of 32
+    assert call(D(1, 8, 8, 64, 63, 3, 3, 1, 1, 2, 2), scale=FAKE, nxt=FAKE, clip=1.0, nbits=2) == qnn.QNN_ERR_UNSUPPORTED
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2), scale=FAKE, nxt=FAKE, clip=1.0, nbits=3) == qnn.QNN_ERR_INVALID_ARG
+    # 9 * 5 * 5 * 80000 >= 2^24: beyond exact fp32 accumulation (but fine for int32)
+    assert call(D(1, 8, 8, 80000, 64, 5, 5, 1, 2, 2, 2)) in (qnn.QNN_ERR_RANGE, qnn.QNN_ERR_UNSUPPORTED)
+    assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2), w=ODD) == qnn.QNN_ERR_ALIGNMENT
+    assert call(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
+    assert L.qnn_encode_levels_fp4(FAKE, 0, 64, 1.0, 3, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_levels_fp4(FAKE, 0, 63, 1.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_encode_levels_fp4(FAKE, 2, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED
+    assert L.qnn_levels_to_fp4(FAKE, 63, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_levels_to_fp4(FAKE, 64, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert L.qnn_levels_to_fp4(None, 0, None, None) == qnn.QNN_OK
+
+
 def test_training_gradient_argument_errors(qnn):
     L = qnn.lib()
     assert L.qnn_quantize_ste_backward(FAKE, FAKE, -1, 1.0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG

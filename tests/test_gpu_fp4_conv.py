@@ -1,0 +1,130 @@
+"""GPU parity of the fp4 matrix-core route for 1- and 2-bit convolutions (qnn_encode_levels_fp4,
+qnn_levels_to_fp4, qnn_level_conv2d_fp4) against the CPU oracle: the same int32 accumulators and the
+same levels after every layer, held as fp4 nibbles."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import qnn_workloads as wl
+from gpu_util import dev, levels
+
+pytestmark = pytest.mark.gpu
+
+from paper_1905_13389_amd import qnn  # noqa: E402
+
+RTOL = 1e-5
+
+
+def nibbles(lv):
+    """The documented layout: channel 2i in the low nibble of byte i; nibble = sign << 3 | E2M1 magnitude code."""
+    lv = np.asarray(lv).astype(np.int64)
+    assert lv.shape[-1] % 2 == 0 and set(np.unique(np.abs(lv))) <= {1, 3}
+    code = np.where(lv < 0, 8, 0) | np.where(np.abs(lv) == 3, 5, 2)
+    return (code[..., 0::2] | (code[..., 1::2] << 4)).astype(np.uint8)
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("count", [2, 14, 16, 18, 1000, 4096 * 3 + 6])
+def test_encode_levels_fp4(bits, count):
+    gen = np.random.default_rng(bits * 1000 + count)
+    x = gen.normal(0, 1, size=count).astype(np.float32)
+    x[:2] = [0.0, -5.0]
+    got = qnn.qnn_encode_levels_fp4(dev(x), 1.5, bits)
+    torch.cuda.synchronize()
+    want, _ = oracle.quantize(x, 1.5, bits)
+    assert np.array_equal(got.cpu().numpy(), nibbles(want))
+    xb = torch.from_numpy(x).to(torch.bfloat16)
+    gotb = qnn.qnn_encode_levels_fp4(xb.cuda(), 1.5, bits)
+    torch.cuda.synchronize()
+    wantb, _ = oracle.quantize(xb.to(torch.float32).numpy(), 1.5, bits)
+    assert np.array_equal(gotb.cpu().numpy(), nibbles(wantb))
+
+
+@pytest.mark.parametrize("count", [2, 16, 30, 32, 5000])
+def test_levels_to_fp4(count):
+    gen = np.random.default_rng(count)
+    lv = levels(gen, (count,), 2)
+    got = qnn.qnn_levels_to_fp4(dev(lv))
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), nibbles(lv))
+
+
+GEOMS = [
+    # B, H, W, Cin, Cout, k, stride, pad
+    (2, 7, 9, 32, 4, 3, 1, 1),
+    (1, 8, 8, 64, 6, 3, 2, 1),
+    (2, 6, 5, 96, 38, 1, 1, 0),       # 1x1: reduction shorter than a stage
+    (1, 9, 7, 64, 70, 5, 1, 2),       # ragged columns in the 256 x 128 block
+    (2, 14, 14, 128, 130, 3, 1, 1),   # 256 x 256 block
+    (5, 13, 13, 64, 64, 3, 1, 1),     # several row tiles, ragged tail
+    (2, 24, 24, 32, 300, 3, 1, 1),    # two column tiles
+    (1, 7, 7, 512, 512, 3, 1, 1),     # long reduction
+]
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("bits", [(2, 2), (1, 1), (2, 1), (1, 2)])
+def test_fp4_conv_acc_out_and_next_levels(geom, bits):
+    B, H, W, Cin, Cout, k, stride, pad = geom
+    w_bits, a_bits = bits
+    gen = np.random.default_rng(sum(geom) * 10 + w_bits + a_bits)
+    a, w = levels(gen, (B, H, W, Cin), a_bits), levels(gen, (Cout, k, k, Cin), w_bits)
+    var = (4.0 ** w_bits - 1) / 3 * (4.0 ** a_bits - 1) / 3
+    s = (gen.uniform(0.5, 1.5, size=Cout) / np.sqrt(k * k * Cin * var)).astype(np.float32)
+    a4, w4 = qnn.qnn_levels_to_fp4(dev(a)), qnn.qnn_levels_to_fp4(dev(w))
+    acc, out, nxt = qnn.qnn_level_conv2d_fp4(a4, w4, stride, pad, a_bits, w_bits, scale=dev(s), want_out=True,
+                                             next_clip=2.0, next_bits=2)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(a, w, stride, pad)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s), rtol=RTOL, atol=0)
+    lv, _ = oracle.quantize(oracle.scale(want, s), 2.0, 2)
+    assert np.array_equal(nxt.cpu().numpy(), nibbles(lv))
+    # levels only
+    _, _, nxt2 = qnn.qnn_level_conv2d_fp4(a4, w4, stride, pad, a_bits, w_bits, scale=dev(s), want_acc=False,
+                                          next_clip=2.0, next_bits=2)
+    torch.cuda.synchronize()
+    assert np.array_equal(nxt2.cpu().numpy(), nibbles(lv))
+
+
+def test_fp4_conv_extreme_levels_hit_the_accumulator_bound():
+    # all +3 against all +-3 over the longest test reduction: |acc| = 9 n, exact in fp32
+    Cin, Cout = 1024, 8
+    a = np.full((1, 5, 5, Cin), 3, np.int8)
+    w = np.concatenate([np.full((4, 3, 3, Cin), 3, np.int8), np.full((4, 3, 3, Cin), -3, np.int8)])
+    acc, _, _ = qnn.qnn_level_conv2d_fp4(qnn.qnn_levels_to_fp4(dev(a)), qnn.qnn_levels_to_fp4(dev(w)), 1, 1, 2, 2)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(a, w, 1, 1)
+    assert np.abs(want).max() == 9 * 9 * Cin
+    assert np.array_equal(acc.cpu().numpy(), want)
+
+
+def test_config3_conv_fp4_route_full_size():
+    c = wl.resnet_conv_2x2()
+    x4 = qnn.qnn_encode_levels_fp4(dev(c["x"]), c["clip"], 2)
+    w4 = qnn.qnn_levels_to_fp4(dev(c["w"]))
+    acc, out, _ = qnn.qnn_level_conv2d_fp4(x4, w4, 1, 1, 2, 2, scale=dev(c["scale"]), want_out=True)
+    torch.cuda.synchronize()
+    lv, _ = oracle.quantize(c["x"], c["clip"], 2)
+    want = oracle.conv2d(lv.astype(np.int8), c["w"], 1, 1)
+    assert np.array_equal(x4.cpu().numpy(), nibbles(lv))
+    assert np.array_equal(acc.cpu().numpy(), want)
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, c["scale"]), rtol=RTOL, atol=0)
+
+
+def test_fp4_chain_matches_oracle_stack():
+    # three fused layers, nothing but fp4 levels between them
+    plan = ((64, 64, 1), (64, 128, 2), (128, 128, 1))
+    c = wl.resnet18_stack(batch=2, hw=20, bits=2, plan=plan)
+    want = oracle.conv_stack(c["x"], c["layers"])
+    lv = qnn.qnn_encode_levels_fp4(dev(c["x"]), c["layers"][0]["clip"], 2)
+    for li, L in enumerate(c["layers"]):
+        last = li + 1 == len(c["layers"])
+        assert np.array_equal(lv.cpu().numpy(), nibbles(want[li]["levels"])), li
+        _, out, lv = qnn.qnn_level_conv2d_fp4(lv, qnn.qnn_levels_to_fp4(dev(L["w"])), L["stride"], L["pad"], 2, 2,
+                                              scale=dev(L["scale"]), want_acc=False, want_out=last,
+                                              next_clip=None if last else c["layers"][li + 1]["clip"],
+                                              next_bits=0 if last else 2)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), want[-1]["out"], rtol=RTOL, atol=0)
