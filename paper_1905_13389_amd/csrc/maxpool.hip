@@ -113,6 +113,66 @@ template <bool VEC> __global__ __launch_bounds__(256) void maxpool_levels_kernel
     }
 }
 
+// fp4 levels (two channels per byte; nibble = sign << 3 | magnitude code, 1 = 0b0010, 3 = 0b0101), eight
+// nibbles of a word at once.  Bit 0 of a nibble tells 3 from 1 and bit 3 is the sign, so the order
+// -3 < -1 < +1 < +3 is the 2-bit key (hi = not sign, lo = bit 0 xor sign), held here as two words with
+// one bit per nibble.
+constexpr uint32_t kNib = 0x11111111u;
+
+struct Fp4Keys {
+    uint32_t hi, lo;
+};
+
+__device__ __forceinline__ Fp4Keys fp4_keys(uint32_t w)
+{
+    const uint32_t s = (w >> 3) & kNib, b = w & kNib;
+    return {~s & kNib, (b ^ s) & kNib};
+}
+
+__device__ __forceinline__ Fp4Keys fp4_key_max(Fp4Keys a, Fp4Keys b)
+{
+    const uint32_t gt = (a.hi & ~b.hi) | (~(a.hi ^ b.hi) & a.lo & ~b.lo); // a > b, per nibble
+    return {(a.hi & gt) | (b.hi & ~gt), (a.lo & gt) | (b.lo & ~gt)};
+}
+
+__device__ __forceinline__ uint32_t fp4_from_keys(Fp4Keys k)
+{
+    const uint32_t s = ~k.hi & kNib, b = (k.lo ^ s) & kNib;
+    return (s << 3) | (b << 2) | ((~b & kNib) << 1) | b;
+}
+
+// VEC: 32 channels (16 bytes) per lane (C a multiple of 32), else one byte = 2 channels per lane
+template <bool VEC> __global__ __launch_bounds__(256) void maxpool_fp4_kernel(PoolParams p)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < p.total; idx += stride) {
+        const int c = (int)(idx % p.cw);
+        const int64_t pix = idx / p.cw;
+        const int ox = (int)(pix % p.Wo);
+        const int64_t t = pix / p.Wo;
+        const int oy = (int)(t % p.Ho);
+        const int64_t b = t / p.Ho;
+        Fp4Keys best[4] = {{0u, 0u}, {0u, 0u}, {0u, 0u}, {0u, 0u}}; // the lowest key: level -3
+        for (int ky = 0; ky < p.k; ++ky)
+            for (int kx = 0; kx < p.k; ++kx) {
+                const int y = oy * p.stride - p.pad + ky, x = ox * p.stride - p.pad + kx;
+                if (!in_image(y, x, p)) continue;
+                const int64_t at = ((b * p.H + y) * p.W + x) * p.cw + c;
+                if (VEC) {
+                    const uint4 v = static_cast<const uint4 *>(p.in)[at];
+                    best[0] = fp4_key_max(best[0], fp4_keys(v.x)), best[1] = fp4_key_max(best[1], fp4_keys(v.y));
+                    best[2] = fp4_key_max(best[2], fp4_keys(v.z)), best[3] = fp4_key_max(best[3], fp4_keys(v.w));
+                } else {
+                    best[0] = fp4_key_max(best[0], fp4_keys(static_cast<const uint8_t *>(p.in)[at]));
+                }
+            }
+        if (VEC)
+            static_cast<uint4 *>(p.out)[idx] = make_uint4(fp4_from_keys(best[0]), fp4_from_keys(best[1]),
+                                                          fp4_from_keys(best[2]), fp4_from_keys(best[3]));
+        else static_cast<uint8_t *>(p.out)[idx] = (uint8_t)fp4_from_keys(best[0]);
+    }
+}
+
 static int64_t pool_out(int64_t size, int k, int stride, int pad, int ceil_mode)
 {
     const int64_t span = size + 2 * (int64_t)pad - k;
@@ -197,4 +257,27 @@ extern "C" int qnn_maxpool_levels_i8(const int8_t *levels, int64_t B, int64_t H,
     if (vec) hipLaunchKernelGGL(maxpool_levels_kernel<true>, grid, block, 0, st, p);
     else hipLaunchKernelGGL(maxpool_levels_kernel<false>, grid, block, 0, st, p);
     return check_launch("qnn_maxpool_levels_i8");
+}
+
+extern "C" int qnn_maxpool_levels_fp4(const uint8_t *levels, int64_t B, int64_t H, int64_t W, int64_t C, int k, int stride,
+                                      int pad, int ceil_mode, uint8_t *out_levels, void *stream)
+{
+    int64_t Ho = 0, Wo = 0;
+    const int rc = pool_common("qnn_maxpool_levels_fp4", levels, out_levels, B, H, W, C, k, stride, pad, ceil_mode, Ho, Wo);
+    if (rc != QNN_OK) return rc;
+    if (C % 2 != 0) return fail(QNN_ERR_UNSUPPORTED, "qnn_maxpool_levels_fp4: odd channel count");
+    if (B == 0) return QNN_OK;
+    const bool vec = C % 32 == 0;
+    PoolParams p;
+    p.in = levels, p.out = out_levels;
+    p.H = (int)H, p.W = (int)W, p.cw = (int)(vec ? C / 32 : C / 2), p.Ho = (int)Ho, p.Wo = (int)Wo;
+    p.k = k, p.stride = stride, p.pad = pad;
+    p.in_plane_stride = p.out_plane_stride = 0;
+    p.total = B * Ho * Wo * p.cw;
+    const int64_t blocks = ceil_div(p.total, 256);
+    const dim3 grid((unsigned)(blocks < 256 * 64 ? blocks : 256 * 64)), block(256);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (vec) hipLaunchKernelGGL(maxpool_fp4_kernel<true>, grid, block, 0, st, p);
+    else hipLaunchKernelGGL(maxpool_fp4_kernel<false>, grid, block, 0, st, p);
+    return check_launch("qnn_maxpool_levels_fp4");
 }

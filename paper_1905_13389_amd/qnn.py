@@ -29,7 +29,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
-           "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4",
+           "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_maxpool_levels_fp4",
            "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
            "qnn_last_error", "qnn_version")
 
@@ -118,6 +118,8 @@ def lib():
         L.qnn_levels_to_fp4.restype = i32
         L.qnn_level_conv2d_fp4.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_level_conv2d_fp4.restype = i32
+        L.qnn_maxpool_levels_fp4.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
+        L.qnn_maxpool_levels_fp4.restype = i32
         L.qnn_last_error.argtypes = []
         L.qnn_last_error.restype = ctypes.c_char_p
         L.qnn_version.argtypes = []
@@ -411,6 +413,16 @@ def qnn_level_conv2d_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=
                                       _ptr(next_levels), float(next_clip) if next_clip is not None else 0.0,
                                       int(next_bits), _stream()))
     return acc, out, next_levels
+
+
+def qnn_maxpool_levels_fp4(levels, k, stride, pad=0, ceil_mode=False, out=None):
+    """levels uint8 [B][H][W][C/2] (fp4) -> pooled uint8 [B][Ho][Wo][C/2]."""
+    B, H, W, cb = levels.shape
+    ho, wo = qnn_pool_out_size(H, k, stride, pad, ceil_mode), qnn_pool_out_size(W, k, stride, pad, ceil_mode)
+    if out is None:
+        out = torch.empty((B, max(ho, 0), max(wo, 0), cb), dtype=torch.uint8, device=levels.device)
+    _check(lib().qnn_maxpool_levels_fp4(_ptr(levels), B, H, W, 2 * cb, k, stride, pad, int(ceil_mode), _ptr(out), _stream()))
+    return out
 
 
 def qnn_probe_valu(mode, workgroups, iters, out):

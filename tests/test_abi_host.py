@@ -202,6 +202,10 @@ def test_fp4_convolution_argument_errors(qnn):
     assert L.qnn_levels_to_fp4(FAKE, 63, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
     assert L.qnn_levels_to_fp4(FAKE, 64, ODD, None) == qnn.QNN_ERR_ALIGNMENT
     assert L.qnn_levels_to_fp4(None, 0, None, None) == qnn.QNN_OK
+    assert L.qnn_maxpool_levels_fp4(FAKE, 1, 8, 8, 33, 2, 2, 0, 0, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED   # odd C
+    assert L.qnn_maxpool_levels_fp4(FAKE, 1, 8, 8, 32, 2, 2, 2, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG   # pad > k / 2
+    assert L.qnn_maxpool_levels_fp4(FAKE, 1, 8, 8, 32, 2, 2, 0, 0, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert L.qnn_maxpool_levels_fp4(None, 0, 8, 8, 32, 2, 2, 0, 0, None, None) == qnn.QNN_OK
 
 
 def test_training_gradient_argument_errors(qnn):

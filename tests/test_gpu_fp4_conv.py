@@ -128,3 +128,47 @@ def test_fp4_chain_matches_oracle_stack():
                                               next_bits=0 if last else 2)
     torch.cuda.synchronize()
     np.testing.assert_allclose(out.cpu().numpy(), want[-1]["out"], rtol=RTOL, atol=0)
+
+
+@pytest.mark.parametrize("case", [(2, 8, 8, 32, 2, 2, 0, False), (1, 9, 7, 64, 3, 2, 1, False), (2, 5, 5, 6, 2, 2, 0, True),
+                                  (1, 7, 7, 34, 3, 1, 1, False), (3, 10, 10, 96, 2, 2, 0, False)])
+@pytest.mark.parametrize("bits", [1, 2])
+def test_maxpool_levels_fp4(case, bits):
+    B, H, W, C, k, stride, pad, ceil_mode = case
+    gen = np.random.default_rng(sum(case[:7]) + bits)
+    lv = levels(gen, (B, H, W, C), bits)
+    got = qnn.qnn_maxpool_levels_fp4(qnn.qnn_levels_to_fp4(dev(lv)), k, stride, pad, ceil_mode)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), nibbles(oracle.maxpool(lv, k, stride, pad, ceil_mode)))
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+def test_cifar_network_fp4_route(bits):
+    # the CIFAR-10 network of the paper's Table 3 (from its second layer on) at the widths that table
+    # reports, entirely on fp4 levels: convolutions, pooling on the codes, FC layers as fp4 GEMMs
+    from test_gpu_network import _oracle_network, _next_weighted
+    net = wl.cifar_vgg_network(batch=4, bits=bits)
+    ops = net["ops"]
+    lv = qnn.qnn_encode_levels_fp4(dev(net["x"]), ops[0]["clip"], bits)
+    got, out = [], None
+    for i, op in enumerate(ops):
+        got.append(lv)
+        nw_op = _next_weighted(ops, i)
+        if op["kind"] == "pool":
+            lv = qnn.qnn_maxpool_levels_fp4(lv, op["k"], op["stride"])
+        elif op["kind"] == "conv":
+            _, _, lv = qnn.qnn_level_conv2d_fp4(lv, qnn.qnn_levels_to_fp4(dev(op["w"])), 1, 1, bits, bits,
+                                                scale=dev(op["scale"]), want_acc=False, next_clip=nw_op["clip"],
+                                                next_bits=bits)
+        else:
+            n = op["n"]
+            assert n // 2 == qnn.qnn_fp4_row_bytes(n)          # rows need no padding here
+            _, out = qnn.qnn_level_gemm_fp4(lv.view(lv.shape[0], n // 2), qnn.qnn_levels_to_fp4(dev(op["w"])), n,
+                                            want_acc=False, scale=dev(op["scale"]))
+            if nw_op is not None:
+                lv = qnn.qnn_encode_levels_fp4(out, nw_op["clip"], bits)
+    torch.cuda.synchronize()
+    want, want_out = _oracle_network(net["x"], ops)
+    for i, (g, o) in enumerate(zip(got, want)):
+        assert np.array_equal(g.cpu().numpy().reshape(o.shape[:-1] + (o.shape[-1] // 2,)), nibbles(o)), i
+    np.testing.assert_allclose(out.cpu().numpy(), want_out, rtol=RTOL, atol=0)
