@@ -256,22 +256,20 @@ def test_resnet18_trunk_matrix_core_route_small_batch(bits):
     np.testing.assert_allclose(_np(lean[-1]["y"]), want[-1]["y"], rtol=RTOL, atol=0)
 
 
-def test_resnet18_trunk_full_batch_sampled_images():
-    # batch 256 as bench.py times it; the images are independent, so the oracle's trunk on three of
-    # them gives their exact levels after every layer
-    bits, images = 3, [0, 100, 255]
+def test_resnet18_trunk_full_batch_every_image():
+    # batch 256 as bench.py times it, against the oracle's trunk over the whole batch: the levels between
+    # the two convolutions of every block and the trunk's output, on both routes
+    bits = 3
     net = wl.resnet18_trunk(bits=bits)
-    want = oracle.residual_trunk(net["x"][images], net["blocks"])
+    want = [(t["hq"].astype(np.int8), t["y"] if bi == 7 else None)
+            for bi, t in enumerate(oracle.residual_trunk(net["x"], net["blocks"]))]
     for route, run in (("planes", run_trunk_planes), ("levels", run_trunk_levels)):
         got = run(net, bits, keep=False)
-        for bi, (g, o) in enumerate(zip(got, want)):
-            shape = o["hq"].shape
+        for bi, (g, (hq, _)) in enumerate(zip(got, want)):
             if route == "planes":
-                hq = planes_to_numpy(g["hq"]).reshape(bits, 256, shape[1] * shape[2], -1)[:, images]
-                assert np.array_equal(hq.reshape(bits, -1, hq.shape[-1]),
-                                      oracle.pack_planes(o["hq"].reshape(-1, shape[3]), bits)), (route, bi)
+                assert np.array_equal(planes_to_numpy(g["hq"]), oracle.pack_planes(hq.reshape(-1, hq.shape[-1]), bits)), bi
             else:
-                assert np.array_equal(_np(g["hq"])[images], o["hq"].astype(np.int8)), (route, bi)
-        np.testing.assert_allclose(_np(got[-1]["y"])[images], want[-1]["y"], rtol=RTOL, atol=0)
+                assert np.array_equal(_np(g["hq"]), hq), (route, bi)
+        np.testing.assert_allclose(_np(got[-1]["y"]), want[-1][1], rtol=RTOL, atol=0)
         del got
         torch.cuda.empty_cache()
