@@ -61,6 +61,18 @@ def valu_probe(qnn, torch):
     return res
 
 
+def timed_ms(torch, fn, steps, warmup):
+    """`warmup` untimed calls, then exactly `steps` calls bracketed by device synchronisations: ms per call."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,14 +174,7 @@ def conv_workload(args):
                                next_clip=None if Ln is None else Ln["clip"],
                                next_bits=0 if Ln is None else Ln["a_bits"], next_planes=nxt)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ms = timed_ms(torch, step, args.steps, args.warmup)
     tops = binops / (ms * 1e-3) / 1e12
 
     # the same chain on the matrix cores (comparison only): levels stay decoded as int8 from layer to
@@ -200,14 +205,7 @@ def conv_workload(args):
                                         next_clip=None if Ln is None else Ln["clip"],
                                         next_bits=0 if Ln is None else Ln["a_bits"], next_levels=nxt)
 
-    for _ in range(args.warmup):
-        mfma_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        mfma_step()
-    torch.cuda.synchronize()
-    m_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    m_ms = timed_ms(torch, mfma_step, args.steps, args.warmup)
     int8_tops = 2.0 * macs / (m_ms * 1e-3) / 1e12
 
     # 1- and 2-bit chains also run on the fp4 matrix-core path: two levels per byte, twice the products per clock
@@ -239,14 +237,7 @@ def conv_workload(args):
                                              next_clip=None if Ln is None else Ln["clip"],
                                              next_bits=0 if Ln is None else Ln["a_bits"], next_levels=nxt)
 
-        for _ in range(args.warmup):
-            fp4_step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            fp4_step()
-        torch.cuda.synchronize()
-        f_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        f_ms = timed_ms(torch, fp4_step, args.steps, args.warmup)
         fp4_tops = 2.0 * macs / (f_ms * 1e-3) / 1e12
         fp4 = {"step": "qnn_encode_levels_fp4 + qnn_level_conv2d_fp4 per layer (fused scale/quantize epilogue)",
                "ms_per_step": round(f_ms, 4), "effective_binary_tops": round(binops / (f_ms * 1e-3) / 1e12, 1),
@@ -346,17 +337,7 @@ def trunk_workload(args):
         for a, w, shape, cin, st, pad, sc, kw, nxt, out in l_calls:
             qnn.qnn_level_conv2d_block_i8(a, w, st, pad, bits, bits, sc, next_levels=nxt, out=out, **kw)
 
-    def timed(fn):
-        for _ in range(args.warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / args.steps * 1e3
-
-    ms, m_ms = timed(step), timed(mfma_step)
+    ms, m_ms = (timed_ms(torch, f, args.steps, args.warmup) for f in (step, mfma_step))
     binops = 2.0 * macs * bits * bits
     tops = binops / (ms * 1e-3) / 1e12
     int8_tops = 2.0 * macs / (m_ms * 1e-3) / 1e12
@@ -435,14 +416,7 @@ def pool_workload(args):
                            generator=gen)
     ho = qnn.qnn_pool_out_size(H, 2, 2)
     out = torch.empty((bits, B * ho * ho, cw), dtype=torch.int32, device="cuda")
-    for _ in range(args.warmup):
-        qnn.qnn_maxpool_planes(planes, (B, H, H), C, 2, 2, out=out)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        qnn.qnn_maxpool_planes(planes, (B, H, H), C, 2, 2, out=out)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ms = timed_ms(torch, lambda: qnn.qnn_maxpool_planes(planes, (B, H, H), C, 2, 2, out=out), args.steps, args.warmup)
     nbytes = 4.0 * (planes.numel() + out.numel())
     tbs = nbytes / (ms * 1e-3) / 1e12
     print(json.dumps({
@@ -477,14 +451,7 @@ def deconv_workload(args):
         qnn.qnn_deconv2d(planes, ph, (B, H, H), cin, cout, k, k, s, pad, bits, scale=sc, want_acc=False,
                          next_clip=3.0, next_bits=bits, next_planes=nxt)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    ms = timed_ms(torch, step, args.steps, args.warmup)
     macs = B * H * H * k * k * cin * cout
     tops = 2.0 * macs * bits * bits / (ms * 1e-3) / 1e12
     print(json.dumps({
@@ -512,18 +479,8 @@ def grad_workload(args):
     g = torch.randn((2, n), device="cuda", generator=gen)
     gx = torch.empty_like(x)
 
-    def timed(fn):
-        for _ in range(args.warmup):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / args.steps * 1e3
-
-    ms_ste = timed(lambda: qnn.qnn_quantize_ste_backward(x, g[0], 3.0, grad_x=gx))
-    ms_enc = timed(lambda: qnn.qnn_encoder_backward(x, g, 3.0, grad_x=gx))
+    ms_ste = timed_ms(torch, lambda: qnn.qnn_quantize_ste_backward(x, g[0], 3.0, grad_x=gx), args.steps, args.warmup)
+    ms_enc = timed_ms(torch, lambda: qnn.qnn_encoder_backward(x, g, 3.0, grad_x=gx), args.steps, args.warmup)
     b_ste, b_enc = 12.0 * n, 16.0 * n          # x + gradient(s) read, grad_x written
     tbs = b_enc / (ms_enc * 1e-3) / 1e12
     print(json.dumps({
