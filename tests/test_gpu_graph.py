@@ -64,3 +64,50 @@ def test_fused_stack_step_in_a_hip_graph():
     step()
     torch.cuda.synchronize()
     assert torch.equal(out, step_out) and not torch.equal(out, ref)
+
+
+def test_block_deconv_and_gradient_calls_in_a_hip_graph():
+    # the later entry points under capture: a residual block (shift + shortcut planes), a transposed
+    # convolution on its output planes (one launch over its four phases), and the two training-side gradients
+    gen = np.random.default_rng(3)
+    B, H, C, bits = 2, 10, 64, 2
+    x = torch.from_numpy(gen.normal(0, 1, size=(B * H * H, C)).astype(np.float32)).cuda()
+    top = (1 << bits) - 1
+    lv = lambda shape: torch.from_numpy((2 * gen.integers(0, top + 1, size=shape) - top).astype(np.int8)).cuda()
+    w1 = qnn.qnn_encode_pack(lv((C, 3, 3, C)), 1.0, bits).view(bits, C, 3, 3, -1)
+    ph = qnn.qnn_deconv_pack_weights(qnn.qnn_encode_pack(lv((32, 4, 4, C)), 1.0, bits).view(bits, 32, 4, 4, -1), C, 2)
+    sc1 = torch.full((C,), 0.02, device="cuda")
+    sc2 = torch.full((32,), 0.03, device="cuda")
+    bias = torch.from_numpy(gen.uniform(-0.2, 0.2, size=C).astype(np.float32)).cuda()
+    planes = torch.empty((bits, B * H * H, C // 32), dtype=torch.int32, device="cuda")
+    mid = torch.empty_like(planes)
+    out = torch.empty((B, 2 * H, 2 * H, 32), dtype=torch.float32, device="cuda")
+    g = torch.from_numpy(gen.normal(size=(bits, B * H * H * C)).astype(np.float32)).cuda()
+    gx, gq = torch.empty(B * H * H * C, device="cuda"), torch.empty(B * H * H * C, device="cuda")
+
+    def step():
+        qnn.qnn_encode_pack(x, 3.0, bits, planes=planes)
+        qnn.qnn_conv2d_block(planes, w1, (B, H, H), C, 1, 1, sc1, bias=bias, res_planes=planes, res_scale=0.5,
+                             want_acc=False, next_clip=3.0, next_bits=bits, next_planes=mid)
+        qnn.qnn_deconv2d(mid, ph, (B, H, H), C, 32, 4, 4, 2, 1, bits, scale=sc2, want_acc=False, want_out=True, out=out)
+        qnn.qnn_encoder_backward(x.view(-1), g, 3.0, grad_x=gx)
+        qnn.qnn_quantize_ste_backward(x.view(-1), g[0], 3.0, grad_x=gq)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (out, gx, gq)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (out, gx, gq, mid):
+            t.fill_(rep)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip((out, gx, gq), ref)), rep
