@@ -472,9 +472,35 @@ template <int WB, int AB> struct ConvPick {
     static constexpr int TM = 4, TN = (WB + AB >= 7 ? 2 : 4), KV = (WB + AB >= 6 ? 2 : 4);
 };
 
-template <int WB, int AB, int VW, bool BLK> static int launch_conv_vw(ConvTileParams p, hipStream_t st)
+// A narrower column tile (32 channels) for 5 and 6 planes in all.  Per unit of work it is about 8 %
+// slower than the 64-channel tile (more LDS reads per xor + bitcount pair), but it doubles the tile
+// count, which pays when the wider tiles fill their last round of resident workgroups badly (e.g.
+// 1568 tiles on 512 workgroups: 3.06 -> 4 rounds; 3136 narrow tiles: 6.1 -> 7).
+template <int WB, int AB> struct ConvPickNarrow {
+    static constexpr int TM = 4, TN = 2, KV = 4;
+};
+template <int WB, int AB> constexpr bool kHasNarrow = (WB + AB == 5 || WB + AB == 6);
+
+// share of the resident workgroups' rounds that `tiles` equal tiles fill
+inline double round_fill(int64_t tiles, int slots)
 {
-    using G = ConvPick<WB, AB>;
+    return (double)tiles / (double)(ceil_div(tiles, slots) * slots);
+}
+
+inline int compute_units()
+{
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 256;
+        return n > 0 ? n : 256;
+    }();
+    return cus;
+}
+
+template <int WB, int AB, int VW, bool BLK, class G, bool ALLOW_KEEPW>
+static int launch_conv_vw(ConvTileParams p, hipStream_t st)
+{
     constexpr int TN = G::TN;
     static_assert(TN % 2 == 0, "column tile must be a multiple of 32");
     using T = Tile<WB, AB, G::TM, TN, G::KV, kConvKB>;
@@ -505,15 +531,36 @@ template <int WB, int AB, int VW, bool BLK> static int launch_conv_vw(ConvTilePa
         hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n * phases)), dim3(kTileThreads), dyn, st, p);
         return (int)QNN_OK;
     };
-    if (p.nchunks == 1) return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, true, BLK>);
+    if constexpr (ALLOW_KEEPW) {
+        if (p.nchunks == 1) return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, true, BLK>);
+    }
     return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, false, BLK>);
+}
+
+template <int WB, int AB, bool BLK, class G, bool ALLOW_KEEPW>
+static int launch_conv_tile(const ConvTileParams &p, hipStream_t st)
+{
+    if (p.cw % 4 == 0) return launch_conv_vw<WB, AB, 4, BLK, G, ALLOW_KEEPW>(p, st);
+    if (p.cw % 2 == 0) return launch_conv_vw<WB, AB, 2, BLK, G, ALLOW_KEEPW>(p, st);
+    return launch_conv_vw<WB, AB, 1, BLK, G, ALLOW_KEEPW>(p, st);
 }
 
 template <int WB, int AB, bool BLK> static int launch_conv(const ConvTileParams &p, hipStream_t st)
 {
-    if (p.cw % 4 == 0) return launch_conv_vw<WB, AB, 4, BLK>(p, st);
-    if (p.cw % 2 == 0) return launch_conv_vw<WB, AB, 2, BLK>(p, st);
-    return launch_conv_vw<WB, AB, 1, BLK>(p, st);
+    if constexpr (kHasNarrow<WB, AB>) {
+        // multi-stage reductions only (the one-stage kernels keep their weights resident per column tile)
+        if (p.nw > kConvKB) {
+            using W = Tile<WB, AB, ConvPick<WB, AB>::TM, ConvPick<WB, AB>::TN, ConvPick<WB, AB>::KV, kConvKB>;
+            using N = Tile<WB, AB, ConvPickNarrow<WB, AB>::TM, ConvPickNarrow<WB, AB>::TN, ConvPickNarrow<WB, AB>::KV, kConvKB>;
+            const int phases = BLK && p.nphase > 1 ? p.nphase : 1;
+            int slots = 2 * compute_units() / phases; // both tile shapes run two workgroups per CU
+            if (slots < 1) slots = 1;
+            const double wide = round_fill(ceil_div(p.M, W::BM) * ceil_div(p.Cout, W::BN), slots);
+            const double narrow = round_fill(ceil_div(p.M, N::BM) * ceil_div(p.Cout, N::BN), slots);
+            if (narrow * 0.92 > wide) return launch_conv_tile<WB, AB, BLK, ConvPickNarrow<WB, AB>, false>(p, st);
+        }
+    }
+    return launch_conv_tile<WB, AB, BLK, ConvPick<WB, AB>, true>(p, st);
 }
 
 template <int WB, bool BLK> static int conv_dispatch_a(int a_bits, const ConvTileParams &p, hipStream_t st)
