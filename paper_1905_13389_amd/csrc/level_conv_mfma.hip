@@ -173,8 +173,10 @@ struct LevelConvParams {
 // the same with Cin / 2 bytes per pixel, the product is v_mfma_scale_f32_32x32x64_f8f6f4 with unit
 // scales (64 values per 32-byte k step), accumulated in fp32 -- exact, the host bounds the sums by
 // 2^24 -- and the next layer's levels leave as nibbles.
-template <int MB, int NB, int WM, int WN, int KB, bool FP4>
-__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(MB == 256 && NB == 64 ? 3 : 1))) void
+// BLK: the residual-block terms (shift, shortcut) are part of the epilogue; the plain kernels carry
+// none of their registers.
+template <int MB, int NB, int WM, int WN, int KB, bool FP4, bool BLK>
+__global__ __launch_bounds__(64 * WM * WN) __attribute__((amdgpu_waves_per_eu(MB == 256 && NB == 64 && (BLK || FP4) ? 3 : 1))) void
 level_conv_mfma_kernel(LevelConvParams p)
 {
     constexpr int kKB = KB, kSteps = KB / 32, kUnits = KB / 16; // k steps of 32 bytes, 16-byte units per row
@@ -345,7 +347,7 @@ level_conv_mfma_kernel(LevelConvParams p)
     // The quantized shortcut tile (int8 [MB][NB]) is fetched into LDS with 16-byte loads and read back
     // bytewise; a lane later writes its level to the very byte it read, so the same region serves as
     // the level tile that leaves with 16-byte stores.
-    const int8_t *resq = static_cast<const int8_t *>(p.blk.res_q);
+    const int8_t *resq = BLK ? static_cast<const int8_t *>(p.blk.res_q) : nullptr;
     uint8_t *lv = &smem[0][0]; // [MB][NB] bytes
     constexpr int kVecPerRow = NB / 16;
     if (resq || p.next) {
@@ -369,14 +371,16 @@ level_conv_mfma_kernel(LevelConvParams p)
     }
     // scale, then the residual-block terms in their documented order (one fp32 rounding each);
     // `at`: this output's byte in the LDS tile, `o`: its element offset in the global tensors
-    auto block_y = [&](int32_t v, float sc, float bi, int at, int64_t o) -> float {
+    auto block_y = [&](int32_t v, float sc, float bi, int at, int row, int c) -> float {
         float y = (float)v * sc;
-        if (p.blk.bias) y = y + bi;
-        if (resq) {
-            const float term = (float)(int)(int8_t)lv[at] * p.blk.res_scale;
-            y = y + term;
+        if constexpr (BLK) {
+            if (p.blk.bias) y = y + bi;
+            if (resq) {
+                const float term = (float)(int)(int8_t)lv[at] * p.blk.res_scale;
+                y = y + term;
+            }
+            if (p.blk.res_f32) y = y + p.blk.res_f32[(int64_t)row * p.Cout + c];
         }
-        if (p.blk.res_f32) y = y + p.blk.res_f32[o];
         return y;
     };
 
@@ -390,7 +394,7 @@ level_conv_mfma_kernel(LevelConvParams p)
                 const int c = col0 + cl;
                 if (c >= p.Cout) continue;
                 const float sc = p.out ? p.scale[c] : 0.0f;
-                const float bi = p.out && p.blk.bias ? p.blk.bias[c] : 0.0f;
+                const float bi = BLK && p.out && p.blk.bias ? p.blk.bias[c] : 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rl = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -398,7 +402,7 @@ level_conv_mfma_kernel(LevelConvParams p)
                     const int32_t v = (int32_t)acc[i][j][r]; // fp4: an integer-valued float
                     const int64_t o = (int64_t)(row0 + rl) * p.Cout + c;
                     if (p.acc) p.acc[o] = v;
-                    if (p.out) p.out[o] = block_y(v, sc, bi, rl * NB + cl, o);
+                    if (p.out) p.out[o] = block_y(v, sc, bi, rl * NB + cl, row0 + rl, c);
                 }
             }
     }
@@ -410,13 +414,13 @@ level_conv_mfma_kernel(LevelConvParams p)
                 const int cl = (wn * TN + j) * 32 + (lane & 31);
                 const int c = col0 + cl < p.Cout ? col0 + cl : p.Cout - 1;
                 const float sc = p.scale[c];
-                const float bi = p.blk.bias ? p.blk.bias[c] : 0.0f;
+                const float bi = BLK && p.blk.bias ? p.blk.bias[c] : 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rl = (wm * TM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     // rows past the last pixel and columns past Cout are never stored: any in-range address does
                     const int row = row0 + rl < p.pixels ? row0 + rl : p.pixels - 1;
-                    const float y = block_y((int32_t)acc[i][j][r], sc, bi, rl * NB + cl, (int64_t)row * p.Cout + c);
+                    const float y = block_y((int32_t)acc[i][j][r], sc, bi, rl * NB + cl, row, c);
                     lv[rl * NB + cl] =
                         (uint8_t)(2 * quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) - p.next_top);
                 }
@@ -454,13 +458,17 @@ level_conv_mfma_kernel(LevelConvParams p)
     }
 }
 
-template <int MB, int NB, int WM, int WN, int KB, bool FP4 = false> int launch_level_conv(LevelConvParams &p, hipStream_t st)
+template <int MB_, int NB_, int WM_, int WN_, int KB_> struct BlockShape {
+    static constexpr int MB = MB_, NB = NB_, WM = WM_, WN = WN_, KB = KB_;
+};
+
+template <int MB, int NB, int WM, int WN, int KB, bool FP4, bool BLK> int launch_level_conv_k(LevelConvParams &p, hipStream_t st)
 {
     p.nstages = (int)ceil_div(p.nk, KB);
     const int64_t tiles_m = ceil_div(p.pixels, MB), tiles_n = ceil_div(p.Cout, NB);
     if (tiles_m * tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_conv2d_i8: too many tiles");
     p.tiles_n = (int)tiles_n;
-    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN, KB, FP4>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN),
+    hipLaunchKernelGGL((level_conv_mfma_kernel<MB, NB, WM, WN, KB, FP4, BLK>), dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WM * WN),
                        0, st, p);
     return check_launch("qnn_level_conv2d_i8");
 }
@@ -591,15 +599,22 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
     // workgroups per CU hide each other's prologue and epilogue; above that 256 x 256 with 128-byte
     // stages (one workgroup per CU) when its workgroups fill at least three quarters of the CU rounds
     // they take, otherwise 128 x 128 with four waves, two workgroups per CU.
-    if (d->Cout <= 64) return fp4 ? launch_level_conv<256, 64, 4, 1, 64, true>(p, st) : launch_level_conv<256, 64, 4, 1, 64>(p, st);
-    if (d->Cout <= 128) return fp4 ? launch_level_conv<256, 128, 4, 2, 64, true>(p, st) : launch_level_conv<256, 128, 4, 2, 64>(p, st);
+    const bool terms = blk.bias || blk.res_q || blk.res_f32; // never with fp4 (checked above)
+    auto go = [&](auto shape) {
+        constexpr int MB = decltype(shape)::MB, NB = decltype(shape)::NB, WM = decltype(shape)::WM, WN = decltype(shape)::WN,
+                      KB = decltype(shape)::KB;
+        if (fp4) return launch_level_conv_k<MB, NB, WM, WN, KB, true, false>(p, st);
+        if (terms) return launch_level_conv_k<MB, NB, WM, WN, KB, false, true>(p, st);
+        return launch_level_conv_k<MB, NB, WM, WN, KB, false, false>(p, st);
+    };
+    if (d->Cout <= 64) return go(BlockShape<256, 64, 4, 1, 64>{});
+    if (d->Cout <= 128) return go(BlockShape<256, 128, 4, 2, 64>{});
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (cus < 1) cus = 256;
     const int64_t tiles = ceil_div(p.pixels, 256) * ceil_div(d->Cout, 256);
-    if (4 * tiles >= 3 * ceil_div(tiles, cus) * cus)
-        return fp4 ? launch_level_conv<256, 256, 2, 4, 128, true>(p, st) : launch_level_conv<256, 256, 2, 4, 128>(p, st);
-    return fp4 ? launch_level_conv<128, 128, 2, 2, 128, true>(p, st) : launch_level_conv<128, 128, 2, 2, 128>(p, st);
+    if (4 * tiles >= 3 * ceil_div(tiles, cus) * cus) return go(BlockShape<256, 256, 2, 4, 128>{});
+    return go(BlockShape<128, 128, 2, 2, 128>{});
 }
 
 extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
