@@ -281,23 +281,58 @@ template <bool FP4> __global__ __launch_bounds__(kThreads) void level_gemm_mfma_
     for (; s + kRing < nstages; ++s) stage_body(s, std::true_type{});
     for (; s < nstages; ++s) stage_body(s, std::false_type{});
 
-    // D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) + r % 4
+    // Epilogue.  D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) +
+    // r % 4.  Each 32 x 32 tile goes through a private LDS patch of its wave and leaves row-major, one
+    // lane with 4 consecutive columns of one row: 16-byte stores of acc and out instead of 4-byte ones.
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __syncthreads(); // every wave is past its last operand read: the ring can be reused
+    constexpr int kPatchStride = 36; // words per patch row
+    static_assert(kWavesM * kWavesN * 32 * kPatchStride * 4 <= kRing * kStageBytes, "patches fit the ring");
+    int32_t *patch = reinterpret_cast<int32_t *>(&smem[0][0]) + wave * (32 * kPatchStride);
+    const int prow = lane >> 3, pc4 = (lane & 7) * 4;
+    const bool cols4 = (p.cols & 3) == 0;
 #pragma unroll
-    for (int i = 0; i < kTM; ++i)
+    for (int j = 0; j < kTN; ++j) {
+        const int64_t c = col0 + (wn * kTN + j) * 32 + pc4;
+        float sc[4] = {0.f, 0.f, 0.f, 0.f};
+        if (p.out) {
 #pragma unroll
-        for (int j = 0; j < kTN; ++j) {
-            const int64_t c = col0 + (wn * kTN + j) * 32 + (lane & 31);
-            if (c >= p.cols) continue;
-            const float sc = p.out ? p.scale[c] : 0.0f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = row0 + (wm * kTM + i) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (row >= p.rows) continue;
-                const int32_t v = (int32_t)acc[i][j][r];
-                if (p.acc) p.acc[row * p.cols + c] = v;
-                if (p.out) p.out[row * p.cols + c] = (float)v * sc;
-            }
+            for (int e = 0; e < 4; ++e)
+                if (c + e < p.cols) sc[e] = p.scale[c + e];
         }
+#pragma unroll
+        for (int i = 0; i < kTM; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                patch[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPatchStride + (lane & 31)] = (int32_t)acc[i][j][r];
+            // the wave's own LDS operations complete in order; the compiler must not move the reads up
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int ps = 0; ps < 4; ++ps) {
+                const int4 v = *reinterpret_cast<const int4 *>(patch + (ps * 8 + prow) * kPatchStride + pc4);
+                const int64_t row = row0 + (wm * kTM + i) * 32 + ps * 8 + prow;
+                if (row >= p.rows || c >= p.cols) continue;
+                const int64_t o = row * p.cols + c;
+                const int32_t vi[4] = {v.x, v.y, v.z, v.w};
+                if (cols4) { // c is a multiple of 4, so c + 3 < cols and the address is 16-byte aligned
+                    if (p.acc) *reinterpret_cast<int4 *>(p.acc + o) = v;
+                    if (p.out)
+                        *reinterpret_cast<float4 *>(p.out + o) =
+                            make_float4((float)vi[0] * sc[0], (float)vi[1] * sc[1], (float)vi[2] * sc[2], (float)vi[3] * sc[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < p.cols) {
+                            if (p.acc) p.acc[o + e] = vi[e];
+                            if (p.out) p.out[o + e] = (float)vi[e] * sc[e];
+                        }
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_wave_barrier(); // the patch is rewritten by the next tile
+        }
+    }
 }
 
 } // namespace qnn
