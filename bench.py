@@ -61,6 +61,22 @@ def valu_probe(qnn, torch):
     return res
 
 
+def mfma_probe(qnn, torch):
+    """Sustained rate of the register-only MFMA loops, in TOP/s (int8) and TFLOP/s (fp4)."""
+    wgs, iters = 512, 20000          # 2 waves per SIMD, 16 MFMAs per wave and iteration
+    buf = torch.empty(wgs * 256, dtype=torch.int32, device="cuda")
+    res = {}
+    for mode, name, ops in ((0, "int8", 65536.0), (1, "fp4", 131072.0)):
+        qnn.qnn_probe_mfma(mode, wgs, iters // 10, buf)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        qnn.qnn_probe_mfma(mode, wgs, iters, buf)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = round(ops * 16.0 * iters * wgs * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return res
+
+
 def timed_ms(torch, fn, steps, warmup):
     """`warmup` untimed calls, then exactly `steps` calls bracketed by device synchronisations: ms per call."""
     for _ in range(warmup):
@@ -541,6 +557,7 @@ def main():
     # the register-only issue-rate loops run first: they belong to the roofline object and leave the
     # clocks settled before the W warm-up steps
     probe = valu_probe(qnn, torch)
+    mprobe = mfma_probe(qnn, torch)  # what register-only MFMA loops sustain on this device (the variants' context)
     for _ in range(args.warmup):
         step()
     # one streaming pass of known size (64 MiB read, 64 MiB written at the default size): the
@@ -629,7 +646,8 @@ def main():
             "speedup_vs_xor_bitcount_step": round(ms_per_step / m_ms, 2),
             "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel<int8>", "achieved": round(int8_tops, 1),
                          "peak": 5000.0, "unit": "int8 TOP/s", "frac": round(int8_tops / 5000.0, 4),
-                         "kernel_ms": round(m_gemm_ms, 4)}}
+                         "kernel_ms": round(m_gemm_ms, 4), "probe_mfma_loop": mprobe["int8"],
+                         "frac_of_probe": round(int8_tops / mprobe["int8"], 4)}}
 
     # 1- and 2-bit codes also fit the fp4 matrix-core path (levels -3..3 are exact fp4 values)
     if max(wb, ab) <= 2:
@@ -665,7 +683,8 @@ def main():
             "speedup_vs_xor_bitcount_step": round(ms_per_step / f_ms, 2),
             "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel<fp4>", "achieved": round(fp4_tops, 1),
                          "peak": 10100.0, "unit": "fp4 TFLOP/s", "frac": round(fp4_tops / 10100.0, 4),
-                         "kernel_ms": round(f_gemm_ms, 4)}}
+                         "kernel_ms": round(f_gemm_ms, 4), "probe_mfma_loop": mprobe["fp4"],
+                         "frac_of_probe": round(fp4_tops / mprobe["fp4"], 4)}}
 
     if args.sweep:
         sweep = {}

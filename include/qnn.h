@@ -330,6 +330,17 @@ int qnn_maxpool_levels_fp4(const uint8_t *levels, int64_t B, int64_t H, int64_t 
  */
 int qnn_probe_valu(int mode, int workgroups, int iters, uint32_t *out, void *stream);
 
+/*
+ * qnn_probe_mfma -- the same kind of aid for the matrix-core comparison routes: every workgroup of 256
+ * lanes runs `iters` iterations of 16 register-only MFMA instructions per wave on four independent
+ * accumulators, which gives the rate the matrix cores sustain on the device at hand (clocks under load
+ * included) next to the published peak.
+ *   mode 0: v_mfma_i32_32x32x32_i8 (65536 operations each); 1: v_mfma_scale_f32_32x32x64_f8f6f4 on fp4
+ *   operands (131072 operations each)
+ *   out  DEVICE, workgroups * 256 uint32
+ */
+int qnn_probe_mfma(int mode, int workgroups, int iters, uint32_t *out, void *stream);
+
 /* Message for the last error returned on the calling thread ("" if none). Never NULL. */
 const char *qnn_last_error(void);
 

@@ -2,6 +2,7 @@
 // product.  A measurement aid (the benchmark derives the VALU roofline of qnn_binary_gemm from
 // it), not part of the hot path.  Every loop iteration issues 64 VALU instructions per wave.
 #include "qnn_host.h"
+#include <type_traits>
 
 namespace qnn {
 
@@ -47,9 +48,64 @@ template <int MODE> __global__ __launch_bounds__(256) void probe_kernel(uint32_t
     out[blockIdx.x * blockDim.x + threadIdx.x] = p0 + p1 + p2 + p3 + p4 + p5 + p6 + p7 + t0 + t1 + t2 + t3;
 }
 
+typedef int pv4i __attribute__((ext_vector_type(4)));
+typedef int pv8i __attribute__((ext_vector_type(8)));
+typedef int pv16i __attribute__((ext_vector_type(16)));
+typedef float pv16f __attribute__((ext_vector_type(16)));
+
+// Register-only matrix-core loops: 16 MFMAs per wave and iteration on four independent accumulators.
+// MODE 0: v_mfma_i32_32x32x32_i8; 1: v_mfma_scale_f32_32x32x64_f8f6f4 on fp4 operands, unit scales.
+template <int MODE> __global__ __launch_bounds__(256) void mfma_probe_kernel(uint32_t *out, int iters)
+{
+    // int8: small values; fp4: +1 against alternating +1 / -1, so the sums stay at 0
+    const pv4i a = MODE == 0 ? pv4i{0x01010101, 0x01010101, 0x01010101, 0x01010101}
+                             : pv4i{0x22222222, 0x22222222, 0x22222222, 0x22222222};
+    const pv4i b = MODE == 0 ? pv4i{0x01ff01ff, 0x01ff01ff, 0x01ff01ff, 0x01ff01ff}
+                             : pv4i{0x2a2a2a2a, 0x2a2a2a2a, 0x2a2a2a2a, 0x2a2a2a2a};
+    using Acc = typename std::conditional<MODE == 0, pv16i, pv16f>::type;
+    Acc acc[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[k][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if constexpr (MODE == 0) {
+                    acc[k] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[k], 0, 0, 0);
+                } else {
+                    const pv8i a8 = __builtin_shufflevector(a, a, 0, 1, 2, 3, -1, -1, -1, -1);
+                    const pv8i b8 = __builtin_shufflevector(b, b, 0, 1, 2, 3, -1, -1, -1, -1);
+                    acc[k] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, acc[k], 4, 4, 0, 127, 0, 127);
+                }
+            }
+    }
+    uint32_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += (uint32_t)(int)acc[k][r];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
+
 } // namespace qnn
 
 using namespace qnn;
+
+extern "C" int qnn_probe_mfma(int mode, int workgroups, int iters, uint32_t *out, void *stream)
+{
+    if (mode < 0 || mode > 1) return fail(QNN_ERR_INVALID_ARG, "qnn_probe_mfma: mode must be 0 or 1");
+    if (workgroups < 1 || workgroups > 65536 || iters < 0 || iters > (1 << 24))
+        return fail(QNN_ERR_INVALID_ARG, "qnn_probe_mfma: workgroups in [1,65536], iters in [0,2^24]");
+    if (!out) return fail(QNN_ERR_INVALID_ARG, "qnn_probe_mfma: NULL output buffer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)workgroups), block(256);
+    if (mode == 0) hipLaunchKernelGGL(mfma_probe_kernel<0>, grid, block, 0, st, out, iters);
+    else hipLaunchKernelGGL(mfma_probe_kernel<1>, grid, block, 0, st, out, iters);
+    return check_launch("qnn_probe_mfma");
+}
 
 extern "C" int qnn_probe_valu(int mode, int workgroups, int iters, uint32_t *out, void *stream)
 {

@@ -26,7 +26,7 @@ QNN_DTYPE_I8 = 2
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d", "qnn_conv2d_block",
            "qnn_level_conv2d_block_i8", "qnn_deconv_phase_words", "qnn_deconv_pack_weights", "qnn_deconv2d",
            "qnn_quantize_ste_backward", "qnn_encoder_backward",
-           "qnn_probe_valu", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
+           "qnn_probe_valu", "qnn_probe_mfma", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
            "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_maxpool_levels_fp4",
@@ -80,6 +80,8 @@ def lib():
         L.qnn_level_conv2d_block_i8.restype = i32
         L.qnn_probe_valu.argtypes = [i32, i32, i32, vp, vp]
         L.qnn_probe_valu.restype = i32
+        L.qnn_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
+        L.qnn_probe_mfma.restype = i32
         L.qnn_level_row_bytes.argtypes = [i64]
         L.qnn_level_row_bytes.restype = i64
         L.qnn_plane_sum_i8.argtypes = [vp, i32, i64, i64, vp, vp]
@@ -429,6 +431,12 @@ def qnn_probe_valu(mode, workgroups, iters, out):
     """Launch the register-only issue-rate loop (see include/qnn.h); out: int32 [workgroups*256]."""
     assert out.numel() >= workgroups * 256
     _check(lib().qnn_probe_valu(int(mode), int(workgroups), int(iters), _ptr(out), _stream()))
+
+
+def qnn_probe_mfma(mode, workgroups, iters, out):
+    """Launch the register-only MFMA loop (see include/qnn.h); out: int32 [workgroups*256]."""
+    assert out.numel() >= workgroups * 256
+    _check(lib().qnn_probe_mfma(int(mode), int(workgroups), int(iters), _ptr(out), _stream()))
 
 
 def qnn_dequant_scale(acc, scale, out=None):

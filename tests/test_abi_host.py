@@ -208,6 +208,15 @@ def test_fp4_convolution_argument_errors(qnn):
     assert L.qnn_maxpool_levels_fp4(None, 0, 8, 8, 32, 2, 2, 0, 0, None, None) == qnn.QNN_OK
 
 
+def test_probe_argument_errors(qnn):
+    L = qnn.lib()
+    for f in (L.qnn_probe_valu, L.qnn_probe_mfma):
+        assert f(9, 1, 1, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+        assert f(0, 0, 1, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+        assert f(0, 1, -1, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+        assert f(0, 1, 1, None, None) == qnn.QNN_ERR_INVALID_ARG
+
+
 def test_training_gradient_argument_errors(qnn):
     L = qnn.lib()
     assert L.qnn_quantize_ste_backward(FAKE, FAKE, -1, 1.0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
