@@ -147,7 +147,7 @@ def conv_workload(args):
         L = {"w": c["w"], "scale": c["scale"], "clip": c["clip"], "a_bits": 2, "w_bits": 2, "stride": 1,
              "pad": 1, "cin": 64, "cout": 64}
         groups = [{"x": c["x"], "layers": [L]}]
-        name = "ResNet-18-shaped 3x3 conv 64->64 @56x56, batch %d, 2x2 bit" % c["x"].shape[0]
+        name = "ResNet-18-shaped 3x3 conv 64->64 @56x56, batch %d, 2x2 bit, int32 acc + fp32 scaled out" % c["x"].shape[0]
     elif args.workload == "stack4":
         c = wl.resnet18_stack(batch=args.batch or 256)
         groups = [c]
@@ -157,6 +157,7 @@ def conv_workload(args):
         name = "VGG16-style detection stack of 12 quantized 3x3 convs @300x300, batch %d, 4x4 bit" \
             % groups[0]["x"].shape[0]
 
+    single = args.workload == "conv3"
     plans, macs, binops = [], 0, 0.0
     for g in groups:
         B, H, W, C = g["x"].shape
@@ -173,8 +174,10 @@ def conv_workload(args):
             nxt = None if last else torch.empty((g["layers"][li + 1]["a_bits"], B * ho * wo, (L["cout"] + 31) // 32),
                                                 dtype=torch.int32, device="cuda")
             out = torch.empty((B, ho, wo, L["cout"]), dtype=torch.float32, device="cuda") if last else None
+            # the single-layer configuration hands out both results, int32 accumulators and fp32 scaled values
+            acc = torch.empty((B, ho, wo, L["cout"]), dtype=torch.int32, device="cuda") if single else None
             steps.append((planes, wp, (B, H, W), L, torch.from_numpy(L["scale"]).cuda(), out, nxt,
-                          None if last else g["layers"][li + 1]))
+                          None if last else g["layers"][li + 1], acc))
             m = B * ho * wo * L["cout"] * 9 * L["cin"]
             macs += m
             binops += 2.0 * m * L["w_bits"] * L["a_bits"]
@@ -184,8 +187,8 @@ def conv_workload(args):
     def step():
         for d_x, L0, first, steps in plans:
             qnn.qnn_encode_pack(d_x, L0["clip"], L0["a_bits"], planes=first)
-            for planes, wp, shape, L, sc, out, nxt, Ln in steps:
-                qnn.qnn_conv2d(planes, wp, shape, L["cin"], L["stride"], L["pad"], scale=sc, want_acc=False,
+            for planes, wp, shape, L, sc, out, nxt, Ln, acc in steps:
+                qnn.qnn_conv2d(planes, wp, shape, L["cin"], L["stride"], L["pad"], scale=sc, want_acc=False, acc=acc,
                                want_out=out is not None, out=out,
                                next_clip=None if Ln is None else Ln["clip"],
                                next_bits=0 if Ln is None else Ln["a_bits"], next_planes=nxt)
@@ -207,17 +210,18 @@ def conv_workload(args):
             last = li + 1 == len(g["layers"])
             nxt = None if last else torch.empty((B, ho, wo, L["cout"]), dtype=torch.int8, device="cuda")
             out = torch.empty((B, ho, wo, L["cout"]), dtype=torch.float32, device="cuda") if last else None
+            acc = torch.empty((B, ho, wo, L["cout"]), dtype=torch.int32, device="cuda") if single else None
             msteps.append((lv, torch.from_numpy(L["w"]).cuda(), L, torch.from_numpy(L["scale"]).cuda(), out, nxt,
-                           None if last else g["layers"][li + 1]))
+                           None if last else g["layers"][li + 1], acc))
             lv, H, W = nxt, ho, wo
         mplans.append((d_x, g["layers"][0], first, msteps))
 
     def mfma_step():
         for d_x, L0, first, msteps in mplans:
             qnn.qnn_encode_levels_i8(d_x, L0["clip"], L0["a_bits"], levels=first)
-            for lv, w, L, sc, out, nxt, Ln in msteps:
+            for lv, w, L, sc, out, nxt, Ln, acc in msteps:
                 qnn.qnn_level_conv2d_i8(lv, w, L["stride"], L["pad"], L["a_bits"], L["w_bits"], scale=sc,
-                                        want_acc=False, want_out=out is not None, out=out,
+                                        want_acc=False, acc=acc, want_out=out is not None, out=out,
                                         next_clip=None if Ln is None else Ln["clip"],
                                         next_bits=0 if Ln is None else Ln["a_bits"], next_levels=nxt)
 
@@ -239,17 +243,18 @@ def conv_workload(args):
                 last = li + 1 == len(g["layers"])
                 nxt = None if last else torch.empty((B, ho, wo, L["cout"] // 2), dtype=torch.uint8, device="cuda")
                 out = torch.empty((B, ho, wo, L["cout"]), dtype=torch.float32, device="cuda") if last else None
+                acc = torch.empty((B, ho, wo, L["cout"]), dtype=torch.int32, device="cuda") if single else None
                 fsteps.append((lv, qnn.qnn_levels_to_fp4(torch.from_numpy(L["w"]).cuda()), L,
-                               torch.from_numpy(L["scale"]).cuda(), out, nxt, None if last else g["layers"][li + 1]))
+                               torch.from_numpy(L["scale"]).cuda(), out, nxt, None if last else g["layers"][li + 1], acc))
                 lv, H, W = nxt, ho, wo
             fplans.append((d_x, g["layers"][0], first, fsteps))
 
         def fp4_step():
             for d_x, L0, first, fsteps in fplans:
                 qnn.qnn_encode_levels_fp4(d_x, L0["clip"], L0["a_bits"], levels=first)
-                for lv, w, L, sc, out, nxt, Ln in fsteps:
+                for lv, w, L, sc, out, nxt, Ln, acc in fsteps:
                     qnn.qnn_level_conv2d_fp4(lv, w, L["stride"], L["pad"], L["a_bits"], L["w_bits"], scale=sc,
-                                             want_acc=False, want_out=out is not None, out=out,
+                                             want_acc=False, acc=acc, want_out=out is not None, out=out,
                                              next_clip=None if Ln is None else Ln["clip"],
                                              next_bits=0 if Ln is None else Ln["a_bits"], next_levels=nxt)
 
