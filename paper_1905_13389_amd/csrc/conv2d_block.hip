@@ -7,8 +7,9 @@
 // i s + ky - p = y, j s + kx - p = x of a[i][j] . w[ky][kx].  For a fixed y only the taps
 // ky = fy + t s (fy = (y + p) mod s) take part, and with q = (y + p - fy) / s the sum runs over
 // a[q - t] w[fy + t s]: a stride-1 convolution of the input with the sub-kernel of phase fy, flipped.
-// So the s x s phases are s^2 ordinary launches of the tile kernel, each on its own sub-kernel
-// (gathered once by qnn_deconv_pack_weights), each writing every s-th output pixel per axis.
+// So the s x s phases are ordinary runs of the tile kernel, each on its own sub-kernel (gathered once
+// by qnn_deconv_pack_weights), each writing every s-th output pixel per axis: one launch with the
+// resident workgroups divided among the phases when all phases have one shape, else one launch each.
 #include "conv2d_tile.h"
 
 namespace qnn {
