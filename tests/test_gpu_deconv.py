@@ -123,3 +123,27 @@ def test_deconv_random_geometry(geom):
     np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s), rtol=RTOL, atol=0)
     lv, _ = oracle.quantize(oracle.scale(want, s), 1.0, 2)
     assert np.array_equal(planes_to_numpy(nxt), oracle.pack_planes(lv.reshape(-1, Cout), 2)), geom
+
+
+def test_deconv_benchmark_configuration_sampled_images():
+    # the layer bench.py --workload deconv times (batch 64, 28x28x128 -> 56x56x64, 4x4 stride 2, 2x2 bit, one launch
+    # over the four phases, fused next-layer planes); images are independent, so the oracle on three of them is exact
+    import qnn_workloads as wl
+    B, H, cin, cout, k, s, pad, bits = 64, 28, 128, 64, 4, 2, 1, 2
+    x = wl.rng(7, 0).standard_normal((B * H * H, cin), dtype="float32")
+    w = wl.odd_levels(wl.rng(7, 1), (cout, k, k, cin), bits)
+    sc = wl.channel_scales(wl.rng(7, 2), cout)
+    ph = qnn.qnn_deconv_pack_weights(pack_levels(w, bits).view(bits, cout, k, k, -1), cin, s)
+    planes = qnn.qnn_encode_pack(dev(x), 3.0, bits)
+    acc, out, nxt = qnn.qnn_deconv2d(planes, ph, (B, H, H), cin, cout, k, k, s, pad, bits, scale=dev(sc), want_out=True,
+                                     next_clip=3.0, next_bits=bits)
+    torch.cuda.synchronize()
+    images = [0, 37, 63]
+    lv, _ = oracle.quantize(x.reshape(B, H, H, cin)[images], 3.0, bits)
+    want = oracle.deconv2d(lv.astype(np.int8), w, s, pad)
+    assert np.array_equal(acc.cpu().numpy()[images], want)
+    wout = oracle.scale(want, sc)
+    np.testing.assert_allclose(out.cpu().numpy()[images], wout, rtol=RTOL, atol=0)
+    nlv, _ = oracle.quantize(wout, 3.0, bits)
+    got = planes_to_numpy(nxt).reshape(bits, B, 56 * 56, -1)[:, images].reshape(bits, -1, cout // 32)
+    assert np.array_equal(got, oracle.pack_planes(nlv.reshape(-1, cout), bits))
