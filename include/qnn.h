@@ -316,6 +316,11 @@ int qnn_levels_to_fp4(const int8_t *levels, int64_t count, uint8_t *fp4, void *s
 int qnn_level_conv2d_fp4(const qnn_conv_desc *desc, const uint8_t *a_levels, const uint8_t *w_levels,
                          const float *scale, int32_t *acc, float *out, uint8_t *next_levels,
                          float next_clip, int next_bits, void *stream);
+/* qnn_level_conv2d_block_fp4: qnn_level_conv2d_fp4 with the residual-block terms of qnn_conv2d_block; epi->res_q is
+ * DEVICE uint8 fp4 levels [B][Ho][Wo][Cout / 2] of a 1- or 2-bit code (Cout even). */
+int qnn_level_conv2d_block_fp4(const qnn_conv_desc *desc, const uint8_t *a_levels, const uint8_t *w_levels,
+                               const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                               uint8_t *next_levels, float next_clip, int next_bits, void *stream);
 /* qnn_maxpool_levels_fp4: qnn_maxpool_levels_i8 on fp4 levels, DEVICE uint8 [B][H][W][C / 2] -> [B][Ho][Wo][C / 2], C even. */
 int qnn_maxpool_levels_fp4(const uint8_t *levels, int64_t B, int64_t H, int64_t W, int64_t C, int k, int stride,
                            int pad, int ceil_mode, uint8_t *out_levels, void *stream);

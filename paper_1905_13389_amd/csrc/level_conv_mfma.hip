@@ -360,6 +360,26 @@ level_conv_mfma_kernel(LevelConvParams p)
             const int rl = v / kVecPerRow, cv = (v % kVecPerRow) * 16;
             const int row = row0 + rl, c = col0 + cv;
             if (row >= p.pixels || c >= p.Cout) continue;
+            if constexpr (FP4) {
+                // the shortcut holds nibbles: expand them to int8 levels on the way into LDS (Cout is even)
+                const uint8_t *src = reinterpret_cast<const uint8_t *>(resq) + ((int64_t)row * p.Cout + c) / 2;
+                uint32_t nib[2] = {0u, 0u};
+                if (c + 16 <= p.Cout && (p.Cout & 15) == 0) {
+                    const uint2 t = *reinterpret_cast<const uint2 *>(src);
+                    nib[0] = t.x, nib[1] = t.y;
+                } else {
+                    for (int e = 0; e < 8 && c + 2 * e < p.Cout; ++e) nib[e >> 2] |= (uint32_t)src[e] << (8 * (e & 3));
+                }
+                uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const uint32_t n = (nib[e >> 3] >> (4 * (e & 7))) & 15u;
+                    const int level = ((n & 1u) ? 3 : 1) * ((n & 8u) ? -1 : 1);
+                    o[e >> 2] |= ((uint32_t)level & 0xffu) << (8 * (e & 3));
+                }
+                *reinterpret_cast<uint4 *>(lv + rl * NB + cv) = make_uint4(o[0], o[1], o[2], o[3]);
+                continue;
+            }
             const int8_t *src = resq + (int64_t)row * p.Cout + c;
             if (c + 16 <= p.Cout && (p.Cout & 15) == 0) {
                 *reinterpret_cast<uint4 *>(lv + rl * NB + cv) = *reinterpret_cast<const uint4 *>(src);
@@ -533,8 +553,8 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
         return fail(QNN_ERR_INVALID_ARG, "%s: bits must be in [1,%d]", who, hard_bits);
     if (d->a_bits > max_bits || d->w_bits > max_bits)
         return fail(QNN_ERR_UNSUPPORTED, "%s: more than %d bits (%s levels)", who, max_bits, fp4 ? "fp4" : "int8");
-    if (fp4 && (blk.bias || blk.res_q || blk.res_f32))
-        return fail(QNN_ERR_UNSUPPORTED, "%s: residual-block terms are not built for fp4 levels", who);
+    if (fp4 && blk.res_q && (blk.res_bits > 2 || d->Cout % 2 != 0))
+        return fail(QNN_ERR_UNSUPPORTED, "%s: an fp4 shortcut holds 1- or 2-bit codes of an even channel count", who);
     if (d->B < 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0)
         return fail(QNN_ERR_INVALID_ARG, "%s: bad tensor size", who);
     if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
@@ -599,10 +619,11 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
     // workgroups per CU hide each other's prologue and epilogue; above that 256 x 256 with 128-byte
     // stages (one workgroup per CU) when its workgroups fill at least three quarters of the CU rounds
     // they take, otherwise 128 x 128 with four waves, two workgroups per CU.
-    const bool terms = blk.bias || blk.res_q || blk.res_f32; // never with fp4 (checked above)
+    const bool terms = blk.bias || blk.res_q || blk.res_f32;
     auto go = [&](auto shape) {
         constexpr int MB = decltype(shape)::MB, NB = decltype(shape)::NB, WM = decltype(shape)::WM, WN = decltype(shape)::WN,
                       KB = decltype(shape)::KB;
+        if (fp4 && terms) return launch_level_conv_k<MB, NB, WM, WN, KB, true, true>(p, st);
         if (fp4) return launch_level_conv_k<MB, NB, WM, WN, KB, true, false>(p, st);
         if (terms) return launch_level_conv_k<MB, NB, WM, WN, KB, false, true>(p, st);
         return launch_level_conv_k<MB, NB, WM, WN, KB, false, false>(p, st);
@@ -639,6 +660,15 @@ extern "C" int qnn_level_conv2d_fp4(const qnn_conv_desc *d, const uint8_t *a_lev
 {
     return level_conv_run("qnn_level_conv2d_fp4", true, d, reinterpret_cast<const int8_t *>(a_levels),
                           reinterpret_cast<const int8_t *>(w_levels), scale, nullptr, acc, out,
+                          reinterpret_cast<int8_t *>(next_levels), next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_level_conv2d_block_fp4(const qnn_conv_desc *d, const uint8_t *a_levels, const uint8_t *w_levels,
+                                          const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                                          uint8_t *next_levels, float next_clip, int next_bits, void *stream)
+{
+    return level_conv_run("qnn_level_conv2d_block_fp4", true, d, reinterpret_cast<const int8_t *>(a_levels),
+                          reinterpret_cast<const int8_t *>(w_levels), scale, epi, acc, out,
                           reinterpret_cast<int8_t *>(next_levels), next_clip, next_bits, stream);
 }
 

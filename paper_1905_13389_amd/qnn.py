@@ -29,7 +29,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_probe_valu", "qnn_probe_mfma", "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
-           "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_maxpool_levels_fp4",
+           "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_level_conv2d_block_fp4", "qnn_maxpool_levels_fp4",
            "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
            "qnn_last_error", "qnn_version")
 
@@ -120,6 +120,8 @@ def lib():
         L.qnn_levels_to_fp4.restype = i32
         L.qnn_level_conv2d_fp4.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_level_conv2d_fp4.restype = i32
+        L.qnn_level_conv2d_block_fp4.argtypes = L.qnn_conv2d_block.argtypes
+        L.qnn_level_conv2d_block_fp4.restype = i32
         L.qnn_maxpool_levels_fp4.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
         L.qnn_maxpool_levels_fp4.restype = i32
         L.qnn_last_error.argtypes = []
@@ -393,10 +395,8 @@ def qnn_levels_to_fp4(levels, out=None):
     return out
 
 
-def qnn_level_conv2d_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=None, want_acc=True, want_out=False,
-                         next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
-    """a_levels uint8 [B][H][W][Cin/2], w_levels uint8 [Cout][kh][kw][Cin/2] (fp4, two channels per byte).
-    Returns (acc, out, next_levels [B][Ho][Wo][Cout/2]); entries not requested are None."""
+def _level_conv_fp4(entry, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale, want_acc, want_out, next_clip,
+                    next_bits, acc, out, next_levels):
     B, H, W, cinb = a_levels.shape
     cout, kh, kw, cinb2 = w_levels.shape
     assert cinb == cinb2 and a_levels.dtype == torch.uint8 and w_levels.dtype == torch.uint8
@@ -411,10 +411,28 @@ def qnn_level_conv2d_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=
         out = torch.empty((B, ho, wo, cout), dtype=torch.float32, device=dev)
     if next_clip is not None and next_levels is None:
         next_levels = torch.empty((B, ho, wo, cout // 2), dtype=torch.uint8, device=dev)
-    _check(lib().qnn_level_conv2d_fp4(ctypes.byref(d), _ptr(a_levels), _ptr(w_levels), _ptr(scale), _ptr(acc), _ptr(out),
-                                      _ptr(next_levels), float(next_clip) if next_clip is not None else 0.0,
-                                      int(next_bits), _stream()))
+    head = (ctypes.byref(d), _ptr(a_levels), _ptr(w_levels), _ptr(scale))
+    tail = (_ptr(acc), _ptr(out), _ptr(next_levels), float(next_clip) if next_clip is not None else 0.0,
+            int(next_bits), _stream())
+    _check(entry(*head, *tail) if epi is None else entry(*head, ctypes.byref(epi), *tail))
     return acc, out, next_levels
+
+
+def qnn_level_conv2d_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=None, want_acc=True, want_out=False,
+                         next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """a_levels uint8 [B][H][W][Cin/2], w_levels uint8 [Cout][kh][kw][Cin/2] (fp4, two channels per byte).
+    Returns (acc, out, next_levels [B][Ho][Wo][Cout/2]); entries not requested are None."""
+    return _level_conv_fp4(lib().qnn_level_conv2d_fp4, None, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
+                           want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
+
+
+def qnn_level_conv2d_block_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale, bias=None, res_levels=None,
+                               res_bits=0, res_scale=0.0, res_f32=None, want_acc=True, want_out=False,
+                               next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """qnn_level_conv2d_fp4 with the residual-block terms; res_levels uint8 fp4 [B][Ho][Wo][Cout/2]."""
+    epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32)
+    return _level_conv_fp4(lib().qnn_level_conv2d_block_fp4, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
+                           want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
 
 
 def qnn_maxpool_levels_fp4(levels, k, stride, pad=0, ceil_mode=False, out=None):

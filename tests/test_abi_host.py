@@ -196,6 +196,14 @@ def test_fp4_convolution_argument_errors(qnn):
     assert call(D(1, 8, 8, 80000, 64, 5, 5, 1, 2, 2, 2)) in (qnn.QNN_ERR_RANGE, qnn.QNN_ERR_UNSUPPORTED)
     assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2), w=ODD) == qnn.QNN_ERR_ALIGNMENT
     assert call(D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
+    E = qnn.qnn_block_epilogue
+    okd = D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)
+    blk = lambda e, d=okd: L.qnn_level_conv2d_block_fp4(ctypes.byref(d), FAKE, FAKE, FAKE, ctypes.byref(e), FAKE, None, None,
+                                                         0.0, 0, None)
+    assert blk(E(None, FAKE.value, 3, 1.0, None)) == qnn.QNN_ERR_UNSUPPORTED            # a 3-bit shortcut is not fp4
+    assert blk(E(None, FAKE.value, 2, 1.0, None), D(1, 8, 8, 64, 63, 3, 3, 1, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED
+    assert blk(E(ODD.value, None, 0, 0.0, None)) == qnn.QNN_ERR_ALIGNMENT
+    assert blk(E(FAKE.value, FAKE.value, 2, 1.0, FAKE.value), D(0, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)) == qnn.QNN_OK
     assert L.qnn_encode_levels_fp4(FAKE, 0, 64, 1.0, 3, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
     assert L.qnn_encode_levels_fp4(FAKE, 0, 63, 1.0, 2, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
     assert L.qnn_encode_levels_fp4(FAKE, 2, 64, 1.0, 2, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED

@@ -172,3 +172,64 @@ def test_cifar_network_fp4_route(bits):
     for i, (g, o) in enumerate(zip(got, want)):
         assert np.array_equal(g.cpu().numpy().reshape(o.shape[:-1] + (o.shape[-1] // 2,)), nibbles(o)), i
     np.testing.assert_allclose(out.cpu().numpy(), want_out, rtol=RTOL, atol=0)
+
+
+@pytest.mark.parametrize("geom", [(2, 7, 9, 32, 4, 3, 1, 1), (2, 6, 5, 96, 38, 1, 1, 0), (2, 14, 14, 128, 130, 3, 1, 1),
+                                  (5, 13, 13, 64, 64, 3, 1, 1)])
+@pytest.mark.parametrize("which", ["bias", "res_q", "res_f32", "all"])
+@pytest.mark.parametrize("res_bits", [1, 2])
+def test_fp4_block_terms(geom, which, res_bits):
+    B, H, W, Cin, Cout, k, stride, pad = geom
+    gen = np.random.default_rng(sum(geom) + len(which) + res_bits)
+    a, w = levels(gen, (B, H, W, Cin), 2), levels(gen, (Cout, k, k, Cin), 2)
+    s = (gen.uniform(0.5, 1.5, size=Cout) / np.sqrt(k * k * Cin * 25.0)).astype(np.float32)
+    want_acc = oracle.conv2d(a, w, stride, pad)
+    bias = gen.uniform(-1, 1, size=Cout).astype(np.float32) if which in ("bias", "all") else None
+    res_lv = levels(gen, want_acc.shape, res_bits) if which in ("res_q", "all") else None
+    res_f = gen.normal(0, 1, size=want_acc.shape).astype(np.float32) if which in ("res_f32", "all") else None
+    rs = np.float32(0.41)
+    opt = lambda t: None if t is None else dev(t)
+    acc, out, nxt = qnn.qnn_level_conv2d_block_fp4(
+        qnn.qnn_levels_to_fp4(dev(a)), qnn.qnn_levels_to_fp4(dev(w)), stride, pad, 2, 2, dev(s), bias=opt(bias),
+        res_levels=None if res_lv is None else qnn.qnn_levels_to_fp4(dev(res_lv)), res_bits=res_bits, res_scale=float(rs),
+        res_f32=opt(res_f), want_out=True, next_clip=2.0, next_bits=2)
+    torch.cuda.synchronize()
+    want = oracle.block_epilogue(want_acc, s, bias, res_lv, rs, res_f)
+    assert np.array_equal(acc.cpu().numpy(), want_acc)
+    np.testing.assert_allclose(out.cpu().numpy(), want, rtol=RTOL, atol=0)
+    lv, _ = oracle.quantize(want, 2.0, 2)
+    assert np.array_equal(nxt.cpu().numpy(), nibbles(lv))
+
+
+def test_resnet18_trunk_fp4_route():
+    # the residual trunk at 2 bits entirely on fp4 levels: shifts, identity shortcuts read back as nibbles,
+    # 1x1 shortcut convolutions handed over in fp32
+    bits = 2
+    net = wl.resnet18_trunk(batch=2, bits=bits)
+    x, blocks = net["x"], net["blocks"]
+    f4 = lambda t: qnn.qnn_levels_to_fp4(dev(t))
+    a = qnn.qnn_encode_levels_fp4(dev(x), blocks[0]["conv1"]["clip"], bits)
+    got = []
+    for bi, blk in enumerate(blocks):
+        c1, c2, dn = blk["conv1"], blk["conv2"], blk["down"]
+        nxt_clip = blocks[bi + 1]["conv1"]["clip"] if bi + 1 < len(blocks) else None
+        st = c1["stride"]
+        _, _, hq = qnn.qnn_level_conv2d_block_fp4(a, f4(c1["w"]), st, 1, bits, bits, dev(c1["scale"]), bias=dev(c1["bias"]),
+                                                  want_acc=False, next_clip=c2["clip"], next_bits=bits)
+        if dn is not None:
+            _, short, _ = qnn.qnn_level_conv2d_block_fp4(a, f4(dn["w"]), st, 0, bits, bits, dev(dn["scale"]),
+                                                         bias=dev(dn["bias"]), want_acc=False, want_out=True)
+            kw = {"res_f32": short}
+        else:
+            kw = {"res_levels": a, "res_bits": bits, "res_scale": blk["res_scale"]}
+        _, y, nxt = qnn.qnn_level_conv2d_block_fp4(hq, f4(c2["w"]), 1, 1, bits, bits, dev(c2["scale"]), bias=dev(c2["bias"]),
+                                                   want_acc=False, want_out=True, next_clip=nxt_clip,
+                                                   next_bits=bits if nxt_clip is not None else 0, **kw)
+        got.append((a, hq, y))
+        a = nxt
+    torch.cuda.synchronize()
+    want = oracle.residual_trunk(x, blocks)
+    for bi, ((ga, ghq, gy), o) in enumerate(zip(got, want)):
+        assert np.array_equal(ga.cpu().numpy(), nibbles(o["a"])), bi
+        assert np.array_equal(ghq.cpu().numpy(), nibbles(o["hq"])), bi
+        np.testing.assert_allclose(gy.cpu().numpy(), o["y"], rtol=RTOL, atol=0)
