@@ -49,11 +49,17 @@ template <int WB, int AB, int TM, int TN, int KV = 4, int KB = kBK> struct Tile 
 };
 
 // Lane tile per (w_bits, a_bits): TM*TN*(WB+AB-1) counters plus KV*(TM*AB + TN*WB) operand
-// registers must stay well inside the 256-register budget of a lane (2 waves per SIMD).
+// registers must stay well inside the 256-register budget of a lane (2 waves per SIMD).  Rectangular
+// tiles put their short side on the operand with more planes: a k group then reads TM*AB + TN*WB
+// operand words for its TM*TN*WB*AB pairs, and fewer reads per pair is what the low bit widths lack.
 template <int WB, int AB> struct TilePick { static constexpr int TM = 4, TN = 4, KV = (WB + AB >= 7 ? 2 : 4); };
 template <> struct TilePick<1, 1> { static constexpr int TM = 8, TN = 8, KV = 4; };
-template <> struct TilePick<1, 2> { static constexpr int TM = 8, TN = 4, KV = 4; };
-template <> struct TilePick<2, 1> { static constexpr int TM = 4, TN = 8, KV = 4; };
+template <> struct TilePick<1, 2> { static constexpr int TM = 4, TN = 8, KV = 4; };
+template <> struct TilePick<2, 1> { static constexpr int TM = 8, TN = 4, KV = 4; };
+template <> struct TilePick<1, 4> { static constexpr int TM = 4, TN = 8, KV = 2; };
+template <> struct TilePick<4, 1> { static constexpr int TM = 8, TN = 4, KV = 2; };
+template <> struct TilePick<2, 3> { static constexpr int TM = 4, TN = 8, KV = 2; };
+template <> struct TilePick<3, 2> { static constexpr int TM = 8, TN = 4, KV = 2; };
 template <> struct TilePick<2, 2> { static constexpr int TM = 8, TN = 4, KV = 4; };
 template <> struct TilePick<1, 3> { static constexpr int TM = 4, TN = 8, KV = 4; };
 template <> struct TilePick<3, 1> { static constexpr int TM = 8, TN = 4, KV = 4; };
