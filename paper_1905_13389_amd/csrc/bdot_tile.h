@@ -215,8 +215,10 @@ template <int KV> __device__ __forceinline__ void lds_read_words(const uint32_t 
 }
 
 // `nkq` = number of KV-word groups of this stage that hold reduction words (fewer for the last
-// stage of a reduction: nothing is spent on the zero tail).
-template <int WB, int AB, int TM, int TN, int KV, int KB>
+// stage of a reduction: nothing is spent on the zero tail).  The activation stage holds APR rows per
+// plane and the lane's row i sits at row ty + ASTEP * i of it (the whole tile: BM rows, step 16; a
+// wave's private quarter of the tile: BM / 4 rows, step 4, ty = the lane's row group inside the wave).
+template <int WB, int AB, int TM, int TN, int KV, int KB, int APR = 16 * TM, int ASTEP = 16>
 __device__ __forceinline__ void tile_mac(const uint32_t *__restrict__ As,
                                          const uint32_t *__restrict__ Ws, int ty, int tx, int nkq,
                                          uint32_t (&P)[TM][TN][WB + AB - 1])
@@ -231,7 +233,7 @@ __device__ __forceinline__ void tile_mac(const uint32_t *__restrict__ As,
 #pragma unroll
             for (int j = 0; j < AB; ++j) {
                 uint32_t v[KV];
-                lds_read_words<KV>(As + (j * T::BM + ty + 16 * i) * T::BKP + KV * kq, v);
+                lds_read_words<KV>(As + (j * APR + ty + ASTEP * i) * T::BKP + KV * kq, v);
 #pragma unroll
                 for (int kk = 0; kk < KV; ++kk) a[i][kk][j] = v[kk];
             }

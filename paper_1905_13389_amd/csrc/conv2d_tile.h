@@ -106,7 +106,13 @@ __device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
 // rolled over the rows of the tile, and the next layer's plane words are assembled from 8 lanes'
 // nibbles with three DPP ORs.
 // KEEPW: the reduction fits one stage (nchunks == 1) and the weight stage is written to LDS once per
-// workgroup instead of once per row tile; the two stage buffers then hold activations only.
+// workgroup instead of once per row tile; the two stage buffers then hold activations only.  Nothing
+// else is shared between the waves then, so each wave runs its quarter of every tile on its own: a
+// wave owns the tile rows ty + 16 i of its 4 row groups ty, gathers exactly those rows into its own
+// quarter of a stage buffer, hands its accumulators over through the same quarter, and finishes the
+// rows it owns in the row-major half of the epilogue.  The three workgroup barriers per tile become
+// wave-local ordering points, and the waves of a workgroup drift apart instead of idling together
+// (short reductions spend a large share of a tile outside the xor + bitcount block).
 // BLK: the residual-block terms (bias, shortcut) are part of the epilogue.
 template <int WB, int AB, int TM, int TN, int KV, int VW, bool KEEPW, bool BLK>
 __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void
@@ -132,6 +138,40 @@ bconv_tile_kernel(ConvTileParams p)
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
+    const int lane = tid & 63, wave = tid >> 6;
+    constexpr int WR = BM / 4;               // tile rows of one wave; tile row ty + 16 i <-> its row (ty & 3) + 4 i
+    constexpr int WAVE_UNITS = AB * WR * UQ; // stage units of one wave's rows
+    constexpr int A_PT = KEEPW ? (WAVE_UNITS + 63) / 64 : T::A_PER_THREAD;
+    constexpr int CHUNK = STAGE_ALLOC / 4;   // a wave's quarter of a stage buffer (its rows' stage, then its V rows)
+    static_assert(STAGE_ALLOC % 16 == 0 && CHUNK >= AB * WR * T::BKP && CHUNK >= WR * EPI_STRIDE, "wave quarters");
+    // ordering point between a tile's phases
+    auto tile_sync = [&]() {
+        if constexpr (KEEPW) {
+            // a wave's LDS operations execute in order; the compiler must keep them in program order
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            __syncthreads();
+        }
+    };
+    // stage unit u of this lane: plane and tile row it belongs to, 4-word unit inside the row, LDS word offset
+    auto unit = [&](int u, int &plane, int &trow, int &q, int &lds) {
+        if constexpr (KEEPW) {
+            const int idx = lane + u * 64;
+            const int rp = idx / UQ, slot = rp % WR; // rp = plane * WR + row of the wave
+            q = idx % UQ, plane = rp / WR;
+            trow = 4 * wave + (slot & 3) + 16 * (slot >> 2);
+            lds = wave * CHUNK + rp * T::BKP + 4 * q;
+            return WAVE_UNITS % 64 == 0 || idx < WAVE_UNITS;
+        } else {
+            const int idx = tid + u * kTileThreads;
+            const int rp = idx / UQ;
+            q = idx % UQ, plane = rp / BM, trow = rp % BM;
+            lds = rp * T::BKP + 4 * q;
+            return T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS;
+        }
+    };
     int bid = (int)blockIdx.x;
     const uint32_t *wbase = p.w;
     int pad_y = BLK ? p.pad_y : p.pad, pad_x = BLK ? p.pad_x : p.pad, oy0 = 0, ox0 = 0;
@@ -191,31 +231,32 @@ bconv_tile_kernel(ConvTileParams p)
     }
 
     // where this lane's stage units start in the activation planes, and their padded taps
-    int abase[T::A_PER_THREAD];
-    uint32_t apad[T::A_PER_THREAD];
+    int abase[A_PT];
+    uint32_t apad[A_PT];
     auto locate = [&](int row0) {
 #pragma unroll
-        for (int u = 0; u < T::A_PER_THREAD; ++u) {
-            const int idx = tid + u * kTileThreads;
-            const int rp = idx / UQ;
-            const int m = row0 + rp % BM;
-            const bool ok = (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS) && m < p.M;
+        for (int u = 0; u < A_PT; ++u) {
+            int plane, trow, q, lds;
+            const bool in_stage = unit(u, plane, trow, q, lds);
+            const int m = row0 + trow;
+            const bool ok = in_stage && m < p.M;
             const uint32_t mm = ok ? (uint32_t)m : 0u;
             const uint32_t b = fdiv(mm, p.div_howo), rem = mm - b * p.div_howo.d;
             const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
             apad[u] = ok ? (ymask[ho] | xmask[wo]) : 0xffffffffu;
-            abase[u] = (rp / BM) * p.a_plane_stride +
+            abase[u] = plane * p.a_plane_stride +
                        ((int)b * p.HW + ((int)ho * p.stride - pad_y) * p.W + (int)wo * p.stride - pad_x) * p.cw;
         }
     };
 
-    uint4 ra[T::A_PER_THREAD], rw[T::W_PER_THREAD];
+    uint4 ra[A_PT], rw[T::W_PER_THREAD];
     constexpr bool keep_w = KEEPW;
     bool w_staged = false;
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int u = 0; u < T::A_PER_THREAD; ++u) {
-            const int q = (tid + u * kTileThreads) % UQ;
+        for (int u = 0; u < A_PT; ++u) {
+            int plane, trow, q, lds;
+            unit(u, plane, trow, q, lds);
             ra[u] = gather4<VW>(p.a, tap_table, 4 * q < p.kb ? p.nw : 0, apad[u], abase[u], k0 + 4 * q);
         }
         if (w_staged) return;
@@ -231,10 +272,9 @@ bconv_tile_kernel(ConvTileParams p)
     auto stash = [&](int buf) {
         uint32_t *As = smem[buf], *Ws = keep_w ? w_resident : smem[buf] + T::A_WORDS;
 #pragma unroll
-        for (int u = 0; u < T::A_PER_THREAD; ++u) {
-            const int idx = tid + u * kTileThreads;
-            if (T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS)
-                lds_write_unit<KV>(As + (idx / UQ) * T::BKP + 4 * (idx % UQ), ra[u]);
+        for (int u = 0; u < A_PT; ++u) {
+            int plane, trow, q, lds;
+            if (unit(u, plane, trow, q, lds)) lds_write_unit<KV>(As + lds, ra[u]);
         }
         if (w_staged) return;
         w_staged = keep_w;
@@ -249,6 +289,11 @@ bconv_tile_kernel(ConvTileParams p)
     // this lane's 4 channels in the row-major half of the epilogue
     constexpr int LPR = BN / 4;            // lanes per pixel row
     constexpr int RPP = kTileThreads / LPR; // pixel rows per pass
+    static_assert(LPR <= 16, "a pass row lies inside one 16-lane row group");
+    // tile row of this lane in pass `pass`: consecutive rows, or (KEEPW) rows its own wave owns
+    auto pass_row = [&](int pass) {
+        return KEEPW ? ty + 16 * (pass * (16 / LPR) + (tid & 15) / LPR) : pass * RPP + tid / LPR;
+    };
     const int c4 = (tid % LPR) * 4;
     const int cidx = col0 + c4;
     const bool cols4 = cidx + 3 < p.Cout && (p.Cout & 3) == 0; // 16-byte accesses are whole and aligned
@@ -287,20 +332,24 @@ bconv_tile_kernel(ConvTileParams p)
             }
             const int left = p.nw - c * p.kb;
             const int nkq = ((left < p.kb ? left : p.kb) + KV - 1) / KV;
-            tile_mac<WB, AB, TM, TN, KV, kConvKB>(smem[buf], keep_w ? w_resident : smem[buf] + T::A_WORDS, ty, tx, nkq, P);
+            if constexpr (KEEPW)
+                tile_mac<WB, AB, TM, TN, KV, kConvKB, WR, 4>(smem[buf] + wave * CHUNK, w_resident, ty & 3, tx, nkq, P);
+            else
+                tile_mac<WB, AB, TM, TN, KV, kConvKB>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P);
             if (more || next_tile) stash(buf ^ 1);
-            __syncthreads();
+            tile_sync();
             buf ^= 1;
         }
         // stage `buf` now holds the next tile's first stage (if any); stage buf^1 is free
 
         // ---- epilogue, first half: recombine and hand the tile over to a row-major layout ----
-        int32_t *V = reinterpret_cast<int32_t *>(&smem[buf ^ 1][0]);
+        int32_t *V = reinterpret_cast<int32_t *>(&smem[buf ^ 1][0]) + (KEEPW ? wave * CHUNK : 0);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int n = 0; n < TN; ++n)
-                V[(ty + 16 * i) * EPI_STRIDE + tx + 16 * n] = recombine<T::S>(P[i][n], p.n_times_top);
+                V[(KEEPW ? (ty & 3) + 4 * i : ty + 16 * i) * EPI_STRIDE + tx + 16 * n] =
+                    recombine<T::S>(P[i][n], p.n_times_top);
         // this lane's nibble of the 32-channel plane word its 4 channels belong to
         const int wword = (col0 >> 5) + (tid % LPR) / 8;
         const int nib_shift = 4 * (tid & 7);
@@ -314,7 +363,7 @@ bconv_tile_kernel(ConvTileParams p)
             const uint32_t *rq = static_cast<const uint32_t *>(p.blk.res_q);
 #pragma unroll
             for (int ps = 0; ps < NPASS; ++ps) {
-                const int r = row0 + ps * RPP + tid / LPR;
+                const int r = row0 + pass_row(ps);
                 const bool rvalid = r < p.M;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -336,14 +385,14 @@ bconv_tile_kernel(ConvTileParams p)
                 }
             }
         }
-        __syncthreads();
+        tile_sync();
 
         // ---- second half: padding correction, stores, scale, quantize, plane split ----
         auto do_pass = [&](const int pass, const uint32_t (&rqw)[8], const float4 rf) {
-            const int rl = pass * RPP + tid / LPR;
+            const int rl = pass_row(pass);
             const int r = row0 + rl;
             const bool rvalid = r < p.M;
-            const int4 vv = *reinterpret_cast<const int4 *>(V + rl * EPI_STRIDE + c4);
+            const int4 vv = *reinterpret_cast<const int4 *>(V + (KEEPW ? (rl & 3) + 4 * (rl >> 4) : rl) * EPI_STRIDE + c4);
             int32_t v[4] = {vv.x, vv.y, vv.z, vv.w};
             // padded taps of this output pixel
             uint32_t padded = 0;
@@ -449,7 +498,7 @@ bconv_tile_kernel(ConvTileParams p)
 #pragma unroll 1
             for (int pass = 0; pass < NPASS; ++pass) do_pass(pass, rq_pre[0], rf_pre[0]);
         }
-        __syncthreads(); // V's stage is about to be refilled by the next tile's pipeline
+        tile_sync(); // V's stage is about to be refilled by the next tile's pipeline
     }
 }
 
