@@ -13,7 +13,10 @@ float64 convolution block by block) are in tests/test_oracle_block.py.  deconv2d
 (the library's transposed convolution in float64, the adjoint identity with conv2d, brute force) are in
 tests/test_oracle_deconv.py.  quantize_ste_backward /
 encoder_backward are numpy float64; their pins (Eq. 12-13's printed values, finite differences of the sines,
-the sines' signs against the quantizer's planes) are in tests/test_oracle_training.py.
+the sines' signs against the quantizer's planes) are in tests/test_oracle_training.py.  dense_conv2d /
+dense_layer / global_avgpool / dense_fc (the unquantized ends of a network) are numpy float64; their pins
+(brute-force loops, the library's float64 convolution, shifted copies through one-hot kernels, tap counts
+of all-ones tensors, the integer convolution on integer-valued inputs) are in tests/test_oracle_dense.py.
 """
 import ctypes
 import os
@@ -360,3 +363,67 @@ def maxpool(levels, k, stride, pad=0, ceil_mode=False):
     if (out == lowest).any():
         raise ValueError("a pooling window holds no image element")
     return out.astype(a.dtype)
+
+
+def dense_conv2d(x, w, stride, pad):
+    """Unquantized convolution in float64, written as its definition: out[b][ho][wo][co] = sum over
+    (ky, kx, ci) of x[b][ho stride + ky - pad][wo stride + kx - pad][ci] w[co][ky][kx][ci], taps outside
+    the image contribute 0.  The networks of the experiments section keep their first and last layers
+    unquantized (the ResNet-18 workload says so); this is the first one.
+    x: [B][H][W][Cin], w: [Cout][kh][kw][Cin] -> float64 [B][Ho][Wo][Cout]."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    B, H, W, Cin = x.shape
+    Cout, kh, kw, Cin2 = w.shape
+    assert Cin == Cin2 and stride >= 1 and pad >= 0
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    assert Ho >= 1 and Wo >= 1
+    xp = np.zeros((B, H + 2 * pad, W + 2 * pad, Cin))
+    xp[:, pad:pad + H, pad:pad + W, :] = x
+    out = np.zeros((B, Ho, Wo, Cout))
+    for ky in range(kh):
+        for kx in range(kw):
+            view = xp[:, ky:ky + (Ho - 1) * stride + 1:stride, kx:kx + (Wo - 1) * stride + 1:stride, :]
+            out += view @ w[:, ky, kx, :].T
+    return out
+
+
+def dense_layer(x, w, stride, pad, scale_vec=None, shift=None, relu=False):
+    """dense_conv2d, then per output channel y = conv * scale[c] + shift[c] (a folded batch normalisation)
+    and optionally max(y, 0), all in float64; the absolute sum sum |x| |w| of every output comes back as
+    well, since the float32 rounding error of any summation order is bounded by a multiple of it."""
+    y = dense_conv2d(x, w, stride, pad)
+    mag = dense_conv2d(np.abs(np.asarray(x, dtype=np.float64)), np.abs(np.asarray(w, dtype=np.float64)), stride, pad)
+    if scale_vec is not None:
+        sv = np.asarray(scale_vec, dtype=np.float64)
+        y, mag = y * sv, mag * np.abs(sv)
+    if shift is not None:
+        sh = np.asarray(shift, dtype=np.float64)
+        y, mag = y + sh, mag + np.abs(sh)
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y, mag
+
+
+def global_avgpool(x):
+    """Mean over the image positions of every channel, float64: [B][H][W][C] -> [B][C] (the pooling in
+    front of ResNet-18's classifier)."""
+    x = np.asarray(x, dtype=np.float64)
+    B, H, W, C = x.shape
+    total = np.zeros((B, C))
+    for i in range(H):
+        for j in range(W):
+            total += x[:, i, j, :]
+    return total / (H * W)
+
+
+def dense_fc(x, w, bias=None):
+    """Unquantized fully connected layer in float64: out[b][o] = sum_i x[b][i] w[o][i] + bias[o] (Eq. 1
+    without quantization; the last layer of the ResNet-18 workload).  Also returns sum |x| |w| + |bias|."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    out, mag = x @ w.T, np.abs(x) @ np.abs(w).T
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        out, mag = out + b, mag + np.abs(b)
+    return out, mag
