@@ -359,6 +359,38 @@ def trunk_workload(args):
             qnn.qnn_level_conv2d_block_i8(a, w, st, pad, bits, bits, sc, next_levels=nxt, out=out, **kw)
 
     ms, m_ms = (timed_ms(torch, f, args.steps, args.warmup) for f in (step, mfma_step))
+
+    # the unquantized ends around the trunk: image -> first convolution (fp32, planes out) -> 3x3 stride-2
+    # pooling of the planes -> trunk -> global average pooling -> classifier
+    ends = wl.resnet18_ends(batch=B)
+    img, w0, s0, b0 = (up(ends[k]) for k in ("image", "stem_w", "stem_scale", "stem_shift"))
+    fc_w, fc_b = up(ends["fc_w"]), up(ends["fc_b"])
+    side = (img.shape[1] + 2 * 3 - 7) // 2 + 1
+    stem_planes = torch.empty((bits, B * side * side, 2), dtype=torch.int32, device="cuda")
+    y_last = p_calls[-1][-1]
+    feat = torch.empty((B, y_last.shape[-1]), dtype=torch.float32, device="cuda")
+    logits = torch.empty((B, fc_w.shape[0]), dtype=torch.float32, device="cuda")
+
+    def stem():
+        qnn.qnn_dense_conv2d_f32(img, w0, 2, 3, scale=s0, shift=b0, relu=True, want_out=False, next_clip=clip0,
+                                 next_bits=bits, next_planes=stem_planes)
+        qnn.qnn_maxpool_planes(stem_planes, (B, side, side), 64, 3, 2, 1, out=p_first)
+
+    def head():
+        qnn.qnn_global_avgpool_f32(y_last, out=feat)
+        qnn.qnn_dense_fc_f32(feat, fc_w, fc_b, out=logits)
+
+    def network():
+        stem()
+        for a, w, shape, cin, st, pad, sc, kw, nxt, out in p_calls:
+            qnn.qnn_conv2d_block(a, w, shape, cin, st, pad, sc, next_planes=nxt, out=out, **kw)
+        head()
+
+    assert side // 2 == H0, "the pooled stem output is the trunk's input"
+    conv_only = lambda: qnn.qnn_dense_conv2d_f32(img, w0, 2, 3, scale=s0, shift=b0, relu=True, want_out=False,
+                                                 next_clip=clip0, next_bits=bits, next_planes=stem_planes)
+    stem_ms, conv_ms, head_ms, net_ms = (timed_ms(torch, f, args.steps, args.warmup) for f in (stem, conv_only, head, network))
+    stem_tflops = 2.0 * B * side * side * 64 * 147 / (conv_ms * 1e-3) / 1e12
     binops = 2.0 * macs * bits * bits
     tops = binops / (ms * 1e-3) / 1e12
     int8_tops = 2.0 * macs / (m_ms * 1e-3) / 1e12
@@ -374,6 +406,13 @@ def trunk_workload(args):
                      "unit": "binary TOP/s", "frac": round(tops / PEAK_BINARY_TOPS, 4), "traffic": None,
                      "frac_of_16_lane_nominal": round(tops / NOMINAL_BINARY_TOPS, 4),
                      "note": "whole step (encode + all conv launches), not a single kernel"},
+        "network": {"step": "qnn_dense_conv2d_f32 (image -> planes) + qnn_maxpool_planes + trunk + "
+                            "qnn_global_avgpool_f32 + qnn_dense_fc_f32: %dx%d images to %d logits" % (img.shape[1], img.shape[2], fc_w.shape[0]),
+                    "ms_per_step": round(net_ms, 4), "images_per_s": round(B / (net_ms * 1e-3), 1),
+                    "stem_ms": round(stem_ms, 4), "head_ms": round(head_ms, 4),
+                    "stem_roofline": {"bound": "mfma", "kernel": "dense_conv_kernel", "achieved": round(stem_tflops, 1),
+                                      "peak": 157.3, "unit": "fp32 TFLOP/s", "frac": round(stem_tflops / 157.3, 4),
+                                      "kernel_ms": round(conv_ms, 4)}},
         "mfma_variant": {"step": "qnn_encode_levels_i8 + qnn_level_conv2d_block_i8 per convolution",
                          "ms_per_step": round(m_ms, 4), "effective_binary_tops": round(binops / (m_ms * 1e-3) / 1e12, 1),
                          "speedup_vs_xor_bitcount_step": round(ms / m_ms, 2),

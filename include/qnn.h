@@ -326,6 +326,37 @@ int qnn_maxpool_levels_fp4(const uint8_t *levels, int64_t B, int64_t H, int64_t 
                            int pad, int ceil_mode, uint8_t *out_levels, void *stream);
 
 /*
+ * The unquantized ends of a network (the ResNet-18 workload of the ImageNet experiment keeps its first
+ * convolution and its classifier in full precision; nothing of Eq. 9 is involved).  fp32 throughout,
+ * products and sums on the matrix cores in fp32: a result differs from the real-number value by at most
+ * a small multiple of 2^-24 sum |x| |w| (the summation order is the kernel's own).
+ *
+ * qnn_dense_conv2d_f32: y[b][ho][wo][c] = sum over (ky, kx, ci) of x[b][ho stride + ky - pad][wo stride + kx - pad][ci]
+ *     w[c][ky][kx][ci] (taps outside the image contribute 0), then y * scale[c] (if scale), + shift[c] (if shift),
+ *     max(y, 0) (if relu), one fp32 operation each.
+ *   x  DEVICE in fp32 [B][H][W][Cin];  w  DEVICE in fp32 [Cout][kh][kw][Cin];  scale, shift  DEVICE in fp32 [Cout] or NULL
+ *   out  DEVICE out fp32 [B][Ho][Wo][Cout] or NULL, Ho = (H + 2 pad - kh) / stride + 1
+ *   next_planes  DEVICE out uint32 [next_bits][B Ho Wo][ceil(Cout / 32)] or NULL: the planes qnn_encode_pack would
+ *     make of y with (next_clip, next_bits) -- the first quantized layer's input without y going through memory
+ *   At least one output; all pointers 16-byte aligned; the caller owns every buffer.  QNN_ERR_INVALID_ARG,
+ *   QNN_ERR_ALIGNMENT, QNN_ERR_RANGE (2^31 output pixels, 2^24 reduction values or more) before any launch.
+ * qnn_global_avgpool_f32: out[b][c] = (sum over the hw positions of x[b][.][c]) / hw; x DEVICE fp32 [B][hw][C],
+ *     out DEVICE fp32 [B][C].
+ * qnn_dense_fc_f32: out[r][o] = sum_i x[r][i] w[o][i] + bias[o] (Eq. 1 on unquantized values); x DEVICE fp32
+ *     [rows][n], w DEVICE fp32 [cols][n], bias DEVICE fp32 [cols] or NULL, out DEVICE fp32 [rows][cols].
+ */
+typedef struct {
+    int64_t B, H, W, Cin, Cout;
+    int kh, kw, stride, pad;
+} qnn_dense_conv_desc;
+int qnn_dense_conv2d_f32(const qnn_dense_conv_desc *desc, const float *x, const float *w, const float *scale,
+                         const float *shift, int relu, float *out, uint32_t *next_planes, float next_clip,
+                         int next_bits, void *stream);
+int qnn_global_avgpool_f32(const float *x, int64_t B, int64_t hw, int64_t C, float *out, void *stream);
+int qnn_dense_fc_f32(const float *x, const float *w, const float *bias, int64_t rows, int64_t cols, int64_t n,
+                     float *out, void *stream);
+
+/*
  * qnn_probe_valu -- measurement aid, not part of the hot path: launches `workgroups` workgroups
  * of 256 lanes that each run `iters` iterations of a register-only loop of 64 VALU instructions
  * per wave, so that the issue rate of the binary dot product's two instructions (the "xnor" and

@@ -31,6 +31,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
            "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_level_conv2d_block_fp4", "qnn_maxpool_levels_fp4",
            "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
+           "qnn_dense_conv2d_f32", "qnn_global_avgpool_f32", "qnn_dense_fc_f32",
            "qnn_last_error", "qnn_version")
 
 
@@ -45,6 +46,12 @@ class qnn_conv_desc(ctypes.Structure):
                 ("Cin", ctypes.c_int64), ("Cout", ctypes.c_int64),
                 ("kh", ctypes.c_int32), ("kw", ctypes.c_int32), ("stride", ctypes.c_int32),
                 ("pad", ctypes.c_int32), ("a_bits", ctypes.c_int32), ("w_bits", ctypes.c_int32)]
+
+
+class qnn_dense_conv_desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
+                ("Cin", ctypes.c_int64), ("Cout", ctypes.c_int64),
+                ("kh", ctypes.c_int32), ("kw", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32)]
 
 
 class qnn_block_epilogue(ctypes.Structure):
@@ -78,6 +85,12 @@ def lib():
         L.qnn_conv2d_block.restype = i32
         L.qnn_level_conv2d_block_i8.argtypes = L.qnn_conv2d_block.argtypes
         L.qnn_level_conv2d_block_i8.restype = i32
+        L.qnn_dense_conv2d_f32.argtypes = [ctypes.POINTER(qnn_dense_conv_desc), vp, vp, vp, vp, i32, vp, vp, f32, i32, vp]
+        L.qnn_dense_conv2d_f32.restype = i32
+        L.qnn_global_avgpool_f32.argtypes = [vp, i64, i64, i64, vp, vp]
+        L.qnn_global_avgpool_f32.restype = i32
+        L.qnn_dense_fc_f32.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
+        L.qnn_dense_fc_f32.restype = i32
         L.qnn_probe_valu.argtypes = [i32, i32, i32, vp, vp]
         L.qnn_probe_valu.restype = i32
         L.qnn_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
@@ -442,6 +455,48 @@ def qnn_maxpool_levels_fp4(levels, k, stride, pad=0, ceil_mode=False, out=None):
     if out is None:
         out = torch.empty((B, max(ho, 0), max(wo, 0), cb), dtype=torch.uint8, device=levels.device)
     _check(lib().qnn_maxpool_levels_fp4(_ptr(levels), B, H, W, 2 * cb, k, stride, pad, int(ceil_mode), _ptr(out), _stream()))
+    return out
+
+
+def qnn_dense_conv2d_f32(x, w, stride, pad, scale=None, shift=None, relu=False, want_out=True, next_clip=None,
+                         next_bits=0, out=None, next_planes=None):
+    """x fp32 [B][H][W][Cin], w fp32 [Cout][kh][kw][Cin] -> (out fp32 [B][Ho][Wo][Cout] or None,
+    next planes int32 [next_bits][B*Ho*Wo][ceil(Cout/32)] or None)."""
+    B, H, W, cin = x.shape
+    cout, kh, kw, cin2 = w.shape
+    assert cin == cin2
+    ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    if want_out and out is None:
+        out = torch.empty((B, max(ho, 0), max(wo, 0), cout), dtype=torch.float32, device=x.device)
+    if next_bits and next_planes is None:
+        next_planes = torch.empty((next_bits, B * max(ho, 0) * max(wo, 0), (cout + 31) // 32), dtype=torch.int32,
+                                  device=x.device)
+    d = qnn_dense_conv_desc(B, H, W, cin, cout, kh, kw, stride, pad)
+    _check(lib().qnn_dense_conv2d_f32(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(scale), _ptr(shift), int(bool(relu)),
+                                      _ptr(out), _ptr(next_planes), float(next_clip or 0.0), int(next_bits), _stream()))
+    return out, next_planes
+
+
+def qnn_global_avgpool_f32(x, out=None):
+    """x fp32 [B][H][W][C] (or [B][hw][C]) -> fp32 [B][C]."""
+    B, C = x.shape[0], x.shape[-1]
+    hw = 1
+    for extent in x.shape[1:-1]:
+        hw *= extent
+    if out is None:
+        out = torch.empty((B, C), dtype=torch.float32, device=x.device)
+    _check(lib().qnn_global_avgpool_f32(_ptr(x), B, hw, C, _ptr(out), _stream()))
+    return out
+
+
+def qnn_dense_fc_f32(x, w, bias=None, out=None):
+    """x fp32 [rows][n], w fp32 [cols][n], bias fp32 [cols] or None -> fp32 [rows][cols]."""
+    rows, n = x.shape
+    cols = w.shape[0]
+    assert w.shape[1] == n
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=x.device)
+    _check(lib().qnn_dense_fc_f32(_ptr(x), _ptr(w), _ptr(bias), rows, cols, n, _ptr(out), _stream()))
     return out
 
 

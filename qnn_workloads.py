@@ -216,3 +216,17 @@ def resnet18_trunk(batch=256, hw=56, bits=3, config_index=6, plan=RESNET18_BLOCK
         t += 3
         blocks.append(blk)
     return {"x": x, "blocks": blocks}
+
+
+def resnet18_ends(batch=256, image=224, classes=1000, config_index=7):
+    """The unquantized ends of ResNet-18 around the trunk: the 7x7 stride-2 first convolution (3 -> 64
+    channels, folded batch-norm scale and shift, ReLU) on an N(0,1) image batch, and the classifier
+    (512 -> classes) behind the global average pooling.  Weights N(0, 1/fan_in): post-scale outputs of
+    about unit variance, so the first quantizer's clip of 3 sees a realistic spread."""
+    g = [rng(config_index, t) for t in range(6)]
+    return {"image": g[0].standard_normal((batch, image, image, 3), dtype=np.float32),
+            "stem_w": (g[1].standard_normal((64, 7, 7, 3), dtype=np.float32) / np.float32(np.sqrt(147.0))),
+            "stem_scale": g[2].uniform(0.8, 1.2, size=64).astype(np.float32),
+            "stem_shift": g[3].normal(0.0, 0.2, size=64).astype(np.float32),
+            "fc_w": (g[4].standard_normal((classes, 512), dtype=np.float32) / np.float32(np.sqrt(512.0))),
+            "fc_b": g[5].normal(0.0, 0.1, size=classes).astype(np.float32)}

@@ -304,3 +304,41 @@ def test_pool_argument_errors_and_out_size(qnn):
     assert ml(FAKE, 1, 8, 8, 0, 2, 2, 0, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
     assert ml(ODD, 1, 8, 8, 16, 2, 2, 0, 0, FAKE, None) == qnn.QNN_ERR_ALIGNMENT
     assert ml(None, 0, 8, 8, 16, 2, 2, 0, 0, None, None) == qnn.QNN_OK
+
+
+def test_dense_layer_argument_errors(qnn):
+    L = qnn.lib()
+    assert ctypes.sizeof(qnn.qnn_dense_conv_desc) == 5 * 8 + 4 * 4
+    dc = L.qnn_dense_conv2d_f32
+    d = qnn.qnn_dense_conv_desc(2, 8, 8, 3, 16, 3, 3, 1, 1)
+    ok = (ctypes.byref(d), FAKE, FAKE, None, None, 0)
+    assert dc(None, FAKE, FAKE, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_ERR_INVALID_ARG
+    assert dc(*ok, None, None, 0.0, 0, None) == qnn.QNN_ERR_INVALID_ARG               # no output at all
+    assert dc(*ok, None, FAKE, 1.0, 0, None) == qnn.QNN_ERR_INVALID_ARG               # planes without bits
+    assert dc(*ok, None, FAKE, 1.0, 9, None) == qnn.QNN_ERR_INVALID_ARG
+    assert dc(*ok, None, FAKE, 0.0, 2, None) == qnn.QNN_ERR_INVALID_ARG               # planes without a clip
+    assert dc(*ok, None, FAKE, float("inf"), 2, None) == qnn.QNN_ERR_INVALID_ARG
+    assert dc(ctypes.byref(d), None, FAKE, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_ERR_INVALID_ARG
+    assert dc(ctypes.byref(d), FAKE, FAKE, None, None, 0, ODD, None, 0.0, 0, None) == qnn.QNN_ERR_ALIGNMENT
+    assert dc(ctypes.byref(d), ODD, FAKE, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_ERR_ALIGNMENT
+    for bad in (qnn.qnn_dense_conv_desc(2, 8, 8, 0, 16, 3, 3, 1, 1), qnn.qnn_dense_conv_desc(2, 8, 8, 3, 16, 3, 3, 0, 1),
+                qnn.qnn_dense_conv_desc(2, 8, 8, 3, 16, 3, 3, 1, -1), qnn.qnn_dense_conv_desc(2, 2, 2, 3, 16, 5, 5, 1, 1),
+                qnn.qnn_dense_conv_desc(-1, 8, 8, 3, 16, 3, 3, 1, 1)):
+        assert dc(ctypes.byref(bad), FAKE, FAKE, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_ERR_INVALID_ARG
+    big = qnn.qnn_dense_conv_desc(1 << 20, 64, 64, 3, 16, 3, 3, 1, 1)                  # 2^32 output pixels
+    assert dc(ctypes.byref(big), FAKE, FAKE, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_ERR_RANGE
+    empty = qnn.qnn_dense_conv_desc(0, 8, 8, 3, 16, 3, 3, 1, 1)
+    assert dc(ctypes.byref(empty), None, None, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_OK
+    ap = L.qnn_global_avgpool_f32
+    assert ap(FAKE, 2, 0, 8, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert ap(FAKE, 2, 4, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert ap(None, 2, 4, 8, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert ap(None, 0, 4, 8, None, None) == qnn.QNN_OK
+    assert ap(FAKE, 1 << 40, 1 << 20, 8, FAKE, None) == qnn.QNN_ERR_RANGE
+    fc = L.qnn_dense_fc_f32
+    assert fc(FAKE, FAKE, None, 4, 0, 8, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert fc(FAKE, FAKE, None, 4, 8, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert fc(FAKE, FAKE, None, 4, 8, 8, None, None) == qnn.QNN_ERR_INVALID_ARG
+    assert fc(None, FAKE, None, 4, 8, 8, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert fc(FAKE, FAKE, None, 4, 8, 8, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert fc(None, None, None, 0, 8, 8, FAKE, None) == qnn.QNN_OK
