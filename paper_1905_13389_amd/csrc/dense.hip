@@ -8,7 +8,10 @@
 // k = (ky, kx, ci).  A workgroup of 4 waves owns 64 pixels x 64 channels, one 32 x 32 MFMA tile per wave.
 // The reduction runs in chunks of up to kChunk values: the 64 pixel rows and the 64 weight rows of a chunk
 // are staged in LDS with an odd row stride, so that the 32 rows a half-wave reads for one MFMA operand
-// fall into 32 different banks; two workgroups fit a CU and cover each other's staging phases.
+// fall into 32 different banks; two workgroups fit a CU and cover each other's staging phases.  Workgroups
+// are persistent: each walks the pixel tiles of one column tile, and when the reduction fits one chunk (the
+// 7 x 7 x 3 first convolution: 147 values) its weights are staged once.  A per-chunk table in LDS maps a
+// reduction value to its offset from the window origin, so the gather is a batch of independent loads.
 #include "qnn_host.h"
 #include "quantize.h"
 #include "fastdiv.h"
@@ -21,16 +24,17 @@ constexpr int kDenseThreads = 256;
 constexpr int kDenseTile = 64;             // pixels and channels per workgroup
 constexpr int kChunk = 152;                // reduction values per LDS stage (even)
 constexpr int kChunkStride = kChunk + 1;   // odd: conflict-free operand reads
-static_assert(kChunk % 2 == 0 && 2 * kDenseTile * kChunkStride * 4 <= 80 * 1024, "two workgroups per CU");
+static_assert(kChunk % 2 == 0 && 2 * kDenseTile * kChunkStride * 4 + kChunk * 8 <= 80 * 1024, "two workgroups per CU");
 
 struct DenseConvParams {
     const float *x, *w, *scale, *shift;
     float *out;
     uint32_t *next;
     int H, W, Cin, Cout, kh, kw, stride, pad, Ho, Wo;
-    int64_t M; // output pixels
+    int64_t M, tiles_m; // output pixels, pixel tiles
     int K;     // kh kw Cin
     int relu, next_bits, next_top, cwo;
+    int fast_offsets; // the input tensor is smaller than 4 GiB: 32-bit byte offsets reach all of it
     float next_inv_clip, next_half_top;
     FastDiv div_howo, div_wo;
 };
@@ -39,86 +43,189 @@ __global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvPara
 {
     __shared__ float As[kDenseTile * kChunkStride];
     __shared__ float Ws[kDenseTile * kChunkStride];
+    __shared__ int2 taps[kChunk]; // per reduction value of the chunk: byte offset from the window origin, ky << 16 | kx
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row0 = (int64_t)blockIdx.x * kDenseTile;
     const int col0 = (int)blockIdx.y * kDenseTile;
+    const int nchunks = (p.K + kChunk - 1) / kChunk;
 
-    // staging: thread -> row tid / 4 of the tile (a pixel for A, a channel for W), every 4th reduction value
+    // staging: thread -> row tid / 4 of the tile (a pixel for A, a channel for W) and the reduction values
+    // sub + 4 t of the chunk, t < kSlots: all of them are fetched and stored (the row has room for them);
+    // those past the chunk hold 0 or are never read
     const int srow = tid >> 2, sub = tid & 3;
-    const int64_t m = row0 + srow;
-    const bool pix_ok = m < p.M;
-    int hi0 = 0, wi0 = 0;
-    const float *xb = p.x;
-    if (pix_ok) {
-        const uint32_t mm = (uint32_t)m;
-        const uint32_t b = fdiv(mm, p.div_howo), rem = mm - b * p.div_howo.d;
-        const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
-        hi0 = (int)ho * p.stride - p.pad, wi0 = (int)wo * p.stride - p.pad;
-        xb = p.x + (int64_t)b * p.H * p.W * p.Cin;
-    }
+    constexpr int kSlots = kChunk / 4, kHalf = kSlots / 2;
+    static_assert(kSlots == 2 * kHalf, "the gather runs in two halves");
     const bool ch_ok = col0 + srow < p.Cout;
     const float *wb = p.w + (int64_t)(ch_ok ? col0 + srow : 0) * p.K;
 
-    // (ky, kx, ci) of this thread's next reduction value, advanced by 4 per step
-    int ci = sub, kx = 0, ky = 0;
-    auto normalize = [&]() {
-        while (ci >= p.Cin) {
-            ci -= p.Cin;
-            if (++kx == p.kw) kx = 0, ++ky;
+    auto stage_taps = [&](int k0, int kc) {
+        for (int kk = tid; kk < kChunk; kk += kDenseThreads) {
+            const int k = k0 + kk, tap = k / p.Cin, ci = k - tap * p.Cin, ky = tap / p.kw, kx = tap - ky * p.kw;
+            taps[kk] = kk < kc ? make_int2(4 * ((ky * p.W + kx) * p.Cin + ci), (ky << 16) | kx) : make_int2(0, 0);
         }
     };
-    normalize();
-
-    v16f acc;
+    auto stage_w = [&](int k0, int kc) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-    const int arow = 32 * (wave & 1) + (lane & 31), brow = 32 * (wave >> 1) + (lane & 31), khalf = lane >> 5;
-
-    for (int k0 = 0; k0 < p.K; k0 += kChunk) {
-        const int kc = p.K - k0 < kChunk ? p.K - k0 : kChunk;
-        const int kc2 = (kc + 1) & ~1; // MFMA steps take two values; an odd tail reads one staged zero
-        for (int kk = sub; kk < kc2; kk += 4) {
-            float xv = 0.0f, wv = 0.0f;
-            if (kk < kc) {
-                const int y = hi0 + ky, xx = wi0 + kx;
-                if (pix_ok && (unsigned)y < (unsigned)p.H && (unsigned)xx < (unsigned)p.W)
-                    xv = xb[((int64_t)y * p.W + xx) * p.Cin + ci];
-                if (ch_ok) wv = wb[k0 + kk];
-                ci += 4;
-                normalize();
+        for (int h = 0; h < 2; ++h) {
+            float v[kHalf];
+#pragma unroll
+            for (int t = 0; t < kHalf; ++t) {
+                const int kk = sub + 4 * (h * kHalf + t);
+                const bool in_w = ch_ok && kk < kc;
+                const float got = *(in_w ? wb + k0 + kk : p.w); // unconditional loads stay independent
+                v[t] = in_w ? got : 0.0f;
             }
-            As[srow * kChunkStride + kk] = xv;
-            Ws[srow * kChunkStride + kk] = wv;
+#pragma unroll
+            for (int t = 0; t < kHalf; ++t) Ws[srow * kChunkStride + sub + 4 * (h * kHalf + t)] = v[t];
         }
-        __syncthreads();
-        const float *ap = As + arow * kChunkStride + khalf, *bp = Ws + brow * kChunkStride + khalf;
-#pragma unroll 8
-        for (int s = 0; s < kc2; s += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[s], bp[s], acc, 0, 0, 0);
-        __syncthreads();
-    }
+    };
 
-    // D layout of the 32 x 32 tile: this lane holds channel lane % 32 of the pixels 8 (r / 4) + 4 (lane / 32) + r % 4
+    // this lane's pixel of a tile: window origin and whether the whole window lies inside the image
+    struct Pixel {
+        bool ok, inside;
+        int hi0, wi0;
+        const char *origin;
+    };
+    auto locate = [&](int64_t tile) {
+        Pixel q = {false, false, 0, 0, reinterpret_cast<const char *>(p.x)};
+        const int64_t m = tile * kDenseTile + srow;
+        if (m < p.M) {
+            const uint32_t mm = (uint32_t)m;
+            const uint32_t b = fdiv(mm, p.div_howo), rem = mm - b * p.div_howo.d;
+            const uint32_t ho = fdiv(rem, p.div_wo), wo = rem - ho * p.div_wo.d;
+            q.ok = true;
+            q.hi0 = (int)ho * p.stride - p.pad, q.wi0 = (int)wo * p.stride - p.pad;
+            q.origin = reinterpret_cast<const char *>(p.x + (((int64_t)b * p.H + q.hi0) * p.W + q.wi0) * p.Cin);
+            q.inside = q.hi0 >= 0 && q.hi0 + p.kh <= p.H && q.wi0 >= 0 && q.wi0 + p.kw <= p.W;
+        }
+        return q;
+    };
+    // The chunk's values of this lane's pixel into registers.  A wave whose 16 pixels all have their whole
+    // window inside the image (and whose tensor 32-bit byte offsets reach) gathers with one table read,
+    // one add and one load per value; otherwise every tap is tested against the image, and the load goes
+    // to a safe address when the test fails, so that the loads of a half stay independent of each other.
+    // (In two halves of kHalf values each: half h holds the slots t = h kHalf ... .)
+    auto gather = [&](const Pixel &q, int kc, int h, float (&v)[kHalf]) {
+        if (p.fast_offsets && __all(q.inside)) {
+            const uint32_t origin = (uint32_t)(q.origin - reinterpret_cast<const char *>(p.x));
+#pragma unroll
+            for (int t = 0; t < kHalf; ++t)
+                v[t] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(p.x) +
+                                                        (origin + (uint32_t)taps[sub + 4 * (h * kHalf + t)].x));
+        } else {
+#pragma unroll
+            for (int t = 0; t < kHalf; ++t) {
+                const int kk = sub + 4 * (h * kHalf + t);
+                const int2 e = taps[kk];
+                const int y = q.hi0 + (e.y >> 16), xx = q.wi0 + (e.y & 0xffff);
+                const bool in_image = q.ok && kk < kc && (unsigned)y < (unsigned)p.H && (unsigned)xx < (unsigned)p.W;
+                const float got = *(in_image ? reinterpret_cast<const float *>(q.origin + e.x) : p.x);
+                v[t] = in_image ? got : 0.0f;
+            }
+        }
+    };
+    auto stash = [&](int h, const float (&v)[kHalf]) {
+#pragma unroll
+        for (int t = 0; t < kHalf; ++t) As[srow * kChunkStride + sub + 4 * (h * kHalf + t)] = v[t];
+    };
+    auto stage_pixels = [&](const Pixel &q, int kc) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            float v[kHalf];
+            gather(q, kc, h, v);
+            stash(h, v);
+        }
+        // the fast gather leaves the window origin's value in the slots past the chunk: an odd chunk reads one of them
+        if ((kc & 1) && sub == (kc & 3)) As[srow * kChunkStride + kc] = 0.0f;
+    };
+
+    const int arow = 32 * (wave & 1) + (lane & 31), brow = 32 * (wave >> 1) + (lane & 31), khalf = lane >> 5;
+    const float *ap = As + arow * kChunkStride + khalf, *bp = Ws + brow * kChunkStride + khalf;
+    auto contract = [&](int kc2, v16f &acc) {
+        // groups of kGroup MFMA steps: all operand reads of a group are issued before its first MFMA
+        constexpr int kGroup = 16;
+        int s = 0;
+        for (; s + 2 * kGroup <= kc2; s += 2 * kGroup) {
+            float a[kGroup], b[kGroup];
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) a[u] = ap[s + 2 * u], b[u] = bp[s + 2 * u];
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u], acc, 0, 0, 0);
+        }
+        for (; s < kc2; s += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[s], bp[s], acc, 0, 0, 0);
+    };
+
     const int c = col0 + 32 * (wave >> 1) + (lane & 31);
     const bool c_ok = c < p.Cout;
     const float sc = p.scale && c_ok ? p.scale[c] : 1.0f, sh = p.shift && c_ok ? p.shift[c] : 0.0f;
     const int wword = (col0 >> 5) + (wave >> 1);
+    // D layout of the 32 x 32 tile: this lane holds channel lane % 32 of the pixels 8 (r / 4) + 4 (lane / 32) + r % 4
+    auto finish = [&](int64_t tile, const v16f &acc) {
+        const int64_t row0 = tile * kDenseTile;
+        int code[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int64_t pix = row0 + 32 * (wave & 1) + 8 * (r >> 2) + 4 * khalf + (r & 3);
-        const bool ok = pix < p.M && c_ok;
-        float y = acc[r];
-        if (p.scale) y = y * sc;
-        if (p.shift) y = y + sh;
-        if (p.relu) y = fmaxf(y, 0.0f);
-        if (p.out && ok) p.out[pix * p.Cout + c] = y;
+        for (int r = 0; r < 16; ++r) {
+            const int64_t pix = row0 + 32 * (wave & 1) + 8 * (r >> 2) + 4 * khalf + (r & 3);
+            const bool ok = pix < p.M && c_ok;
+            float y = acc[r];
+            if (p.scale) y = y * sc;
+            if (p.shift) y = y + sh;
+            if (p.relu) y = fmaxf(y, 0.0f);
+            if (p.out && ok) p.out[pix * p.Cout + c] = y;
+            code[r] = p.next && ok ? quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) : 0;
+        }
         if (p.next) {
-            const int code = ok ? quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) : 0;
+            // The 32 lanes of a half-wave hold the 32 channels of one plane word: one ballot per register
+            // and bit gives the words of two pixels.  Lane L < 32 collects the word of the wave's pixel L,
+            // so that a plane leaves with one store of 32 lanes instead of 16 stores of 2.
+            const int64_t pix = row0 + 32 * (wave & 1) + lane;
             for (int j = 0; j < p.next_bits; ++j) {
-                // the 32 lanes of a half-wave hold the 32 channels of one plane word
-                const unsigned long long bits = __ballot((code >> j) & 1);
-                if ((lane & 31) == 0 && pix < p.M && wword < p.cwo)
-                    p.next[((int64_t)j * p.M + pix) * p.cwo + wword] = (uint32_t)(bits >> (32 * khalf));
+                uint32_t mine = 0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const unsigned long long bits = __ballot((code[r] >> j) & 1);
+                    const int slot = 8 * (r >> 2) + (r & 3); // pixel of the lower half-wave; the upper one's is 4 further
+                    if (lane == slot) mine = (uint32_t)bits;
+                    if (lane == slot + 4) mine = (uint32_t)(bits >> 32);
+                }
+                if (lane < 32 && pix < p.M && wword < p.cwo) p.next[((int64_t)j * p.M + pix) * p.cwo + wword] = mine;
             }
+        }
+    };
+
+    if (nchunks == 1) {
+        // One chunk (the 7 x 7 x 3 first convolution): table and weights are staged once.
+        const int kc = p.K, kc2 = (kc + 1) & ~1;
+        stage_taps(0, kc);
+        stage_w(0, kc);
+        __syncthreads();
+        for (int64_t tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
+            stage_pixels(locate(tile), kc);
+            __syncthreads();
+            v16f acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+            contract(kc2, acc);
+            __syncthreads(); // every wave is done with the stage
+            finish(tile, acc);
+        }
+    } else {
+        for (int64_t tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
+            const Pixel q = locate(tile);
+            v16f acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+            for (int ch = 0; ch < nchunks; ++ch) {
+                const int k0 = ch * kChunk;
+                const int kc = p.K - k0 < kChunk ? p.K - k0 : kChunk;
+                stage_taps(k0, kc);
+                stage_w(k0, kc);
+                __syncthreads();
+                stage_pixels(q, kc);
+                __syncthreads();
+                contract((kc + 1) & ~1, acc);
+                __syncthreads(); // the stage may be overwritten
+            }
+            finish(tile, acc);
         }
     }
 }
@@ -157,6 +264,7 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
     const int64_t Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1, Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
     const int64_t M = d->B * Ho * Wo, K = (int64_t)d->kh * d->kw * d->Cin;
     if (M >= (1LL << 31) || K >= (1LL << 24) || d->Cout >= (1LL << 24) || d->H >= (1LL << 24) || d->W >= (1LL << 24) ||
+        d->kh > 4096 || d->kw > 4096 || (int64_t)d->kh * d->W * d->Cin >= (1LL << 29) ||
         ceil_div(d->Cout, kDenseTile) > 65535)
         return fail(QNN_ERR_RANGE, "%s: tensor too large", who);
     DenseConvParams p;
@@ -170,7 +278,16 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
     p.next_inv_clip = next_planes ? 1.0f / next_clip : 0.0f;
     p.next_half_top = 0.5f * (float)p.next_top;
     p.div_howo = make_fastdiv((uint32_t)(Ho * Wo)), p.div_wo = make_fastdiv((uint32_t)Wo);
-    const dim3 grid((unsigned)ceil_div(M, kDenseTile), (unsigned)ceil_div(d->Cout, kDenseTile));
+    p.fast_offsets = d->B * d->H * d->W * d->Cin < (1LL << 30) ? 1 : 0;
+    // persistent workgroups: two per CU share the pixel tiles of their column tile round-robin
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return fail(QNN_ERR_LAUNCH, "%s: device query failed", who);
+    p.tiles_m = ceil_div(M, kDenseTile);
+    const int64_t col_tiles = ceil_div(d->Cout, kDenseTile);
+    int64_t per_col = ceil_div(2 * (int64_t)cus, col_tiles);
+    if (per_col > p.tiles_m) per_col = p.tiles_m;
+    const dim3 grid((unsigned)per_col, (unsigned)col_tiles);
     hipLaunchKernelGGL(dense_conv_kernel, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
     return check_launch(who);
 }
