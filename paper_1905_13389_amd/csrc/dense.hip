@@ -24,7 +24,7 @@ constexpr int kDenseThreads = 256;
 constexpr int kDenseTile = 64;             // pixels and channels per workgroup
 constexpr int kChunk = 152;                // reduction values per LDS stage (even)
 constexpr int kChunkStride = kChunk + 1;   // odd: conflict-free operand reads
-static_assert(kChunk % 2 == 0 && 2 * kDenseTile * kChunkStride * 4 + kChunk * 8 <= 80 * 1024, "two workgroups per CU");
+static_assert(kChunk % 8 == 0 && 2 * kDenseTile * kChunkStride * 4 + kChunk * 8 <= 80 * 1024, "two workgroups per CU");
 
 struct DenseConvParams {
     const float *x, *w, *scale, *shift;
@@ -39,10 +39,13 @@ struct DenseConvParams {
     FastDiv div_howo, div_wo;
 };
 
-__global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvParams p)
+// ONE: the reduction is one chunk.  Every lane then keeps its weight operands (its channel's values 2 u + lane / 32)
+// in registers for all pixel tiles of the workgroup: no weight stage in LDS (three to four workgroups fit a CU
+// instead of two) and no weight reads in the MFMA loop.
+template <bool ONE> __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3))) void dense_conv_kernel(DenseConvParams p)
 {
     __shared__ float As[kDenseTile * kChunkStride];
-    __shared__ float Ws[kDenseTile * kChunkStride];
+    __shared__ float Ws[ONE ? 4 : kDenseTile * kChunkStride];
     __shared__ int2 taps[kChunk]; // per reduction value of the chunk: byte offset from the window origin, ky << 16 | kx
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col0 = (int)blockIdx.y * kDenseTile;
@@ -52,8 +55,7 @@ __global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvPara
     // sub + 4 t of the chunk, t < kSlots: all of them are fetched and stored (the row has room for them);
     // those past the chunk hold 0 or are never read
     const int srow = tid >> 2, sub = tid & 3;
-    constexpr int kSlots = kChunk / 4, kHalf = kSlots / 2;
-    static_assert(kSlots == 2 * kHalf, "the gather runs in two halves");
+    constexpr int kSlots = kChunk / 4, kPart = 19, kParts = (kSlots + kPart - 1) / kPart; // values in flight per lane
     const bool ch_ok = col0 + srow < p.Cout;
     const float *wb = p.w + (int64_t)(ch_ok ? col0 + srow : 0) * p.K;
 
@@ -65,17 +67,19 @@ __global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvPara
     };
     auto stage_w = [&](int k0, int kc) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            float v[kHalf];
+        for (int h = 0; h < kParts; ++h) {
+            float v[kPart];
 #pragma unroll
-            for (int t = 0; t < kHalf; ++t) {
-                const int kk = sub + 4 * (h * kHalf + t);
+            for (int t = 0; t < kPart; ++t) {
+                if (h * kPart + t >= kSlots) continue; // the last part is shorter
+                const int kk = sub + 4 * (h * kPart + t);
                 const bool in_w = ch_ok && kk < kc;
                 const float got = *(in_w ? wb + k0 + kk : p.w); // unconditional loads stay independent
                 v[t] = in_w ? got : 0.0f;
             }
 #pragma unroll
-            for (int t = 0; t < kHalf; ++t) Ws[srow * kChunkStride + sub + 4 * (h * kHalf + t)] = v[t];
+            for (int t = 0; t < kPart; ++t)
+                if (h * kPart + t < kSlots) Ws[srow * kChunkStride + sub + 4 * (h * kPart + t)] = v[t];
         }
     };
 
@@ -103,18 +107,20 @@ __global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvPara
     // window inside the image (and whose tensor 32-bit byte offsets reach) gathers with one table read,
     // one add and one load per value; otherwise every tap is tested against the image, and the load goes
     // to a safe address when the test fails, so that the loads of a half stay independent of each other.
-    // (In two halves of kHalf values each: half h holds the slots t = h kHalf ... .)
-    auto gather = [&](const Pixel &q, int kc, int h, float (&v)[kHalf]) {
+    // (In kParts parts of up to kPart values each: part h holds the slots t = h kPart ... .)
+    auto gather = [&](const Pixel &q, int kc, int h, float (&v)[kPart]) {
         if (p.fast_offsets && __all(q.inside)) {
             const uint32_t origin = (uint32_t)(q.origin - reinterpret_cast<const char *>(p.x));
 #pragma unroll
-            for (int t = 0; t < kHalf; ++t)
-                v[t] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(p.x) +
-                                                        (origin + (uint32_t)taps[sub + 4 * (h * kHalf + t)].x));
+            for (int t = 0; t < kPart; ++t)
+                if (h * kPart + t < kSlots)
+                    v[t] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(p.x) +
+                                                            (origin + (uint32_t)taps[sub + 4 * (h * kPart + t)].x));
         } else {
 #pragma unroll
-            for (int t = 0; t < kHalf; ++t) {
-                const int kk = sub + 4 * (h * kHalf + t);
+            for (int t = 0; t < kPart; ++t) {
+                if (h * kPart + t >= kSlots) continue;
+                const int kk = sub + 4 * (h * kPart + t);
                 const int2 e = taps[kk];
                 const int y = q.hi0 + (e.y >> 16), xx = q.wi0 + (e.y & 0xffff);
                 const bool in_image = q.ok && kk < kc && (unsigned)y < (unsigned)p.H && (unsigned)xx < (unsigned)p.W;
@@ -123,19 +129,21 @@ __global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvPara
             }
         }
     };
-    auto stash = [&](int h, const float (&v)[kHalf]) {
+    auto stash = [&](int h, const float (&v)[kPart]) {
 #pragma unroll
-        for (int t = 0; t < kHalf; ++t) As[srow * kChunkStride + sub + 4 * (h * kHalf + t)] = v[t];
+        for (int t = 0; t < kPart; ++t)
+            if (h * kPart + t < kSlots) As[srow * kChunkStride + sub + 4 * (h * kPart + t)] = v[t];
     };
     auto stage_pixels = [&](const Pixel &q, int kc) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            float v[kHalf];
+        for (int h = 0; h < kParts; ++h) {
+            float v[kPart];
             gather(q, kc, h, v);
             stash(h, v);
         }
-        // the fast gather leaves the window origin's value in the slots past the chunk: an odd chunk reads one of them
-        if ((kc & 1) && sub == (kc & 3)) As[srow * kChunkStride + kc] = 0.0f;
+        // the fast gather leaves the window origin's value in the slots past the chunk; the MFMA loops read up
+        // to the next multiple of 8: zeros there (slot kk belongs to the lane with sub = kk % 4, which wrote it)
+        for (int kk = kc + ((sub - kc) & 3); kk < ((kc + 7) & ~7); kk += 4) As[srow * kChunkStride + kk] = 0.0f;
     };
 
     const int arow = 32 * (wave & 1) + (lane & 31), brow = 32 * (wave >> 1) + (lane & 31), khalf = lane >> 5;
@@ -192,11 +200,20 @@ __global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvPara
         }
     };
 
-    if (nchunks == 1) {
-        // One chunk (the 7 x 7 x 3 first convolution): table and weights are staged once.
-        const int kc = p.K, kc2 = (kc + 1) & ~1;
+    if constexpr (ONE) {
+        // One chunk (the 7 x 7 x 3 first convolution): the table is staged once, the weights go to registers.
+        const int kc = p.K;
         stage_taps(0, kc);
-        stage_w(0, kc);
+        constexpr int kSteps = kChunk / 2, kGroup = 4; // MFMA steps of a full chunk; steps per uniform branch
+        static_assert(kSteps % kGroup == 0 && 2 * kSteps <= kChunkStride, "groups of steps stay inside the stage row");
+        float breg[kSteps];
+        const float *wrow = p.w + (int64_t)(c_ok ? c : 0) * p.K;
+#pragma unroll
+        for (int u = 0; u < kSteps; ++u) {
+            const bool in_w = c_ok && 2 * u + khalf < kc;
+            const float got = *(in_w ? wrow + 2 * u + khalf : p.w);
+            breg[u] = in_w ? got : 0.0f;
+        }
         __syncthreads();
         for (int64_t tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
             stage_pixels(locate(tile), kc);
@@ -204,7 +221,17 @@ __global__ __launch_bounds__(kDenseThreads) void dense_conv_kernel(DenseConvPara
             v16f acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
-            contract(kc2, acc);
+#pragma unroll
+            for (int g = 0; g < kSteps / kGroup; ++g) {
+                if (2 * kGroup * g < kc) { // same for all lanes; the stage holds zeros up to the next multiple of 8
+                    float a[kGroup];
+#pragma unroll
+                    for (int u = 0; u < kGroup; ++u) a[u] = ap[2 * (kGroup * g + u)];
+#pragma unroll
+                    for (int u = 0; u < kGroup; ++u)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], breg[kGroup * g + u], acc, 0, 0, 0);
+                }
+            }
             __syncthreads(); // every wave is done with the stage
             finish(tile, acc);
         }
@@ -279,16 +306,23 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
     p.next_half_top = 0.5f * (float)p.next_top;
     p.div_howo = make_fastdiv((uint32_t)(Ho * Wo)), p.div_wo = make_fastdiv((uint32_t)Wo);
     p.fast_offsets = d->B * d->H * d->W * d->Cin < (1LL << 30) ? 1 : 0;
-    // persistent workgroups: two per CU share the pixel tiles of their column tile round-robin
+    // persistent workgroups: as many as are resident at one time share the pixel tiles of their column tile round-robin
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
         return fail(QNN_ERR_LAUNCH, "%s: device query failed", who);
     p.tiles_m = ceil_div(M, kDenseTile);
     const int64_t col_tiles = ceil_div(d->Cout, kDenseTile);
-    int64_t per_col = ceil_div(2 * (int64_t)cus, col_tiles);
+    const bool one = K <= kChunk;
+    int per_cu = 0;
+    if ((one ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dense_conv_kernel<true>, kDenseThreads, 0)
+             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dense_conv_kernel<false>, kDenseThreads, 0)) != hipSuccess ||
+        per_cu < 1)
+        return fail(QNN_ERR_LAUNCH, "%s: occupancy query failed", who);
+    int64_t per_col = ceil_div((int64_t)per_cu * cus, col_tiles);
     if (per_col > p.tiles_m) per_col = p.tiles_m;
     const dim3 grid((unsigned)per_col, (unsigned)col_tiles);
-    hipLaunchKernelGGL(dense_conv_kernel, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
+    if (one) hipLaunchKernelGGL(dense_conv_kernel<true>, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
+    else hipLaunchKernelGGL(dense_conv_kernel<false>, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
     return check_launch(who);
 }
 
