@@ -218,40 +218,51 @@ template <int KV> __device__ __forceinline__ void lds_read_words(const uint32_t 
 // stage of a reduction: nothing is spent on the zero tail).  The activation stage holds APR rows per
 // plane and the lane's row i sits at row ty + ASTEP * i of it (the whole tile: BM rows, step 16; a
 // wave's private quarter of the tile: BM / 4 rows, step 4, ty = the lane's row group inside the wave).
-template <int WB, int AB, int TM, int TN, int KV, int KB, int APR = 16 * TM, int ASTEP = 16>
-__device__ __forceinline__ void tile_mac(const uint32_t *__restrict__ As,
-                                         const uint32_t *__restrict__ Ws, int ty, int tx, int nkq,
-                                         uint32_t (&P)[TM][TN][WB + AB - 1])
+// One group of G reduction words starting at word `word0` of the stage (G = 4: 16-byte reads, G = 2: 8-byte reads).
+template <int WB, int AB, int TM, int TN, int KV, int KB, int APR, int ASTEP, int G>
+__device__ __forceinline__ void tile_mac_group(const uint32_t *__restrict__ As, const uint32_t *__restrict__ Ws,
+                                               int ty, int tx, int word0, uint32_t (&P)[TM][TN][WB + AB - 1])
 {
     using T = Tile<WB, AB, TM, TN, KV, KB>;
-#pragma unroll 1
-    for (int kq = 0; kq < nkq; ++kq) {
-        uint32_t a[TM][KV][AB]; // [row][word][plane]
-        uint32_t w[TN][KV][WB];
+    uint32_t a[TM][G][AB]; // [row][word][plane]
+    uint32_t w[TN][G][WB];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < AB; ++j) {
+            uint32_t v[G];
+            lds_read_words<G>(As + (j * APR + ty + ASTEP * i) * T::BKP + word0, v);
+#pragma unroll
+            for (int kk = 0; kk < G; ++kk) a[i][kk][j] = v[kk];
+        }
+#pragma unroll
+    for (int n = 0; n < TN; ++n)
+#pragma unroll
+        for (int j = 0; j < WB; ++j) {
+            uint32_t v[G];
+            lds_read_words<G>(Ws + (j * T::BN + tx + 16 * n) * T::BKP + word0, v);
+#pragma unroll
+            for (int kk = 0; kk < G; ++kk) w[n][kk][j] = v[kk];
+        }
+#pragma unroll
+    for (int kk = 0; kk < G; ++kk)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < AB; ++j) {
-                uint32_t v[KV];
-                lds_read_words<KV>(As + (j * APR + ty + ASTEP * i) * T::BKP + KV * kq, v);
-#pragma unroll
-                for (int kk = 0; kk < KV; ++kk) a[i][kk][j] = v[kk];
-            }
-#pragma unroll
-        for (int n = 0; n < TN; ++n)
-#pragma unroll
-            for (int j = 0; j < WB; ++j) {
-                uint32_t v[KV];
-                lds_read_words<KV>(Ws + (j * T::BN + tx + 16 * n) * T::BKP + KV * kq, v);
-#pragma unroll
-                for (int kk = 0; kk < KV; ++kk) w[n][kk][j] = v[kk];
-            }
-#pragma unroll
-        for (int kk = 0; kk < KV; ++kk)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int n = 0; n < TN; ++n) xor_bcnt_pairs<WB, AB>(w[n][kk], a[i][kk], P[i][n]);
+            for (int n = 0; n < TN; ++n) xor_bcnt_pairs<WB, AB>(w[n][kk], a[i][kk], P[i][n]);
+}
+
+// HALF (KV = 4 only): `half_tail` asks for one more group of 2 words behind the nkq groups of 4 -- a stage
+// that ends 1 or 2 words into a group spends nothing on the other two (zero) words.
+template <int WB, int AB, int TM, int TN, int KV, int KB, int APR = 16 * TM, int ASTEP = 16, bool HALF = false>
+__device__ __forceinline__ void tile_mac(const uint32_t *__restrict__ As,
+                                         const uint32_t *__restrict__ Ws, int ty, int tx, int nkq,
+                                         uint32_t (&P)[TM][TN][WB + AB - 1], bool half_tail = false)
+{
+#pragma unroll 1
+    for (int kq = 0; kq < nkq; ++kq) tile_mac_group<WB, AB, TM, TN, KV, KB, APR, ASTEP, KV>(As, Ws, ty, tx, KV * kq, P);
+    if constexpr (HALF && KV == 4) {
+        if (half_tail) tile_mac_group<WB, AB, TM, TN, KV, KB, APR, ASTEP, 2>(As, Ws, ty, tx, KV * nkq, P);
     }
 }
 

@@ -331,11 +331,18 @@ bconv_tile_kernel(ConvTileParams p)
                 fetch(0);
             }
             const int left = p.nw - c * p.kb;
-            const int nkq = ((left < p.kb ? left : p.kb) + KV - 1) / KV;
+            const int words = left < p.kb ? left : p.kb;
+            // up to 4 planes in all, a stage that ends 1 or 2 words into a 4-word group finishes with a 2-word
+            // group (with more planes the lane has no registers left for that second copy of the block)
+            constexpr bool HALF = KV == 4 && WB + AB <= 4;
+            const bool half_tail = HALF && ((words & 3) == 1 || (words & 3) == 2);
+            const int nkq = half_tail ? words / KV : (words + KV - 1) / KV;
             if constexpr (KEEPW)
-                tile_mac<WB, AB, TM, TN, KV, kConvKB, WR, 4>(smem[buf] + wave * CHUNK, w_resident, ty & 3, tx, nkq, P);
+                tile_mac<WB, AB, TM, TN, KV, kConvKB, WR, 4, HALF>(smem[buf] + wave * CHUNK, w_resident, ty & 3, tx, nkq, P,
+                                                                  half_tail);
             else
-                tile_mac<WB, AB, TM, TN, KV, kConvKB>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P);
+                tile_mac<WB, AB, TM, TN, KV, kConvKB, 16 * TM, 16, HALF>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P,
+                                                                        half_tail);
             if (more || next_tile) stash(buf ^ 1);
             tile_sync();
             buf ^= 1;
