@@ -11,4 +11,4 @@ char *error_buffer()
 
 extern "C" const char *qnn_last_error(void) { return qnn::error_buffer(); }
 
-extern "C" int qnn_version(void) { return 0 * 10000 + 2 * 100 + 0; }
+extern "C" int qnn_version(void) { return 0 * 10000 + 3 * 100 + 0; }
