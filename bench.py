@@ -473,6 +473,19 @@ def fc_workload(args):
         graph.replay()
     torch.cuda.synchronize()
     graph_ms = (time.perf_counter() - t0) / (steps // per_graph * per_graph) * 1e3
+    # the whole layer in one launch (qnn_fc_fused): same acc and out
+    acc.zero_(), out.zero_()
+    fused = lambda: qnn.qnn_fc_fused(d_a, 1.0, 2, w_planes, acc=acc, scale=d_scale, out=out)
+    for _ in range(20):
+        fused()
+    torch.cuda.synchronize()
+    if not (torch.equal(acc, ref_acc) and torch.equal(out, ref_out)):
+        raise SystemExit("bench.py: qnn_fc_fused differs from the two-launch step")
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fused()
+    torch.cuda.synchronize()
+    fused_ms = (time.perf_counter() - t0) / steps * 1e3
     ops = 2.0 * 64 * 256 * 512 * 4
     tops = ops / (ms * 1e-3) / 1e12
     print(json.dumps({
@@ -485,6 +498,8 @@ def fc_workload(args):
         "roofline": {"bound": "alu", "achieved": round(tops, 4), "peak": round(PEAK_BINARY_TOPS, 1),
                      "unit": "binary TOP/s", "frac": round(tops / PEAK_BINARY_TOPS, 6), "traffic": None,
                      "note": "launch / latency bound: 0.04 us of VALU work per step"},
+        "fused": {"step": "qnn_fc_fused: encoders, binary branches, recombination and scale in one launch",
+                  "ms_per_step": round(fused_ms, 5), "checked": "acc and out equal the two-launch step's"},
         "hip_graph": {"step": "20 steps (40 launches) captured once and replayed", "ms_per_step": round(graph_ms, 5),
                       "checked": "acc and out of the replays equal the eager step's"}}))
 

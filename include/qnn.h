@@ -326,6 +326,22 @@ int qnn_maxpool_levels_fp4(const uint8_t *levels, int64_t B, int64_t H, int64_t 
                            int pad, int ceil_mode, uint8_t *out_levels, void *stream);
 
 /*
+ * qnn_fc_fused -- qnn_encode_pack followed by qnn_binary_gemm (Fig. 1: encoders, M x K binary branches, decoder
+ * with its scale) in ONE launch, for layers too small to fill the chip, where the two-launch form costs the
+ * device's latency from one dependent kernel to the next.  Same results, bit for bit; the activation planes
+ * never reach memory.
+ *   src  DEVICE in, [rows][row_stride_elems] of dtype (QNN_DTYPE_F32 / BF16 values quantized with clip and
+ *        a_bits as qnn_encode_pack does, or QNN_DTYPE_I8 odd levels), n elements used per row
+ *   w_planes  DEVICE in uint32 [w_bits][cols][ceil(n/32)];  scale  DEVICE in fp32 [cols] (required with out)
+ *   acc  DEVICE out int32 [rows][cols] or NULL;  out  DEVICE out fp32 [rows][cols] or NULL (at least one)
+ * QNN_ERR_UNSUPPORTED when a_bits * ceil(n/32) exceeds 1024 words (the planes of 4 rows must fit 16 KiB of LDS:
+ * use the two-launch form); otherwise the argument errors of the two calls it replaces.
+ */
+int qnn_fc_fused(const void *src, int dtype, int64_t rows, int64_t n, int64_t row_stride_elems, float clip, int a_bits,
+                 const uint32_t *w_planes, int w_bits, int64_t cols, const float *scale, int32_t *acc, float *out,
+                 void *stream);
+
+/*
  * The unquantized ends of a network (the ResNet-18 workload of the ImageNet experiment keeps its first
  * convolution and its classifier in full precision; nothing of Eq. 9 is involved).  fp32 throughout,
  * products and sums on the matrix cores in fp32: a result differs from the real-number value by at most

@@ -13,7 +13,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqnn.so")
 SOURCES = ["qnn_api.hip", "encode_pack.hip", "dequant_scale.hip", "binary_gemm.hip", "conv2d.hip", "conv2d_block.hip", "probe.hip",
-           "level_gemm_mfma.hip", "level_conv_mfma.hip", "maxpool.hip", "ste_backward.hip", "dense.hip"]
+           "level_gemm_mfma.hip", "level_conv_mfma.hip", "maxpool.hip", "ste_backward.hip", "dense.hip", "fc_fused.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

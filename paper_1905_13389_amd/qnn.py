@@ -31,7 +31,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
            "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_level_conv2d_block_fp4", "qnn_maxpool_levels_fp4",
            "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
-           "qnn_dense_conv2d_f32", "qnn_global_avgpool_f32", "qnn_dense_fc_f32",
+           "qnn_dense_conv2d_f32", "qnn_global_avgpool_f32", "qnn_dense_fc_f32", "qnn_fc_fused",
            "qnn_last_error", "qnn_version")
 
 
@@ -91,6 +91,8 @@ def lib():
         L.qnn_global_avgpool_f32.restype = i32
         L.qnn_dense_fc_f32.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
         L.qnn_dense_fc_f32.restype = i32
+        L.qnn_fc_fused.argtypes = [vp, i32, i64, i64, i64, f32, i32, vp, i32, i64, vp, vp, vp, vp]
+        L.qnn_fc_fused.restype = i32
         L.qnn_probe_valu.argtypes = [i32, i32, i32, vp, vp]
         L.qnn_probe_valu.restype = i32
         L.qnn_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
@@ -177,6 +179,22 @@ def qnn_encode_pack(src, clip, bits, planes=None):
     _check(lib().qnn_encode_pack(_ptr(src), _DTYPES[src.dtype], rows, n, n, float(clip), int(bits),
                                  _ptr(planes), _stream()))
     return planes
+
+
+def qnn_fc_fused(src, clip, a_bits, w_planes, want_acc=True, scale=None, acc=None, out=None):
+    """src [rows][n] (fp32 / bf16 values or int8 levels, contiguous), w_planes [w_bits][cols][nw] ->
+    (acc int32 [rows][cols] or None, out fp32 [rows][cols] or None): qnn_encode_pack + qnn_binary_gemm in one launch."""
+    assert src.is_cuda and src.is_contiguous() and src.dtype in _DTYPES and src.dim() == 2
+    rows, n = src.shape
+    w_bits, cols, nw = w_planes.shape
+    assert nw == (n + 31) // 32
+    if want_acc and acc is None:
+        acc = torch.empty((rows, cols), dtype=torch.int32, device=src.device)
+    if scale is not None and out is None:
+        out = torch.empty((rows, cols), dtype=torch.float32, device=src.device)
+    _check(lib().qnn_fc_fused(_ptr(src), _DTYPES[src.dtype], rows, n, n, float(clip), int(a_bits), _ptr(w_planes), w_bits,
+                              cols, _ptr(scale), _ptr(acc), _ptr(out), _stream()))
+    return acc, out
 
 
 def qnn_binary_gemm(a_planes, w_planes, n, want_acc=True, scale=None, acc=None, out=None):

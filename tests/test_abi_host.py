@@ -342,3 +342,27 @@ def test_dense_layer_argument_errors(qnn):
     assert fc(None, FAKE, None, 4, 8, 8, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
     assert fc(FAKE, FAKE, None, 4, 8, 8, ODD, None) == qnn.QNN_ERR_ALIGNMENT
     assert fc(None, None, None, 0, 8, 8, FAKE, None) == qnn.QNN_OK
+
+
+def test_fc_fused_argument_errors(qnn):
+    f = qnn.lib().qnn_fc_fused
+    good = dict(src=FAKE, dtype=qnn.QNN_DTYPE_F32, rows=4, n=64, stride=64, clip=1.0, a_bits=2, w=FAKE, w_bits=2, cols=8,
+                scale=FAKE, acc=FAKE, out=FAKE)
+
+    def call(**kw):
+        a = dict(good, **kw)
+        return f(a["src"], a["dtype"], a["rows"], a["n"], a["stride"], a["clip"], a["a_bits"], a["w"], a["w_bits"], a["cols"],
+                 a["scale"], a["acc"], a["out"], None)
+
+    assert call(dtype=7) == qnn.QNN_ERR_UNSUPPORTED
+    assert call(a_bits=0) == qnn.QNN_ERR_INVALID_ARG and call(w_bits=9) == qnn.QNN_ERR_INVALID_ARG
+    assert call(dtype=qnn.QNN_DTYPE_I8, a_bits=8) == qnn.QNN_ERR_UNSUPPORTED
+    assert call(rows=-1) == qnn.QNN_ERR_INVALID_ARG and call(stride=63) == qnn.QNN_ERR_INVALID_ARG
+    assert call(clip=0.0) == qnn.QNN_ERR_INVALID_ARG and call(clip=float("nan")) == qnn.QNN_ERR_INVALID_ARG
+    assert call(acc=None, out=None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(scale=None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(src=None) == qnn.QNN_ERR_INVALID_ARG and call(w=None) == qnn.QNN_ERR_INVALID_ARG
+    assert call(w=ODD) == qnn.QNN_ERR_ALIGNMENT and call(acc=ODD) == qnn.QNN_ERR_ALIGNMENT
+    assert call(n=1 << 20, stride=1 << 20, a_bits=8, w_bits=8) == qnn.QNN_ERR_RANGE
+    assert call(n=40000, stride=40000) == qnn.QNN_ERR_UNSUPPORTED          # planes of 4 rows do not fit LDS
+    assert call(rows=0, src=None) == qnn.QNN_OK and call(cols=0) == qnn.QNN_OK

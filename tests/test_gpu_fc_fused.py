@@ -1,0 +1,72 @@
+"""qnn_fc_fused (encoders + binary branches + recombination + scale in one launch) against the oracle and,
+bit for bit, against the two-launch form it replaces."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import qnn_workloads as wl
+from gpu_util import dev, pack_levels, levels
+
+pytestmark = pytest.mark.gpu
+
+from paper_1905_13389_amd import qnn  # noqa: E402
+
+SHAPES = [(64, 512, 256), (1, 1, 1), (5, 33, 7), (9, 100, 300), (4, 64, 256), (131, 777, 513), (3, 4096, 20)]
+
+
+def test_config_1_layer():
+    c = wl.fc_2x2()
+    wp = pack_levels(c["w"], 2)
+    acc, out = qnn.qnn_fc_fused(dev(c["a"]), 1.0, 2, wp, scale=dev(c["scale"]))
+    torch.cuda.synchronize()
+    want = oracle.gemm(c["a"], c["w"])
+    assert np.array_equal(acc.cpu().numpy(), want)
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, c["scale"]), rtol=1e-5, atol=0)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("bits", [(1, 1), (2, 2), (3, 2), (1, 4), (4, 4), (5, 3), (2, 7)])
+def test_int8_levels_in(shape, bits):
+    rows, n, cols = shape
+    w_bits, a_bits = bits
+    gen = np.random.default_rng(rows + n + cols + 10 * w_bits + a_bits)
+    a, w = levels(gen, (rows, n), a_bits), levels(gen, (cols, n), w_bits)
+    s = gen.uniform(0.01, 0.1, size=cols).astype(np.float32)
+    wp = pack_levels(w, w_bits)
+    acc, out = qnn.qnn_fc_fused(dev(a), 1.0, a_bits, wp, scale=dev(s))
+    torch.cuda.synchronize()
+    want = oracle.gemm(a, w)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s), rtol=1e-5, atol=0)
+    acc2, out2 = qnn.qnn_binary_gemm(pack_levels(a, a_bits), wp, n, scale=dev(s))
+    assert torch.equal(acc, acc2) and torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("shape", SHAPES[:6])
+@pytest.mark.parametrize("a_bits", [1, 2, 3, 8])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_float_values_in(shape, a_bits, dtype):
+    rows, n, cols = shape
+    gen = np.random.default_rng(rows + n + cols + a_bits)
+    x = gen.normal(0, 1, size=(rows, n)).astype(np.float32)
+    d_x = dev(x)
+    if dtype == "bf16":
+        d_x = d_x.to(torch.bfloat16)
+        x = d_x.to(torch.float32).cpu().numpy()          # the values the kernel sees
+    w = levels(gen, (cols, n), 2)
+    lv, _ = oracle.quantize(x, 2.5, a_bits)
+    only_out = qnn.qnn_fc_fused(d_x, 2.5, a_bits, pack_levels(w, 2), want_acc=False, scale=torch.ones(cols, device="cuda"))
+    acc, _ = qnn.qnn_fc_fused(d_x, 2.5, a_bits, pack_levels(w, 2))
+    torch.cuda.synchronize()
+    want = oracle.gemm(lv, w)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    assert only_out[0] is None and np.array_equal(only_out[1].cpu().numpy(), want.astype(np.float32))
+
+
+def test_layers_too_long_for_the_fused_form_are_refused():
+    a = torch.zeros((4, 40000), dtype=torch.int8, device="cuda")
+    wp = torch.zeros((2, 8, 1250), dtype=torch.int32, device="cuda")
+    with pytest.raises(qnn.QnnError) as e:
+        qnn.qnn_fc_fused(a, 1.0, 2, wp)
+    assert e.value.code == qnn.QNN_ERR_UNSUPPORTED
