@@ -9,9 +9,10 @@
 // The reduction runs in chunks of up to kChunk values: the 64 pixel rows and the 64 weight rows of a chunk
 // are staged in LDS with an odd row stride, so that the 32 rows a half-wave reads for one MFMA operand
 // fall into 32 different banks; two workgroups fit a CU and cover each other's staging phases.  Workgroups
-// are persistent: each walks the pixel tiles of one column tile, and when the reduction fits one chunk (the
-// 7 x 7 x 3 first convolution: 147 values) its weights are staged once.  A per-chunk table in LDS maps a
-// reduction value to its offset from the window origin, so the gather is a batch of independent loads.
+// are persistent: each walks the pixel tiles of one column tile.  A per-chunk table in LDS maps a reduction
+// value to its byte offset from the window origin, so the gather is a batch of independent loads.  When the
+// reduction fits one chunk (the 7 x 7 x 3 first convolution: 147 values) the table is built once and the
+// weights live in registers instead of LDS (see the kernel's ONE parameter): three workgroups per CU.
 #include "qnn_host.h"
 #include "quantize.h"
 #include "fastdiv.h"
@@ -34,7 +35,7 @@ struct DenseConvParams {
     int64_t M, tiles_m; // output pixels, pixel tiles
     int K;     // kh kw Cin
     int relu, next_bits, next_top, cwo;
-    int fast_offsets; // the input tensor is smaller than 4 GiB: 32-bit byte offsets reach all of it
+    int fast_offsets; // the input tensor is smaller than 4 GiB: 32-bit byte offsets reach all of it (wrap-around sums too)
     float next_inv_clip, next_half_top;
     FastDiv div_howo, div_wo;
 };
