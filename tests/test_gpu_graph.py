@@ -111,3 +111,50 @@ def test_block_deconv_and_gradient_calls_in_a_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert all(torch.equal(a, b) for a, b in zip((out, gx, gq), ref)), rep
+
+
+def test_network_ends_and_one_launch_layer_in_a_hip_graph():
+    # fp32 first convolution with planes out -> pooling of the planes; average pooling -> fp32 classifier;
+    # and the one-launch quantized layer: captured together, replayed with eager work in between
+    gen = np.random.default_rng(5)
+    B, bits = 2, 2
+    img = torch.from_numpy(gen.normal(size=(B, 32, 32, 3)).astype(np.float32)).cuda()
+    w0 = torch.from_numpy((gen.normal(size=(64, 7, 7, 3)) / 12).astype(np.float32)).cuda()
+    sc, sh = torch.full((64,), 1.1, device="cuda"), torch.full((64,), -0.1, device="cuda")
+    planes = torch.empty((bits, B * 16 * 16, 2), dtype=torch.int32, device="cuda")
+    pooled = torch.empty((bits, B * 8 * 8, 2), dtype=torch.int32, device="cuda")
+    feat_in = torch.from_numpy(gen.normal(size=(B, 7, 7, 96)).astype(np.float32)).cuda()
+    feat, logits = torch.empty((B, 96), device="cuda"), torch.empty((B, 10), device="cuda")
+    fc_w = torch.from_numpy(gen.normal(size=(10, 96)).astype(np.float32)).cuda()
+    fc_b = torch.from_numpy(gen.normal(size=10).astype(np.float32)).cuda()
+    top = (1 << bits) - 1
+    a = torch.from_numpy((2 * gen.integers(0, top + 1, size=(6, 200)) - top).astype(np.int8)).cuda()
+    wq = qnn.qnn_encode_pack(torch.from_numpy((2 * gen.integers(0, top + 1, size=(33, 200)) - top).astype(np.int8)).cuda(), 1.0, bits)
+    acc = torch.empty((6, 33), dtype=torch.int32, device="cuda")
+
+    def step():
+        qnn.qnn_dense_conv2d_f32(img, w0, 2, 3, scale=sc, shift=sh, relu=True, want_out=False, next_clip=3.0,
+                                 next_bits=bits, next_planes=planes)
+        qnn.qnn_maxpool_planes(planes, (B, 16, 16), 64, 3, 2, 1, out=pooled)
+        qnn.qnn_global_avgpool_f32(feat_in, out=feat)
+        qnn.qnn_dense_fc_f32(feat, fc_w, fc_b, out=logits)
+        qnn.qnn_fc_fused(a, 1.0, bits, wq, acc=acc)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (pooled, logits, acc)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (planes, pooled, feat, logits, acc):
+            t.fill_(rep)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(x, y) for x, y in zip((pooled, logits, acc), ref)), rep
