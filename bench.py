@@ -386,10 +386,23 @@ def trunk_workload(args):
             qnn.qnn_conv2d_block(a, w, shape, cin, st, pad, sc, next_planes=nxt, out=out, **kw)
         head()
 
+    # the same graph on the matrix-core route: int8 levels from the first convolution on
+    stem_levels = torch.empty((B, side, side, 64), dtype=torch.int8, device="cuda")
+    ym_last = l_calls[-1][-1]
+
+    def mfma_network():
+        qnn.qnn_dense_conv2d_f32_levels(img, w0, 2, 3, clip0, bits, scale=s0, shift=b0, relu=True, next_levels=stem_levels)
+        qnn.qnn_maxpool_levels_i8(stem_levels, 3, 2, 1, out=l_first)
+        for a, w, shape, cin, st, pad, sc, kw, nxt, out in l_calls:
+            qnn.qnn_level_conv2d_block_i8(a, w, st, pad, bits, bits, sc, next_levels=nxt, out=out, **kw)
+        qnn.qnn_global_avgpool_f32(ym_last, out=feat)
+        qnn.qnn_dense_fc_f32(feat, fc_w, fc_b, out=logits)
+
     assert side // 2 == H0, "the pooled stem output is the trunk's input"
     conv_only = lambda: qnn.qnn_dense_conv2d_f32(img, w0, 2, 3, scale=s0, shift=b0, relu=True, want_out=False,
                                                  next_clip=clip0, next_bits=bits, next_planes=stem_planes)
-    stem_ms, conv_ms, head_ms, net_ms = (timed_ms(torch, f, args.steps, args.warmup) for f in (stem, conv_only, head, network))
+    stem_ms, conv_ms, head_ms, net_ms, mnet_ms = (timed_ms(torch, f, args.steps, args.warmup)
+                                                  for f in (stem, conv_only, head, network, mfma_network))
     stem_tflops = 2.0 * B * side * side * 64 * 147 / (conv_ms * 1e-3) / 1e12
     binops = 2.0 * macs * bits * bits
     tops = binops / (ms * 1e-3) / 1e12
@@ -410,6 +423,9 @@ def trunk_workload(args):
                             "qnn_global_avgpool_f32 + qnn_dense_fc_f32: %dx%d images to %d logits" % (img.shape[1], img.shape[2], fc_w.shape[0]),
                     "ms_per_step": round(net_ms, 4), "images_per_s": round(B / (net_ms * 1e-3), 1),
                     "stem_ms": round(stem_ms, 4), "head_ms": round(head_ms, 4),
+                    "matrix_core_route": {"step": "qnn_dense_conv2d_f32_levels + qnn_maxpool_levels_i8 + trunk on "
+                                                  "qnn_level_conv2d_block_i8 + the same head",
+                                          "ms_per_step": round(mnet_ms, 4), "images_per_s": round(B / (mnet_ms * 1e-3), 1)},
                     "stem_roofline": {"bound": "mfma", "kernel": "dense_conv_kernel", "achieved": round(stem_tflops, 1),
                                       "peak": 157.3, "unit": "fp32 TFLOP/s", "frac": round(stem_tflops / 157.3, 4),
                                       "kernel_ms": round(conv_ms, 4)}},

@@ -368,6 +368,11 @@ typedef struct {
 int qnn_dense_conv2d_f32(const qnn_dense_conv_desc *desc, const float *x, const float *w, const float *scale,
                          const float *shift, int relu, float *out, uint32_t *next_planes, float next_clip,
                          int next_bits, void *stream);
+/* qnn_dense_conv2d_f32_levels: the same layer with the quantized output as int8 levels 2 u - (2^next_bits - 1), DEVICE out
+ * int8 [B][Ho][Wo][Cout] or NULL (next_bits <= 7): the input of qnn_level_conv2d_i8 / qnn_maxpool_levels_i8. */
+int qnn_dense_conv2d_f32_levels(const qnn_dense_conv_desc *desc, const float *x, const float *w, const float *scale,
+                                const float *shift, int relu, float *out, int8_t *next_levels, float next_clip,
+                                int next_bits, void *stream);
 int qnn_global_avgpool_f32(const float *x, int64_t B, int64_t hw, int64_t C, float *out, void *stream);
 int qnn_dense_fc_f32(const float *x, const float *w, const float *bias, int64_t rows, int64_t cols, int64_t n,
                      float *out, void *stream);

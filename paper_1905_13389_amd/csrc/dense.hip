@@ -31,6 +31,7 @@ struct DenseConvParams {
     const float *x, *w, *scale, *shift;
     float *out;
     uint32_t *next;
+    int8_t *next_lv; // the same codes as int8 levels 2 u - top, [pixels][Cout] (the matrix-core route's layout)
     int H, W, Cin, Cout, kh, kw, stride, pad, Ho, Wo;
     int64_t M, tiles_m; // output pixels, pixel tiles
     int K;     // kh kw Cin
@@ -180,7 +181,8 @@ template <bool ONE> __global__ __launch_bounds__(kDenseThreads) __attribute__((a
             if (p.shift) y = y + sh;
             if (p.relu) y = fmaxf(y, 0.0f);
             if (p.out && ok) p.out[pix * p.Cout + c] = y;
-            code[r] = p.next && ok ? quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) : 0;
+            code[r] = (p.next || p.next_lv) && ok ? quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) : 0;
+            if (p.next_lv && ok) p.next_lv[pix * p.Cout + c] = (int8_t)(2 * code[r] - p.next_top);
         }
         if (p.next) {
             // The 32 lanes of a half-wave hold the 32 channels of one plane word: one ballot per register
@@ -273,8 +275,8 @@ __global__ __launch_bounds__(256) void global_avgpool_kernel(const float *__rest
 }
 
 static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const float *x, const float *w, const float *scale,
-                          const float *shift, int relu, float *out, uint32_t *next_planes, float next_clip, int next_bits,
-                          void *stream)
+                          const float *shift, int relu, float *out, uint32_t *next_planes, int8_t *next_levels,
+                          float next_clip, int next_bits, void *stream)
 {
     if (!d) return fail(QNN_ERR_INVALID_ARG, "%s: NULL descriptor", who);
     if (d->B < 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0 || d->kh <= 0 || d->kw <= 0 || d->stride <= 0 ||
@@ -283,11 +285,12 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
     if (d->H + 2 * (int64_t)d->pad < d->kh || d->W + 2 * (int64_t)d->pad < d->kw)
         return fail(QNN_ERR_INVALID_ARG, "%s: kernel larger than the padded image", who);
     if (d->B == 0) return QNN_OK; // nothing to compute: the (empty) buffers may be NULL
-    if (!out && !next_planes) return fail(QNN_ERR_INVALID_ARG, "%s: out and next_planes are both NULL", who);
-    if (next_planes && (next_bits < 1 || next_bits > 8 || !(next_clip > 0.0f) || next_clip > 3.0e38f))
-        return fail(QNN_ERR_INVALID_ARG, "%s: next_bits in [1,8] and a finite next_clip > 0 are required with next_planes", who);
+    if (!out && !next_planes && !next_levels) return fail(QNN_ERR_INVALID_ARG, "%s: no output given", who);
+    if ((next_planes || next_levels) && (next_bits < 1 || next_bits > 8 || !(next_clip > 0.0f) || next_clip > 3.0e38f))
+        return fail(QNN_ERR_INVALID_ARG, "%s: next_bits in [1,8] and a finite next_clip > 0 are required with a quantized output", who);
+    if (next_levels && next_bits > 7) return fail(QNN_ERR_UNSUPPORTED, "%s: int8 levels hold at most 7 bits", who);
     if (!x || !w) return fail(QNN_ERR_INVALID_ARG, "%s: NULL input pointer", who);
-    if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(next_planes))
+    if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(next_planes) || !aligned16(next_levels))
         return fail(QNN_ERR_ALIGNMENT, "%s: pointers must be 16-byte aligned", who);
     const int64_t Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1, Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
     const int64_t M = d->B * Ho * Wo, K = (int64_t)d->kh * d->kw * d->Cin;
@@ -296,14 +299,14 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
         ceil_div(d->Cout, kDenseTile) > 65535)
         return fail(QNN_ERR_RANGE, "%s: tensor too large", who);
     DenseConvParams p;
-    p.x = x, p.w = w, p.scale = scale, p.shift = shift, p.out = out, p.next = next_planes;
+    p.x = x, p.w = w, p.scale = scale, p.shift = shift, p.out = out, p.next = next_planes, p.next_lv = next_levels;
     p.H = (int)d->H, p.W = (int)d->W, p.Cin = (int)d->Cin, p.Cout = (int)d->Cout;
     p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad, p.Ho = (int)Ho, p.Wo = (int)Wo;
     p.M = M, p.K = (int)K, p.relu = relu ? 1 : 0;
-    p.next_bits = next_planes ? next_bits : 0;
+    p.next_bits = next_planes || next_levels ? next_bits : 0;
     p.next_top = (1 << p.next_bits) - 1;
     p.cwo = (int)ceil_div(d->Cout, 32);
-    p.next_inv_clip = next_planes ? 1.0f / next_clip : 0.0f;
+    p.next_inv_clip = next_planes || next_levels ? 1.0f / next_clip : 0.0f;
     p.next_half_top = 0.5f * (float)p.next_top;
     p.div_howo = make_fastdiv((uint32_t)(Ho * Wo)), p.div_wo = make_fastdiv((uint32_t)Wo);
     p.fast_offsets = d->B * d->H * d->W * d->Cin < (1LL << 30) ? 1 : 0;
@@ -335,7 +338,15 @@ extern "C" int qnn_dense_conv2d_f32(const qnn_dense_conv_desc *d, const float *x
                                     const float *shift, int relu, float *out, uint32_t *next_planes, float next_clip,
                                     int next_bits, void *stream)
 {
-    return dense_conv_run("qnn_dense_conv2d_f32", d, x, w, scale, shift, relu, out, next_planes, next_clip, next_bits, stream);
+    return dense_conv_run("qnn_dense_conv2d_f32", d, x, w, scale, shift, relu, out, next_planes, nullptr, next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_dense_conv2d_f32_levels(const qnn_dense_conv_desc *d, const float *x, const float *w, const float *scale,
+                                           const float *shift, int relu, float *out, int8_t *next_levels, float next_clip,
+                                           int next_bits, void *stream)
+{
+    return dense_conv_run("qnn_dense_conv2d_f32_levels", d, x, w, scale, shift, relu, out, nullptr, next_levels, next_clip,
+                          next_bits, stream);
 }
 
 extern "C" int qnn_dense_fc_f32(const float *x, const float *w, const float *bias, int64_t rows, int64_t cols, int64_t n,
@@ -345,7 +356,7 @@ extern "C" int qnn_dense_fc_f32(const float *x, const float *w, const float *bia
     if (!out) return fail(QNN_ERR_INVALID_ARG, "qnn_dense_fc_f32: NULL output");
     // a 1 x 1 convolution over 1 x 1 images: pixels = rows, channels = n -> cols
     const qnn_dense_conv_desc d = {rows, 1, 1, n, cols, 1, 1, 1, 0};
-    return dense_conv_run("qnn_dense_fc_f32", &d, x, w, nullptr, bias, 0, out, nullptr, 0.0f, 0, stream);
+    return dense_conv_run("qnn_dense_fc_f32", &d, x, w, nullptr, bias, 0, out, nullptr, nullptr, 0.0f, 0, stream);
 }
 
 extern "C" int qnn_global_avgpool_f32(const float *x, int64_t B, int64_t hw, int64_t C, float *out, void *stream)

@@ -31,7 +31,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
            "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_level_conv2d_block_fp4", "qnn_maxpool_levels_fp4",
            "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
-           "qnn_dense_conv2d_f32", "qnn_global_avgpool_f32", "qnn_dense_fc_f32", "qnn_fc_fused",
+           "qnn_dense_conv2d_f32", "qnn_dense_conv2d_f32_levels", "qnn_global_avgpool_f32", "qnn_dense_fc_f32", "qnn_fc_fused",
            "qnn_last_error", "qnn_version")
 
 
@@ -87,6 +87,8 @@ def lib():
         L.qnn_level_conv2d_block_i8.restype = i32
         L.qnn_dense_conv2d_f32.argtypes = [ctypes.POINTER(qnn_dense_conv_desc), vp, vp, vp, vp, i32, vp, vp, f32, i32, vp]
         L.qnn_dense_conv2d_f32.restype = i32
+        L.qnn_dense_conv2d_f32_levels.argtypes = L.qnn_dense_conv2d_f32.argtypes
+        L.qnn_dense_conv2d_f32_levels.restype = i32
         L.qnn_global_avgpool_f32.argtypes = [vp, i64, i64, i64, vp, vp]
         L.qnn_global_avgpool_f32.restype = i32
         L.qnn_dense_fc_f32.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
@@ -493,6 +495,23 @@ def qnn_dense_conv2d_f32(x, w, stride, pad, scale=None, shift=None, relu=False, 
     _check(lib().qnn_dense_conv2d_f32(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(scale), _ptr(shift), int(bool(relu)),
                                       _ptr(out), _ptr(next_planes), float(next_clip or 0.0), int(next_bits), _stream()))
     return out, next_planes
+
+
+def qnn_dense_conv2d_f32_levels(x, w, stride, pad, next_clip, next_bits, scale=None, shift=None, relu=False, want_out=False,
+                                out=None, next_levels=None):
+    """As qnn_dense_conv2d_f32 with the quantized output as int8 levels [B][Ho][Wo][Cout]: (out or None, levels)."""
+    B, H, W, cin = x.shape
+    cout, kh, kw, cin2 = w.shape
+    assert cin == cin2
+    ho, wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    if want_out and out is None:
+        out = torch.empty((B, max(ho, 0), max(wo, 0), cout), dtype=torch.float32, device=x.device)
+    if next_levels is None:
+        next_levels = torch.empty((B, max(ho, 0), max(wo, 0), cout), dtype=torch.int8, device=x.device)
+    d = qnn_dense_conv_desc(B, H, W, cin, cout, kh, kw, stride, pad)
+    _check(lib().qnn_dense_conv2d_f32_levels(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(scale), _ptr(shift), int(bool(relu)),
+                                             _ptr(out), _ptr(next_levels), float(next_clip), int(next_bits), _stream()))
+    return out, next_levels
 
 
 def qnn_global_avgpool_f32(x, out=None):

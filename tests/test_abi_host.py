@@ -329,6 +329,10 @@ def test_dense_layer_argument_errors(qnn):
     assert dc(ctypes.byref(big), FAKE, FAKE, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_ERR_RANGE
     empty = qnn.qnn_dense_conv_desc(0, 8, 8, 3, 16, 3, 3, 1, 1)
     assert dc(ctypes.byref(empty), None, None, None, None, 0, FAKE, None, 0.0, 0, None) == qnn.QNN_OK
+    dl = L.qnn_dense_conv2d_f32_levels
+    assert dl(*ok, None, FAKE, 1.0, 8, None) == qnn.QNN_ERR_UNSUPPORTED               # int8 levels hold 7 bits
+    assert dl(*ok, None, None, 1.0, 3, None) == qnn.QNN_ERR_INVALID_ARG
+    assert dl(*ok, None, ODD, 1.0, 3, None) == qnn.QNN_ERR_ALIGNMENT
     ap = L.qnn_global_avgpool_f32
     assert ap(FAKE, 2, 0, 8, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
     assert ap(FAKE, 2, 4, 0, FAKE, None) == qnn.QNN_ERR_INVALID_ARG

@@ -78,6 +78,26 @@ def test_stem_at_the_workload_shape():
     assert np.array_equal(planes_to_numpy(pooled), oracle.pack_planes(want_pool.reshape(-1, 64), 2))
 
 
+@pytest.mark.parametrize("geom", GEOMS[:4])
+@pytest.mark.parametrize("bits", [1, 3, 7])
+def test_dense_conv_levels_out(geom, bits):
+    B, H, W, Cin, Cout, kh, kw, stride, pad = geom
+    x, w, sc, sh = _data(geom, seed=1)
+    out, lv = qnn.qnn_dense_conv2d_f32_levels(dev(x), dev(w), stride, pad, 2.0, bits, scale=dev(sc), shift=dev(sh), relu=True,
+                                              want_out=True)
+    _, planes = qnn.qnn_dense_conv2d_f32(dev(x), dev(w), stride, pad, scale=dev(sc), shift=dev(sh), relu=True,
+                                         want_out=False, next_clip=2.0, next_bits=bits)
+    torch.cuda.synchronize()
+    want, mag = oracle.dense_layer(x, w, stride, pad, sc, sh, True)
+    got = out.cpu().numpy()
+    assert (np.abs(got.astype(np.float64) - want) <= (kh * kw * Cin + 4) * U * mag + 1e-30).all()
+    want_lv, _ = oracle.quantize(got, 2.0, bits)
+    assert np.array_equal(lv.cpu().numpy(), want_lv.astype(np.int8))
+    assert np.array_equal(planes_to_numpy(planes), oracle.pack_planes(want_lv.reshape(-1, Cout), bits))
+    only, _ = qnn.qnn_dense_conv2d_f32_levels(dev(x), dev(w), stride, pad, 2.0, bits, scale=dev(sc), shift=dev(sh), relu=True)
+    assert only is None
+
+
 @pytest.mark.parametrize("shape", [(3, 7, 7, 512), (2, 1, 1, 5), (5, 4, 9, 33), (1, 56, 56, 64)])
 def test_global_avgpool(shape):
     gen = np.random.default_rng(sum(shape))
