@@ -44,7 +44,10 @@ struct DenseConvParams {
 // ONE: the reduction is one chunk.  Every lane then keeps its weight operands (its channel's values 2 u + lane / 32)
 // in registers for all pixel tiles of the workgroup: no weight stage in LDS (three to four workgroups fit a CU
 // instead of two) and no weight reads in the MFMA loop.
-template <bool ONE> __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3))) void dense_conv_kernel(DenseConvParams p)
+// KIND: which outputs exist, as bits 1 (fp32 out), 2 (planes), 4 (int8 levels), so that the epilogue carries only
+// their code; -1 = decided at run time.
+template <bool ONE, int KIND>
+__global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3))) void dense_conv_kernel(DenseConvParams p)
 {
     __shared__ float As[kDenseTile * kChunkStride];
     __shared__ float Ws[ONE ? 4 : kDenseTile * kChunkStride];
@@ -171,6 +174,10 @@ template <bool ONE> __global__ __launch_bounds__(kDenseThreads) __attribute__((a
     // D layout of the 32 x 32 tile: this lane holds channel lane % 32 of the pixels 8 (r / 4) + 4 (lane / 32) + r % 4
     auto finish = [&](int64_t tile, const v16f &acc) {
         const int64_t row0 = tile * kDenseTile;
+        // outputs that the instantiation rules out are compile-time null: their tests and stores disappear
+        float *const o_out = KIND < 0 || (KIND & 1) ? p.out : nullptr;
+        uint32_t *const o_next = KIND < 0 || (KIND & 2) ? p.next : nullptr;
+        int8_t *const o_lv = KIND < 0 || (KIND & 4) ? p.next_lv : nullptr;
         int code[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -180,11 +187,11 @@ template <bool ONE> __global__ __launch_bounds__(kDenseThreads) __attribute__((a
             if (p.scale) y = y * sc;
             if (p.shift) y = y + sh;
             if (p.relu) y = fmaxf(y, 0.0f);
-            if (p.out && ok) p.out[pix * p.Cout + c] = y;
-            code[r] = (p.next || p.next_lv) && ok ? quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) : 0;
-            if (p.next_lv && ok) p.next_lv[pix * p.Cout + c] = (int8_t)(2 * code[r] - p.next_top);
+            if (o_out && ok) o_out[pix * p.Cout + c] = y;
+            code[r] = (o_next || o_lv) && ok ? quantize_code(y, p.next_inv_clip, p.next_half_top, p.next_top) : 0;
+            if (o_lv && ok) o_lv[pix * p.Cout + c] = (int8_t)(2 * code[r] - p.next_top);
         }
-        if (p.next) {
+        if (o_next) {
             // The 32 lanes of a half-wave hold the 32 channels of one plane word: one ballot per register
             // and bit gives the words of two pixels.  Lane L < 32 collects the word of the wave's pixel L,
             // so that a plane leaves with one store of 32 lanes instead of 16 stores of 2.
@@ -198,7 +205,7 @@ template <bool ONE> __global__ __launch_bounds__(kDenseThreads) __attribute__((a
                     if (lane == slot) mine = (uint32_t)bits;
                     if (lane == slot + 4) mine = (uint32_t)(bits >> 32);
                 }
-                if (lane < 32 && pix < p.M && wword < p.cwo) p.next[((int64_t)j * p.M + pix) * p.cwo + wword] = mine;
+                if (lane < 32 && pix < p.M && wword < p.cwo) o_next[((int64_t)j * p.M + pix) * p.cwo + wword] = mine;
             }
         }
     };
@@ -318,15 +325,24 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
     const int64_t col_tiles = ceil_div(d->Cout, kDenseTile);
     const bool one = K <= kChunk;
     int per_cu = 0;
-    if ((one ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dense_conv_kernel<true>, kDenseThreads, 0)
-             : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dense_conv_kernel<false>, kDenseThreads, 0)) != hipSuccess ||
-        per_cu < 1)
+    const int kind = (out ? 1 : 0) | (next_planes ? 2 : 0) | (next_levels ? 4 : 0);
+    void (*kernel)(DenseConvParams) = dense_conv_kernel<false, -1>;
+    if (one) {
+        switch (kind) {
+        case 1: kernel = dense_conv_kernel<true, 1>; break;
+        case 2: kernel = dense_conv_kernel<true, 2>; break;
+        case 3: kernel = dense_conv_kernel<true, 3>; break;
+        case 4: kernel = dense_conv_kernel<true, 4>; break;
+        case 5: kernel = dense_conv_kernel<true, 5>; break;
+        default: kernel = dense_conv_kernel<true, -1>; break;
+        }
+    }
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kDenseThreads, 0) != hipSuccess || per_cu < 1)
         return fail(QNN_ERR_LAUNCH, "%s: occupancy query failed", who);
     int64_t per_col = ceil_div((int64_t)per_cu * cus, col_tiles);
     if (per_col > p.tiles_m) per_col = p.tiles_m;
     const dim3 grid((unsigned)per_col, (unsigned)col_tiles);
-    if (one) hipLaunchKernelGGL(dense_conv_kernel<true>, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
-    else hipLaunchKernelGGL(dense_conv_kernel<false>, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
+    hipLaunchKernelGGL(kernel, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
     return check_launch(who);
 }
 
