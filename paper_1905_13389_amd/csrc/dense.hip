@@ -27,6 +27,10 @@ constexpr int kChunk = 152;                // reduction values per LDS stage (ev
 constexpr int kChunkStride = kChunk + 1;   // odd: conflict-free operand reads
 static_assert(kChunk % 8 == 0 && 2 * kDenseTile * kChunkStride * 4 + kChunk * 8 <= 80 * 1024, "two workgroups per CU");
 
+// A zero in device memory: loads whose tap or weight does not exist read it instead of being skipped or masked
+// afterwards, so that a batch of loads stays independent and no mask has to live until the data arrives.
+static __device__ float dense_zero = 0.0f;
+
 struct DenseConvParams {
     const float *x, *w, *scale, *shift;
     float *out;
@@ -79,8 +83,7 @@ __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3
                 if (h * kPart + t >= kSlots) continue; // the last part is shorter
                 const int kk = sub + 4 * (h * kPart + t);
                 const bool in_w = ch_ok && kk < kc;
-                const float got = *(in_w ? wb + k0 + kk : p.w); // unconditional loads stay independent
-                v[t] = in_w ? got : 0.0f;
+                v[t] = *(in_w ? wb + k0 + kk : &dense_zero);
             }
 #pragma unroll
             for (int t = 0; t < kPart; ++t)
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3
     // The chunk's values of this lane's pixel into registers.  A wave whose 16 pixels all have their whole
     // window inside the image (and whose tensor 32-bit byte offsets reach) gathers with one table read,
     // one add and one load per value; otherwise every tap is tested against the image, and the load goes
-    // to a safe address when the test fails, so that the loads of a half stay independent of each other.
+    // to the zero word when the test fails.
     // (In kParts parts of up to kPart values each: part h holds the slots t = h kPart ... .)
     auto gather = [&](const Pixel &q, int kc, int h, float (&v)[kPart]) {
         if (p.fast_offsets && __all(q.inside)) {
@@ -129,8 +132,7 @@ __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3
                 const int2 e = taps[kk];
                 const int y = q.hi0 + (e.y >> 16), xx = q.wi0 + (e.y & 0xffff);
                 const bool in_image = q.ok && kk < kc && (unsigned)y < (unsigned)p.H && (unsigned)xx < (unsigned)p.W;
-                const float got = *(in_image ? reinterpret_cast<const float *>(q.origin + e.x) : p.x);
-                v[t] = in_image ? got : 0.0f;
+                v[t] = *(in_image ? reinterpret_cast<const float *>(q.origin + e.x) : &dense_zero);
             }
         }
     };
@@ -221,8 +223,7 @@ __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3
 #pragma unroll
         for (int u = 0; u < kSteps; ++u) {
             const bool in_w = c_ok && 2 * u + khalf < kc;
-            const float got = *(in_w ? wrow + 2 * u + khalf : p.w);
-            breg[u] = in_w ? got : 0.0f;
+            breg[u] = *(in_w ? wrow + 2 * u + khalf : &dense_zero);
         }
         __syncthreads();
         for (int64_t tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
