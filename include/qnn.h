@@ -154,6 +154,8 @@ typedef struct qnn_block_epilogue {
     int32_t res_bits;
     float res_scale;
     const float *res_f32;
+    int32_t relu; /* nonzero: y = max(y, 0) after the other terms -- the lower limit of HReLU (Table 1); the upper
+                     one is the next quantizer's clip, so the encoder sees clamp(y / clip, 0, 1) */
 } qnn_block_epilogue;
 
 int qnn_conv2d_block(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32_t *w_planes,

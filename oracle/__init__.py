@@ -224,14 +224,15 @@ def deconv2d(a_levels, w_levels, stride, pad):
     return np.ascontiguousarray(out.astype(np.int32))
 
 
-def block_epilogue(acc, scale_vec, bias=None, res_levels=None, res_scale=None, res_f32=None):
+def block_epilogue(acc, scale_vec, bias=None, res_levels=None, res_scale=None, res_f32=None, relu=False):
     """What a residual block adds between the decoder's scale factor and the next quantizer (the
     ResNet-18 of the experiments section has shortcuts and batch normalisation; the derivation itself
     leaves the bias out): a per-channel shift -- a folded batch-norm -- and the shortcut term, either
     quantized levels times one real factor or an fp32 tensor.  fp32 throughout, one rounding per step,
     in this order:
         y = (float)acc * scale[c];  y = y + bias[c];  y = y + ((float)res_level * res_scale);
-        y = y + res_f32.
+        y = y + res_f32;  y = max(y, 0) if relu -- the lower limit of HReLU (Table 1); the next quantizer's clip
+        is the upper one, so that the encoder sees clamp(y / clip, 0, 1).
     numpy float32 array arithmetic is one IEEE single-precision operation per element per operator.
     """
     y = scale(acc, scale_vec)
@@ -247,6 +248,8 @@ def block_epilogue(acc, scale_vec, bias=None, res_levels=None, res_scale=None, r
         r = np.asarray(res_f32)
         assert r.dtype == np.float32 and r.shape == y.shape
         y = y + r
+    if relu:
+        y = np.maximum(y, np.float32(0.0))
     assert y.dtype == np.float32
     return y
 

@@ -2,7 +2,8 @@
 // convolution kernels take them: a per-channel shift (a folded batch-norm) and a shortcut held
 // either as quantized codes or in fp32.  The paper's derivation drops the bias; its ResNet-18
 // experiments need both.  Order and rounding are fixed (one fp32 operation per step):
-//   y = (float)acc * scale[c];  y = y + bias[c];  y = y + ((float)level * res_scale);  y = y + res_f32.
+//   y = (float)acc * scale[c];  y = y + bias[c];  y = y + ((float)level * res_scale);  y = y + res_f32;
+//   y = max(y, 0) (relu: HReLU's lower limit, Table 1).
 #pragma once
 
 #include <math.h>
@@ -17,6 +18,8 @@ struct BlockTerms {
     const float *res_f32 = nullptr; // [pixels][Cout]
     int res_bits = 0, res_top = 0;  // level = 2 code - res_top
     float res_scale = 0.0f;
+    int relu = 0;
+    bool any() const { return bias || res_q || res_f32 || relu; }
 };
 
 // Host-side check and translation of the caller's struct (NULL: no terms).
@@ -32,7 +35,7 @@ inline int block_terms(const char *who, const qnn_block_epilogue *epi, const flo
     }
     if (!aligned16(epi->bias) || !aligned16(epi->res_q) || !aligned16(epi->res_f32))
         return fail(QNN_ERR_ALIGNMENT, "%s: block-term pointers must be 16-byte aligned", who);
-    t.bias = epi->bias, t.res_q = epi->res_q, t.res_f32 = epi->res_f32;
+    t.bias = epi->bias, t.res_q = epi->res_q, t.res_f32 = epi->res_f32, t.relu = epi->relu ? 1 : 0;
     if (epi->res_q) t.res_bits = epi->res_bits, t.res_top = (1 << epi->res_bits) - 1, t.res_scale = epi->res_scale;
     return QNN_OK;
 }

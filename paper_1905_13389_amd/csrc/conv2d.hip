@@ -73,6 +73,7 @@ __global__ __launch_bounds__(256) void bconv_plain_kernel(ConvParams p, int w_bi
             o = o + term;
         }
         if (p.blk.res_f32) o = o + p.blk.res_f32[idx];
+        if (p.blk.relu) o = fmaxf(o, 0.0f);
         p.out[idx] = o;
     }
 }
@@ -173,7 +174,7 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
         t.pad_y = t.pad_x = d->pad;
         t.nphase = 1, t.wgs_per_phase = 0, t.phase_words = 0;
         t.scatter = 0, t.os = 1, t.oy0 = t.ox0 = 0, t.HO = (int)p.Ho, t.WO = (int)p.Wo, t.M_out = (int)p.M;
-        const bool has_terms = blk.bias || blk.res_q || blk.res_f32;
+        const bool has_terms = blk.any();
         t.partial = acc ? acc : reinterpret_cast<int32_t *>(out);
         const int w_chunks = (d->w_bits + 3) / 4, a_chunks = (d->a_bits + 3) / 4;
         const int64_t w_plane_words = (int64_t)d->Cout * p.nw;

@@ -464,6 +464,7 @@ bconv_tile_kernel(ConvTileParams p)
                     }
                 }
                 if (p.blk.res_f32) o[0] = o[0] + rf.x, o[1] = o[1] + rf.y, o[2] = o[2] + rf.z, o[3] = o[3] + rf.w;
+                if (p.blk.relu) o[0] = fmaxf(o[0], 0.0f), o[1] = fmaxf(o[1], 0.0f), o[2] = fmaxf(o[2], 0.0f), o[3] = fmaxf(o[3], 0.0f);
             }
             if (rvalid) {
                 const int64_t off = ro * p.Cout + cidx;

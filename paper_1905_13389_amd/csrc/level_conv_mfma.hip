@@ -400,6 +400,7 @@ level_conv_mfma_kernel(LevelConvParams p)
                 y = y + term;
             }
             if (p.blk.res_f32) y = y + p.blk.res_f32[(int64_t)row * p.Cout + c];
+            if (p.blk.relu) y = fmaxf(y, 0.0f);
         }
         return y;
     };
@@ -619,7 +620,7 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
     // workgroups per CU hide each other's prologue and epilogue; above that 256 x 256 with 128-byte
     // stages (one workgroup per CU) when its workgroups fill at least three quarters of the CU rounds
     // they take, otherwise 128 x 128 with four waves, two workgroups per CU.
-    const bool terms = blk.bias || blk.res_q || blk.res_f32;
+    const bool terms = blk.any();
     auto go = [&](auto shape) {
         constexpr int MB = decltype(shape)::MB, NB = decltype(shape)::NB, WM = decltype(shape)::WM, WN = decltype(shape)::WN,
                       KB = decltype(shape)::KB;

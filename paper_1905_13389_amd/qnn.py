@@ -56,7 +56,7 @@ class qnn_dense_conv_desc(ctypes.Structure):
 
 class qnn_block_epilogue(ctypes.Structure):
     _fields_ = [("bias", ctypes.c_void_p), ("res_q", ctypes.c_void_p), ("res_bits", ctypes.c_int32),
-                ("res_scale", ctypes.c_float), ("res_f32", ctypes.c_void_p)]
+                ("res_scale", ctypes.c_float), ("res_f32", ctypes.c_void_p), ("relu", ctypes.c_int32)]
 
 
 _lib = None
@@ -309,8 +309,8 @@ def qnn_encode_levels_i8(src, clip, bits, levels=None):
     return levels
 
 
-def _block_epilogue(bias, res_q, res_bits, res_scale, res_f32):
-    return qnn_block_epilogue(_ptr(bias), _ptr(res_q), int(res_bits), float(res_scale), _ptr(res_f32))
+def _block_epilogue(bias, res_q, res_bits, res_scale, res_f32, relu=False):
+    return qnn_block_epilogue(_ptr(bias), _ptr(res_q), int(res_bits), float(res_scale), _ptr(res_f32), int(bool(relu)))
 
 
 def _level_conv(entry, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale, want_acc, want_out, next_clip,
@@ -346,10 +346,10 @@ def qnn_level_conv2d_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=N
 
 def qnn_level_conv2d_block_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale, bias=None, res_levels=None,
                               res_bits=0, res_scale=0.0, res_f32=None, want_acc=True, want_out=False,
-                              next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+                              next_clip=None, next_bits=0, acc=None, out=None, next_levels=None, relu=False):
     """qnn_level_conv2d_i8 with the residual-block terms: bias fp32 [Cout], res_levels int8 [B][Ho][Wo][Cout]
-    with its factor res_scale, res_f32 fp32 [B][Ho][Wo][Cout]."""
-    epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32)
+    with its factor res_scale, res_f32 fp32 [B][Ho][Wo][Cout], relu (max(y, 0) after them)."""
+    epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32, relu)
     return _level_conv(lib().qnn_level_conv2d_block_i8, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
                        want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
 
@@ -461,9 +461,9 @@ def qnn_level_conv2d_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=
 
 def qnn_level_conv2d_block_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale, bias=None, res_levels=None,
                                res_bits=0, res_scale=0.0, res_f32=None, want_acc=True, want_out=False,
-                               next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+                               next_clip=None, next_bits=0, acc=None, out=None, next_levels=None, relu=False):
     """qnn_level_conv2d_fp4 with the residual-block terms; res_levels uint8 fp4 [B][Ho][Wo][Cout/2]."""
-    epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32)
+    epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32, relu)
     return _level_conv_fp4(lib().qnn_level_conv2d_block_fp4, epi, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
                            want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
 
@@ -590,10 +590,10 @@ def qnn_conv2d(a_planes, w_planes, shape, cin, stride, pad, scale=None, want_acc
 
 def qnn_conv2d_block(a_planes, w_planes, shape, cin, stride, pad, scale, bias=None, res_planes=None, res_scale=0.0,
                      res_f32=None, want_acc=True, want_out=False, next_clip=None, next_bits=0, acc=None, out=None,
-                     next_planes=None):
+                     next_planes=None, relu=False):
     """qnn_conv2d with the residual-block terms: bias fp32 [Cout], res_planes [res_bits][B*Ho*Wo][ceil(Cout/32)]
-    with its factor res_scale, res_f32 fp32 [B][Ho][Wo][Cout]."""
+    with its factor res_scale, res_f32 fp32 [B][Ho][Wo][Cout], relu (max(y, 0) after them)."""
     res_bits = res_planes.shape[0] if res_planes is not None else 0
-    epi = _block_epilogue(bias, res_planes, res_bits, res_scale, res_f32)
+    epi = _block_epilogue(bias, res_planes, res_bits, res_scale, res_f32, relu)
     return _conv(lib().qnn_conv2d_block, epi, a_planes, w_planes, shape, cin, stride, pad, scale, want_acc, want_out,
                  next_clip, next_bits, acc, out, next_planes)

@@ -121,8 +121,9 @@ def test_conv2d_argument_errors(qnn):
 def test_block_epilogue_argument_errors(qnn):
     L = qnn.lib()
     D, E = qnn.qnn_conv_desc, qnn.qnn_block_epilogue
-    # pointer, pointer, int32, float, pointer
-    assert ctypes.sizeof(E) == 32 and E.res_bits.offset == 16 and E.res_scale.offset == 20 and E.res_f32.offset == 24
+    # pointer, pointer, int32, float, pointer, int32 (+ tail padding)
+    assert ctypes.sizeof(E) == 40 and E.res_bits.offset == 16 and E.res_scale.offset == 20 and E.res_f32.offset == 24
+    assert E.relu.offset == 32
     ok = D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2)
     F, O = FAKE.value, ODD.value
 

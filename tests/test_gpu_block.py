@@ -273,3 +273,41 @@ def test_resnet18_trunk_full_batch_every_image():
         np.testing.assert_allclose(_np(got[-1]["y"]), want[-1][1], rtol=RTOL, atol=0)
         del got
         torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("geom", [GEOMS[0], GEOMS[3], GEOMS[5]])
+@pytest.mark.parametrize("which", ["relu", "bias+relu", "all+relu"])
+def test_relu_term_all_routes(geom, which):
+    # max(y, 0) after the other terms (HReLU's lower limit), then the fused quantizer: planes / levels of the
+    # upper half only.  xor + bitcount route, int8 matrix-core route, and the plain one-lane kernel's shape.
+    B, H, W, Cin, Cout, k, stride, pad = geom
+    w_bits = a_bits = res_bits = 2
+    gen = np.random.default_rng(sum(geom) + len(which))
+    a, w = levels(gen, (B, H, W, Cin), a_bits), levels(gen, (Cout, k, k, Cin), w_bits)
+    s = (gen.uniform(0.5, 1.5, size=Cout) / np.sqrt(k * k * Cin * 25.0)).astype(np.float32)
+    want_acc = oracle.conv2d(a, w, stride, pad)
+    base = "all" if which.startswith("all") else which.replace("+relu", "").replace("relu", "")
+    bias, res_lv, rs, res_f = _terms(gen, base, want_acc.shape, res_bits) if base else (None, None, np.float32(0.37), None)
+    want = oracle.block_epilogue(want_acc, s, bias, res_lv, rs, res_f, relu=True)
+    assert (want >= 0).all() and (want == 0).any()
+    lv, _ = oracle.quantize(want, 2.5, 3)
+    assert lv.min() >= 1
+
+    wp = pack_levels(w, w_bits).view(w_bits, Cout, k, k, -1)
+    res_planes = None if res_lv is None else pack_levels(res_lv.reshape(-1, Cout), res_bits)
+    acc, out, nxt = qnn.qnn_conv2d_block(pack_levels(a, a_bits), wp, (B, H, W), Cin, stride, pad, dev(s), bias=_opt(bias),
+                                         res_planes=res_planes, res_scale=float(rs), res_f32=_opt(res_f), relu=True,
+                                         want_out=True, next_clip=2.5, next_bits=3)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), want_acc)
+    np.testing.assert_allclose(out.cpu().numpy(), want, rtol=RTOL, atol=0)
+    assert np.array_equal(planes_to_numpy(nxt), oracle.pack_planes(lv.reshape(-1, Cout), 3))
+
+    if Cin % 16 == 0:
+        acc, out, nl = qnn.qnn_level_conv2d_block_i8(dev(a), dev(w), stride, pad, a_bits, w_bits, dev(s), bias=_opt(bias),
+                                                     res_levels=_opt(res_lv), res_bits=res_bits, res_scale=float(rs),
+                                                     res_f32=_opt(res_f), relu=True, want_out=True, next_clip=2.5, next_bits=3)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc.cpu().numpy(), want_acc)
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=RTOL, atol=0)
+        assert np.array_equal(nl.cpu().numpy(), lv.astype(np.int8))

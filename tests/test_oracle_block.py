@@ -128,3 +128,27 @@ def test_trunk_activations_stay_in_range():
         for lv in (t["a"], t["hq"]):
             assert len(np.unique(lv)) == 8
             assert (np.abs(lv) == 7).mean() < 0.1
+
+
+def test_relu_term_is_hrelu_in_front_of_the_quantizer():
+    # Table 1: HReLU(x) = 1 for x > 1, x in between, 0 for x < 0.  With the relu term the next quantizer
+    # (clamp of y / clip to [-1, 1]) sees exactly HReLU(y / clip): only the codes of the upper half occur,
+    # and with 1 bit every activation is +1 -- the special case the experiments section notes.
+    gen = np.random.default_rng(21)
+    acc = gen.integers(-400, 400, size=(2, 5, 5, 8)).astype(np.int32)
+    s = gen.uniform(0.005, 0.02, size=8).astype(np.float32)
+    bias = gen.normal(0, 0.2, size=8).astype(np.float32)
+    plain = oracle.block_epilogue(acc, s, bias)
+    y = oracle.block_epilogue(acc, s, bias, relu=True)
+    assert np.array_equal(y, np.where(plain > 0, plain, np.float32(0))) and (plain < 0).any()
+    clip = 2.0
+    hrelu = np.minimum(np.maximum(y.astype(np.float64) / clip, 0.0), 1.0)
+    for bits in (1, 2, 3):
+        lv, _ = oracle.quantize(y, clip, bits)
+        top = (1 << bits) - 1
+        # the quantizer's own range limit gives the same value as HReLU on these inputs
+        lv_ref, _ = oracle.quantize((hrelu * clip).astype(np.float32), clip, bits)
+        assert np.array_equal(lv, lv_ref)
+        assert lv.min() >= 1 and lv.max() == top          # levels of the upper half only
+        if bits == 1:
+            assert (lv == 1).all()
