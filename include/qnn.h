@@ -139,6 +139,7 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
  *     y = y + bias[c]                               if bias     (a folded batch-norm shift)
  *     y = y + ((float)res_level * res_scale)        if res_q    (shortcut held as quantized codes)
  *     y = y + res_f32[...]                          if res_f32  (shortcut held in fp32)
+ *     y = max(y, 0)                                 if relu     (HReLU's lower limit, Table 1)
  * `out` receives y and next_planes its codes; `acc` stays the integer product.
  *   bias     DEVICE fp32 [Cout], or NULL
  *   res_q    DEVICE bit-planes [res_bits][B][Ho][Wo][ceil(Cout/32)] (as qnn_encode_pack or a fused
