@@ -42,35 +42,54 @@ GEMM_2X2_4096_TRAFFIC_BYTES = 182.7e6
 EVENT_EVERY = 5
 
 
-def valu_probe(qnn, torch):
-    """Cycles per wave64 VALU instruction and SIMD (at 2.4 GHz) of the register-only loops."""
+VALU_PROBE_MODES = ((0, "v_xor_b32"), (1, "v_bcnt_u32_b32"), (2, "xor_bcnt_pair"), (3, "pair_back_to_back"),
+                    (4, "pair_two_deep"), (5, "pair_groups_of_4"), (6, "pair_two_deep_nop"))
+
+
+def valu_probe(torch):
+    """The register-only issue-rate loops: per mode the time per wave64 instruction and SIMD in ns, and the two
+    in-kernel counters across the loop (s_memtime and the constant 100 MHz s_memrealtime).  Where s_memtime
+    follows the shader clock, their ratio is the clock the chip held under that very load, and the time per
+    instruction becomes real cycles; where it does not (ratio 1: both constant-rate), cycles are left out
+    rather than derived from a nominal clock."""
+    from paper_1905_13389_amd import probe
     wgs, iters = 512, 20000          # 2 waves per SIMD, 64 VALU instructions per iteration
     buf = torch.empty(wgs * 256, dtype=torch.int32, device="cuda")
-    res = {}
-    for mode, name in ((0, "v_xor_b32"), (1, "v_bcnt_u32_b32"), (2, "xor_bcnt_pair")):
-        qnn.qnn_probe_valu(mode, wgs, iters // 10, buf)
+    clocks = torch.zeros((wgs * 4, 2), dtype=torch.int64, device="cuda")
+    res = {"unit": "ns per wave64 instruction per SIMD, 2 waves per SIMD"}
+    for mode, name in VALU_PROBE_MODES:
+        probe.qnn_probe_valu(mode, wgs, iters // 10, buf)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        qnn.qnn_probe_valu(mode, wgs, iters, buf)
+        probe.qnn_probe_valu(mode, wgs, iters, buf, clocks)
         e1.record()
         torch.cuda.synchronize()
         instr_per_simd = 64.0 * iters * (wgs / 256)
-        res[name] = round(e0.elapsed_time(e1) * 1e-3 * CLOCK_HZ / instr_per_simd, 3)
-    res["unit"] = "cycles per wave64 instruction per SIMD at 2.4 GHz, 2 waves per SIMD"
-    res["pair_binary_tops"] = round(SIMDS * CLOCK_HZ / (2 * res["xor_bcnt_pair"]) * 64 * 64 / 1e12, 1)
+        ns = e0.elapsed_time(e1) * 1e6 / instr_per_simd
+        c = clocks.double().mean(dim=0).tolist()
+        ratio = c[0] / c[1] if c[1] > 0 else 0.0
+        entry = {"ns": round(ns, 4), "memtime_over_realtime": round(ratio, 4)}
+        if ratio > 1.5:   # s_memtime counts shader cycles: clock = ratio x 100 MHz
+            entry["clock_ghz"] = round(ratio * 0.1, 4)
+            entry["cycles"] = round(c[0] / (64.0 * iters * 2), 3)   # per instruction of the SIMD's 2 waves
+        res[name] = entry
+    best = min(res[n]["ns"] for _, n in VALU_PROBE_MODES[2:])
+    res["best_pair_order"] = [n for _, n in VALU_PROBE_MODES[2:] if res[n]["ns"] == best][0]
+    res["pair_binary_tops"] = round(SIMDS / (2 * best * 1e-9) * 64 * 64 / 1e12, 1)
     return res
 
 
-def mfma_probe(qnn, torch):
+def mfma_probe(torch):
     """Sustained rate of the register-only MFMA loops, in TOP/s (int8) and TFLOP/s (fp4)."""
+    from paper_1905_13389_amd import probe
     wgs, iters = 512, 20000          # 2 waves per SIMD, 16 MFMAs per wave and iteration
     buf = torch.empty(wgs * 256, dtype=torch.int32, device="cuda")
     res = {}
     for mode, name, ops in ((0, "int8", 65536.0), (1, "fp4", 131072.0)):
-        qnn.qnn_probe_mfma(mode, wgs, iters // 10, buf)
+        probe.qnn_probe_mfma(mode, wgs, iters // 10, buf)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        qnn.qnn_probe_mfma(mode, wgs, iters, buf)
+        probe.qnn_probe_mfma(mode, wgs, iters, buf)
         e1.record()
         torch.cuda.synchronize()
         res[name] = round(ops * 16.0 * iters * wgs * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
@@ -657,8 +676,8 @@ def main():
 
     # the register-only issue-rate loops run first: they belong to the roofline object and leave the
     # clocks settled before the W warm-up steps
-    probe = valu_probe(qnn, torch)
-    mprobe = mfma_probe(qnn, torch)  # what register-only MFMA loops sustain on this device (the variants' context)
+    probe = valu_probe(torch)
+    mprobe = mfma_probe(torch)  # what register-only MFMA loops sustain on this device (the variants' context)
     for _ in range(args.warmup):
         step()
     # one streaming pass of known size (64 MiB read, 64 MiB written at the default size): the

@@ -380,32 +380,15 @@ int qnn_global_avgpool_f32(const float *x, int64_t B, int64_t hw, int64_t C, flo
 int qnn_dense_fc_f32(const float *x, const float *w, const float *bias, int64_t rows, int64_t cols, int64_t n,
                      float *out, void *stream);
 
-/*
- * qnn_probe_valu -- measurement aid, not part of the hot path: launches `workgroups` workgroups
- * of 256 lanes that each run `iters` iterations of a register-only loop of 64 VALU instructions
- * per wave, so that the issue rate of the binary dot product's two instructions (the "xnor" and
- * "bitcount" of the paper's abstract) can be timed on the device at hand.
- *   mode 0: v_xor_b32 only; 1: v_bcnt_u32_b32 only; 2: xor/count pairs in the GEMM kernels' order
- *   out  DEVICE, workgroups * 256 uint32 (receives the loops' results so they are not removed)
- */
-int qnn_probe_valu(int mode, int workgroups, int iters, uint32_t *out, void *stream);
-
-/*
- * qnn_probe_mfma -- the same kind of aid for the matrix-core comparison routes: every workgroup of 256
- * lanes runs `iters` iterations of 16 register-only MFMA instructions per wave on four independent
- * accumulators, which gives the rate the matrix cores sustain on the device at hand (clocks under load
- * included) next to the published peak.
- *   mode 0: v_mfma_i32_32x32x32_i8 (65536 operations each); 1: v_mfma_scale_f32_32x32x64_f8f6f4 on fp4
- *   operands (131072 operations each)
- *   out  DEVICE, workgroups * 256 uint32
- */
-int qnn_probe_mfma(int mode, int workgroups, int iters, uint32_t *out, void *stream);
-
 /* Message for the last error returned on the calling thread ("" if none). Never NULL. */
 const char *qnn_last_error(void);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int qnn_version(void);
+
+/* Hex digest of the source files this library was compiled from (the build script passes it in; "" when built by
+ * hand).  The Python binding compares it with the sources beside it and rebuilds a library that is out of date. */
+const char *qnn_build_id(void);
 
 #ifdef __cplusplus
 }

@@ -37,7 +37,6 @@ def lib():
         L = ctypes.CDLL(path)
         i64, i32, f32 = ctypes.c_int64, ctypes.c_int, ctypes.c_float
         p = ctypes.c_void_p
-        L.oracle_quantize.argtypes = [p, i64, f32, i32, p, p]
         L.oracle_quantize16.argtypes = [p, i64, f32, i32, p, p]
         L.oracle_pack_planes.argtypes = [p, i64, i64, i32, p]
         L.oracle_unpack_planes.argtypes = [p, i64, i64, i32, p]

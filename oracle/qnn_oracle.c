@@ -40,30 +40,7 @@
 /*   h = (2^b - 1) / 2 (exact in fp32); r = fma(t, h, h) + 0.5f; u = floor(r) */
 /* NaN input is outside the contract.                                        */
 /* ------------------------------------------------------------------------- */
-int oracle_quantize(const float *x, int64_t count, float clip, int bits,
-                    int8_t *level /* may be NULL */, uint8_t *code /* may be NULL */)
-{
-    if (!x || count < 0 || bits < 1 || bits > 7 || !(clip > 0.0f) || isinf(clip))
-        return -1; /* int8 levels hold up to 7 bits; 8-bit levels use oracle_quantize16 */
-    const int top = (1 << bits) - 1;
-    const float inv = 1.0f / clip;
-    const float h = (float)top * 0.5f;
-    for (int64_t i = 0; i < count; ++i) {
-        float t = x[i] * inv;
-        t = fmaxf(t, -1.0f);
-        t = fminf(t, 1.0f);
-        float r = fmaf(t, h, h);
-        r = r + 0.5f;
-        int u = (int)floorf(r);
-        if (u < 0) u = 0;
-        if (u > top) u = top;
-        if (code) code[i] = (uint8_t)u;
-        if (level) level[i] = (int8_t)(2 * u - top);
-    }
-    return 0;
-}
-
-/* Same quantizer, int16 levels, so that 8-bit codes (levels up to +-255) fit. */
+/* Levels are int16 so that 8-bit codes (levels up to +-255) fit. */
 int oracle_quantize16(const float *x, int64_t count, float clip, int bits,
                       int16_t *level, uint8_t *code)
 {

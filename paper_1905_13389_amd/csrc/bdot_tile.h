@@ -48,21 +48,34 @@ template <int WB, int AB, int TM, int TN, int KV = 4, int KB = kBK> struct Tile 
     static constexpr int STAGE_WORDS = (A_ROWPLANES + W_ROWPLANES) * BKP;
 };
 
-// Lane tile per (w_bits, a_bits): TM*TN*(WB+AB-1) counters plus KV*(TM*AB + TN*WB) operand
-// registers must stay well inside the 256-register budget of a lane (2 waves per SIMD).  Rectangular
-// tiles put their short side on the operand with more planes: a k group then reads TM*AB + TN*WB
-// operand words for its TM*TN*WB*AB pairs, and fewer reads per pair is what the low bit widths lack.
-template <int WB, int AB> struct TilePick { static constexpr int TM = 4, TN = 4, KV = (WB + AB >= 7 ? 2 : 4); };
-template <> struct TilePick<1, 1> { static constexpr int TM = 8, TN = 8, KV = 4; };
-template <> struct TilePick<1, 2> { static constexpr int TM = 4, TN = 8, KV = 4; };
-template <> struct TilePick<2, 1> { static constexpr int TM = 8, TN = 4, KV = 4; };
-template <> struct TilePick<1, 4> { static constexpr int TM = 4, TN = 8, KV = 2; };
-template <> struct TilePick<4, 1> { static constexpr int TM = 8, TN = 4, KV = 2; };
-template <> struct TilePick<2, 3> { static constexpr int TM = 4, TN = 8, KV = 2; };
-template <> struct TilePick<3, 2> { static constexpr int TM = 8, TN = 4, KV = 2; };
-template <> struct TilePick<2, 2> { static constexpr int TM = 8, TN = 4, KV = 4; };
-template <> struct TilePick<1, 3> { static constexpr int TM = 4, TN = 8, KV = 4; };
-template <> struct TilePick<3, 1> { static constexpr int TM = 8, TN = 4, KV = 4; };
+// Lane tile, LDS read width and occupancy per (w_bits, a_bits), chosen by measurement at 4096^3 (every candidate
+// below was timed against the others on one device).  What decides: a wave issues at most one instruction every
+// four to five cycles, so one xor / count pair (plus the s_nop that keeps the pairs from stalling each other)
+// costs a wave about 13 cycles and a SIMD needs two waves that are ready to issue at every moment to reach its
+// 6.5 cycles per pair.  With two resident waves per SIMD every LDS wait, barrier or store of one wave idles half
+// the SIMD; with four (at most 128 registers per lane) two may wait while two issue.  So the tiles are small:
+// TM*TN*(WB+AB-1) counters plus KV*(TM*AB + TN*WB) operand registers stay near 100, the short side of a
+// rectangular tile is on the operand with more planes (a k group reads TM*AB + TN*WB operand words for its
+// TM*TN*WB*AB pairs), and only 4 x 4 bits, whose 2 x 2 lane tile would fit even more waves, gains nothing from
+// a larger tile at lower occupancy.  Fractions of the VALU peak at 4096^3, before -> after this choice:
+// 1x1 0.62 -> 0.74, 1x2 0.62 -> 0.77, 2x2 0.75 -> 0.83, 3x3 0.82 -> 0.86, 4x4 0.84 -> 0.87.
+template <int WB, int AB> struct TilePick;
+template <> struct TilePick<1, 1> { static constexpr int TM = 8, TN = 4, KV = 4, WPE = 4; };
+template <> struct TilePick<1, 2> { static constexpr int TM = 4, TN = 4, KV = 4, WPE = 4; };
+template <> struct TilePick<2, 1> { static constexpr int TM = 4, TN = 4, KV = 4, WPE = 4; };
+template <> struct TilePick<1, 3> { static constexpr int TM = 2, TN = 4, KV = 4, WPE = 4; };
+template <> struct TilePick<3, 1> { static constexpr int TM = 4, TN = 2, KV = 4, WPE = 4; };
+template <> struct TilePick<1, 4> { static constexpr int TM = 2, TN = 4, KV = 4, WPE = 4; };
+template <> struct TilePick<4, 1> { static constexpr int TM = 4, TN = 2, KV = 4, WPE = 4; };
+template <> struct TilePick<2, 2> { static constexpr int TM = 4, TN = 4, KV = 2, WPE = 4; };
+template <> struct TilePick<2, 3> { static constexpr int TM = 2, TN = 4, KV = 4, WPE = 4; };
+template <> struct TilePick<3, 2> { static constexpr int TM = 4, TN = 2, KV = 4, WPE = 4; };
+template <> struct TilePick<2, 4> { static constexpr int TM = 2, TN = 4, KV = 2, WPE = 4; };
+template <> struct TilePick<4, 2> { static constexpr int TM = 4, TN = 2, KV = 2, WPE = 4; };
+template <> struct TilePick<3, 3> { static constexpr int TM = 4, TN = 2, KV = 4, WPE = 4; };
+template <> struct TilePick<3, 4> { static constexpr int TM = 2, TN = 4, KV = 2, WPE = 4; };
+template <> struct TilePick<4, 3> { static constexpr int TM = 4, TN = 2, KV = 2, WPE = 4; };
+template <> struct TilePick<4, 4> { static constexpr int TM = 2, TN = 2, KV = 2, WPE = 4; };
 
 // Workgroup id -> tile id so that the workgroups an XCD receives (ids congruent mod 8 under
 // round-robin dispatch) cover one contiguous band of tiles and share operands in that XCD's L2.

@@ -23,8 +23,9 @@ struct GemmParams {
     int32_t *partial_out;       // where to leave the running sum (not the last chunk pair), or nullptr
 };
 
-template <int WB, int AB, int TM, int TN, int KV>
-__global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void bgemm_tile_kernel(GemmParams p)
+// WPE = waves per SIMD the kernel is compiled for (2: up to 256 registers per lane, 4: up to 128).
+template <int WB, int AB, int TM, int TN, int KV, int WPE>
+__global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(WPE, WPE))) void bgemm_tile_kernel(GemmParams p)
 {
     using T = Tile<WB, AB, TM, TN, KV>;
     __shared__ __attribute__((aligned(16))) uint32_t smem[2][T::STAGE_WORDS];
@@ -169,20 +170,20 @@ __global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2,
     }
 }
 
-template <int WB, int AB, int TM, int TN, int KV> static void launch_tile(GemmParams p, hipStream_t st)
+template <int WB, int AB, int TM, int TN, int KV, int WPE> static void launch_tile(GemmParams p, hipStream_t st)
 {
     using T = Tile<WB, AB, TM, TN, KV>;
     const int64_t tiles_m = ceil_div(p.rows, T::BM);
     p.tiles_n = ceil_div(p.cols, T::BN);
     p.nblocks = tiles_m * p.tiles_n;
-    hipLaunchKernelGGL((bgemm_tile_kernel<WB, AB, TM, TN, KV>), dim3((unsigned)p.nblocks),
+    hipLaunchKernelGGL((bgemm_tile_kernel<WB, AB, TM, TN, KV, WPE>), dim3((unsigned)p.nblocks),
                        dim3(kTileThreads), 0, st, p);
 }
 
 template <int WB, int AB> static void launch_pick(const GemmParams &p, hipStream_t st)
 {
     using G = TilePick<WB, AB>;
-    launch_tile<WB, AB, G::TM, G::TN, G::KV>(p, st);
+    launch_tile<WB, AB, G::TM, G::TN, G::KV, G::WPE>(p, st);
 }
 
 template <int WB> static bool dispatch_a(int a_bits, const GemmParams &p, hipStream_t st)

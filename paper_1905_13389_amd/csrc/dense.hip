@@ -301,11 +301,15 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(next_planes) || !aligned16(next_levels))
         return fail(QNN_ERR_ALIGNMENT, "%s: pointers must be 16-byte aligned", who);
     const int64_t Ho = (d->H + 2 * d->pad - d->kh) / d->stride + 1, Wo = (d->W + 2 * d->pad - d->kw) / d->stride + 1;
-    const int64_t M = d->B * Ho * Wo, K = (int64_t)d->kh * d->kw * d->Cin;
-    if (M >= (1LL << 31) || K >= (1LL << 24) || d->Cout >= (1LL << 24) || d->H >= (1LL << 24) || d->W >= (1LL << 24) ||
-        d->kh > 4096 || d->kw > 4096 || (int64_t)d->kh * d->W * d->Cin >= (1LL << 29) ||
-        ceil_div(d->Cout, kDenseTile) > 65535)
+    // extents first, then their products: every product below stays far inside 64 bits
+    if (d->H >= (1LL << 24) || d->W >= (1LL << 24) || d->Cin >= (1LL << 24) || d->Cout >= (1LL << 24) || d->kh > 4096 ||
+        d->kw > 4096 || d->pad >= (1 << 24) || d->B >= (1LL << 31) || ceil_div(d->Cout, kDenseTile) > 65535)
         return fail(QNN_ERR_RANGE, "%s: tensor too large", who);
+    const int64_t K = (int64_t)d->kh * d->kw * d->Cin;
+    if (K >= (1LL << 24) || (int64_t)d->kh * d->W * d->Cin >= (1LL << 29) || Ho * Wo >= (1LL << 31) ||
+        d->B > ((1LL << 31) - 1) / (Ho * Wo))
+        return fail(QNN_ERR_RANGE, "%s: tensor too large", who);
+    const int64_t M = d->B * Ho * Wo;
     DenseConvParams p;
     p.x = x, p.w = w, p.scale = scale, p.shift = shift, p.out = out, p.next = next_planes, p.next_lv = next_levels;
     p.H = (int)d->H, p.W = (int)d->W, p.Cin = (int)d->Cin, p.Cout = (int)d->Cout;

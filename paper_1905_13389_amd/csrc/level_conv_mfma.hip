@@ -590,7 +590,7 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
     const int64_t Wo = (d->W + 2 * (int64_t)d->pad - d->kw) / d->stride + 1;
     // the kernel indexes both tensors and the output pixels with 32-bit integers
     if (d->H > (1 << 20) || d->W > (1 << 20) || d->B > (1LL << 31) / (d->H * d->W * cinb) - 1 ||
-        d->B * Ho * Wo >= (1LL << 31) - 1024 || d->Cout * nk >= (1LL << 31) ||
+        d->B > ((1LL << 31) - 1025) / (Ho * Wo) || d->Cout > ((1LL << 31) - 1) / nk ||
         ((int64_t)d->kh * d->W + d->kw) * cinb >= (1LL << 24))
         return fail(QNN_ERR_RANGE, "%s: tensor too large for 32-bit indexing", who);
     if (d->B == 0) return QNN_OK;

@@ -1,4 +1,4 @@
-// Library-wide entry points: version and the thread-local error message.
+// Library-wide entry points: version, build id and the thread-local error message.
 #include "qnn_host.h"
 
 namespace qnn {
@@ -11,4 +11,9 @@ char *error_buffer()
 
 extern "C" const char *qnn_last_error(void) { return qnn::error_buffer(); }
 
-extern "C" int qnn_version(void) { return 0 * 10000 + 3 * 100 + 0; }
+extern "C" int qnn_version(void) { return 0 * 10000 + 4 * 100 + 0; }
+
+#ifndef QNN_BUILD_ID
+#define QNN_BUILD_ID ""
+#endif
+extern "C" const char *qnn_build_id(void) { return QNN_BUILD_ID; }

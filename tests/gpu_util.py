@@ -42,3 +42,19 @@ def oracle_full_batch(config):
         res.append(([t["levels"].astype(np.int8) for t in trace], trace[-1]["out"]))
         del trace
     return res
+
+
+def codes_explained_by_bound(got32, want64, bound, clip, bits):
+    """Number of elements whose code from the fp32 value differs from the code of the float64 value; asserts that
+    each of them has its float64 value within `bound` (plus the quantizer's own fp32 roundings) of a threshold."""
+    top = (1 << bits) - 1
+    lv_got, _ = oracle.quantize(got32, clip, bits)
+    lv_ref, _ = oracle.quantize(want64.astype(np.float32), clip, bits)
+    differ = lv_got != lv_ref
+    if differ.any():
+        thresholds = (2.0 * (np.arange(top) + 0.5) / top - 1.0) * clip
+        dist = np.abs(want64[differ][:, None] - thresholds[None, :]).min(axis=1)
+        slack = bound[differ] + 8 * 2.0 ** -24 * (np.abs(want64[differ]) + clip)
+        assert (dist <= slack).all(), "a code differs although the value is not near a threshold"
+        assert (np.abs(lv_got.astype(np.int32) - lv_ref)[differ] == 2).all(), "codes differ by more than one step"
+    return int(differ.sum())

@@ -217,13 +217,29 @@ def test_fp4_convolution_argument_errors(qnn):
     assert L.qnn_maxpool_levels_fp4(None, 0, 8, 8, 32, 2, 2, 0, 0, None, None) == qnn.QNN_OK
 
 
-def test_probe_argument_errors(qnn):
-    L = qnn.lib()
-    for f in (L.qnn_probe_valu, L.qnn_probe_mfma):
-        assert f(9, 1, 1, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
-        assert f(0, 0, 1, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
-        assert f(0, 1, -1, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
-        assert f(0, 1, 1, None, None) == qnn.QNN_ERR_INVALID_ARG
+def _declared_in(header, prefix="qnn_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(%s[a-z0-9_]+)\s*\(" % prefix, text)))
+
+
+def test_probe_library_exports_and_argument_errors():
+    # the issue-rate loops live in a library of their own (include/qnn_probe.h), outside the product library
+    from paper_1905_13389_amd import probe
+    L = probe.lib()
+    assert set(_declared_in("qnn_probe.h")) == set(probe.EXPORTS)
+    for n in probe.EXPORTS:
+        assert getattr(L, n) is not None
+    product = ctypes.CDLL(os.path.join(os.path.dirname(probe.LIB_PATH), "libqnn.so"))
+    for n in ("qnn_probe_valu", "qnn_probe_mfma"):
+        assert not hasattr(product, n)
+    assert L.qnn_probe_valu(99, 1, 1, FAKE, None, None) < 0 and b"mode" in L.qnn_probe_last_error()
+    assert L.qnn_probe_valu(0, 0, 1, FAKE, None, None) < 0
+    assert L.qnn_probe_valu(0, 1, -1, FAKE, None, None) < 0
+    assert L.qnn_probe_valu(0, 1, 1, None, None, None) < 0
+    assert L.qnn_probe_mfma(2, 1, 1, FAKE, None) < 0
+    assert L.qnn_probe_mfma(0, 70000, 1, FAKE, None) < 0
+    assert L.qnn_probe_mfma(0, 1, 1, None, None) < 0
 
 
 def test_training_gradient_argument_errors(qnn):

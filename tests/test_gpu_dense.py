@@ -2,13 +2,17 @@
 qnn_dense_fc_f32) against the float64 oracle.  fp32 sums in the kernel's own order: the bound is the
 worst case of recursive summation, (terms + 4) 2^-24 sum |x| |w| per output (products, partial sums, the
 scale and the shift each round once).  The fused next-layer planes are a decision taken in fp32 on the
-kernel's own fp32 value, so they must equal the oracle's quantizer applied to that value, bit for bit."""
+kernel's own fp32 value (the fp32 sum has no unique value: it depends on the summation order, and the quantizer
+acts on whichever value the kernel holds), so they are compared, bit for bit, with the oracle's quantizer applied
+to the GPU's own fp32 output -- never with an oracle-only chain.  What that leaves open is closed separately:
+the fp32 value is bounded against the float64 oracle, and every code that differs from the code of the float64
+value is counted and must lie within that bound of a threshold of the ladder (codes_explained_by_bound)."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
-from gpu_util import dev, planes_to_numpy
+from gpu_util import codes_explained_by_bound, dev, planes_to_numpy
 
 pytestmark = pytest.mark.gpu
 
@@ -54,6 +58,7 @@ def test_dense_conv_against_oracle(geom, terms):
     assert (np.abs(got.astype(np.float64) - want) <= bound).all(), float((np.abs(got - want) / bound).max())
     lv, _ = oracle.quantize(got, 2.0, 3)
     assert np.array_equal(planes_to_numpy(planes), oracle.pack_planes(lv.reshape(-1, Cout), 3))
+    assert codes_explained_by_bound(got, want, bound, 2.0, 3) <= max(2, got.size // 500)
     # planes only: the fp32 tensor never leaves the chip
     none, planes2 = qnn.qnn_dense_conv2d_f32(dev(x), dev(w), stride, pad, scale=dev(sc) if use_sc else None,
                                              shift=dev(sh) if use_sh else None, relu=relu, want_out=False,
@@ -70,6 +75,7 @@ def test_stem_at_the_workload_shape():
     want, mag = oracle.dense_layer(x, w, 2, 3, sc, sh, True)
     got = out.cpu().numpy()
     assert (np.abs(got.astype(np.float64) - want) <= (147 + 4) * U * mag + 1e-30).all()
+    assert codes_explained_by_bound(got, want, (147 + 4) * U * mag + 1e-30, 3.0, 2) <= got.size // 1000
     lv, _ = oracle.quantize(got, 3.0, 2)
     assert np.array_equal(planes_to_numpy(planes), oracle.pack_planes(lv.reshape(-1, 64), 2))
     # the pooled planes feed the first quantized layer: 3x3 stride-2 pooling of the codes

@@ -49,6 +49,44 @@ def test_encode_bf16(bits):
     assert np.array_equal(got, _expect_planes(x.to(torch.float32).numpy(), 2.0, bits))
 
 
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 8])
+@pytest.mark.parametrize("shape", [(1, 32), (3, 64), (5, 4096), (2, 9, 9, 64), (257, 96), (1, 1024 * 37)])
+def test_encode_bf16_whole_word_rows(bits, shape):
+    # rows that are whole words long and contiguous take the streaming kernel (one long bit-vector, vector loads,
+    # lane-to-bit mapping of its own for 2-byte elements); sizes span less than one wave's chunk, ragged numbers
+    # of chunks and many workgroups
+    gen = np.random.default_rng(500 + bits + shape[-1])
+    x = torch.from_numpy(gen.standard_normal(shape, dtype=np.float32) * 1.3).to(torch.bfloat16)
+    got = planes_to_numpy(qnn.qnn_encode_pack(x.cuda(), 2.0, bits))
+    assert np.array_equal(got, _expect_planes(x.to(torch.float32).numpy(), 2.0, bits))
+
+
+def _strided_case(gen, dtype, rows, n, stride, bits):
+    """A [rows][stride] matrix of which the first n columns of every row are encoded (row_stride_elems > n)."""
+    if dtype == "int8":
+        wide = torch.from_numpy(levels(gen, (rows, stride), bits))
+        want = oracle.pack_planes(wide[:, :n].numpy().astype(np.int16), bits)
+    else:
+        wide = torch.from_numpy(gen.standard_normal((rows, stride), dtype=np.float32))
+        if dtype == "bf16":
+            wide = wide.to(torch.bfloat16)
+        want = _expect_planes(np.ascontiguousarray(wide[:, :n].to(torch.float32).numpy()), 1.5, bits)
+    return wide, want
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "int8"])
+@pytest.mark.parametrize("rows,n,stride", [(7, 64, 96), (5, 100, 133), (33, 32, 40), (3, 300, 1024), (4, 256, 257),
+                                            (1, 64, 4096)])
+@pytest.mark.parametrize("bits", [2, 5])
+def test_encode_rows_a_stride_apart(dtype, rows, n, stride, bits):
+    gen = np.random.default_rng(rows * 1000 + n + stride + bits)
+    wide, want = _strided_case(gen, dtype, rows, n, stride, bits)
+    view = wide.cuda()[:, :n]
+    assert rows == 1 or not view.is_contiguous()
+    got = planes_to_numpy(qnn.qnn_encode_pack(view, 1.5, bits))
+    assert np.array_equal(got, want)
+
+
 @pytest.mark.parametrize("bits", range(1, 8))
 @pytest.mark.parametrize("shape", [(4, 512), (3, 70), (2, 33)])
 def test_encode_int8_levels(bits, shape):

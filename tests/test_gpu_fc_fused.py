@@ -64,6 +64,31 @@ def test_float_values_in(shape, a_bits, dtype):
     assert only_out[0] is None and np.array_equal(only_out[1].cpu().numpy(), want.astype(np.float32))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "int8"])
+@pytest.mark.parametrize("rows,n,stride,cols", [(6, 64, 96, 40), (9, 100, 133, 300), (64, 512, 520, 256), (3, 32, 4096, 5)])
+def test_rows_a_stride_apart(dtype, rows, n, stride, cols):
+    # the layer's input is a column range of a wider matrix: row_stride_elems > n
+    a_bits = 3
+    gen = np.random.default_rng(rows + n + stride + cols)
+    if dtype == "int8":
+        wide = torch.from_numpy(levels(gen, (rows, stride), a_bits))
+        lv = wide[:, :n].numpy()
+    else:
+        wide = torch.from_numpy(gen.normal(0, 1, size=(rows, stride)).astype(np.float32))
+        if dtype == "bf16":
+            wide = wide.to(torch.bfloat16)
+        lv, _ = oracle.quantize(np.ascontiguousarray(wide[:, :n].to(torch.float32).numpy()), 2.5, a_bits)
+    w = levels(gen, (cols, n), 2)
+    s = gen.uniform(0.01, 0.1, size=cols).astype(np.float32)
+    view = wide.cuda()[:, :n]
+    assert not view.is_contiguous()
+    acc, out = qnn.qnn_fc_fused(view, 2.5, a_bits, pack_levels(w, 2), scale=dev(s))
+    torch.cuda.synchronize()
+    want = oracle.gemm(np.ascontiguousarray(lv), w)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    np.testing.assert_allclose(out.cpu().numpy(), oracle.scale(want, s), rtol=1e-5, atol=0)
+
+
 def test_layers_too_long_for_the_fused_form_are_refused():
     a = torch.zeros((4, 40000), dtype=torch.int8, device="cuda")
     wp = torch.zeros((2, 8, 1250), dtype=torch.int32, device="cuda")
