@@ -131,6 +131,25 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
                float next_clip, int next_bits, void *stream);
 
 /*
+ * qnn_conv2d_chain_static -- qnn_conv2d in its layer-to-layer form (planes in, the next layer's planes out, no acc
+ * and no out) for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Above 4 bits qnn_conv2d needs an acc or out buffer for the running int32 sum of
+ * its plane-chunk launches; such callers have none to lend, so here that sum lives in a device array that is part
+ * of the library image: qnn_conv2d_chain_static_max_outputs() = 2^23 int32 (32 MiB on every GPU the library
+ * runs on, held until the process ends).  The call allocates and frees nothing and gives the same next_planes,
+ * bit for bit, as qnn_conv2d with a caller-owned acc.  Up to 4 bits it is qnn_conv2d(acc = out = NULL).
+ *   arguments as qnn_conv2d; scale and next_planes are required.
+ *   QNN_ERR_RANGE when B Ho Wo Cout exceeds qnn_conv2d_chain_static_max_outputs() (nothing is enqueued): use
+ *   qnn_conv2d with a buffer of your own.  Other errors as qnn_conv2d.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams, or
+ * different host threads without ordering between their streams) race on it.  Calls on one stream are ordered.  The first plane-chunk launch of
+ * a call overwrites the array, so no state carries over from one call to the next.
+ */
+int64_t qnn_conv2d_chain_static_max_outputs(void);
+int qnn_conv2d_chain_static(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32_t *w_planes,
+                            const float *scale, uint32_t *next_planes, float next_clip, int next_bits, void *stream);
+
+/*
  * qnn_conv2d_block -- qnn_conv2d with the terms a residual block puts between the scale factor and
  * the next quantizer (the experiments section's ResNet-18 has shortcuts and batch normalisation; the
  * derivation itself leaves the bias out).  With epi == NULL it is qnn_conv2d.  Otherwise, per output

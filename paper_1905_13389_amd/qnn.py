@@ -26,6 +26,7 @@ QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d", "qnn_conv2d_block",
+           "qnn_conv2d_chain_static", "qnn_conv2d_chain_static_max_outputs",
            "qnn_level_conv2d_block_i8", "qnn_deconv_phase_words", "qnn_deconv_pack_weights", "qnn_deconv2d",
            "qnn_quantize_ste_backward", "qnn_encoder_backward",
            "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
@@ -98,6 +99,10 @@ def lib():
         L.qnn_conv2d_block.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, ctypes.POINTER(qnn_block_epilogue),
                                        vp, vp, vp, f32, i32, vp]
         L.qnn_conv2d_block.restype = i32
+        L.qnn_conv2d_chain_static.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, f32, i32, vp]
+        L.qnn_conv2d_chain_static.restype = i32
+        L.qnn_conv2d_chain_static_max_outputs.argtypes = []
+        L.qnn_conv2d_chain_static_max_outputs.restype = i64
         L.qnn_level_conv2d_block_i8.argtypes = L.qnn_conv2d_block.argtypes
         L.qnn_level_conv2d_block_i8.restype = i32
         L.qnn_dense_conv2d_f32.argtypes = [ctypes.POINTER(qnn_dense_conv_desc), vp, vp, vp, vp, i32, vp, vp, f32, i32, vp]
@@ -697,3 +702,22 @@ def qnn_conv2d_block(a_planes, w_planes, shape, cin, stride, pad, scale, bias=No
     return _conv(lib().qnn_conv2d_block, (bias, res_planes, res_scale, res_f32, relu), a_planes, w_planes, shape, cin,
                  stride, pad, scale, want_acc, want_out, next_clip, next_bits, acc, out, next_planes)
 
+
+def qnn_conv2d_chain_static_max_outputs():
+    return int(lib().qnn_conv2d_chain_static_max_outputs())
+
+
+def qnn_conv2d_chain_static(a_planes, w_planes, shape, cin, stride, pad, scale, next_clip, next_bits, next_planes=None):
+    """qnn_conv2d from planes to the next layer's planes with no acc / out buffer at any bit width (the running sum
+    of wide bit widths lives in the library's own fixed device array; the call allocates nothing when next_planes
+    is passed in).  Returns next_planes [next_bits][B*Ho*Wo][ceil(Cout/32)]."""
+    B, H, W = shape
+    w_bits, cout, kh, kw, _ = _conv_w_planes(w_planes, cin)
+    a_bits = _act_planes("a_planes", a_planes, B, H, W, cin)
+    ho, wo = _conv_out_shape(H, W, kh, kw, stride, pad)
+    _arg("scale", scale, _F32, shape=(cout,))
+    d = qnn_conv_desc(B, H, W, cin, cout, kh, kw, stride, pad, a_bits, w_bits)
+    next_planes = _out("next_planes", next_planes, torch.int32, (next_bits, B * ho * wo, (cout + 31) // 32), a_planes)
+    _check(lib().qnn_conv2d_chain_static(ctypes.byref(d), _ptr(a_planes), _ptr(w_planes), _ptr(scale), _ptr(next_planes),
+                                         float(next_clip), int(next_bits), _stream()))
+    return next_planes

@@ -74,7 +74,7 @@ int main()
     EXPECT(qnn_dequant_scale(FI, FF, -1, 4, FF, nullptr), QNN_ERR_INVALID_ARG);
     EXPECT(qnn_dequant_scale(FI, FF, 4, 4, reinterpret_cast<float *>(ODD), nullptr), QNN_ERR_ALIGNMENT);
 
-    // qnn_conv2d / qnn_conv2d_block / qnn_deconv2d: descriptors
+    // qnn_conv2d / qnn_conv2d_block / qnn_conv2d_chain_static / qnn_deconv2d: descriptors
     const qnn_conv_desc ok = {1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2};
     auto with = [&](auto edit) { qnn_conv_desc d = ok; edit(d); return d; };
     const qnn_conv_desc bad[] = {
@@ -114,6 +114,16 @@ int main()
     EXPECT(qnn_conv2d_block(&ok, FAKE, FAKE, nullptr, &epi, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR); // no scale
     EXPECT(qnn_level_conv2d_block_i8(&ok, F8, F8, nullptr, &epi, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
     EXPECT(qnn_level_conv2d_block_fp4(&ok, FU, FU, nullptr, &epi, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
+
+    // the static-accumulator form: too many outputs for its array, and the usual argument errors
+    const qnn_conv_desc huge = with([](qnn_conv_desc &d) { d.B = 64, d.H = d.W = 64, d.Cout = 256, d.a_bits = d.w_bits = 5; });
+    EXPECT(qnn_conv2d_chain_static(&huge, FAKE, FAKE, FF, FAKE, 1.0f, 2, nullptr), QNN_ERR_RANGE);
+    EXPECT(qnn_conv2d_chain_static(&wide, FAKE, FAKE, FF, nullptr, 1.0f, 2, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_conv2d_chain_static(&wide, FAKE, FAKE, nullptr, FAKE, 1.0f, 2, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_conv2d_chain_static(&wide, FAKE, ODD, FF, FAKE, 1.0f, 2, nullptr), QNN_ERR_ALIGNMENT);
+    EXPECT(qnn_conv2d_chain_static(&wide, FAKE, FAKE, FF, FAKE, 0.0f, 2, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_conv2d_chain_static(nullptr, FAKE, FAKE, FF, FAKE, 1.0f, 2, nullptr), QNN_ERR_INVALID_ARG);
+    if (qnn_conv2d_chain_static_max_outputs() != (int64_t(1) << 23)) ++g_failures;
 
     // transposed convolution
     EXPECT((int)(qnn_deconv_phase_words(2, 64, 4, 4, 64, 0) >= 0 ? 0 : -1), ANY_ERROR);
