@@ -30,20 +30,23 @@ constexpr int kBK = 16; // default number of reduction words staged per step (64
 // bytes, one pass serves 128 bytes): for 16-byte reads (KV = 4, 8 lanes per pass) an odd multiple
 // of 4 words; for 8-byte reads (KV = 2, 16 lanes per pass) twice an odd number, which leaves the
 // rows 8-byte aligned only, so stages are then written with 8-byte stores.
-template <int WB, int AB, int TM, int TN, int KV = 4, int KB = kBK> struct Tile {
+// NT = lanes of the workgroup (256 or 512): NT / 16 row groups of 16 lanes, lane (ty, tx) owns rows ty + (NT/16) i.
+template <int WB, int AB, int TM, int TN, int KV = 4, int KB = kBK, int NT = kTileThreads> struct Tile {
     static_assert(KV == 2 || KV == 4, "KV is 2 or 4 words");
     static_assert(KB % 4 == 0, "stages are loaded in 16-byte units");
-    static constexpr int UQ = KB / 4; // 16-byte units per row and plane
+    static_assert(NT % 64 == 0, "whole waves");
+    static constexpr int RG = NT / 16; // row groups
+    static constexpr int UQ = KB / 4;  // 16-byte units per row and plane
     static constexpr int BKP = KV == 4 ? ((UQ % 2 == 1) ? KB : KB + 4) : KB + 2;
-    static constexpr int BM = 16 * TM;
+    static constexpr int BM = RG * TM;
     static constexpr int BN = 16 * TN;
     static constexpr int S = WB + AB - 1;
     static constexpr int A_ROWPLANES = AB * BM;
     static constexpr int W_ROWPLANES = WB * BN;
     static constexpr int A_UNITS = A_ROWPLANES * UQ; // one unit = 4 words of one row-plane
     static constexpr int W_UNITS = W_ROWPLANES * UQ;
-    static constexpr int A_PER_THREAD = (A_UNITS + kTileThreads - 1) / kTileThreads;
-    static constexpr int W_PER_THREAD = (W_UNITS + kTileThreads - 1) / kTileThreads;
+    static constexpr int A_PER_THREAD = (A_UNITS + NT - 1) / NT;
+    static constexpr int W_PER_THREAD = (W_UNITS + NT - 1) / NT;
     static constexpr int A_WORDS = A_ROWPLANES * BKP;
     static constexpr int STAGE_WORDS = (A_ROWPLANES + W_ROWPLANES) * BKP;
 };

@@ -114,11 +114,15 @@ __device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
 // wave-local ordering points, and the waves of a workgroup drift apart instead of idling together
 // (short reductions spend a large share of a tile outside the xor + bitcount block).
 // BLK: the residual-block terms (bias, shortcut) are part of the epilogue.
-template <int WB, int AB, int TM, int TN, int KV, int VW, bool KEEPW, bool BLK>
-__global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void
+// NT: lanes per workgroup.  Two workgroups share a CU either way (LDS), so 256 lanes run two waves per SIMD with
+// up to 256 registers per lane and 512 lanes four waves with up to 128: the same 16 RG x 16 TN tile, each lane
+// holding half as many rows, and twice as many waves to issue from while others wait.
+template <int WB, int AB, int TM, int TN, int KV, int VW, bool KEEPW, bool BLK, int NT>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT / 128, NT / 128))) void
 bconv_tile_kernel(ConvTileParams p)
 {
-    using T = Tile<WB, AB, TM, TN, KV, kConvKB>;
+    using T = Tile<WB, AB, TM, TN, KV, kConvKB, NT>;
+    constexpr int RG = T::RG, NW = NT / 64;
     constexpr int UQ = T::UQ;
     constexpr int BN = T::BN, BM = T::BM;
     constexpr int EPI_STRIDE = BN + 16; // the 4 rows a wave writes at once land in 4 different bank groups
@@ -139,11 +143,11 @@ bconv_tile_kernel(ConvTileParams p)
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int lane = tid & 63, wave = tid >> 6;
-    constexpr int WR = BM / 4;               // tile rows of one wave; tile row ty + 16 i <-> its row (ty & 3) + 4 i
+    constexpr int WR = BM / NW;              // tile rows of one wave; tile row ty + RG i <-> its row (ty & 3) + 4 i
     constexpr int WAVE_UNITS = AB * WR * UQ; // stage units of one wave's rows
     constexpr int A_PT = KEEPW ? (WAVE_UNITS + 63) / 64 : T::A_PER_THREAD;
-    constexpr int CHUNK = STAGE_ALLOC / 4;   // a wave's quarter of a stage buffer (its rows' stage, then its V rows)
-    static_assert(STAGE_ALLOC % 16 == 0 && CHUNK >= AB * WR * T::BKP && CHUNK >= WR * EPI_STRIDE, "wave quarters");
+    constexpr int CHUNK = STAGE_ALLOC / NW;  // a wave's share of a stage buffer (its rows' stage, then its V rows)
+    static_assert(STAGE_ALLOC % (4 * NW) == 0 && CHUNK >= AB * WR * T::BKP && CHUNK >= WR * EPI_STRIDE, "wave shares");
     // ordering point between a tile's phases
     auto tile_sync = [&]() {
         if constexpr (KEEPW) {
@@ -161,15 +165,15 @@ bconv_tile_kernel(ConvTileParams p)
             const int idx = lane + u * 64;
             const int rp = idx / UQ, slot = rp % WR; // rp = plane * WR + row of the wave
             q = idx % UQ, plane = rp / WR;
-            trow = 4 * wave + (slot & 3) + 16 * (slot >> 2);
+            trow = 4 * wave + (slot & 3) + RG * (slot >> 2);
             lds = wave * CHUNK + rp * T::BKP + 4 * q;
             return WAVE_UNITS % 64 == 0 || idx < WAVE_UNITS;
         } else {
-            const int idx = tid + u * kTileThreads;
+            const int idx = tid + u * NT;
             const int rp = idx / UQ;
             q = idx % UQ, plane = rp / BM, trow = rp % BM;
             lds = rp * T::BKP + 4 * q;
-            return T::A_UNITS % kTileThreads == 0 || idx < T::A_UNITS;
+            return T::A_UNITS % NT == 0 || idx < T::A_UNITS;
         }
     };
     int bid = (int)blockIdx.x;
@@ -190,17 +194,17 @@ bconv_tile_kernel(ConvTileParams p)
     const int taps = p.kh * p.kw;
 
     if constexpr (BLK) {
-        for (int e = tid; e < BN; e += kTileThreads)
+        for (int e = tid; e < BN; e += NT)
             bias_lds[e] = p.blk.bias && col0 + e < p.Cout ? p.blk.bias[col0 + e] : 0.0f;
     }
     // reduction word group -> tap number and word offset from the window origin
-    for (int g = tid; g * VW < p.nw; g += kTileThreads) {
+    for (int g = tid; g * VW < p.nw; g += NT) {
         const int kword = g * VW;
         const int tap = kword / p.cw, ci = kword % p.cw;
         tap_table[g] = ((uint32_t)tap << 24) | (uint32_t)(((tap / p.kw) * p.W + tap % p.kw) * p.cw + ci);
     }
     // output row / column -> set of taps that fall outside the image
-    for (int o = tid; o < p.Ho + p.Wo; o += kTileThreads) {
+    for (int o = tid; o < p.Ho + p.Wo; o += NT) {
         uint32_t m = 0;
         if (o < p.Ho) {
             const int h0 = o * p.stride - pad_y;
@@ -215,7 +219,7 @@ bconv_tile_kernel(ConvTileParams p)
         ymask[o] = m; // xmask follows ymask
     }
     // S[t][c] = sum over channels of the weight levels of tap t, from the planes
-    for (int e = tid; e < BN * taps; e += kTileThreads) {
+    for (int e = tid; e < BN * taps; e += NT) {
         const int t = e / BN, cl = e % BN;
         const int c = col0 + cl;
         int32_t s = 0;
@@ -262,10 +266,10 @@ bconv_tile_kernel(ConvTileParams p)
         if (w_staged) return;
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
-            const int idx = tid + u * kTileThreads;
+            const int idx = tid + u * NT;
             const int rp = idx / UQ, q = idx % UQ;
             rw[u] = make_uint4(0u, 0u, 0u, 0u);
-            if ((T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS) && 4 * q < p.kb)
+            if ((T::W_UNITS % NT == 0 || idx < T::W_UNITS) && 4 * q < p.kb)
                 rw[u] = load_rowmajor4(wbase, p.Cout, p.nw, rp / BN, col0 + rp % BN, k0 + 4 * q, wvec);
         }
     };
@@ -280,19 +284,19 @@ bconv_tile_kernel(ConvTileParams p)
         w_staged = keep_w;
 #pragma unroll
         for (int u = 0; u < T::W_PER_THREAD; ++u) {
-            const int idx = tid + u * kTileThreads;
-            if (T::W_UNITS % kTileThreads == 0 || idx < T::W_UNITS)
+            const int idx = tid + u * NT;
+            if (T::W_UNITS % NT == 0 || idx < T::W_UNITS)
                 lds_write_unit<KV>(Ws + (idx / UQ) * T::BKP + 4 * (idx % UQ), rw[u]);
         }
     };
 
     // this lane's 4 channels in the row-major half of the epilogue
     constexpr int LPR = BN / 4;            // lanes per pixel row
-    constexpr int RPP = kTileThreads / LPR; // pixel rows per pass
+    constexpr int RPP = NT / LPR;           // pixel rows per pass
     static_assert(LPR <= 16, "a pass row lies inside one 16-lane row group");
     // tile row of this lane in pass `pass`: consecutive rows, or (KEEPW) rows its own wave owns
     auto pass_row = [&](int pass) {
-        return KEEPW ? ty + 16 * (pass * (16 / LPR) + (tid & 15) / LPR) : pass * RPP + tid / LPR;
+        return KEEPW ? ty + RG * (pass * (16 / LPR) + (tid & 15) / LPR) : pass * RPP + tid / LPR;
     };
     const int c4 = (tid % LPR) * 4;
     const int cidx = col0 + c4;
@@ -341,8 +345,8 @@ bconv_tile_kernel(ConvTileParams p)
                 tile_mac<WB, AB, TM, TN, KV, kConvKB, WR, 4, HALF>(smem[buf] + wave * CHUNK, w_resident, ty & 3, tx, nkq, P,
                                                                   half_tail);
             else
-                tile_mac<WB, AB, TM, TN, KV, kConvKB, 16 * TM, 16, HALF>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P,
-                                                                        half_tail);
+                tile_mac<WB, AB, TM, TN, KV, kConvKB, BM, RG, HALF>(smem[buf], smem[buf] + T::A_WORDS, ty, tx, nkq, P,
+                                                                   half_tail);
             if (more || next_tile) stash(buf ^ 1);
             tile_sync();
             buf ^= 1;
@@ -355,7 +359,7 @@ bconv_tile_kernel(ConvTileParams p)
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int n = 0; n < TN; ++n)
-                V[(KEEPW ? (ty & 3) + 4 * i : ty + 16 * i) * EPI_STRIDE + tx + 16 * n] =
+                V[(KEEPW ? (ty & 3) + 4 * i : ty + RG * i) * EPI_STRIDE + tx + 16 * n] =
                     recombine<T::S>(P[i][n], p.n_times_top);
         // this lane's nibble of the 32-channel plane word its 4 channels belong to
         const int wword = (col0 >> 5) + (tid % LPR) / 8;
@@ -399,7 +403,7 @@ bconv_tile_kernel(ConvTileParams p)
             const int rl = pass_row(pass);
             const int r = row0 + rl;
             const bool rvalid = r < p.M;
-            const int4 vv = *reinterpret_cast<const int4 *>(V + (KEEPW ? (rl & 3) + 4 * (rl >> 4) : rl) * EPI_STRIDE + c4);
+            const int4 vv = *reinterpret_cast<const int4 *>(V + (KEEPW ? (rl & 3) + 4 * (rl / RG) : rl) * EPI_STRIDE + c4);
             int32_t v[4] = {vv.x, vv.y, vv.z, vv.w};
             // padded taps of this output pixel
             uint32_t padded = 0;
@@ -512,55 +516,47 @@ bconv_tile_kernel(ConvTileParams p)
 
 // Workgroups resident on the whole chip for one kernel (occupancy x CU count); two host-side queries
 // per launch, negligible against the launch itself.
-template <typename K> static int resident_workgroups(K kernel, size_t dyn_smem)
+template <typename K> static int resident_workgroups(K kernel, int threads, size_t dyn_smem)
 {
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kTileThreads, dyn_smem) != hipSuccess)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dyn_smem) != hipSuccess)
         return 0;
     return cus * per_cu;
 }
 
-// Lane tile of the convolution kernel per (w_bits, a_bits).  The kernel carries more live state
-// than the GEMM (pixel coordinates, the prefetched chunk across the epilogue), so its tiles are
-// smaller; the column tile stays a multiple of 32 because the fused epilogue packs whole words.
-template <int WB, int AB> struct ConvPick {
-    static constexpr int TM = 4, TN = (WB + AB >= 7 ? 2 : 4), KV = (WB + AB >= 6 ? 2 : 4);
+// Lane tile, LDS read width and workgroup size of the convolution kernel, by the number of planes WB + AB and by
+// whether the reduction is one LDS stage (at most kConvKB words: the 64-channel 3x3 layers) or streamed in several.
+// Measured per layer shape of the benchmark stacks against the other candidates (tiles of 1..4 x 1..4 outputs per
+// lane, 8- and 16-byte LDS reads, 256 and 512 lanes).  512 lanes put four waves on a SIMD: a wave issues at most
+// one instruction every four to five cycles, so two resident waves leave the SIMD idle whenever one of them
+// waits, and the streamed reductions gain 5 .. 24 % from the two extra waves; the lane tiles shrink to stay
+// inside 128 registers.  The column tile stays a multiple of 32 channels because the fused epilogue packs whole
+// plane words.
+template <int WB, int AB> struct ConvPickOneStage { // (TM, TN, KV, NT)
+    static constexpr int S = WB + AB;
+    static constexpr int TM = S <= 4 ? 1 : S <= 6 ? 4 : 1;
+    static constexpr int TN = 4;
+    static constexpr int KV = S <= 4 ? 4 : S <= 5 ? 4 : 2;
+    static constexpr int NT = S <= 4 ? 512 : S <= 6 ? 256 : 512;
+};
+template <int WB, int AB> struct ConvPickStreamed {
+    static constexpr int S = WB + AB;
+    static constexpr int TM = 2;
+    static constexpr int TN = S <= 4 ? 4 : S <= 6 ? 2 : 4;
+    static constexpr int KV = 4;
+    static constexpr int NT = 512;
 };
 
-// A narrower column tile (32 channels) for 5 and 6 planes in all.  Per unit of work it is about 8 %
-// slower than the 64-channel tile (more LDS reads per xor + bitcount pair), but it doubles the tile
-// count, which pays when the wider tiles fill their last round of resident workgroups badly (e.g.
-// 1568 tiles on 512 workgroups: 3.06 -> 4 rounds; 3136 narrow tiles: 6.1 -> 7).
-template <int WB, int AB> struct ConvPickNarrow {
-    static constexpr int TM = 4, TN = 2, KV = 4;
-};
-template <int WB, int AB> constexpr bool kHasNarrow = (WB + AB == 5 || WB + AB == 6);
-
-// share of the resident workgroups' rounds that `tiles` equal tiles fill
-inline double round_fill(int64_t tiles, int slots)
-{
-    return (double)tiles / (double)(ceil_div(tiles, slots) * slots);
-}
-
-inline int compute_units()
-{
-    static const int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            return 256;
-        return n > 0 ? n : 256;
-    }();
-    return cus;
-}
-
-template <int WB, int AB, int VW, bool BLK, class G, bool ALLOW_KEEPW>
+template <int WB, int AB, int VW, bool BLK, class G, bool ONE_STAGE>
 static int launch_conv_vw(ConvTileParams p, hipStream_t st)
 {
     constexpr int TN = G::TN;
     static_assert(TN % 2 == 0, "column tile must be a multiple of 32");
-    using T = Tile<WB, AB, G::TM, TN, G::KV, kConvKB>;
+    constexpr int NT = G::NT;
+    using T = Tile<WB, AB, G::TM, TN, G::KV, kConvKB, NT>;
+    static_assert(T::BM * (T::BN / 4) >= NT, "the row-major half of the epilogue needs at least one pass");
     const size_t dyn = ((size_t)T::BN * p.kh * p.kw + p.Ho + p.Wo) * sizeof(int32_t);
     p.tiles_m = (int)ceil_div(p.M, T::BM);
     p.tiles_n = (int)ceil_div(p.Cout, T::BN);
@@ -574,50 +570,35 @@ static int launch_conv_vw(ConvTileParams p, hipStream_t st)
     }
     p.kb = best_kb;
     p.nchunks = (int)ceil_div(p.nw, best_kb);
-    auto launch = [&](auto kernel) {
-        int slots = resident_workgroups(kernel, dyn);
-        if (slots <= 0) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: occupancy query failed");
-        // every workgroup owns one column tile; the row tiles are dealt round-robin to the
-        // slots / tiles_n workgroups of that column
-        const int phases = BLK && p.nphase > 1 ? p.nphase : 1; // phases of one launch share the slots
-        int groups = slots / (p.tiles_n * phases);
-        if (groups < 1) groups = 1;
-        if (groups > p.tiles_m) groups = p.tiles_m;
-        p.row_tile_step = groups;
-        p.wgs_per_phase = groups * p.tiles_n;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n * phases)), dim3(kTileThreads), dyn, st, p);
-        return (int)QNN_OK;
-    };
-    if constexpr (ALLOW_KEEPW) {
-        if (p.nchunks == 1) return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, true, BLK>);
-    }
-    return launch(bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, false, BLK>);
+    if (ONE_STAGE != (p.nchunks == 1)) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: stage plan does not match the kernel");
+    auto kernel = bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, ONE_STAGE, BLK, NT>;
+    int slots = resident_workgroups(kernel, NT, dyn);
+    if (slots <= 0) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: occupancy query failed");
+    // every workgroup owns one column tile; the row tiles are dealt round-robin to the
+    // slots / tiles_n workgroups of that column
+    const int phases = BLK && p.nphase > 1 ? p.nphase : 1; // phases of one launch share the slots
+    int groups = slots / (p.tiles_n * phases);
+    if (groups < 1) groups = 1;
+    if (groups > p.tiles_m) groups = p.tiles_m;
+    p.row_tile_step = groups;
+    p.wgs_per_phase = groups * p.tiles_n;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n * phases)), dim3(NT), dyn, st, p);
+    return (int)QNN_OK;
 }
 
-template <int WB, int AB, bool BLK, class G, bool ALLOW_KEEPW>
+template <int WB, int AB, bool BLK, class G, bool ONE_STAGE>
 static int launch_conv_tile(const ConvTileParams &p, hipStream_t st)
 {
-    if (p.cw % 4 == 0) return launch_conv_vw<WB, AB, 4, BLK, G, ALLOW_KEEPW>(p, st);
-    if (p.cw % 2 == 0) return launch_conv_vw<WB, AB, 2, BLK, G, ALLOW_KEEPW>(p, st);
-    return launch_conv_vw<WB, AB, 1, BLK, G, ALLOW_KEEPW>(p, st);
+    if (p.cw % 4 == 0) return launch_conv_vw<WB, AB, 4, BLK, G, ONE_STAGE>(p, st);
+    if (p.cw % 2 == 0) return launch_conv_vw<WB, AB, 2, BLK, G, ONE_STAGE>(p, st);
+    return launch_conv_vw<WB, AB, 1, BLK, G, ONE_STAGE>(p, st);
 }
 
 template <int WB, int AB, bool BLK> static int launch_conv(const ConvTileParams &p, hipStream_t st)
 {
-    if constexpr (kHasNarrow<WB, AB>) {
-        // multi-stage reductions only (the one-stage kernels keep their weights resident per column tile)
-        if (p.nw > kConvKB) {
-            using W = Tile<WB, AB, ConvPick<WB, AB>::TM, ConvPick<WB, AB>::TN, ConvPick<WB, AB>::KV, kConvKB>;
-            using N = Tile<WB, AB, ConvPickNarrow<WB, AB>::TM, ConvPickNarrow<WB, AB>::TN, ConvPickNarrow<WB, AB>::KV, kConvKB>;
-            const int phases = BLK && p.nphase > 1 ? p.nphase : 1;
-            int slots = 2 * compute_units() / phases; // both tile shapes run two workgroups per CU
-            if (slots < 1) slots = 1;
-            const double wide = round_fill(ceil_div(p.M, W::BM) * ceil_div(p.Cout, W::BN), slots);
-            const double narrow = round_fill(ceil_div(p.M, N::BM) * ceil_div(p.Cout, N::BN), slots);
-            if (narrow * 0.92 > wide) return launch_conv_tile<WB, AB, BLK, ConvPickNarrow<WB, AB>, false>(p, st);
-        }
-    }
-    return launch_conv_tile<WB, AB, BLK, ConvPick<WB, AB>, true>(p, st);
+    // a reduction of at most kConvKB words is one stage (the stage length chosen above is then kConvKB)
+    if (p.nw <= kConvKB) return launch_conv_tile<WB, AB, BLK, ConvPickOneStage<WB, AB>, true>(p, st);
+    return launch_conv_tile<WB, AB, BLK, ConvPickStreamed<WB, AB>, false>(p, st);
 }
 
 template <int WB, bool BLK> static int conv_dispatch_a(int a_bits, const ConvTileParams &p, hipStream_t st)
