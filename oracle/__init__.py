@@ -5,7 +5,9 @@ tests/, the smoke check and the benchmark's cpu_baseline leg may import this pac
 the GPU library never does and shares no code with it.
 
 Every function cites the passage of the paper it follows; the C file's header lists
-what pins each of them.  maxpool / pool_out_size are plain numpy here; their pins (the library
+what pins each of them.  layer_graph composes quantize / conv2d / scale / maxpool over a node list; its pin (the
+library's float64 convolution and pooling on the decoded real values, node by node, on a small instance of the
+detection graph) is in tests/test_oracle_graph.py.  maxpool / pool_out_size are plain numpy here; their pins (the library
 pooling routine on the same integers, commutation with the quantizer, brute force) are in
 tests/test_oracle_pool.py.  block_epilogue / residual_trunk are numpy float32 here; their pins (the same
 sums in float64, the library's batch normalisation, Table 2's real values as the shortcut, the library's
@@ -198,6 +200,36 @@ def conv_stack(x, layers):
         trace.append({"levels": lv, "acc": acc, "out": out})
         cur = out
     return trace
+
+
+def layer_graph(x, clip0, bits, nodes):
+    """A network of quantized layers given as a list of nodes in execution order (the detection network of the
+    experiments section is such a graph: a backbone whose maps feed both the next layer and the detector's heads).
+
+    x: float32 [B][H][W][C], quantized once with (clip0, bits) (Table 1 range limit, Eq. 15); the result is node
+    "input".  Every node names its source node:
+      conv  levels(src) -> conv2d (zero padding) -> scale -> out (float32); unless the node is a head, out is
+            quantized with (clip, a_bits) and the levels are what its consumers read
+      pool  max-pooling of the source's levels (taken on the codes: the quantizer is monotone)
+    Returns {name: {"levels" (or None for heads), "acc", "out"}} with "input" included.
+    """
+    assert 1 <= bits <= 7, "int8 level path holds up to 7 bits"
+    lv, _ = quantize(np.ascontiguousarray(x, dtype=np.float32), clip0, bits)
+    values = {"input": {"levels": lv, "acc": None, "out": None}}
+    for nd in nodes:
+        src = values[nd["src"]]["levels"]
+        assert src is not None, "a head's output feeds nothing"
+        if nd["kind"] == "pool":
+            values[nd["name"]] = {"levels": maxpool(src, nd["k"], nd["stride"], nd["pad"], nd["ceil_mode"]),
+                                  "acc": None, "out": None}
+            continue
+        acc = conv2d(src.astype(np.int8), nd["w"], nd["stride"], nd["pad"])
+        out = scale(acc, nd["scale"])
+        lv = None
+        if not nd["head"]:
+            lv, _ = quantize(out, nd["clip"], nd["a_bits"])
+        values[nd["name"]] = {"levels": lv, "acc": acc, "out": out}
+    return values
 
 
 def deconv2d(a_levels, w_levels, stride, pad):

@@ -139,6 +139,82 @@ def vgg_ssd_stack(batch=32, bits=4, config_index=4, plan=VGG_SSD_PLAN):
     return groups
 
 
+# --------------------------------------------------------------------------- detection network as one chain
+def _graph_conv(ci, t, name, src, cin, cout, k, bits, stride, pad, head=False):
+    """A convolution node: weights uniform over the odd levels, per-channel scale that keeps unit-variance inputs at
+    unit variance (heads: raw box / class scores of unit variance), input quantizer clipping at 3.0."""
+    gen_w, gen_s = rng(ci, 10 + 2 * t), rng(ci, 11 + 2 * t)
+    n = k * k * cin
+    g = gen_s.uniform(0.5, 1.5, size=cout)
+    s = g / np.sqrt(n * _uniform_level_variance(bits) * _gaussian_level_variance(bits))
+    return {"kind": "conv", "name": name, "src": src, "w": odd_levels(gen_w, (cout, k, k, cin), bits),
+            "scale": s.astype(np.float32), "clip": 3.0, "a_bits": bits, "w_bits": bits, "k": k, "stride": stride,
+            "pad": pad, "cin": cin, "cout": cout, "head": head}
+
+
+def _graph_pool(name, src, k, stride, pad=0, ceil_mode=False):
+    return {"kind": "pool", "name": name, "src": src, "k": k, "stride": stride, "pad": pad, "ceil_mode": ceil_mode, "head": False}
+
+
+def vgg_ssd_chained(batch=32, bits=4, image=300, config_index=8, heads=True):
+    """The detection network of the benchmark's fifth configuration as ONE graph on one input tensor: the twelve
+    3x3 convolutions of the VGG16 backbone from its second layer on, joined by 2x2 stride-2 max-pooling (ceil mode
+    at 75 -> 38), then the layers an SSD-style detector puts on top: a 3x3 stride-1 pooling, a 3x3 and a 1x1
+    convolution with 1024 channels, four pairs of 1x1 / 3x3 convolutions that take the map from 19x19 down to
+    1x1 (two with stride 2, two without padding), and a 3x3 localisation and a 3x3 class-score convolution on each
+    of the six maps the detector reads (4 or 6 boxes per position, 21 classes).  The original's dilated 3x3
+    convolution is an ordinary 3x3 here (dilation is not built).  Every quantizer clips at 3.0 except the
+    first (3 sigma of the input); heads write fp32 scores and feed nothing.
+    Returns {"x", "clip0", "bits", "nodes"}: nodes in execution order, each naming its source node ("input" first)."""
+    ci = config_index
+    x = rng(ci, 0).standard_normal((batch, image, image, 64), dtype=np.float32)
+    clip0 = float(np.float32(3.0 * np.std(x.astype(np.float64))))
+    nodes, t = [], 0
+
+    def conv(name, src, cin, cout, k=3, stride=1, pad=1, head=False):
+        nonlocal t
+        nodes.append(_graph_conv(ci, t, name, src, cin, cout, k, bits, stride, pad, head))
+        t += 1
+        return name
+
+    def pool(name, src, k=2, stride=2, pad=0, ceil_mode=False):
+        nodes.append(_graph_pool(name, src, k, stride, pad, ceil_mode))
+        return name
+
+    cur = conv("conv1_2", "input", 64, 64)
+    cur = pool("pool1", cur)
+    cur = conv("conv2_1", cur, 64, 128)
+    cur = conv("conv2_2", cur, 128, 128)
+    cur = pool("pool2", cur)
+    cur = conv("conv3_1", cur, 128, 256)
+    cur = conv("conv3_2", cur, 256, 256)
+    cur = conv("conv3_3", cur, 256, 256)
+    cur = pool("pool3", cur, ceil_mode=True)
+    cur = conv("conv4_1", cur, 256, 512)
+    cur = conv("conv4_2", cur, 512, 512)
+    f1 = cur = conv("conv4_3", cur, 512, 512)
+    cur = pool("pool4", cur)
+    cur = conv("conv5_1", cur, 512, 512)
+    cur = conv("conv5_2", cur, 512, 512)
+    cur = conv("conv5_3", cur, 512, 512)
+    cur = pool("pool5", cur, k=3, stride=1, pad=1)
+    cur = conv("conv6", cur, 512, 1024)
+    f2 = cur = conv("conv7", cur, 1024, 1024, k=1, pad=0)
+    cur = conv("conv8_1", cur, 1024, 256, k=1, pad=0)
+    f3 = cur = conv("conv8_2", cur, 256, 512, stride=2)
+    cur = conv("conv9_1", cur, 512, 128, k=1, pad=0)
+    f4 = cur = conv("conv9_2", cur, 128, 256, stride=2)
+    cur = conv("conv10_1", cur, 256, 128, k=1, pad=0)
+    f5 = cur = conv("conv10_2", cur, 128, 256, pad=0)
+    cur = conv("conv11_1", cur, 256, 128, k=1, pad=0)
+    f6 = cur = conv("conv11_2", cur, 128, 256, pad=0)
+    if heads:
+        for src, cin, boxes in ((f1, 512, 4), (f2, 1024, 6), (f3, 512, 6), (f4, 256, 6), (f5, 256, 4), (f6, 256, 4)):
+            conv("loc_" + src, src, cin, 4 * boxes, head=True)
+            conv("conf_" + src, src, cin, 21 * boxes, head=True)
+    return {"x": x, "clip0": clip0, "bits": bits, "nodes": nodes}
+
+
 # --------------------------------------------------------------------------- whole network
 CIFAR_VGG_PLAN = (
     # The CIFAR-10 network of the paper's Table 3 (the BinaryConnect / BNN architecture it cites:
