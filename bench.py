@@ -121,7 +121,7 @@ def parse():
     ap.add_argument("--repeats", type=int, default=5, help="default workload: repetitions of the K timed steps (the median is reported)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "trunk", "pool", "grad", "deconv"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "ssd", "trunk", "pool", "grad", "deconv"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -546,6 +546,122 @@ def trunk_workload(args):
                                       "note": "whole step, not a single kernel"}}}
 
 
+def graph_workload(args):
+    """The detection network of configuration 5 as ONE chain on one input (wl.vgg_ssd_chained): the backbone's twelve
+    convolutions joined by max-pooling of the planes, the SSD-style extra layers down to 1x1 and the heads on the
+    six maps, 4x4 bit, on both machine routes.  Between layers only planes (or int8 levels) exist; the heads write
+    fp32 scores."""
+    import torch
+    import qnn_workloads as wl
+    from paper_1905_13389_amd import qnn
+
+    B = args.batch or 32
+    net = wl.vgg_ssd_chained(batch=B, bits=4)
+    bits, nodes = net["bits"], net["nodes"]
+    up = lambda a: torch.from_numpy(a).cuda()
+    d_x = up(net["x"])
+    _, H0, W0, C0 = net["x"].shape
+
+    def build(route):
+        planes = route == "planes"
+        new = (lambda h, c: torch.empty((bits, B * h * h, (c + 31) // 32), dtype=torch.int32, device="cuda")) if planes \
+            else (lambda h, c: torch.empty((B, h, h, c), dtype=torch.int8, device="cuda"))
+        first = new(H0, C0)
+        val = {"input": (first, H0, C0)}
+        calls, macs = [], 0
+        for nd in nodes:
+            src, H, C = val[nd["src"]]
+            if nd["kind"] == "pool":
+                ho = qnn.qnn_pool_out_size(H, nd["k"], nd["stride"], nd["pad"], nd["ceil_mode"])
+                dst = new(ho, C)
+                if planes:
+                    fn = lambda src=src, H=H, C=C, nd=nd, dst=dst: qnn.qnn_maxpool_planes(
+                        src, (B, H, H), C, nd["k"], nd["stride"], nd["pad"], nd["ceil_mode"], out=dst)
+                else:
+                    fn = lambda src=src, nd=nd, dst=dst: qnn.qnn_maxpool_levels_i8(
+                        src, nd["k"], nd["stride"], nd["pad"], nd["ceil_mode"], out=dst)
+                calls.append((nd["name"], 0.0, fn))
+                val[nd["name"]] = (dst, ho, C)
+                continue
+            k, head = nd["k"], nd["head"]
+            ho = (H + 2 * nd["pad"] - k) // nd["stride"] + 1
+            sc = up(nd["scale"])
+            dst = None if head else new(ho, nd["cout"])
+            out = torch.empty((B, ho, ho, nd["cout"]), dtype=torch.float32, device="cuda") if head else None
+            m = B * ho * ho * nd["cout"] * k * k * nd["cin"]
+            macs += m
+            if planes:
+                wp = qnn.qnn_encode_pack(up(nd["w"]), 1.0, bits).view(bits, nd["cout"], k, k, -1)
+                fn = lambda src=src, wp=wp, H=H, C=C, nd=nd, sc=sc, dst=dst, out=out, head=head: qnn.qnn_conv2d(
+                    src, wp, (B, H, H), C, nd["stride"], nd["pad"], scale=sc, want_acc=False, want_out=head, out=out,
+                    next_clip=None if head else nd["clip"], next_bits=0 if head else bits, next_planes=dst)
+            else:
+                wl_ = up(nd["w"])
+                fn = lambda src=src, wl_=wl_, nd=nd, sc=sc, dst=dst, out=out, head=head: qnn.qnn_level_conv2d_i8(
+                    src, wl_, nd["stride"], nd["pad"], bits, bits, scale=sc, want_acc=False, want_out=head, out=out,
+                    next_clip=None if head else nd["clip"], next_bits=0 if head else bits, next_levels=dst)
+            calls.append(("%s %d->%d@%d k%d%s" % (nd["name"], nd["cin"], nd["cout"], H, k, " s2" if nd["stride"] == 2 else ""),
+                          2.0 * m * bits * bits, fn))
+            val[nd["name"]] = (dst, ho, nd["cout"])
+        return first, calls, macs
+
+    p_first, p_calls, macs = build("planes")
+    l_first, l_calls, _ = build("levels")
+    binops = 2.0 * macs * bits * bits
+
+    def step():
+        qnn.qnn_encode_pack(d_x, net["clip0"], bits, planes=p_first)
+        for _, _, fn in p_calls:
+            fn()
+
+    def mfma_step():
+        qnn.qnn_encode_levels_i8(d_x, net["clip0"], bits, levels=l_first)
+        for _, _, fn in l_calls:
+            fn()
+
+    ms, m_ms = (timed_ms(torch, f, args.steps, args.warmup) for f in (step, mfma_step))
+    tops = binops / (ms * 1e-3) / 1e12
+    # every launch of the planes route between its own events, 4 back-to-back launches each (see conv_workload)
+    evs = []
+    for _ in range(2):                      # the first pass settles the clocks, the second is read
+        evs = []
+        for label, ops, fn in p_calls:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(4):
+                fn()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+    per = [(label, ops, e0.elapsed_time(e1) / 4) for (label, ops, _), (e0, e1) in zip(p_calls, evs)]
+    conv_ms = sum(t for _, ops, t in per if ops > 0)
+    pool_ms = sum(t for _, ops, t in per if ops == 0)
+    conv_tops = binops / (conv_ms * 1e-3) / 1e12
+    fr = [(label, ops / (t * 1e-3) / 1e12 / PEAK_BINARY_TOPS, t) for label, ops, t in per if ops > 0]
+    worst = min((e for e in fr if e[2] > 0.01 * conv_ms), key=lambda e: e[1])   # among layers that matter
+    int8_tops = 2.0 * macs / (m_ms * 1e-3) / 1e12
+    return {
+        "metric": "effective binary TOPS (xnor+popcount) and % of VALU/HBM roofline, 1 MI355X", "value": round(tops, 2),
+        "unit": "binary TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 bit-planes, int32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "VGG16 + SSD-style detection network as one chain: 12 backbone convolutions joined by max-pooling, "
+                               "10 extra convolutions down to 1x1, 12 head convolutions on six maps; batch %d, 300x300, 4x4 bit" % B,
+                   "macs": macs, "images_per_s": round(B / (ms * 1e-3), 1),
+                   "step": "qnn_encode_pack + qnn_conv2d (fused scale/quantize/pack epilogue) / qnn_maxpool_planes per node"},
+        "roofline": {"bound": "alu", "kernel": "bconv_tile_kernel (%d launches per step)" % sum(1 for e in per if e[1] > 0),
+                     "achieved": round(conv_tops, 2), "peak": round(PEAK_BINARY_TOPS, 1), "unit": "binary TOP/s",
+                     "frac": round(conv_tops / PEAK_BINARY_TOPS, 4), "traffic": None, "kernel_ms": round(conv_ms, 4),
+                     "pooling_ms": round(pool_ms, 4), "step_frac": round(tops / PEAK_BINARY_TOPS, 4),
+                     "slowest_layer_above_1pct_of_time": {"layer": worst[0], "frac": round(worst[1], 4), "ms": round(worst[2], 4)},
+                     "peak_note": PEAK_NOTE},
+        "mfma_variant": {"step": "qnn_encode_levels_i8 + qnn_level_conv2d_i8 / qnn_maxpool_levels_i8 per node",
+                         "ms_per_step": round(m_ms, 4), "images_per_s": round(B / (m_ms * 1e-3), 1),
+                         "speedup_vs_xor_bitcount_step": round(ms / m_ms, 2),
+                         "roofline": {"bound": "mfma", "achieved": round(int8_tops, 1), "peak": 5000.0, "unit": "int8 TOP/s",
+                                      "frac": round(int8_tops / 5000.0, 4), "note": "whole step, not a single kernel"}}}
+
+
 def fc_workload(args):
     """Config 1: one FC layer, 2 x 2 bit, A [64][512] x W [256][512]: 6.7e7 binary operations, far too
     little to load the chip -- the figure of interest is the latency of the two launches."""
@@ -768,7 +884,7 @@ def main():
               "exchange; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
     runners = {"trunk": trunk_workload, "pool": pool_workload, "grad": grad_workload, "deconv": deconv_workload,
-               "fc1": fc_workload, "gemm": gemm_workload}
+               "fc1": fc_workload, "gemm": gemm_workload, "ssd": graph_workload}
     result = runners.get(args.workload, conv_workload)(args)
     if args.workload == "gemm" and not args.no_configs:
         result["configs"] = config_summaries(args)
