@@ -86,12 +86,13 @@ __device__ __forceinline__ uint4 gather4(const uint32_t *__restrict__ a, const u
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// OR of a value over each aligned group of 8 lanes (every lane of the group gets the result).
-__device__ __forceinline__ uint32_t or_reduce8(uint32_t v)
+// OR of a value over each aligned group of LANES = 4 or 8 lanes (every lane of the group gets the result).
+template <int LANES> __device__ __forceinline__ uint32_t or_reduce_lanes(uint32_t v)
 {
+    static_assert(LANES == 4 || LANES == 8, "groups of 4 or 8 lanes");
     v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
     v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
-    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true); // row_half_mirror
+    if constexpr (LANES == 8) v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true); // row_half_mirror
     return v;
 }
 
@@ -290,23 +291,25 @@ bconv_tile_kernel(ConvTileParams p)
         }
     };
 
-    // this lane's 4 channels in the row-major half of the epilogue
-    constexpr int LPR = BN / 4;            // lanes per pixel row
+    // this lane's EW consecutive channels of one pixel in the row-major half of the epilogue: 8 where the tile
+    // has that many outputs per lane (fewer passes, and a plane word is assembled from 4 lanes' bytes with two
+    // DPP steps instead of 8 lanes' nibbles with three), else 4
+    constexpr int EW = (BM * BN) / NT >= 8 ? 8 : 4;
+    constexpr int EQ = EW / 4;              // 16-byte pieces per lane
+    constexpr int LPR = BN / EW;            // lanes per pixel row
     constexpr int RPP = NT / LPR;           // pixel rows per pass
-    static_assert(LPR <= 16, "a pass row lies inside one 16-lane row group");
+    constexpr int LPW = 32 / EW;            // lanes per 32-channel plane word
+    static_assert(LPR <= 16 && BM % RPP == 0 && BM >= RPP, "a pass row lies inside one 16-lane row group; whole passes");
     // tile row of this lane in pass `pass`: consecutive rows, or (KEEPW) rows its own wave owns
     auto pass_row = [&](int pass) {
         return KEEPW ? ty + RG * (pass * (16 / LPR) + (tid & 15) / LPR) : pass * RPP + tid / LPR;
     };
-    const int c4 = (tid % LPR) * 4;
+    const int c4 = (tid % LPR) * EW;
     const int cidx = col0 + c4;
-    const bool cols4 = cidx + 3 < p.Cout && (p.Cout & 3) == 0; // 16-byte accesses are whole and aligned
-    float sc[4] = {0.f, 0.f, 0.f, 0.f};
-    if (p.scale) {
+    const bool cols4 = cidx + EW - 1 < p.Cout && (p.Cout & 3) == 0; // 16-byte accesses are whole and aligned
+    float sc[EW];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (cidx + e < p.Cout) sc[e] = p.scale[cidx + e];
-    }
+    for (int e = 0; e < EW; ++e) sc[e] = p.scale && cidx + e < p.Cout ? p.scale[cidx + e] : 0.f;
 
     uint32_t P[TM][TN][T::S];
     __syncthreads(); // tap_table and S are complete
@@ -361,15 +364,15 @@ bconv_tile_kernel(ConvTileParams p)
             for (int n = 0; n < TN; ++n)
                 V[(KEEPW ? (ty & 3) + 4 * i : ty + RG * i) * EPI_STRIDE + tx + 16 * n] =
                     recombine<T::S>(P[i][n], p.n_times_top);
-        // this lane's nibble of the 32-channel plane word its 4 channels belong to
-        const int wword = (col0 >> 5) + (tid % LPR) / 8;
-        const int nib_shift = 4 * (tid & 7);
+        // this lane's EW bits of the 32-channel plane word its channels belong to
+        const int wword = (col0 >> 5) + (tid % LPR) / LPW;
+        const int nib_shift = EW * (tid & (LPW - 1));
         // The shortcut operands of all passes are requested here, in one go, now that the partial sums
         // no longer occupy registers: one memory latency per tile, hidden behind the barrier, the
         // LDS reads and the other resident workgroup, instead of one per pass.
         constexpr int NPASS = BM / RPP;
         uint32_t rq_pre[BLK ? NPASS : 1][8];
-        float4 rf_pre[BLK ? NPASS : 1];
+        float4 rf_pre[BLK ? NPASS : 1][EQ];
         if constexpr (BLK) {
             const uint32_t *rq = static_cast<const uint32_t *>(p.blk.res_q);
 #pragma unroll
@@ -382,16 +385,19 @@ bconv_tile_kernel(ConvTileParams p)
                     if (rq && rvalid && wword < p.cwo && j < p.blk.res_bits)
                         rq_pre[ps][j] = rq[((int64_t)j * p.M + r) * p.cwo + wword];
                 }
-                rf_pre[ps] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (p.blk.res_f32 && rvalid) {
-                    const float *src = p.blk.res_f32 + ((int64_t)r * p.Cout + cidx);
-                    if (cols4) {
-                        rf_pre[ps] = *reinterpret_cast<const float4 *>(src);
-                    } else {
-                        if (cidx + 0 < p.Cout) rf_pre[ps].x = src[0];
-                        if (cidx + 1 < p.Cout) rf_pre[ps].y = src[1];
-                        if (cidx + 2 < p.Cout) rf_pre[ps].z = src[2];
-                        if (cidx + 3 < p.Cout) rf_pre[ps].w = src[3];
+#pragma unroll
+                for (int q = 0; q < EQ; ++q) {
+                    rf_pre[ps][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (p.blk.res_f32 && rvalid) {
+                        const float *src = p.blk.res_f32 + ((int64_t)r * p.Cout + cidx + 4 * q);
+                        if (cols4) {
+                            rf_pre[ps][q] = *reinterpret_cast<const float4 *>(src);
+                        } else {
+                            if (cidx + 4 * q + 0 < p.Cout) rf_pre[ps][q].x = src[0];
+                            if (cidx + 4 * q + 1 < p.Cout) rf_pre[ps][q].y = src[1];
+                            if (cidx + 4 * q + 2 < p.Cout) rf_pre[ps][q].z = src[2];
+                            if (cidx + 4 * q + 3 < p.Cout) rf_pre[ps][q].w = src[3];
+                        }
                     }
                 }
             }
@@ -399,12 +405,16 @@ bconv_tile_kernel(ConvTileParams p)
         tile_sync();
 
         // ---- second half: padding correction, stores, scale, quantize, plane split ----
-        auto do_pass = [&](const int pass, const uint32_t (&rqw)[8], const float4 rf) {
+        auto do_pass = [&](const int pass, const uint32_t (&rqw)[8], const float4 (&rf)[EQ]) {
             const int rl = pass_row(pass);
             const int r = row0 + rl;
             const bool rvalid = r < p.M;
-            const int4 vv = *reinterpret_cast<const int4 *>(V + (KEEPW ? (rl & 3) + 4 * (rl / RG) : rl) * EPI_STRIDE + c4);
-            int32_t v[4] = {vv.x, vv.y, vv.z, vv.w};
+            int32_t v[EW];
+#pragma unroll
+            for (int q = 0; q < EQ; ++q) {
+                const int4 vv = *reinterpret_cast<const int4 *>(V + (KEEPW ? (rl & 3) + 4 * (rl / RG) : rl) * EPI_STRIDE + c4 + 4 * q);
+                v[4 * q] = vv.x, v[4 * q + 1] = vv.y, v[4 * q + 2] = vv.z, v[4 * q + 3] = vv.w;
+            }
             // padded taps of this output pixel
             uint32_t padded = 0;
             int64_t ro = r, Mo = p.M; // pixel index in the output tensors, their pixel count
@@ -420,64 +430,87 @@ bconv_tile_kernel(ConvTileParams p)
                 }
             }
             if (padded) {
-                int32_t corr[4] = {0, 0, 0, 0};
+                int32_t corr[EW];
+#pragma unroll
+                for (int e = 0; e < EW; ++e) corr[e] = 0;
                 for (uint32_t m = padded; m; m &= m - 1) {
-                    const int4 s4 = *reinterpret_cast<const int4 *>(S + __builtin_ctz(m) * BN + c4);
-                    corr[0] += s4.x, corr[1] += s4.y, corr[2] += s4.z, corr[3] += s4.w;
+#pragma unroll
+                    for (int q = 0; q < EQ; ++q) {
+                        const int4 s4 = *reinterpret_cast<const int4 *>(S + __builtin_ctz(m) * BN + c4 + 4 * q);
+                        corr[4 * q] += s4.x, corr[4 * q + 1] += s4.y, corr[4 * q + 2] += s4.z, corr[4 * q + 3] += s4.w;
+                    }
                 }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] += p.top_a * corr[e];
+                for (int e = 0; e < EW; ++e) v[e] += p.top_a * corr[e];
             }
             if (p.partial_mode | p.shift) {
                 const int64_t off = ro * p.Cout + cidx;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
+                for (int e = 0; e < EW; ++e) {
                     v[e] = (int32_t)((uint32_t)v[e] << p.shift);
                     if ((p.partial_mode & 1) && rvalid && cidx + e < p.Cout) v[e] += p.partial[off + e];
                 }
                 if (p.partial_mode & 2) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
+                    for (int e = 0; e < EW; ++e)
                         if (rvalid && cidx + e < p.Cout) p.partial[off + e] = v[e];
                     return;
                 }
             }
-            float o[4];
+            float o[EW];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (float)v[e] * sc[e];
+            for (int e = 0; e < EW; ++e) o[e] = (float)v[e] * sc[e];
             // residual-block terms, in the documented order (one fp32 rounding each)
             if constexpr (BLK) {
                 if (p.blk.bias) {
-                    const float4 bi = *reinterpret_cast<const float4 *>(bias_lds + c4);
-                    o[0] = o[0] + bi.x, o[1] = o[1] + bi.y, o[2] = o[2] + bi.z, o[3] = o[3] + bi.w;
+#pragma unroll
+                    for (int q = 0; q < EQ; ++q) {
+                        const float4 bi = *reinterpret_cast<const float4 *>(bias_lds + c4 + 4 * q);
+                        o[4 * q] = o[4 * q] + bi.x, o[4 * q + 1] = o[4 * q + 1] + bi.y;
+                        o[4 * q + 2] = o[4 * q + 2] + bi.z, o[4 * q + 3] = o[4 * q + 3] + bi.w;
+                    }
                 }
                 if (p.blk.res_q) {
-                    uint32_t code[4] = {0u, 0u, 0u, 0u};
+                    uint32_t code[EW];
+#pragma unroll
+                    for (int e = 0; e < EW; ++e) code[e] = 0u;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         if (j < p.blk.res_bits) {
                             const uint32_t nib = rqw[j] >> nib_shift;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) code[e] |= ((nib >> e) & 1u) << j;
+                            for (int e = 0; e < EW; ++e) code[e] |= ((nib >> e) & 1u) << j;
                         }
                     }
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
+                    for (int e = 0; e < EW; ++e) {
                         const float term = (float)(2 * (int)code[e] - p.blk.res_top) * p.blk.res_scale;
                         o[e] = o[e] + term;
                     }
                 }
-                if (p.blk.res_f32) o[0] = o[0] + rf.x, o[1] = o[1] + rf.y, o[2] = o[2] + rf.z, o[3] = o[3] + rf.w;
-                if (p.blk.relu) o[0] = fmaxf(o[0], 0.0f), o[1] = fmaxf(o[1], 0.0f), o[2] = fmaxf(o[2], 0.0f), o[3] = fmaxf(o[3], 0.0f);
+                if (p.blk.res_f32) {
+#pragma unroll
+                    for (int q = 0; q < EQ; ++q) {
+                        o[4 * q] = o[4 * q] + rf[q].x, o[4 * q + 1] = o[4 * q + 1] + rf[q].y;
+                        o[4 * q + 2] = o[4 * q + 2] + rf[q].z, o[4 * q + 3] = o[4 * q + 3] + rf[q].w;
+                    }
+                }
+                if (p.blk.relu) {
+#pragma unroll
+                    for (int e = 0; e < EW; ++e) o[e] = fmaxf(o[e], 0.0f);
+                }
             }
             if (rvalid) {
                 const int64_t off = ro * p.Cout + cidx;
                 if (cols4) {
-                    if (p.acc) *reinterpret_cast<int4 *>(p.acc + off) = make_int4(v[0], v[1], v[2], v[3]);
-                    if (p.out) *reinterpret_cast<float4 *>(p.out + off) = make_float4(o[0], o[1], o[2], o[3]);
+#pragma unroll
+                    for (int q = 0; q < EQ; ++q) {
+                        if (p.acc) *reinterpret_cast<int4 *>(p.acc + off + 4 * q) = make_int4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+                        if (p.out) *reinterpret_cast<float4 *>(p.out + off + 4 * q) = make_float4(o[4 * q], o[4 * q + 1], o[4 * q + 2], o[4 * q + 3]);
+                    }
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
+                    for (int e = 0; e < EW; ++e)
                         if (cidx + e < p.Cout) {
                             if (p.acc) p.acc[off + e] = v[e];
                             if (p.out) p.out[off + e] = o[e];
@@ -485,20 +518,29 @@ bconv_tile_kernel(ConvTileParams p)
                 }
             }
             if (p.next) {
-                // four byte codes in one register; channels past Cout give 0 bits (pad bits are 0)
-                uint32_t cw4 = 0;
+                // byte codes, four to a register; channels past Cout give 0 bits (pad bits are 0)
+                uint32_t cw4[EQ];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t code = cidx + e < p.Cout
-                                              ? (uint32_t)quantize_code(o[e], p.next_inv_clip, p.next_half_top, p.next_top)
-                                              : 0u;
-                    cw4 |= code << (8 * e);
+                for (int q = 0; q < EQ; ++q) {
+                    cw4[q] = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t code = cols4 || cidx + 4 * q + e < p.Cout
+                                                  ? (uint32_t)quantize_code(o[4 * q + e], p.next_inv_clip, p.next_half_top, p.next_top)
+                                                  : 0u;
+                        cw4[q] |= code << (8 * e);
+                    }
                 }
                 for (int j = 0; j < p.next_bits; ++j) {
-                    // bit j of the four codes -> a nibble -> this lane's place in the 32-channel word
-                    const uint32_t x = (cw4 >> j) & 0x01010101u;
-                    const uint32_t word = or_reduce8((((x * 0x00204081u) >> 21) & 15u) << nib_shift);
-                    if ((tid & 7) == 0 && rvalid && wword < p.cwo)
+                    // bit j of the lane's codes -> EW bits -> this lane's place in the 32-channel word
+                    uint32_t piece = 0;
+#pragma unroll
+                    for (int q = 0; q < EQ; ++q) {
+                        const uint32_t x = (cw4[q] >> j) & 0x01010101u;
+                        piece |= (((x * 0x00204081u) >> 21) & 15u) << (4 * q);
+                    }
+                    const uint32_t word = or_reduce_lanes<LPW>(piece << nib_shift);
+                    if ((tid & (LPW - 1)) == 0 && rvalid && wword < p.cwo)
                         p.next[((int64_t)j * Mo + ro) * p.cwo + wword] = word;
                 }
             }
@@ -545,7 +587,7 @@ template <int WB, int AB> struct ConvPickStreamed {
     static constexpr int S = WB + AB;
     static constexpr int TM = 2;
     static constexpr int TN = S <= 4 ? 4 : S <= 6 ? 2 : 4;
-    static constexpr int KV = 4;
+    static constexpr int KV = S <= 4 ? 2 : 4;
     static constexpr int NT = 512;
 };
 

@@ -17,10 +17,10 @@ __device__ __forceinline__ int quantize_code(float x, float inv_clip, float half
     t = fminf(t, 1.0f);
     float r = __builtin_fmaf(t, half_top, half_top);
     r = r + 0.5f;
-    int u = (int)floorf(r);
-    u = max(u, 0);
-    u = min(u, top);
-    return u;
+    // t lies in [-1, 1], so fma(t, h, h) lies in [0, 2h] = [0, top] (both ends exact) and floor(r + 0.5) in
+    // [0, top]: no integer clamp is needed.  (A NaN converts to 0, also inside the range.)
+    (void)top;
+    return (int)floorf(r);
 }
 
 } // namespace qnn
