@@ -199,8 +199,9 @@ int qnn_conv2d_block(const qnn_conv_desc *desc, const uint32_t *a_planes, const 
  * qnn_deconv2d: desc->H, W, Cin describe the input, Cout / kh / kw / stride / pad the transposed
  *     convolution; a_planes DEVICE [a_bits][B][H][W][ceil(Cin/32)]; scale, acc, out, next_planes,
  *     next_clip, next_bits as in qnn_conv2d on the [B][Ho][Wo][Cout] output; bias DEVICE fp32 [Cout] or
- *     NULL, added after the scale as in qnn_conv2d_block.  QNN_ERR_UNSUPPORTED for bit widths above 4,
- *     kh or kw below stride (output pixels that no tap reaches) or above 16, stride above 8.
+ *     NULL, added after the scale as in qnn_conv2d_block.  Bit widths above 4 run as plane chunks like qnn_conv2d and
+ *     need acc or out for the running sum.  QNN_ERR_UNSUPPORTED for kh or kw below stride (output pixels that no
+ *     tap reaches) or above 16, stride above 8.
  */
 int64_t qnn_deconv_phase_words(int w_bits, int64_t Cout, int kh, int kw, int64_t Cin, int stride);
 int qnn_deconv_pack_weights(const uint32_t *w_planes, int w_bits, int64_t Cout, int kh, int kw, int64_t Cin,

@@ -121,7 +121,8 @@ extern "C" int qnn_deconv2d(const qnn_conv_desc *d, const uint32_t *a_planes, co
     if (!d) return fail(QNN_ERR_INVALID_ARG, "qnn_deconv2d: NULL descriptor");
     if (d->a_bits < 1 || d->a_bits > 8 || d->w_bits < 1 || d->w_bits > 8)
         return fail(QNN_ERR_INVALID_ARG, "qnn_deconv2d: bits must be in [1,8]");
-    if (d->a_bits > 4 || d->w_bits > 4) return fail(QNN_ERR_UNSUPPORTED, "qnn_deconv2d: more than 4 bits");
+    if ((d->a_bits > 4 || d->w_bits > 4) && !acc && !out)
+        return fail(QNN_ERR_UNSUPPORTED, "qnn_deconv2d: above 4 bits an acc or out buffer is needed for the running sum of the plane chunks");
     if (d->B < 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0)
         return fail(QNN_ERR_INVALID_ARG, "qnn_deconv2d: bad tensor size");
     if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0) return fail(QNN_ERR_INVALID_ARG, "qnn_deconv2d: bad kernel geometry");
@@ -160,7 +161,6 @@ extern "C" int qnn_deconv2d(const qnn_conv_desc *d, const uint32_t *a_planes, co
     t.cw = (int)cw, t.cwo = (int)cwo;
     t.stride = 1, t.pad = 0;
     t.a_plane_stride = (int)(d->B * d->H * d->W * cw);
-    t.top_a = (1 << d->a_bits) - 1;
     t.next_bits = next_planes ? next_bits : 0;
     t.next_top = next_planes ? (1 << next_bits) - 1 : 0;
     t.next_inv_clip = next_planes ? 1.0f / next_clip : 0.0f;
@@ -168,52 +168,76 @@ extern "C" int qnn_deconv2d(const qnn_conv_desc *d, const uint32_t *a_planes, co
     t.blk.bias = bias;
     t.scatter = 1, t.os = s, t.HO = (int)HO, t.WO = (int)WO, t.M_out = (int)(d->B * HO * WO);
     t.nphase = 1;
-    // Phases of one shape (kernel extents and output extents multiples of the stride: the usual
-    // upsampling layers) run as one launch, the resident workgroups divided among them.
-    if (s > 1 && d->kh % s == 0 && d->kw % s == 0 && HO % s == 0 && WO % s == 0) {
-        const PhaseAxis ay0 = phase_axis(0, d->kh, s, d->pad, HO), ax0 = phase_axis(0, d->kw, s, d->pad, WO);
-        const int64_t words = phase_words(d->w_bits, d->Cout, ay0.taps, ax0.taps, (int)cw);
-        if (words * s * s < (1LL << 31)) {
-            ConvTileParams q = t;
-            q.w = phase_planes;
-            q.nphase = s * s, q.phase_words = (int)words;
-            for (int f = 0; f < s; ++f) {
-                const PhaseAxis ay = phase_axis(f, d->kh, s, d->pad, HO), ax = phase_axis(f, d->kw, s, d->pad, WO);
-                q.ph_pad_y[f] = ay.pad, q.ph_first_y[f] = ay.first, q.ph_pad_x[f] = ax.pad, q.ph_first_x[f] = ax.first;
-            }
-            q.kh = ay0.taps, q.kw = ax0.taps;
-            q.nw = (int)(ay0.taps * ax0.taps * cw);
-            q.wvec = q.nw % 4 == 0 ? 1 : 0;
-            q.Ho = ay0.count, q.Wo = ax0.count, q.M = (int)(d->B * ay0.count * ax0.count);
-            q.n_times_top = (uint32_t)((int64_t)ay0.taps * ax0.taps * d->Cin * ((1 << d->w_bits) - 1) * q.top_a);
-            q.div_howo = make_fastdiv((uint32_t)(ay0.count * ax0.count));
-            q.div_wo = make_fastdiv((uint32_t)ax0.count);
-            const int rc = conv_dispatch<true>(d->w_bits, d->a_bits, q, st);
-            return rc != QNN_OK ? rc : check_launch("qnn_deconv2d");
-        }
-    }
-    int64_t w_off = 0;
-    for (int fy = 0; fy < s; ++fy)
-        for (int fx = 0; fx < s; ++fx) {
-            const PhaseAxis ay = phase_axis(fy, d->kh, s, d->pad, HO), ax = phase_axis(fx, d->kw, s, d->pad, WO);
-            const int64_t words = phase_words(d->w_bits, d->Cout, ay.taps, ax.taps, (int)cw);
-            if (ay.count > 0 && ax.count > 0) {
-                ConvTileParams q = t;
-                q.w = phase_planes + w_off;
-                q.kh = ay.taps, q.kw = ax.taps;
-                q.nw = (int)(ay.taps * ax.taps * cw);
+    // All phases for one chunk pair of planes (w_bits, a_bits <= 4: the only pair): wb x ab planes starting at
+    // weight plane w0 and activation plane a0, entering the running sum with weight 2^shift.
+    auto run_phases = [&](int wb, int ab, int w0, int a0, int shift, int partial_mode) -> int {
+        ConvTileParams base = t;
+        base.a = a_planes + (int64_t)a0 * t.a_plane_stride;
+        base.top_a = (1 << ab) - 1;
+        base.shift = shift, base.partial_mode = partial_mode;
+        base.partial = acc ? acc : reinterpret_cast<int32_t *>(out);
+        const int64_t top = (int64_t)((1 << wb) - 1) * base.top_a;
+        // Phases of one shape (kernel extents and output extents multiples of the stride: the usual
+        // upsampling layers) run as one launch, the resident workgroups divided among them.
+        if (s > 1 && d->kh % s == 0 && d->kw % s == 0 && HO % s == 0 && WO % s == 0) {
+            const PhaseAxis ay0 = phase_axis(0, d->kh, s, d->pad, HO), ax0 = phase_axis(0, d->kw, s, d->pad, WO);
+            const int64_t words = phase_words(d->w_bits, d->Cout, ay0.taps, ax0.taps, (int)cw);
+            if (words * s * s < (1LL << 31)) {
+                ConvTileParams q = base;
+                q.nphase = s * s, q.phase_words = (int)words;
+                for (int f = 0; f < s; ++f) {
+                    const PhaseAxis ay = phase_axis(f, d->kh, s, d->pad, HO), ax = phase_axis(f, d->kw, s, d->pad, WO);
+                    q.ph_pad_y[f] = ay.pad, q.ph_first_y[f] = ay.first, q.ph_pad_x[f] = ax.pad, q.ph_first_x[f] = ax.first;
+                }
+                q.kh = ay0.taps, q.kw = ax0.taps;
+                q.nw = (int)(ay0.taps * ax0.taps * cw);
+                q.w = phase_planes + (int64_t)w0 * d->Cout * q.nw; // plane w0 of every phase (phases are phase_words apart)
                 q.wvec = q.nw % 4 == 0 ? 1 : 0;
-                q.Ho = ay.count, q.Wo = ax.count, q.M = (int)(d->B * ay.count * ax.count);
-                q.pad_y = ay.pad, q.pad_x = ax.pad, q.oy0 = ay.first, q.ox0 = ax.first;
-                q.n_times_top = (uint32_t)((int64_t)ay.taps * ax.taps * d->Cin * ((1 << d->w_bits) - 1) * q.top_a);
-                q.div_howo = make_fastdiv((uint32_t)(ay.count * ax.count));
-                q.div_wo = make_fastdiv((uint32_t)ax.count);
-                int rc = conv_dispatch<true>(d->w_bits, d->a_bits, q, st);
-                if (rc != QNN_OK) return rc;
-                rc = check_launch("qnn_deconv2d");
-                if (rc != QNN_OK) return rc;
+                q.Ho = ay0.count, q.Wo = ax0.count, q.M = (int)(d->B * ay0.count * ax0.count);
+                q.n_times_top = (uint32_t)((int64_t)ay0.taps * ax0.taps * d->Cin * top);
+                q.div_howo = make_fastdiv((uint32_t)(ay0.count * ax0.count));
+                q.div_wo = make_fastdiv((uint32_t)ax0.count);
+                const int rc = conv_dispatch<true>(wb, ab, q, st);
+                return rc != QNN_OK ? rc : check_launch("qnn_deconv2d");
             }
-            w_off += words;
+        }
+        int64_t w_off = 0;
+        for (int fy = 0; fy < s; ++fy)
+            for (int fx = 0; fx < s; ++fx) {
+                const PhaseAxis ay = phase_axis(fy, d->kh, s, d->pad, HO), ax = phase_axis(fx, d->kw, s, d->pad, WO);
+                const int64_t words = phase_words(d->w_bits, d->Cout, ay.taps, ax.taps, (int)cw);
+                if (ay.count > 0 && ax.count > 0) {
+                    ConvTileParams q = base;
+                    q.kh = ay.taps, q.kw = ax.taps;
+                    q.nw = (int)(ay.taps * ax.taps * cw);
+                    q.w = phase_planes + w_off + (int64_t)w0 * d->Cout * q.nw;
+                    q.wvec = q.nw % 4 == 0 ? 1 : 0;
+                    q.Ho = ay.count, q.Wo = ax.count, q.M = (int)(d->B * ay.count * ax.count);
+                    q.pad_y = ay.pad, q.pad_x = ax.pad, q.oy0 = ay.first, q.ox0 = ax.first;
+                    q.n_times_top = (uint32_t)((int64_t)ay.taps * ax.taps * d->Cin * top);
+                    q.div_howo = make_fastdiv((uint32_t)(ay.count * ax.count));
+                    q.div_wo = make_fastdiv((uint32_t)ax.count);
+                    int rc = conv_dispatch<true>(wb, ab, q, st);
+                    if (rc != QNN_OK) return rc;
+                    rc = check_launch("qnn_deconv2d");
+                    if (rc != QNN_OK) return rc;
+                }
+                w_off += words;
+            }
+        return QNN_OK;
+    };
+    // Bit widths above 4: chunk pairs of at most 4 x 4 planes as in qnn_conv2d; every output pixel belongs to
+    // exactly one phase, so the running sum (in acc, or in the memory of out) is read and written by the same
+    // phase of consecutive chunk pairs; only the last pair writes the outputs and the next layer's planes.
+    const int w_chunks = (d->w_bits + 3) / 4, a_chunks = (d->a_bits + 3) / 4;
+    int launch = 0;
+    for (int cwi = 0; cwi < w_chunks; ++cwi)
+        for (int cai = 0; cai < a_chunks; ++cai, ++launch) {
+            const int wb = d->w_bits - 4 * cwi < 4 ? d->w_bits - 4 * cwi : 4;
+            const int ab = d->a_bits - 4 * cai < 4 ? d->a_bits - 4 * cai : 4;
+            const int mode = (launch > 0 ? 1 : 0) | (launch + 1 < w_chunks * a_chunks ? 2 : 0);
+            const int rc = run_phases(wb, ab, 4 * cwi, 4 * cai, 4 * (cwi + cai), mode);
+            if (rc != QNN_OK) return rc;
         }
     return QNN_OK;
 }

@@ -168,7 +168,8 @@ def test_deconv_argument_errors_and_phase_words(qnn):
     ok = D(1, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)
     assert call(None) == qnn.QNN_ERR_INVALID_ARG
     assert call(D(1, 8, 8, 64, 32, 4, 4, 2, 1, 0, 2)) == qnn.QNN_ERR_INVALID_ARG
-    assert call(D(1, 8, 8, 64, 32, 4, 4, 2, 1, 5, 2)) == qnn.QNN_ERR_UNSUPPORTED       # more than 4 bits
+    # above 4 bits the plane chunks need acc or out for their running sum
+    assert call(D(1, 8, 8, 64, 32, 4, 4, 2, 1, 5, 2), scale=FAKE, acc=None, nxt=FAKE, clip=1.0, nbits=2) == qnn.QNN_ERR_UNSUPPORTED
     assert call(D(1, 8, 8, 64, 32, 1, 1, 2, 0, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED       # kernel below stride
     assert call(D(1, 1, 1, 64, 32, 2, 2, 2, 1, 2, 2)) == qnn.QNN_ERR_INVALID_ARG       # pad eats the whole output
     assert call(ok, acc=None) == qnn.QNN_ERR_INVALID_ARG

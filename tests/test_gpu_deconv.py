@@ -56,6 +56,50 @@ def test_deconv_acc_out_and_next_planes(geom, bits):
     assert np.array_equal(planes_to_numpy(nxt), oracle.pack_planes(lv.reshape(-1, Cout), 3))
 
 
+def _wide(gen, shape, bits):
+    top = (1 << bits) - 1
+    return (2 * gen.integers(0, top + 1, size=shape) - top).astype(np.int16)
+
+
+@pytest.mark.parametrize("bits", [(5, 5), (8, 8), (6, 2), (3, 7), (4, 5)])
+@pytest.mark.parametrize("geom", [GEOMS[0], GEOMS[1], GEOMS[5], GEOMS[7], GEOMS[4]])
+def test_deconv_wide_bits(geom, bits):
+    # widths above 4 run as chunk pairs of at most 4 x 4 planes over all phases, the running sum kept per output
+    # pixel by the phase that owns it (one-launch phases and per-phase launches, masked border taps included)
+    B, H, W, Cin, Cout, k, stride, pad = geom
+    w_bits, a_bits = bits
+    gen = np.random.default_rng(sum(geom) * 7 + 10 * w_bits + a_bits)
+    a, w = _wide(gen, (B, H, W, Cin), a_bits), _wide(gen, (Cout, k, k, Cin), w_bits)
+    var = (4.0 ** w_bits - 1) / 3 * (4.0 ** a_bits - 1) / 3
+    taps = (-(-k // stride)) ** 2
+    s = (gen.uniform(0.5, 1.5, size=Cout) / np.sqrt(taps * Cin * var)).astype(np.float32)
+    bias = gen.uniform(-0.5, 0.5, size=Cout).astype(np.float32)
+    ap = dev(oracle.pack_planes(a.reshape(-1, Cin), a_bits).view(np.int32))
+    wp = dev(oracle.pack_planes(w.reshape(-1, Cin), w_bits).view(np.int32)).view(w_bits, Cout, k, k, -1)
+    ph = qnn.qnn_deconv_pack_weights(wp, Cin, stride)
+    acc, out, nxt = qnn.qnn_deconv2d(ap, ph, (B, H, W), Cin, Cout, k, k, stride, pad, w_bits, scale=dev(s), bias=dev(bias),
+                                     want_out=True, next_clip=2.5, next_bits=5)
+    _, out_only, nxt2 = qnn.qnn_deconv2d(ap, ph, (B, H, W), Cin, Cout, k, k, stride, pad, w_bits, scale=dev(s), bias=dev(bias),
+                                         want_acc=False, want_out=True, next_clip=2.5, next_bits=5)
+    torch.cuda.synchronize()
+    want_acc = oracle.deconv2d(a, w, stride, pad)
+    assert np.array_equal(acc.cpu().numpy(), want_acc)
+    want = oracle.block_epilogue(want_acc, s, bias)
+    np.testing.assert_allclose(out.cpu().numpy(), want, rtol=RTOL, atol=0)
+    lv, _ = oracle.quantize(want, 2.5, 5)
+    assert np.array_equal(planes_to_numpy(nxt), oracle.pack_planes(lv.reshape(-1, Cout), 5))
+    assert torch.equal(out, out_only) and torch.equal(nxt, nxt2)   # the running sum kept in the memory of out
+
+
+def test_deconv_wide_bits_need_a_buffer_for_the_running_sum():
+    ap = torch.zeros((5, 16, 1), dtype=torch.int32, device="cuda")
+    ph = torch.zeros((5 * 8 * 16 * 1,), dtype=torch.int32, device="cuda")
+    with pytest.raises(qnn.QnnError) as e:
+        qnn.qnn_deconv2d(ap, ph, (1, 4, 4), 32, 8, 4, 4, 2, 1, 5, scale=torch.ones(8, device="cuda"), want_acc=False,
+                         next_clip=1.0, next_bits=2)
+    assert e.value.code == qnn.QNN_ERR_UNSUPPORTED
+
+
 def test_deconv_acc_only_without_scale():
     gen = np.random.default_rng(4)
     a, w = levels(gen, (2, 6, 6, 64), 2), levels(gen, (32, 4, 4, 64), 2)
