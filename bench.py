@@ -36,7 +36,7 @@ PEAK_NOTE = ("v_xor_b32 at 32 lanes/clk/SIMD (2 cycles per wave64) + v_bcnt_u32_
 
 # HBM bytes of one default-workload GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/bgemm_2x2_4096_hbm_counters.txt); only valid for size 4096, 2x2 bit
-GEMM_2X2_4096_TRAFFIC_BYTES = 182.7e6
+GEMM_2X2_4096_TRAFFIC_BYTES = 205.9e6
 
 # HIP event pairs are put around every EVENT_EVERY-th GEMM launch of a timed region
 EVENT_EVERY = 5
@@ -121,7 +121,7 @@ def parse():
     ap.add_argument("--repeats", type=int, default=5, help="default workload: repetitions of the K timed steps (the median is reported)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "ssd", "trunk", "pool", "grad", "deconv"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "ssd", "trunk", "pool", "grad", "deconv", "probe"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -279,7 +279,7 @@ def conv_workload(args):
     # single short kernel between two events also shows the device's latency from one dependent kernel to the
     # next (about 10 us here), which is not the kernel's own time.
     reps, back_to_back = 3, 4
-    per_launch = [0.0] * len(calls)
+    samples = [[] for _ in calls]
     for _ in range(reps):
         evs = []
         for _, _, launch in calls:
@@ -291,7 +291,8 @@ def conv_workload(args):
             evs.append((e0, e1))
         torch.cuda.synchronize()
         for i, (e0, e1) in enumerate(evs):
-            per_launch[i] += e0.elapsed_time(e1) / (reps * back_to_back)
+            samples[i].append(e0.elapsed_time(e1) / back_to_back)
+    per_launch = [sorted(v)[reps // 2] for v in samples]      # the median: one disturbed pass does not count
     conv_ms = sum(t for (label, ops, _), t in zip(calls, per_launch) if ops > 0)
     conv_tops = binops / (conv_ms * 1e-3) / 1e12
     layer_fracs = [(label, ops / (t * 1e-3) / 1e12 / PEAK_BINARY_TOPS, t) for (label, ops, _), t in zip(calls, per_launch) if ops > 0]
@@ -380,7 +381,7 @@ def conv_workload(args):
                      "achieved": round(conv_tops, 2), "peak": round(PEAK_BINARY_TOPS, 1),
                      "unit": "binary TOP/s", "frac": round(conv_tops / PEAK_BINARY_TOPS, 4), "traffic": None,
                      "kernel_ms": round(conv_ms, 4),
-                     "kernel_ms_note": "sum over the step's convolution launches, each timed between its own HIP events as the average of 4 back-to-back launches",
+                     "kernel_ms_note": "sum over the step's convolution launches, each timed between its own HIP events as the average of 4 back-to-back launches (median of 3 passes)",
                      "step_frac": round(tops / PEAK_BINARY_TOPS, 4),
                      "slowest_layer": {"layer": worst[0], "frac": round(worst[1], 4), "ms": round(worst[2], 4)},
                      "fastest_layer": {"layer": best[0], "frac": round(best[1], 4), "ms": round(best[2], 4)},
@@ -662,6 +663,45 @@ def graph_workload(args):
                                       "frac": round(int8_tops / 5000.0, 4), "note": "whole step, not a single kernel"}}}
 
 
+def probe_workload(args):
+    """The register-only issue-rate loops of libqnn_probe over 1, 2, 3, 4 and 8 waves per SIMD: per order the cost of a
+    wave64 instruction in real cycles (kernel time x the clock read inside the kernel / instructions per SIMD) and what
+    a single wave sees (cycles between its own instructions).  The evidence behind the VALU roofline's notes."""
+    import torch
+    from paper_1905_13389_amd import probe
+    names = {0: "v_xor_b32", 1: "v_bcnt_u32_b32", 2: "pair, s_nop after each", 3: "pair back to back", 4: "two deep, rotating temporaries",
+             5: "4 xors then 4 counts", 6: "two deep + s_nop", 7: "count + s_nop", 8: "2 xors + s_nop", 9: "xor xor count count s_nop",
+             10: "two pairs + s_nop", 11: "xor s_nop count", 12: "count xor s_nop"}
+    iters = 10000
+    table = {}
+    for wps in (1, 2, 3, 4, 8):
+        wgs = 256 * wps
+        buf = torch.empty(wgs * 256, dtype=torch.int32, device="cuda")
+        clk = torch.zeros((wgs * 4, 2), dtype=torch.int64, device="cuda")
+        row = {}
+        for mode, label in names.items():
+            probe.qnn_probe_valu(mode, wgs, iters // 10, buf)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            probe.qnn_probe_valu(mode, wgs, iters, buf, clk)
+            e1.record()
+            torch.cuda.synchronize()
+            c = clk.double()
+            ghz = (c[:, 0].sum() / c[:, 1].sum()).item() * 0.1
+            own = c[:, 0] / (64.0 * iters)
+            row[label] = {"cycles_per_instruction_per_simd": round(e0.elapsed_time(e1) * 1e-3 * ghz * 1e9 / (64.0 * iters * wps), 3),
+                          "clock_ghz": round(ghz, 3), "kernel_ms": round(e0.elapsed_time(e1), 3),
+                          "wave_cycles_between_own_instructions": {"min": round(own.min().item(), 2), "mean": round(own.mean().item(), 2),
+                                                                   "max": round(own.max().item(), 2)}}
+        table["%d waves per SIMD" % wps] = row
+    best = min(v["pair, s_nop after each"]["cycles_per_instruction_per_simd"] for v in table.values())
+    return {"metric": "VALU issue cost of the binary dot product's instructions", "value": round(2 * best, 3),
+            "unit": "cycles per xor + count pair per SIMD (best occupancy)", "n_gpus": 1, "steps": 1, "warmup": 1,
+            "ms_per_step": None, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+            "config": {"workload": "register-only loops of 64 VALU instructions x %d iterations per wave, 256 CUs" % iters},
+            "probe_matrix": table}
+
+
 def fc_workload(args):
     """Config 1: one FC layer, 2 x 2 bit, A [64][512] x W [256][512]: 6.7e7 binary operations, far too
     little to load the chip -- the figure of interest is the latency of the two launches."""
@@ -884,7 +924,7 @@ def main():
               "exchange; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
     runners = {"trunk": trunk_workload, "pool": pool_workload, "grad": grad_workload, "deconv": deconv_workload,
-               "fc1": fc_workload, "gemm": gemm_workload, "ssd": graph_workload}
+               "fc1": fc_workload, "gemm": gemm_workload, "ssd": graph_workload, "probe": probe_workload}
     result = runners.get(args.workload, conv_workload)(args)
     if args.workload == "gemm" and not args.no_configs:
         result["configs"] = config_summaries(args)
