@@ -4,6 +4,8 @@
 // convolution's kernels carry none of their registers or kernel arguments.
 #pragma once
 
+#include <atomic>
+
 #include "bdot_tile.h"
 #include "qnn_host.h"
 #include "quantize.h"
@@ -35,6 +37,10 @@ struct ConvTileParams {
     FastDiv div_howo, div_wo;
     int tiles_m, tiles_n, row_tile_step; // persistent schedule: see bconv_tile_kernel
     int kb, nchunks;                     // reduction words per LDS stage (multiple of 4), stages per tile
+    // pair_hint != 0: the launch puts exactly two workgroups on every CU and they balance their progress through
+    // pair_progress (see there); pair_tag tells this launch's progress words from those of earlier launches
+    int pair_hint;
+    uint32_t pair_tag;
     // Bit widths above 4 run as up to four launches over chunks of at most 4 planes per operand (the
     // double sum of Eq. 9 splits into chunk pairs); `shift` is the weight 2^shift of this pair,
     // `partial` the running int32 sum: read when bit 0 of partial_mode is set, written instead of the
@@ -118,6 +124,24 @@ template <int LANES> __device__ __forceinline__ uint32_t or_reduce_lanes(uint32_
 // NT: lanes per workgroup.  Two workgroups share a CU either way (LDS), so 256 lanes run two waves per SIMD with
 // up to 256 registers per lane and 512 lanes four waves with up to 128: the same 16 RG x 16 TN tile, each lane
 // holding half as many rows, and twice as many waves to issue from while others wait.
+// Progress words of the resident workgroups, one per workgroup: (pair_tag << 32) | reduction stages done.
+// Two persistent workgroups share a CU, and a SIMD issues from its older waves first: left alone, the workgroup
+// that was dispatched first gets about four issue slots out of five, finishes its row tiles long before the
+// other, and the other then runs the rest of the kernel (40 % of it) with half the waves per SIMD.  Workgroups
+// b and b + gridDim.x / 2 are such a pair (the dispatcher fills every CU once before it starts the second
+// round).  So each workgroup publishes its stage count here after every stage, reads its partner's, and raises
+// its own wave priority (s_setprio) while it is behind: both advance at the same average rate, keep four waves
+// on every SIMD until the end, and the kernel ends when both do.  The words are a hint and nothing else: no
+// result depends on them, a stale or foreign word (another launch's tag) only means default priorities, and a
+// pairing other than the assumed one costs the balance, not correctness.  One copy per translation unit.
+constexpr int kPairSlots = 1024;
+static __device__ unsigned long long pair_progress[kPairSlots];
+static inline uint32_t next_pair_tag()
+{
+    static std::atomic<uint32_t> launches{0};
+    return ++launches;
+}
+
 template <int WB, int AB, int TM, int TN, int KV, int VW, bool KEEPW, bool BLK, int NT>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT / 128, NT / 128))) void
 bconv_tile_kernel(ConvTileParams p)
@@ -311,6 +335,15 @@ bconv_tile_kernel(ConvTileParams p)
 #pragma unroll
     for (int e = 0; e < EW; ++e) sc[e] = p.scale && cidx + e < p.Cout ? p.scale[cidx + e] : 0.f;
 
+    const unsigned pair_half = gridDim.x >> 1;
+    const unsigned pair_other = blockIdx.x < pair_half ? blockIdx.x + pair_half : blockIdx.x - pair_half;
+    const bool second_of_pair = blockIdx.x >= pair_half;
+    unsigned pair_steps = 0;          // reduction stages this workgroup has done
+    unsigned long long pair_seen = 0; // the partner's word as of one stage ago
+    if (p.pair_hint && tid == 0)
+        __hip_atomic_store(&pair_progress[blockIdx.x], (unsigned long long)p.pair_tag << 32, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+
     uint32_t P[TM][TN][T::S];
     __syncthreads(); // tap_table and S are complete
     int buf = 0;
@@ -353,6 +386,21 @@ bconv_tile_kernel(ConvTileParams p)
             if (more || next_tile) stash(buf ^ 1);
             tile_sync();
             buf ^= 1;
+            if (p.pair_hint) {
+                // behind the partner (as of its word read one stage ago): issue first; level or ahead: default.
+                // A tie goes to the second workgroup of the pair, the first has its age.
+                ++pair_steps;
+                const unsigned seen_tag = (unsigned)__builtin_amdgcn_readfirstlane((int)(pair_seen >> 32));
+                const unsigned seen_steps = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pair_seen);
+                if (seen_tag == p.pair_tag && (pair_steps < seen_steps || (pair_steps == seen_steps && second_of_pair)))
+                    __builtin_amdgcn_s_setprio(1);
+                else
+                    __builtin_amdgcn_s_setprio(0);
+                if (tid == 0)
+                    __hip_atomic_store(&pair_progress[blockIdx.x], ((unsigned long long)p.pair_tag << 32) | pair_steps,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pair_seen = __hip_atomic_load(&pair_progress[pair_other], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         // stage `buf` now holds the next tile's first stage (if any); stage buf^1 is free
 
@@ -558,13 +606,14 @@ bconv_tile_kernel(ConvTileParams p)
 
 // Workgroups resident on the whole chip for one kernel (occupancy x CU count); two host-side queries
 // per launch, negligible against the launch itself.
-template <typename K> static int resident_workgroups(K kernel, int threads, size_t dyn_smem)
+template <typename K> static int resident_workgroups(K kernel, int threads, size_t dyn_smem, int *cu_count = nullptr)
 {
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dyn_smem) != hipSuccess)
         return 0;
+    if (cu_count) *cu_count = cus;
     return cus * per_cu;
 }
 
@@ -614,7 +663,8 @@ static int launch_conv_vw(ConvTileParams p, hipStream_t st)
     p.nchunks = (int)ceil_div(p.nw, best_kb);
     if (ONE_STAGE != (p.nchunks == 1)) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: stage plan does not match the kernel");
     auto kernel = bconv_tile_kernel<WB, AB, G::TM, TN, G::KV, VW, ONE_STAGE, BLK, NT>;
-    int slots = resident_workgroups(kernel, NT, dyn);
+    int cus = 0;
+    int slots = resident_workgroups(kernel, NT, dyn, &cus);
     if (slots <= 0) return fail(QNN_ERR_LAUNCH, "qnn_conv2d: occupancy query failed");
     // every workgroup owns one column tile; the row tiles are dealt round-robin to the
     // slots / tiles_n workgroups of that column
@@ -624,7 +674,10 @@ static int launch_conv_vw(ConvTileParams p, hipStream_t st)
     if (groups > p.tiles_m) groups = p.tiles_m;
     p.row_tile_step = groups;
     p.wgs_per_phase = groups * p.tiles_n;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(groups * p.tiles_n * phases)), dim3(NT), dyn, st, p);
+    const int grid = groups * p.tiles_n * phases;
+    p.pair_hint = grid == 2 * cus && grid <= kPairSlots;
+    p.pair_tag = next_pair_tag();
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NT), dyn, st, p);
     return (int)QNN_OK;
 }
 
