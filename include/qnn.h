@@ -311,6 +311,34 @@ int qnn_level_conv2d_i8(const qnn_conv_desc *desc, const int8_t *a_levels, const
                         float next_clip, int next_bits, void *stream);
 
 /*
+ * Transposed convolution on decoded levels (matrix-core route of qnn_deconv2d; section "Model Decomposition":
+ * deconvolution layers reduce to the same products).  With stride s and padding p it equals the stride-1
+ * convolution, padding k - 1 - p, of the input with s - 1 zeros inserted between neighbouring pixels and the
+ * kernel flipped in both axes; a zero byte is level 0 (int8) or a pair of +0 (fp4) and contributes exactly 0,
+ * like the convolution's own padding, so the level convolution runs on the widened tensor as it is.
+ *   qnn_level_deconv_workspace_bytes(desc, fp4): bytes of the widened tensor, B ((H-1) s + 1) ((W-1) s + 1) Cin
+ *     (Cin / 2 for fp4); -1 on bad geometry.
+ *   qnn_level_deconv_flip_weights: w_levels DEVICE [Cout][kh][kw][tap_bytes] -> flipped DEVICE, same shape, tap
+ *     (ky, kx) taken from (kh-1-ky, kw-1-kx); tap_bytes = Cin (int8) or Cin / 2 (fp4), a multiple of 16.  Once per layer.
+ *   qnn_level_deconv2d_i8 / _fp4: desc as for qnn_deconv2d (H, W, Cin of the input; Cout, kh, kw, stride, pad of the
+ *     transposed convolution); a_levels DEVICE [B][H][W][Cin (/2)]; flipped_w from qnn_level_deconv_flip_weights;
+ *     workspace DEVICE, qnn_level_deconv_workspace_bytes bytes, 16-byte aligned, owned by the caller and
+ *     overwritten by every call; scale, acc, out, next_levels, next_clip, next_bits as in qnn_level_conv2d_i8 / _fp4
+ *     on the [B][Ho][Wo][Cout] output, Ho = (H-1) s - 2 p + kh; bias DEVICE fp32 [Cout] or NULL, added after the scale.
+ *   QNN_ERR_UNSUPPORTED unless kh == kw and pad <= kh - 1; other limits and errors as qnn_level_conv2d_i8 / _fp4
+ *   (the reduction-length checks count all kh kw taps).  Every check precedes the first launch.
+ */
+int64_t qnn_level_deconv_workspace_bytes(const qnn_conv_desc *desc, int fp4);
+int qnn_level_deconv_flip_weights(const void *w_levels, int64_t Cout, int kh, int kw, int64_t tap_bytes, void *flipped,
+                                  void *stream);
+int qnn_level_deconv2d_i8(const qnn_conv_desc *desc, const int8_t *a_levels, const int8_t *flipped_w, void *workspace,
+                          const float *scale, const float *bias, int32_t *acc, float *out, int8_t *next_levels,
+                          float next_clip, int next_bits, void *stream);
+int qnn_level_deconv2d_fp4(const qnn_conv_desc *desc, const uint8_t *a_levels, const uint8_t *flipped_w, void *workspace,
+                           const float *scale, const float *bias, int32_t *acc, float *out, uint8_t *next_levels,
+                           float next_clip, int next_bits, void *stream);
+
+/*
  * qnn_level_conv2d_block_i8 -- qnn_level_conv2d_i8 with the residual-block terms of qnn_conv2d_block
  * (same steps, same order); here epi->res_q is DEVICE int8 levels [B][Ho][Wo][Cout] and res_bits only
  * bounds them (1..7).

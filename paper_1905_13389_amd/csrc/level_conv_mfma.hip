@@ -540,9 +540,11 @@ extern "C" int qnn_encode_levels_fp4(const void *src, int dtype, int64_t count, 
 
 // fp4: the operands and next_levels hold two levels per byte (1- and 2-bit codes); the kernel then sees
 // Cin / 2 bytes per pixel
+// check_only: every argument check, nothing enqueued (for entry points that enqueue work of their own before the
+// convolution and must refuse a bad call as a whole).
 static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
                           const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
-                          int8_t *next_levels, float next_clip, int next_bits, void *stream)
+                          int8_t *next_levels, float next_clip, int next_bits, void *stream, bool check_only = false)
 {
     const int max_bits = fp4 ? 2 : 7;
     if (!d) return fail(QNN_ERR_INVALID_ARG, "%s: NULL descriptor", who);
@@ -597,6 +599,7 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
     if (!a_levels || !w_levels) return fail(QNN_ERR_INVALID_ARG, "%s: NULL level pointer", who);
     if (!aligned16(a_levels) || !aligned16(w_levels) || !aligned16(acc) || !aligned16(out) || !aligned16(next_levels))
         return fail(QNN_ERR_ALIGNMENT, "%s: pointers must be 16-byte aligned", who);
+    if (check_only) return QNN_OK;
 
     LevelConvParams p;
     p.a = a_levels, p.w = w_levels, p.scale = scale, p.acc = acc, p.out = out, p.next = next_levels;
@@ -683,4 +686,143 @@ extern "C" int qnn_levels_to_fp4(const int8_t *levels, int64_t count, uint8_t *f
     hipLaunchKernelGGL(levels_to_fp4_kernel, dim3((unsigned)(blocks < 256 * 64 ? blocks : 256 * 64)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), levels, count, fp4);
     return check_launch("qnn_levels_to_fp4");
+}
+
+// ---- transposed convolution on decoded levels ----
+// A transposed convolution with stride s and padding p is the stride-1 convolution of the input with s - 1 zeros
+// inserted between neighbouring pixels, the kernel flipped in both axes, and padding k - 1 - p.  A zero byte is
+// level 0 (int8) or two +0 values (fp4): it contributes exactly 0 to every sum, like the padding of the
+// convolution itself, so the level convolution runs unchanged on the widened tensor.
+
+namespace qnn {
+
+struct ZeroInsertParams {
+    const uint4 *a; // [B][H][W][units]
+    uint4 *up;      // [B][Hu][Wu][units]
+    uint32_t units, Wu, HuWu, W, HW, stride, total;
+};
+
+__global__ __launch_bounds__(256) void zero_insert_kernel(ZeroInsertParams p)
+{
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < p.total; i += gridDim.x * 256u) {
+        const uint32_t pix = i / p.units, u = i - pix * p.units;
+        const uint32_t b = pix / p.HuWu, r = pix - b * p.HuWu;
+        const uint32_t y = r / p.Wu, x = r - y * p.Wu;
+        const uint32_t sy = y / p.stride, sx = x / p.stride;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (sy * p.stride == y && sx * p.stride == x) v = p.a[((size_t)b * p.HW + sy * p.W + sx) * p.units + u];
+        p.up[i] = v;
+    }
+}
+
+// flipped[co][ky][kx][:] = w[co][kh - 1 - ky][kw - 1 - kx][:], 16-byte units
+__global__ __launch_bounds__(256) void flip_taps_kernel(const uint4 *w, uint4 *flipped, uint32_t units, uint32_t taps, uint32_t total)
+{
+    for (uint32_t i = blockIdx.x * 256u + threadIdx.x; i < total; i += gridDim.x * 256u) {
+        const uint32_t ct = i / units, u = i - ct * units;
+        const uint32_t co = ct / taps, t = ct - co * taps;
+        flipped[i] = w[((size_t)co * taps + (taps - 1 - t)) * units + u];
+    }
+}
+
+static int level_deconv_geometry(const char *who, bool fp4, const qnn_conv_desc *d, qnn_conv_desc &wide, int64_t &units)
+{
+    if (!d) return fail(QNN_ERR_INVALID_ARG, "%s: NULL descriptor", who);
+    if (d->B < 0 || d->H <= 0 || d->W <= 0 || d->Cin <= 0 || d->Cout <= 0)
+        return fail(QNN_ERR_INVALID_ARG, "%s: bad tensor size", who);
+    if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
+        return fail(QNN_ERR_INVALID_ARG, "%s: bad kernel geometry", who);
+    if (d->H > (1 << 20) || d->W > (1 << 20) || d->stride > (1 << 10))
+        return fail(QNN_ERR_RANGE, "%s: tensor too large for 32-bit indexing", who);
+    if ((d->H - 1) * d->stride - 2 * (int64_t)d->pad + d->kh < 1 || (d->W - 1) * d->stride - 2 * (int64_t)d->pad + d->kw < 1)
+        return fail(QNN_ERR_INVALID_ARG, "%s: empty output", who);
+    if (d->kh != d->kw || d->pad > d->kh - 1)
+        return fail(QNN_ERR_UNSUPPORTED, "%s: the level route needs a square kernel and pad <= k - 1", who);
+    if (d->Cin % (fp4 ? 32 : 16) != 0)
+        return fail(QNN_ERR_UNSUPPORTED, "%s: Cin=%lld is not a multiple of %d", who, (long long)d->Cin, fp4 ? 32 : 16);
+    wide = *d;
+    wide.H = (d->H - 1) * d->stride + 1, wide.W = (d->W - 1) * d->stride + 1;
+    wide.stride = 1, wide.pad = d->kh - 1 - d->pad;
+    units = (fp4 ? d->Cin / 2 : d->Cin) / 16;
+    if (wide.H > (1 << 20) || wide.W > (1 << 20) || (d->B > 0 && d->B > ((1LL << 31) - 1) / (wide.H * wide.W * units)))
+        return fail(QNN_ERR_RANGE, "%s: tensor too large for 32-bit indexing", who);
+    return QNN_OK;
+}
+
+static int level_deconv_run(const char *who, bool fp4, const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *flipped_w,
+                            void *workspace, const float *scale, const float *bias, int32_t *acc, float *out,
+                            int8_t *next_levels, float next_clip, int next_bits, void *stream)
+{
+    qnn_conv_desc wide;
+    int64_t units = 0;
+    int rc = level_deconv_geometry(who, fp4, d, wide, units);
+    if (rc != QNN_OK) return rc;
+    qnn_block_epilogue epi = {};
+    epi.bias = bias;
+    const qnn_block_epilogue *e = bias ? &epi : nullptr;
+    int8_t *up = static_cast<int8_t *>(workspace);
+    // the convolution's own checks, on the widened tensor, before anything is enqueued
+    rc = level_conv_run(who, fp4, &wide, d->B > 0 && up ? up : a_levels, flipped_w, scale, e, acc, out, next_levels,
+                        next_clip, next_bits, stream, true);
+    if (rc != QNN_OK) return rc;
+    if (d->B == 0) return QNN_OK;
+    if (!workspace) return fail(QNN_ERR_INVALID_ARG, "%s: NULL workspace", who);
+    if (!aligned16(workspace) || !aligned16(a_levels)) return fail(QNN_ERR_ALIGNMENT, "%s: pointers must be 16-byte aligned", who);
+    ZeroInsertParams z;
+    z.a = reinterpret_cast<const uint4 *>(a_levels), z.up = reinterpret_cast<uint4 *>(up);
+    z.units = (uint32_t)units, z.Wu = (uint32_t)wide.W, z.HuWu = (uint32_t)(wide.H * wide.W);
+    z.W = (uint32_t)d->W, z.HW = (uint32_t)(d->H * d->W), z.stride = (uint32_t)d->stride;
+    z.total = (uint32_t)(d->B * wide.H * wide.W * units);
+    const int64_t blocks = ceil_div(z.total, 256);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(zero_insert_kernel, dim3((unsigned)(blocks < 256 * 32 ? blocks : 256 * 32)), dim3(256), 0, st, z);
+    rc = check_launch(who);
+    if (rc != QNN_OK) return rc;
+    return level_conv_run(who, fp4, &wide, up, flipped_w, scale, e, acc, out, next_levels, next_clip, next_bits, stream);
+}
+
+} // namespace qnn
+
+extern "C" int64_t qnn_level_deconv_workspace_bytes(const qnn_conv_desc *d, int fp4)
+{
+    qnn_conv_desc wide;
+    int64_t units = 0;
+    if (level_deconv_geometry("qnn_level_deconv_workspace_bytes", fp4 != 0, d, wide, units) != QNN_OK) return -1;
+    return d->B * wide.H * wide.W * units * 16;
+}
+
+extern "C" int qnn_level_deconv_flip_weights(const void *w_levels, int64_t Cout, int kh, int kw, int64_t tap_bytes,
+                                             void *flipped, void *stream)
+{
+    const char *who = "qnn_level_deconv_flip_weights";
+    if (Cout <= 0 || kh < 1 || kw < 1 || tap_bytes <= 0) return fail(QNN_ERR_INVALID_ARG, "%s: bad geometry", who);
+    if (tap_bytes % 16 != 0) return fail(QNN_ERR_UNSUPPORTED, "%s: a tap must be a multiple of 16 bytes", who);
+    if (kh > (1 << 10) || kw > (1 << 10) || Cout > ((1LL << 31) - 1) / ((int64_t)kh * kw * (tap_bytes / 16)))
+        return fail(QNN_ERR_RANGE, "%s: tensor too large for 32-bit indexing", who);
+    if (!w_levels || !flipped) return fail(QNN_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    if (!aligned16(w_levels) || !aligned16(flipped)) return fail(QNN_ERR_ALIGNMENT, "%s: pointers must be 16-byte aligned", who);
+    const uint32_t units = (uint32_t)(tap_bytes / 16), taps = (uint32_t)(kh * kw);
+    const uint32_t total = (uint32_t)(Cout * taps * units);
+    const int64_t blocks = ceil_div(total, 256);
+    hipLaunchKernelGGL(flip_taps_kernel, dim3((unsigned)(blocks < 256 * 32 ? blocks : 256 * 32)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint4 *>(w_levels),
+                       reinterpret_cast<uint4 *>(flipped), units, taps, total);
+    return check_launch(who);
+}
+
+extern "C" int qnn_level_deconv2d_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *flipped_w, void *workspace,
+                                     const float *scale, const float *bias, int32_t *acc, float *out, int8_t *next_levels,
+                                     float next_clip, int next_bits, void *stream)
+{
+    return level_deconv_run("qnn_level_deconv2d_i8", false, d, a_levels, flipped_w, workspace, scale, bias, acc, out,
+                            next_levels, next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_level_deconv2d_fp4(const qnn_conv_desc *d, const uint8_t *a_levels, const uint8_t *flipped_w, void *workspace,
+                                      const float *scale, const float *bias, int32_t *acc, float *out, uint8_t *next_levels,
+                                      float next_clip, int next_bits, void *stream)
+{
+    return level_deconv_run("qnn_level_deconv2d_fp4", true, d, reinterpret_cast<const int8_t *>(a_levels),
+                            reinterpret_cast<const int8_t *>(flipped_w), workspace, scale, bias, acc, out,
+                            reinterpret_cast<int8_t *>(next_levels), next_clip, next_bits, stream);
 }

@@ -33,6 +33,7 @@ EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2
            "qnn_encode_levels_i8", "qnn_level_conv2d_i8",
            "qnn_fp4_row_bytes", "qnn_plane_sum_fp4", "qnn_level_gemm_fp4",
            "qnn_encode_levels_fp4", "qnn_levels_to_fp4", "qnn_level_conv2d_fp4", "qnn_level_conv2d_block_fp4", "qnn_maxpool_levels_fp4",
+           "qnn_level_deconv_workspace_bytes", "qnn_level_deconv_flip_weights", "qnn_level_deconv2d_i8", "qnn_level_deconv2d_fp4",
            "qnn_pool_out_size", "qnn_maxpool_planes", "qnn_maxpool_levels_i8",
            "qnn_dense_conv2d_f32", "qnn_dense_conv2d_f32_levels", "qnn_global_avgpool_f32", "qnn_dense_fc_f32", "qnn_fc_fused",
            "qnn_last_error", "qnn_version", "qnn_build_id")
@@ -153,6 +154,13 @@ def lib():
         L.qnn_levels_to_fp4.restype = i32
         L.qnn_level_conv2d_fp4.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_level_conv2d_fp4.restype = i32
+        L.qnn_level_deconv_workspace_bytes.argtypes = [ctypes.POINTER(qnn_conv_desc), i32]
+        L.qnn_level_deconv_workspace_bytes.restype = i64
+        L.qnn_level_deconv_flip_weights.argtypes = [vp, i64, i32, i32, i64, vp, vp]
+        L.qnn_level_deconv_flip_weights.restype = i32
+        for f in (L.qnn_level_deconv2d_i8, L.qnn_level_deconv2d_fp4):
+            f.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, vp, vp, f32, i32, vp]
+            f.restype = i32
         L.qnn_level_conv2d_block_fp4.argtypes = L.qnn_conv2d_block.argtypes
         L.qnn_level_conv2d_block_fp4.restype = i32
         L.qnn_maxpool_levels_fp4.argtypes = [vp, i64, i64, i64, i64, i32, i32, i32, i32, vp, vp]
@@ -564,6 +572,67 @@ def qnn_level_conv2d_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=
     Returns (acc, out, next_levels [B][Ho][Wo][Cout/2]); entries not requested are None."""
     return _level_conv(lib().qnn_level_conv2d_fp4, None, _U8, 2, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
                        want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
+
+
+def qnn_level_deconv_flip_weights(w_levels, flipped=None):
+    """w_levels int8 [Cout][kh][kw][Cin] or uint8 fp4 [Cout][kh][kw][Cin/2] -> the same tensor with the taps in
+    flipped order, as qnn_level_deconv2d_i8 / _fp4 read it."""
+    _arg("w_levels", w_levels, (torch.int8, torch.uint8))
+    if w_levels.dim() != 4:
+        raise ValueError("w_levels must be [Cout][kh][kw][C], got %s" % (tuple(w_levels.shape),))
+    cout, kh, kw, cb = (int(e) for e in w_levels.shape)
+    flipped = _out("flipped", flipped, w_levels.dtype, (cout, kh, kw, cb), w_levels, True)
+    _check(lib().qnn_level_deconv_flip_weights(_ptr(w_levels), cout, kh, kw, cb, _ptr(flipped), _stream()))
+    return flipped
+
+
+def _level_deconv(entry, dtypes, per_byte, a_levels, flipped_w, stride, pad, a_bits, w_bits, scale, bias, want_acc, want_out,
+                  next_clip, next_bits, acc, out, next_levels, workspace):
+    _arg("a_levels", a_levels, dtypes)
+    _arg("flipped_w", flipped_w, dtypes)
+    if a_levels.dim() != 4 or flipped_w.dim() != 4 or a_levels.shape[3] != flipped_w.shape[3]:
+        raise ValueError("level tensors must be [B][H][W][C] and [Cout][kh][kw][C] with equal C, got %s and %s"
+                         % (tuple(a_levels.shape), tuple(flipped_w.shape)))
+    B, H, W, cb = (int(e) for e in a_levels.shape)
+    cout, kh, kw, _ = (int(e) for e in flipped_w.shape)
+    ho, wo = (H - 1) * stride - 2 * pad + kh, (W - 1) * stride - 2 * pad + kw
+    if ho < 1 or wo < 1:
+        raise ValueError("transposed convolution with an empty output")
+    d = qnn_conv_desc(B, H, W, per_byte * cb, cout, kh, kw, stride, pad, a_bits, w_bits)
+    need = lib().qnn_level_deconv_workspace_bytes(ctypes.byref(d), int(per_byte == 2))
+    if need < 0:
+        raise QnnError(QNN_ERR_UNSUPPORTED, lib().qnn_last_error().decode())
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=a_levels.device)
+    else:
+        _arg("workspace", workspace, _U8)
+        if workspace.numel() < need:
+            raise ValueError("workspace: %d bytes, %d are needed" % (workspace.numel(), need))
+    _arg("scale", scale, _F32, shape=(cout,), optional=True)
+    _arg("bias", bias, _F32, shape=(cout,), optional=True)
+    acc = _out("acc", acc, torch.int32, (B, ho, wo, cout), a_levels, want_acc)
+    out = _out("out", out, torch.float32, (B, ho, wo, cout), a_levels, want_out)
+    next_levels = _out("next_levels", next_levels, a_levels.dtype, (B, ho, wo, cout // per_byte), a_levels,
+                       next_clip is not None)
+    _check(entry(ctypes.byref(d), _ptr(a_levels), _ptr(flipped_w), _ptr(workspace), _ptr(scale), _ptr(bias), _ptr(acc),
+                 _ptr(out), _ptr(next_levels), float(next_clip) if next_clip is not None else 0.0, int(next_bits), _stream()))
+    return acc, out, next_levels
+
+
+def qnn_level_deconv2d_i8(a_levels, flipped_w, stride, pad, a_bits, w_bits, scale=None, bias=None, want_acc=True,
+                          want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None, workspace=None):
+    """Transposed convolution on int8 levels: a_levels [B][H][W][Cin], flipped_w from qnn_level_deconv_flip_weights.
+    workspace: uint8 tensor of qnn_level_deconv_workspace_bytes bytes (made here when None).  Returns (acc, out,
+    next_levels) on the [B][Ho][Wo][Cout] output."""
+    return _level_deconv(lib().qnn_level_deconv2d_i8, _I8, 1, a_levels, flipped_w, stride, pad, a_bits, w_bits, scale, bias,
+                         want_acc, want_out, next_clip, next_bits, acc, out, next_levels, workspace)
+
+
+def qnn_level_deconv2d_fp4(a_levels, flipped_w, stride, pad, a_bits, w_bits, scale=None, bias=None, want_acc=True,
+                           want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None, workspace=None):
+    """qnn_level_deconv2d_i8 on fp4 levels, two channels per byte (1- and 2-bit codes)."""
+    return _level_deconv(lib().qnn_level_deconv2d_fp4, _U8, 2, a_levels, flipped_w, stride, pad, a_bits, w_bits, scale, bias,
+                         want_acc, want_out, next_clip, next_bits, acc, out, next_levels, workspace)
 
 
 def qnn_level_conv2d_block_fp4(a_levels, w_levels, stride, pad, a_bits, w_bits, scale, bias=None, res_levels=None,

@@ -132,6 +132,21 @@ int main()
     EXPECT(qnn_deconv_pack_weights(FAKE, 2, 64, 4, 4, 64, 2, ODD, nullptr), ANY_ERROR);
     const qnn_conv_desc dc = {1, 4, 4, 64, 32, 4, 4, 2, 1, 5, 2};   // above 4 bits the running sum needs acc or out
     EXPECT(qnn_deconv2d(&dc, FAKE, FAKE, FF, nullptr, nullptr, nullptr, FAKE, 1.0f, 2, nullptr), QNN_ERR_UNSUPPORTED);
+    // ... on decoded levels: nothing may be enqueued (the widening kernel included) before an error return
+    for (const qnn_conv_desc &d : bad) {
+        if (d.kh > 7 && d.kh <= 16) continue; // kernels larger than the input are valid transposed convolutions
+        EXPECT(qnn_level_deconv2d_i8(&d, F8, F8, FAKE, FF, nullptr, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
+        EXPECT(qnn_level_deconv2d_fp4(&d, FU, FU, FAKE, FF, nullptr, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
+    }
+    if (qnn_level_deconv_workspace_bytes(nullptr, 0) != -1) ++g_failures;
+    const qnn_conv_desc dl = {1, 4, 4, 64, 32, 4, 4, 2, 1, 2, 2};
+    EXPECT(qnn_level_deconv2d_i8(&dl, F8, F8, nullptr, FF, nullptr, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_level_deconv2d_i8(&dl, F8, F8, ODD, FF, nullptr, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_ALIGNMENT);
+    EXPECT(qnn_level_deconv2d_i8(&dl, F8, F8, FAKE, nullptr, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_level_deconv2d_i8(&dl, F8, F8, FAKE, FF, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_level_deconv_flip_weights(nullptr, 32, 4, 4, 64, FAKE, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_level_deconv_flip_weights(FAKE, 32, 4, 4, 24, FAKE, nullptr), QNN_ERR_UNSUPPORTED);
+    EXPECT(qnn_level_deconv_flip_weights(FAKE, big, 1024, 1024, 64, FAKE, nullptr), QNN_ERR_RANGE);
 
     // pooling
     if (qnn_pool_out_size(8, 0, 2, 0, 0) != -1 || qnn_pool_out_size(8, 2, 0, 0, 0) != -1 || qnn_pool_out_size(8, 2, 2, 3, 0) != -1) ++g_failures;

@@ -182,6 +182,46 @@ def test_deconv_argument_errors_and_phase_words(qnn):
     assert call(D(0, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)) == qnn.QNN_OK
 
 
+def test_level_deconv_argument_errors_and_workspace(qnn):
+    L = qnn.lib()
+    D = qnn.qnn_conv_desc
+    ok = D(2, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)
+    # widened tensor: 2 x 15 x 15 pixels of 64 (int8) or 32 (fp4) bytes
+    assert L.qnn_level_deconv_workspace_bytes(ctypes.byref(ok), 0) == 2 * 15 * 15 * 64
+    assert L.qnn_level_deconv_workspace_bytes(ctypes.byref(ok), 1) == 2 * 15 * 15 * 32
+    assert L.qnn_level_deconv_workspace_bytes(ctypes.byref(D(2, 8, 8, 64, 32, 4, 3, 2, 1, 2, 2)), 0) == -1   # not square
+    assert L.qnn_level_deconv_workspace_bytes(ctypes.byref(D(2, 8, 8, 24, 32, 4, 4, 2, 1, 2, 2)), 0) == -1   # Cin % 16
+    assert L.qnn_level_deconv_workspace_bytes(None, 0) == -1
+    assert L.qnn_level_deconv_flip_weights(None, 32, 4, 4, 64, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+    assert L.qnn_level_deconv_flip_weights(FAKE, 32, 4, 4, 24, FAKE, None) == qnn.QNN_ERR_UNSUPPORTED
+    assert L.qnn_level_deconv_flip_weights(FAKE, 32, 4, 4, 64, ODD, None) == qnn.QNN_ERR_ALIGNMENT
+    assert L.qnn_level_deconv_flip_weights(FAKE, 0, 4, 4, 64, FAKE, None) == qnn.QNN_ERR_INVALID_ARG
+
+    for entry in (L.qnn_level_deconv2d_i8, L.qnn_level_deconv2d_fp4):
+        def call(desc, a=FAKE, w=FAKE, ws=FAKE, scale=None, bias=None, acc=FAKE, out=None, nxt=None, clip=0.0, nbits=0):
+            return entry(ctypes.byref(desc) if desc is not None else None, a, w, ws, scale, bias, acc, out, nxt, clip,
+                         nbits, None)
+        assert call(None) == qnn.QNN_ERR_INVALID_ARG
+        assert call(D(1, 8, 8, 64, 32, 4, 4, 2, 4, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED      # pad > k - 1
+        assert call(D(1, 8, 8, 64, 32, 4, 2, 2, 1, 2, 2)) == qnn.QNN_ERR_UNSUPPORTED      # not square
+        assert call(D(1, 8, 8, 64, 32, 4, 4, 0, 1, 2, 2)) == qnn.QNN_ERR_INVALID_ARG
+        assert call(D(1, 1, 1, 64, 32, 2, 2, 2, 1, 2, 2)) == qnn.QNN_ERR_INVALID_ARG      # pad eats the whole output
+        assert call(D(1, 8, 8, 64, 32, 4, 4, 2, 1, 0, 2)) == qnn.QNN_ERR_INVALID_ARG
+        assert call(ok, acc=None) == qnn.QNN_ERR_INVALID_ARG
+        assert call(ok, out=FAKE) == qnn.QNN_ERR_INVALID_ARG                              # out without scale
+        assert call(ok, bias=FAKE) == qnn.QNN_ERR_INVALID_ARG                             # bias without scale
+        assert call(ok, ws=None) == qnn.QNN_ERR_INVALID_ARG
+        assert call(ok, ws=ODD) == qnn.QNN_ERR_ALIGNMENT
+        assert call(ok, w=ODD) == qnn.QNN_ERR_ALIGNMENT
+        assert call(ok, a=ODD) == qnn.QNN_ERR_ALIGNMENT
+        assert call(ok, scale=FAKE, nxt=FAKE, clip=1.0, nbits=9) == qnn.QNN_ERR_INVALID_ARG
+        assert call(D(0, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)) == qnn.QNN_OK
+    assert L.qnn_level_deconv2d_fp4(ctypes.byref(D(1, 8, 8, 64, 32, 4, 4, 2, 1, 3, 2)), FAKE, FAKE, FAKE, None, None, FAKE,
+                                    None, None, 0.0, 0, None) == qnn.QNN_ERR_UNSUPPORTED
+    assert L.qnn_level_deconv2d_fp4(ctypes.byref(D(1, 8, 8, 48, 32, 4, 4, 2, 1, 2, 2)), FAKE, FAKE, FAKE, None, None, FAKE,
+                                    None, None, 0.0, 0, None) == qnn.QNN_ERR_UNSUPPORTED
+
+
 def test_fp4_convolution_argument_errors(qnn):
     L = qnn.lib()
     D = qnn.qnn_conv_desc
