@@ -121,7 +121,7 @@ def parse():
     ap.add_argument("--repeats", type=int, default=5, help="default workload: repetitions of the K timed steps (the median is reported)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
-    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "ssd", "trunk", "pool", "grad", "deconv", "probe"],
+    ap.add_argument("--workload", default="gemm", choices=["gemm", "fc1", "conv3", "stack4", "stack5", "ssd", "trunk", "pool", "grad", "deconv", "probe", "timeline"],
                     help="gemm (default, the headline 4096^3 GEMM) or one of the convolution workloads: conv3 = "
                          "ResNet-18-shaped 3x3 conv batch 64 (2x2 bit), stack4 = ResNet-18-shaped 16-conv stack "
                          "batch 256 (3x3 bit), stack5 = VGG16-style detection stack batch 32 at 300x300 (4x4 bit)")
@@ -702,6 +702,74 @@ def probe_workload(args):
             "probe_matrix": table}
 
 
+def timeline_workload(args):
+    """Wave timestamps of the convolution kernel (libqnn_timeline.so: the same kernels compiled with s_memrealtime reads
+    at wave start, after the prologue and at wave end), with and without the balance between the two workgroups of a CU:
+    when the workgroups dispatched first / second end, how far the waves' ends are spread, the launch's span."""
+    import torch
+    from paper_1905_13389_amd import probe, qnn
+
+    cases = [("config 3: 64->64 @56x56, batch 64, 2x2 bit, acc + out", 64, 56, 64, 64, 2, "acc+out"),
+             ("64->64 @56x56, batch 64, 2x2 bit, next planes only", 64, 56, 64, 64, 2, "planes"),
+             ("128->128 @28x28, batch 256, 3x3 bit, next planes", 256, 28, 128, 128, 3, "planes"),
+             ("256->256 @14x14, batch 256, 3x3 bit, next planes", 256, 14, 256, 256, 3, "planes"),
+             ("64->64 @300x300, batch 8, 4x4 bit, next planes", 8, 300, 64, 64, 4, "planes")]
+    gen = torch.Generator(device="cuda").manual_seed(190513389)
+    table = {}
+    for label, B, HW, cin, cout, bits, outs in cases:
+        ap = torch.randint(-2**31, 2**31 - 1, (bits, B * HW * HW, cin // 32), dtype=torch.int32, device="cuda", generator=gen)
+        wp = torch.randint(-2**31, 2**31 - 1, (bits, cout, 3, 3, cin // 32), dtype=torch.int32, device="cuda", generator=gen)
+        sc = (torch.rand(cout, device="cuda", generator=gen) + 0.5) / (3.0 * cin ** 0.5 * ((1 << bits) - 1) ** 2 / 3)
+        d = qnn.qnn_conv_desc(B, HW, HW, cin, cout, 3, 3, 1, 1, bits, bits)
+        # the product library's results are what the instrumented kernels must reproduce
+        if outs == "acc+out":
+            r_acc, r_out, _ = qnn.qnn_conv2d(ap, wp, (B, HW, HW), cin, 1, 1, scale=sc, want_out=True)
+            acc, out, nxt, ref = torch.empty_like(r_acc), torch.empty_like(r_out), None, (r_acc, r_out)
+        else:
+            _, _, r_nxt = qnn.qnn_conv2d(ap, wp, (B, HW, HW), cin, 1, 1, scale=sc, want_acc=False, next_clip=3.0, next_bits=bits)
+            acc, out, nxt, ref = None, None, torch.empty_like(r_nxt), (r_nxt,)
+        row = {}
+        for hint in (False, True):
+            buf = torch.zeros((512 * 8, 4), dtype=torch.int64, device="cuda")
+            probe.qnn_timeline_set(buf, pair_hint=hint)
+            launch = lambda: probe.timeline_conv2d(d, ap, wp, sc, acc, out, nxt, 3.0, bits if nxt is not None else 0)  # noqa: E731
+            for _ in range(5):
+                launch()
+            torch.cuda.synchronize()
+            same = all(torch.equal(a, b) for a, b in zip(ref, [t for t in (acc, out, nxt) if t is not None]))
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                launch()
+            e1.record()
+            torch.cuda.synchronize()
+            t = buf.cpu().numpy()
+            t = t[t[:, 0] > 0]
+            waves = len(t)
+            wpw = waves // 512 if waves % 512 == 0 else 0     # waves per workgroup when the grid is 2 per CU
+            base = t[:, 0].min()
+            end = (t[:, 2] - base) * 0.01
+            entry = {"us_per_launch_10_back_to_back": round(e0.elapsed_time(e1) * 100, 1), "waves": waves,
+                     "results_equal_libqnn": bool(same),
+                     "start_spread_us": round(float((t[:, 0] - base).max()) * 0.01, 2),
+                     "prologue_us_mean": round(float((t[:, 1] - t[:, 0]).mean()) * 0.01, 2),
+                     "wave_end_us": {"mean": round(float(end.mean()), 1), "p10": round(float(sorted(end)[waves // 10]), 1),
+                                     "p90": round(float(sorted(end)[waves * 9 // 10]), 1), "max": round(float(end.max()), 1)}}
+            if wpw:
+                half = 256 * wpw
+                entry["first_dispatched_workgroups_end_us_mean"] = round(float(end[:half].mean()), 1)
+                entry["second_dispatched_workgroups_end_us_mean"] = round(float(end[half:].mean()), 1)
+                cu = ((t[:, 3] >> 32) & 15) * 4096 + ((t[:, 3] >> 8) & 0xff)         # XCC id, SE / SH / CU id fields of HW_ID
+                pairs = sum(1 for b in range(256) if cu[b * wpw] == cu[(b + 256) * wpw])
+                entry["workgroups_b_and_b_plus_256_on_one_cu"] = "%d of 256" % pairs
+            row["pair balance on" if hint else "pair balance off"] = entry
+        probe.qnn_timeline_set(None)
+        table[label] = row
+    return {"metric": "wave timeline of the convolution kernel", "value": None, "unit": "us", "n_gpus": 1, "steps": 10, "warmup": 5,
+            "ms_per_step": None, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u32 bit-planes",
+            "data": "synthetic", "config": {"workload": "qnn_conv2d of libqnn_timeline.so, 3x3 stride 1 pad 1"}, "timeline": table}
+
+
 def fc_workload(args):
     """Config 1: one FC layer, 2 x 2 bit, A [64][512] x W [256][512]: 6.7e7 binary operations, far too
     little to load the chip -- the figure of interest is the latency of the two launches."""
@@ -940,7 +1008,8 @@ def main():
               "exchange; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
     runners = {"trunk": trunk_workload, "pool": pool_workload, "grad": grad_workload, "deconv": deconv_workload,
-               "fc1": fc_workload, "gemm": gemm_workload, "ssd": graph_workload, "probe": probe_workload}
+               "fc1": fc_workload, "gemm": gemm_workload, "ssd": graph_workload, "probe": probe_workload,
+               "timeline": timeline_workload}
     result = runners.get(args.workload, conv_workload)(args)
     if args.workload == "gemm" and not args.no_configs:
         result["configs"] = config_summaries(args)

@@ -52,6 +52,21 @@ int qnn_probe_mfma(int mode, int workgroups, int iters, uint32_t *out, void *str
 /* Message for the last error returned on the calling thread ("" if none). Never NULL. */
 const char *qnn_probe_last_error(void);
 
+/*
+ * libqnn_timeline.so -- the convolution entry points of libqnn.so (qnn_conv2d, qnn_conv2d_block, qnn_deconv2d, same
+ * arguments and results, declared in qnn.h) compiled with wave timestamps, plus:
+ *
+ * qnn_timeline_set -- where the convolution kernels launched after this call leave their timestamps.
+ *   buffer     DEVICE, waves * 4 int64, owned by the caller, or NULL with waves = 0 (nothing is recorded).  Wave w of
+ *              workgroup b of a launch with W waves per workgroup writes entry b W + w if it is below `waves`:
+ *              [0] the constant 100 MHz counter (s_memrealtime) at its start, [1] after its workgroup's prologue,
+ *              [2] at its end, [3] its hardware ids (XCC id << 32 | HW_ID register).  Every launch overwrites.
+ *   pair_hint  0: the two workgroups of a CU run with the hardware's default priorities (for comparison);
+ *              otherwise they balance their progress as in libqnn.so
+ *   Returns 0, or QNN_ERR_INVALID_ARG.  Host state of the process, not thread safe.
+ */
+int qnn_timeline_set(int64_t *buffer, int waves, int pair_hint);
+
 #ifdef __cplusplus
 }
 #endif

@@ -210,3 +210,12 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
     }
     return check_launch("qnn_conv2d");
 }
+
+#ifdef QNN_TIMELINE
+extern "C" int qnn_timeline_set(long long *buffer, int waves, int pair_hint)
+{
+    if (waves < 0 || (waves > 0 && !buffer)) return fail(QNN_ERR_INVALID_ARG, "qnn_timeline_set: a buffer of waves x 4 int64 is needed");
+    timeline_state() = {waves > 0 ? buffer : nullptr, waves, pair_hint ? 1 : 0};
+    return QNN_OK;
+}
+#endif

@@ -41,6 +41,10 @@ struct ConvTileParams {
     // pair_progress (see there); pair_tag tells this launch's progress words from those of earlier launches
     int pair_hint;
     uint32_t pair_tag;
+#ifdef QNN_TIMELINE
+    long long *timeline; // [timeline_waves][4] or nullptr
+    int timeline_waves;
+#endif
     // Bit widths above 4 run as up to four launches over chunks of at most 4 planes per operand (the
     // double sum of Eq. 9 splits into chunk pairs); `shift` is the weight 2^shift of this pair,
     // `partial` the running int32 sum: read when bit 0 of partial_mode is set, written instead of the
@@ -134,6 +138,22 @@ template <int LANES> __device__ __forceinline__ uint32_t or_reduce_lanes(uint32_
 // on every SIMD until the end, and the kernel ends when both do.  The words are a hint and nothing else: no
 // result depends on them, a stale or foreign word (another launch's tag) only means default priorities, and a
 // pairing other than the assumed one costs the balance, not correctness.  One copy per translation unit.
+#ifdef QNN_TIMELINE
+// Diagnostic build (libqnn_timeline.so, include/qnn_probe.h): every wave of the convolution kernel leaves the
+// constant-rate counter (100 MHz) at its start, after its workgroup's prologue and at its end, plus its hardware
+// ids, in a caller-owned buffer; the pair balance can be switched off for comparison.  The product library is
+// compiled without any of this.
+struct TimelineState {
+    long long *buf;
+    int waves, pair_hint;
+};
+inline TimelineState &timeline_state()
+{
+    static TimelineState s = {nullptr, 0, 1};
+    return s;
+}
+#endif
+
 constexpr int kPairSlots = 1024;
 static __device__ unsigned long long pair_progress[kPairSlots];
 static inline uint32_t next_pair_tag()
@@ -165,6 +185,10 @@ bconv_tile_kernel(ConvTileParams p)
     uint32_t *ymask = reinterpret_cast<uint32_t *>(dyn_smem) + BN * p.kh * p.kw; // [Ho] taps whose row is outside
     uint32_t *xmask = ymask + p.Ho;                                          // [Wo] taps whose column is outside
 
+#ifdef QNN_TIMELINE
+    const long long tl_start = __builtin_amdgcn_s_memrealtime();
+    long long tl_loop = 0;
+#endif
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int lane = tid & 63, wave = tid >> 6;
@@ -352,6 +376,9 @@ bconv_tile_kernel(ConvTileParams p)
     stash(0);
     __syncthreads();
 
+#ifdef QNN_TIMELINE
+    tl_loop = __builtin_amdgcn_s_memrealtime();
+#endif
     for (int rt = rt_first; rt < p.tiles_m; rt += p.row_tile_step) {
         const int row0 = rt * BM;
         const bool next_tile = rt + p.row_tile_step < p.tiles_m;
@@ -602,6 +629,19 @@ bconv_tile_kernel(ConvTileParams p)
         }
         tile_sync(); // V's stage is about to be refilled by the next tile's pipeline
     }
+#ifdef QNN_TIMELINE
+    {
+        const long long tl_end = __builtin_amdgcn_s_memrealtime();
+        const int w = (int)blockIdx.x * NW + wave;
+        if (p.timeline && lane == 0 && w < p.timeline_waves) {
+            unsigned xcc = 0, hwid = 0;
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+            long long *t = p.timeline + 4 * (int64_t)w;
+            t[0] = tl_start, t[1] = tl_loop, t[2] = tl_end, t[3] = ((long long)xcc << 32) | hwid;
+        }
+    }
+#endif
 }
 
 // Workgroups resident on the whole chip for one kernel (occupancy x CU count); two host-side queries
@@ -677,6 +717,10 @@ static int launch_conv_vw(ConvTileParams p, hipStream_t st)
     const int grid = groups * p.tiles_n * phases;
     p.pair_hint = grid == 2 * cus && grid <= kPairSlots;
     p.pair_tag = next_pair_tag();
+#ifdef QNN_TIMELINE
+    p.timeline = timeline_state().buf, p.timeline_waves = timeline_state().waves;
+    p.pair_hint = p.pair_hint && timeline_state().pair_hint;
+#endif
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NT), dyn, st, p);
     return (int)QNN_OK;
 }

@@ -1,6 +1,7 @@
-"""ctypes binding of libqnn_probe.so (include/qnn_probe.h): register-only issue-rate loops that the benchmark
-uses to state what the vector ALUs and the matrix cores sustain on the device at hand.  Measurement aids, kept
-out of the product library; nothing on the hot path calls them."""
+"""ctypes binding of libqnn_probe.so and libqnn_timeline.so (include/qnn_probe.h): register-only issue-rate loops that
+the benchmark uses to state what the vector ALUs and the matrix cores sustain on the device at hand, and the
+convolution kernels compiled with wave timestamps.  Measurement aids, kept out of the product library; nothing on the
+hot path calls them."""
 import ctypes
 import os
 
@@ -10,7 +11,10 @@ from . import build as _build
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqnn_probe.so")
 EXPORTS = ("qnn_probe_valu", "qnn_probe_mfma", "qnn_probe_last_error")
+TIMELINE_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqnn_timeline.so")
+TIMELINE_EXPORTS = ("qnn_timeline_set", "qnn_conv2d", "qnn_conv2d_block", "qnn_deconv2d", "qnn_last_error")
 _lib = None
+_timeline_lib = None
 
 
 def lib():
@@ -61,3 +65,46 @@ def qnn_probe_valu(mode, workgroups, iters, out, clocks=None):
 def qnn_probe_mfma(mode, workgroups, iters, out):
     """Launch one register-only MFMA loop; out: int32 [workgroups * 256]."""
     _check(lib().qnn_probe_mfma(int(mode), int(workgroups), int(iters), _buf("out", out, workgroups * 256), _stream()))
+
+
+def timeline_lib():
+    global _timeline_lib
+    if _timeline_lib is None:
+        if not os.path.exists(TIMELINE_LIB_PATH):
+            _build.build()
+        from .qnn import qnn_conv_desc
+        L = ctypes.CDLL(TIMELINE_LIB_PATH)
+        vp, i32, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        L.qnn_timeline_set.argtypes = [vp, i32, i32]
+        L.qnn_timeline_set.restype = i32
+        L.qnn_conv2d.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
+        L.qnn_conv2d.restype = i32
+        L.qnn_last_error.argtypes = []
+        L.qnn_last_error.restype = ctypes.c_char_p
+        _timeline_lib = L
+    return _timeline_lib
+
+
+def qnn_timeline_set(buffer, pair_hint=True):
+    """buffer: int64 CUDA tensor [waves][4] (or None: stop recording); see include/qnn_probe.h."""
+    L = timeline_lib()
+    if buffer is None:
+        rc = L.qnn_timeline_set(None, 0, int(bool(pair_hint)))
+    else:
+        if not (buffer.is_cuda and buffer.is_contiguous() and buffer.dtype == torch.int64 and buffer.dim() == 2
+                and buffer.shape[1] == 4):
+            raise ValueError("buffer: a contiguous CUDA int64 tensor [waves][4] is needed")
+        rc = L.qnn_timeline_set(ctypes.c_void_p(buffer.data_ptr()), int(buffer.shape[0]), int(bool(pair_hint)))
+    if rc != 0:
+        raise RuntimeError("libqnn_timeline error %d: %s" % (rc, L.qnn_last_error().decode()))
+
+
+def timeline_conv2d(desc, a_planes, w_planes, scale, acc, out, next_planes, next_clip, next_bits):
+    """qnn_conv2d of libqnn_timeline.so on tensors the caller has checked (the benchmark builds them with the
+    product binding first); None for outputs that are not wanted."""
+    ptr = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())  # noqa: E731
+    L = timeline_lib()
+    rc = L.qnn_conv2d(ctypes.byref(desc), ptr(a_planes), ptr(w_planes), ptr(scale), ptr(acc), ptr(out), ptr(next_planes),
+                      float(next_clip), int(next_bits), _stream())
+    if rc != 0:
+        raise RuntimeError("libqnn_timeline error %d: %s" % (rc, L.qnn_last_error().decode()))
