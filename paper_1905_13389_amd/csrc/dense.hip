@@ -13,6 +13,8 @@
 // value to its byte offset from the window origin, so the gather is a batch of independent loads.  When the
 // reduction fits one chunk (the 7 x 7 x 3 first convolution: 147 values) the table is built once and the
 // weights live in registers instead of LDS (see the kernel's ONE parameter): three workgroups per CU.
+#include <atomic>
+
 #include "qnn_host.h"
 #include "quantize.h"
 #include "fastdiv.h"
@@ -31,6 +33,13 @@ static_assert(kChunk % 8 == 0 && 2 * kDenseTile * kChunkStride * 4 + kChunk * 8 
 // afterwards, so that a batch of loads stays independent and no mask has to live until the data arrives.
 static __device__ float dense_zero = 0.0f;
 
+// Progress words of the resident workgroups: (tag << 32) | pixel tiles done.  The workgroups b, b + CUs, b + 2 CUs ...
+// share a CU (the dispatcher fills every CU once per round) and a SIMD issues from its older waves first, so the one
+// dispatched first would run ahead and the last would finish the kernel alone.  Each publishes its count after
+// every tile and raises its wave priority while a partner is ahead of it.  A hint only: no result depends on it.
+constexpr int kGroupSlots = 1024, kGroupMax = 4;
+static __device__ unsigned long long group_progress[kGroupSlots];
+
 struct DenseConvParams {
     const float *x, *w, *scale, *shift;
     float *out;
@@ -41,6 +50,8 @@ struct DenseConvParams {
     int K;     // kh kw Cin
     int relu, next_bits, next_top, cwo;
     int fast_offsets; // the input tensor is smaller than 4 GiB: 32-bit byte offsets reach all of it (wrap-around sums too)
+    int group, group_stride; // workgroups per CU that balance their progress (0: off) and the distance between their ids
+    uint32_t group_tag;
     float next_inv_clip, next_half_top;
     FastDiv div_howo, div_wo;
 };
@@ -212,6 +223,36 @@ __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3
         }
     };
 
+    unsigned tiles_done = 0;
+    unsigned long long seen[kGroupMax] = {0, 0, 0, 0};
+    if (p.group && tid == 0)
+        __hip_atomic_store(&group_progress[blockIdx.x], (unsigned long long)p.group_tag << 32, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    auto balance = [&]() {
+        if (!p.group) return;
+        ++tiles_done;
+        bool behind = false;
+#pragma unroll
+        for (int g = 0; g < kGroupMax; ++g) {
+            const unsigned tag = (unsigned)__builtin_amdgcn_readfirstlane((int)(seen[g] >> 32));
+            const unsigned done = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)seen[g]);
+            behind = behind || (g < p.group && tag == p.group_tag && done > tiles_done);
+        }
+        if (behind)
+            __builtin_amdgcn_s_setprio(1);
+        else
+            __builtin_amdgcn_s_setprio(0);
+        if (tid == 0)
+            __hip_atomic_store(&group_progress[blockIdx.x], ((unsigned long long)p.group_tag << 32) | tiles_done,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned first = blockIdx.x % (unsigned)p.group_stride;
+#pragma unroll
+        for (int g = 0; g < kGroupMax; ++g)
+            if (g < p.group)
+                seen[g] = __hip_atomic_load(&group_progress[first + g * p.group_stride], __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+    };
+
     if constexpr (ONE) {
         // One chunk (the 7 x 7 x 3 first convolution): the table is staged once, the weights go to registers.
         const int kc = p.K;
@@ -245,6 +286,7 @@ __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3
             }
             __syncthreads(); // every wave is done with the stage
             finish(tile, acc);
+            balance();
         }
     } else {
         for (int64_t tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
@@ -264,6 +306,7 @@ __global__ __launch_bounds__(kDenseThreads) __attribute__((amdgpu_waves_per_eu(3
                 __syncthreads(); // the stage may be overwritten
             }
             finish(tile, acc);
+            balance();
         }
     }
 }
@@ -347,6 +390,11 @@ static int dense_conv_run(const char *who, const qnn_dense_conv_desc *d, const f
     int64_t per_col = ceil_div((int64_t)per_cu * cus, col_tiles);
     if (per_col > p.tiles_m) per_col = p.tiles_m;
     const dim3 grid((unsigned)per_col, (unsigned)col_tiles);
+    // one column tile, every CU holds the same number (2 .. 4) of the resident workgroups: they balance their progress
+    static std::atomic<uint32_t> launches{0};
+    const bool grouped = col_tiles == 1 && per_cu >= 2 && per_cu <= kGroupMax && per_col == (int64_t)per_cu * cus &&
+                         per_col <= kGroupSlots;
+    p.group = grouped ? per_cu : 0, p.group_stride = cus, p.group_tag = ++launches;
     hipLaunchKernelGGL(kernel, grid, dim3(kDenseThreads), 0, static_cast<hipStream_t>(stream), p);
     return check_launch(who);
 }
