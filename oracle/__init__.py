@@ -47,6 +47,7 @@ def lib():
         L.oracle_gemm8_one.argtypes = [p, p, i64]
         L.oracle_gemm8_one.restype = ctypes.c_int32
         L.oracle_conv2d8.argtypes = [p, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, p]
+        L.oracle_conv2d8_dilated.argtypes = [p, p, i64, i64, i64, i64, i64, i32, i32, i32, i32, i32, p]
         L.oracle_scale.argtypes = [p, p, i64, i64, p]
         L.oracle_xnor_bitcount_dot.argtypes = [p, p, i64]
         L.oracle_xnor_bitcount_dot.restype = ctypes.c_int32
@@ -130,19 +131,28 @@ def gemm_one(a_row, w_row):
     return int(lib().oracle_gemm8_one(_ptr(a), _ptr(w), a.size))
 
 
-def conv2d(a_levels, w_levels, stride, pad):
+def conv2d(a_levels, w_levels, stride, pad, dilation=1):
     """Zero-padded convolution on decoded levels.  a: [B][H][W][Cin] int8, w:
-    [Cout][kh][kw][Cin] int8 -> int32 [B][Ho][Wo][Cout] (Section "Model Decomposition")."""
+    [Cout][kh][kw][Cin] int8 -> int32 [B][Ho][Wo][Cout] (Section "Model Decomposition").
+    dilation > 1: the taps are that many pixels apart (the dilated layer of the detection network)."""
     a = np.ascontiguousarray(a_levels, dtype=np.int8)
     w = np.ascontiguousarray(w_levels, dtype=np.int8)
     B, H, W, Cin = a.shape
     Cout, kh, kw, Cin2 = w.shape
     assert Cin == Cin2
-    Ho = (H + 2 * pad - kh) // stride + 1
-    Wo = (W + 2 * pad - kw) // stride + 1
+    if dilation == 1:
+        Ho = (H + 2 * pad - kh) // stride + 1
+        Wo = (W + 2 * pad - kw) // stride + 1
+        acc = np.empty((B, Ho, Wo, Cout), dtype=np.int32)
+        _check(lib().oracle_conv2d8(_ptr(a), _ptr(w), B, H, W, Cin, Cout, kh, kw, stride, pad,
+                                    _ptr(acc)), "conv2d")
+        return acc
+    Ho = (H + 2 * pad - dilation * (kh - 1) - 1) // stride + 1
+    Wo = (W + 2 * pad - dilation * (kw - 1) - 1) // stride + 1
+    assert Ho >= 1 and Wo >= 1
     acc = np.empty((B, Ho, Wo, Cout), dtype=np.int32)
-    _check(lib().oracle_conv2d8(_ptr(a), _ptr(w), B, H, W, Cin, Cout, kh, kw, stride, pad,
-                                _ptr(acc)), "conv2d")
+    _check(lib().oracle_conv2d8_dilated(_ptr(a), _ptr(w), B, H, W, Cin, Cout, kh, kw, stride, pad, dilation,
+                                        _ptr(acc)), "conv2d (dilated)")
     return acc
 
 
@@ -208,7 +218,7 @@ def layer_graph(x, clip0, bits, nodes):
 
     x: float32 [B][H][W][C], quantized once with (clip0, bits) (Table 1 range limit, Eq. 15); the result is node
     "input".  Every node names its source node:
-      conv  levels(src) -> conv2d (zero padding) -> scale -> out (float32); unless the node is a head, out is
+      conv  levels(src) -> conv2d (zero padding; "dilation" if the node has one) -> scale -> out (float32); unless the node is a head, out is
             quantized with (clip, a_bits) and the levels are what its consumers read
       pool  max-pooling of the source's levels (taken on the codes: the quantizer is monotone)
     Returns {name: {"levels" (or None for heads), "acc", "out"}} with "input" included.
@@ -223,7 +233,7 @@ def layer_graph(x, clip0, bits, nodes):
             values[nd["name"]] = {"levels": maxpool(src, nd["k"], nd["stride"], nd["pad"], nd["ceil_mode"]),
                                   "acc": None, "out": None}
             continue
-        acc = conv2d(src.astype(np.int8), nd["w"], nd["stride"], nd["pad"])
+        acc = conv2d(src.astype(np.int8), nd["w"], nd["stride"], nd["pad"], nd.get("dilation", 1))
         out = scale(acc, nd["scale"])
         lv = None
         if not nd["head"]:

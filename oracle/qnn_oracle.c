@@ -201,6 +201,50 @@ int oracle_conv2d8(const int8_t *a, const int8_t *w, int64_t B, int64_t H, int64
 }
 
 /* ------------------------------------------------------------------------- */
+/* The same sum with the taps `dilation` pixels apart (the detection network   */
+/* of the experiments section, SSD on a backbone, has one such layer):         */
+/* tap (y, x) reads input pixel (ho s + y d - p, wo s + x d - p);              */
+/* Ho = (H + 2p - d (kh - 1) - 1)/s + 1, floor.  dilation = 1 is the           */
+/* convolution above.                                                          */
+/* ------------------------------------------------------------------------- */
+int oracle_conv2d8_dilated(const int8_t *a, const int8_t *w, int64_t B, int64_t H, int64_t W,
+                           int64_t Cin, int64_t Cout, int kh, int kw, int stride, int pad,
+                           int dilation, int32_t *acc)
+{
+    if (!a || !w || !acc || B < 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 ||
+        kh <= 0 || kw <= 0 || stride <= 0 || pad < 0 || dilation <= 0)
+        return -1;
+    const int64_t eh = (int64_t)dilation * (kh - 1) + 1, ew = (int64_t)dilation * (kw - 1) + 1;
+    if (H + 2 * pad < eh || W + 2 * pad < ew) return -1;
+    const int64_t Ho = (H + 2 * pad - eh) / stride + 1;
+    const int64_t Wo = (W + 2 * pad - ew) / stride + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t ho = 0; ho < Ho; ++ho) {
+            for (int64_t wo = 0; wo < Wo; ++wo) {
+                for (int64_t co = 0; co < Cout; ++co) {
+                    int32_t s = 0;
+                    for (int y = 0; y < kh; ++y) {
+                        int64_t hi = ho * stride + (int64_t)y * dilation - pad;
+                        if (hi < 0 || hi >= H) continue;
+                        for (int x = 0; x < kw; ++x) {
+                            int64_t wi = wo * stride + (int64_t)x * dilation - pad;
+                            if (wi < 0 || wi >= W) continue;
+                            const int8_t *ap = a + ((b * H + hi) * W + wi) * Cin;
+                            const int8_t *wp = w + ((co * kh + y) * kw + x) * Cin;
+                            for (int64_t ci = 0; ci < Cin; ++ci)
+                                s += (int32_t)ap[ci] * (int32_t)wp[ci];
+                        }
+                    }
+                    acc[((b * Ho + ho) * Wo + wo) * Cout + co] = s;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Decoder scale (Section "M-bit Encoding Functions": the 1/alpha^2 factor,   */
 /* 1/9 in Fig. 1; Eq. 18), generalised to one fp32 factor per output channel. */
 /* One int->fp32 conversion and one IEEE fp32 multiply.                       */

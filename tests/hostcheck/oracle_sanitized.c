@@ -17,6 +17,8 @@ int oracle_gemm8(const int8_t *, const int8_t *, int64_t, int64_t, int64_t, int3
 int32_t oracle_gemm8_one(const int8_t *, const int8_t *, int64_t);
 int oracle_conv2d8(const int8_t *, const int8_t *, int64_t, int64_t, int64_t, int64_t, int64_t, int, int, int, int,
                    int32_t *);
+int oracle_conv2d8_dilated(const int8_t *, const int8_t *, int64_t, int64_t, int64_t, int64_t, int64_t, int, int, int, int,
+                           int, int32_t *);
 int oracle_scale(const int32_t *, const float *, int64_t, int64_t, float *);
 int32_t oracle_xnor_bitcount_dot(const uint32_t *, const uint32_t *, int64_t);
 int oracle_multibranch_gemm(const uint32_t *, int, const uint32_t *, int, int64_t, int64_t, int64_t, int32_t *,
@@ -139,11 +141,24 @@ int main(void)
                 for (int64_t i = 0; i < B * H * W * Cout; ++i) CHECK(ref[i] == acc[i]);
                 free(ref);
             }
+            /* dilation 1 is the same sum; dilation 2 with enough padding keeps the extent */
+            {
+                int32_t *again = malloc((size_t)(B * Ho * Wo * Cout) * sizeof *again);
+                CHECK(oracle_conv2d8_dilated(a, w, B, H, W, Cin, Cout, kh, kw, st, pad, 1, again) == 0);
+                for (int64_t i = 0; i < B * Ho * Wo * Cout; ++i) CHECK(again[i] == acc[i]);
+                free(again);
+                const int64_t H2 = (H + 2 * (pad + kh) - 2 * (kh - 1) - 1) / st + 1, W2 = (W + 2 * (pad + kh) - 2 * (kw - 1) - 1) / st + 1;
+                int32_t *wide = malloc((size_t)(B * H2 * W2 * Cout) * sizeof *wide);
+                CHECK(oracle_conv2d8_dilated(a, w, B, H, W, Cin, Cout, kh, kw, st, pad + kh, 2, wide) == 0);
+                free(wide);
+            }
             free(a), free(w), free(acc);
         }
         int32_t dummy;
         int8_t one = 1;
         CHECK(oracle_conv2d8(&one, &one, 1, 1, 1, 1, 1, 3, 3, 1, 0, &dummy) != 0); /* kernel larger than the image */
+        CHECK(oracle_conv2d8_dilated(&one, &one, 1, 1, 1, 1, 1, 3, 3, 1, 1, 2, &dummy) != 0);
+        CHECK(oracle_conv2d8_dilated(&one, &one, 1, 1, 1, 1, 1, 1, 1, 1, 0, 0, &dummy) != 0);
     }
 
     /* scale: Fig. 1's 1/9 on the worked example's accumulator */

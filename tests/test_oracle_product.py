@@ -168,10 +168,10 @@ def test_zero_one_route_identity():
 
 
 # ----------------------------------------------------------------------------- conv
-def _torch_conv(a, w, stride, pad):
+def _torch_conv(a, w, stride, pad, dilation=1):
     ta = torch.from_numpy(a.astype(np.float64)).permute(0, 3, 1, 2)
     tw = torch.from_numpy(w.astype(np.float64)).permute(0, 3, 1, 2)
-    out = torch.nn.functional.conv2d(ta, tw, stride=stride, padding=pad)
+    out = torch.nn.functional.conv2d(ta, tw, stride=stride, padding=pad, dilation=dilation)
     return out.permute(0, 2, 3, 1).numpy().round().astype(np.int64)
 
 
@@ -190,6 +190,37 @@ def test_conv_against_torch_float64(geom):
     a = _levels(gen, (B, H, W, Cin), 3, np.int8)
     w = _levels(gen, (Cout, k, k, Cin), 2, np.int8)
     assert np.array_equal(oracle.conv2d(a, w, stride, pad), _torch_conv(a, w, stride, pad))
+
+
+@pytest.mark.parametrize("geom", [
+    # B, H, W, Cin, Cout, kh, kw, stride, pad, dilation
+    (1, 19, 19, 6, 4, 3, 3, 1, 6, 6),     # the detection network's layer: 3x3, dilation 6, pad 6, same size
+    (2, 9, 11, 5, 3, 3, 3, 1, 2, 2),
+    (1, 10, 9, 4, 2, 3, 2, 2, 1, 3),      # rectangular kernel, stride 2
+    (1, 7, 7, 3, 2, 2, 2, 1, 0, 4),       # no padding: the output shrinks by dilation (k - 1)
+    (2, 5, 5, 8, 3, 3, 3, 1, 4, 4),       # whole rows of taps outside the image
+    (1, 6, 6, 4, 2, 1, 1, 1, 0, 5),       # 1x1: dilation has no effect
+])
+def test_dilated_conv_against_torch_float64(geom):
+    B, H, W, Cin, Cout, kh, kw, stride, pad, dil = geom
+    gen = np.random.default_rng(sum(geom))
+    a = _levels(gen, (B, H, W, Cin), 3, np.int8)
+    w = _levels(gen, (Cout, kh, kw, Cin), 2, np.int8)
+    got = oracle.conv2d(a, w, stride, pad, dil)
+    assert np.array_equal(got, _torch_conv(a, w, stride, pad, dil))
+    if kh == 1 and kw == 1:
+        assert np.array_equal(got, oracle.conv2d(a, w, stride, pad))
+
+
+def test_dilated_conv_is_the_conv_of_a_kernel_with_zeros_between_its_taps():
+    # brute force through the undilated definition: spread the taps d apart with zero weights between them
+    gen = np.random.default_rng(61)
+    a = _levels(gen, (2, 8, 9, 4), 2, np.int8)
+    w = _levels(gen, (3, 3, 3, 4), 3, np.int8)
+    for d in (2, 3):
+        wide = np.zeros((3, 2 * d + 1, 2 * d + 1, 4), dtype=np.int8)
+        wide[:, ::d, ::d, :] = w
+        assert np.array_equal(oracle.conv2d(a, w, 1, d, d), oracle.conv2d(a, wide, 1, d))
 
 
 def test_conv_rectangular_kernel_and_orientation():
