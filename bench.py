@@ -584,8 +584,8 @@ def graph_workload(args):
                 calls.append((nd["name"], 0.0, fn))
                 val[nd["name"]] = (dst, ho, C)
                 continue
-            k, head = nd["k"], nd["head"]
-            ho = (H + 2 * nd["pad"] - k) // nd["stride"] + 1
+            k, head, dil = nd["k"], nd["head"], nd.get("dilation", 1)
+            ho = (H + 2 * nd["pad"] - dil * (k - 1) - 1) // nd["stride"] + 1
             sc = up(nd["scale"])
             dst = None if head else new(ho, nd["cout"])
             out = torch.empty((B, ho, ho, nd["cout"]), dtype=torch.float32, device="cuda") if head else None
@@ -593,13 +593,13 @@ def graph_workload(args):
             macs += m
             if planes:
                 wp = qnn.qnn_encode_pack(up(nd["w"]), 1.0, bits).view(bits, nd["cout"], k, k, -1)
-                fn = lambda src=src, wp=wp, H=H, C=C, nd=nd, sc=sc, dst=dst, out=out, head=head: qnn.qnn_conv2d(
-                    src, wp, (B, H, H), C, nd["stride"], nd["pad"], scale=sc, want_acc=False, want_out=head, out=out,
+                fn = lambda src=src, wp=wp, H=H, C=C, nd=nd, sc=sc, dst=dst, out=out, head=head, dil=dil: qnn.qnn_conv2d_dilated(
+                    src, wp, (B, H, H), C, nd["stride"], nd["pad"], dil, scale=sc, want_acc=False, want_out=head, out=out,
                     next_clip=None if head else nd["clip"], next_bits=0 if head else bits, next_planes=dst)
             else:
                 wl_ = up(nd["w"])
-                fn = lambda src=src, wl_=wl_, nd=nd, sc=sc, dst=dst, out=out, head=head: qnn.qnn_level_conv2d_i8(
-                    src, wl_, nd["stride"], nd["pad"], bits, bits, scale=sc, want_acc=False, want_out=head, out=out,
+                fn = lambda src=src, wl_=wl_, nd=nd, sc=sc, dst=dst, out=out, head=head, dil=dil: qnn.qnn_level_conv2d_dilated_i8(
+                    src, wl_, nd["stride"], nd["pad"], dil, bits, bits, scale=sc, want_acc=False, want_out=head, out=out,
                     next_clip=None if head else nd["clip"], next_bits=0 if head else bits, next_levels=dst)
             calls.append(("%s %d->%d@%d k%d%s" % (nd["name"], nd["cin"], nd["cout"], H, k, " s2" if nd["stride"] == 2 else ""),
                           2.0 * m * bits * bits, fn))
@@ -647,16 +647,16 @@ def graph_workload(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 bit-planes, int32 accumulate",
         "data": "synthetic",
         "config": {"workload": "VGG16 + SSD-style detection network as one chain: 12 backbone convolutions joined by max-pooling, "
-                               "10 extra convolutions down to 1x1, 12 head convolutions on six maps; batch %d, 300x300, 4x4 bit" % B,
+                               "10 extra convolutions down to 1x1 (one with its taps 6 pixels apart), 12 head convolutions on six maps; batch %d, 300x300, 4x4 bit" % B,
                    "macs": macs, "images_per_s": round(B / (ms * 1e-3), 1),
-                   "step": "qnn_encode_pack + qnn_conv2d (fused scale/quantize/pack epilogue) / qnn_maxpool_planes per node"},
+                   "step": "qnn_encode_pack + qnn_conv2d_dilated (dilation 1 = qnn_conv2d; fused scale/quantize/pack epilogue) / qnn_maxpool_planes per node"},
         "roofline": {"bound": "alu", "kernel": "bconv_tile_kernel (%d launches per step)" % sum(1 for e in per if e[1] > 0),
                      "achieved": round(conv_tops, 2), "peak": round(PEAK_BINARY_TOPS, 1), "unit": "binary TOP/s",
                      "frac": round(conv_tops / PEAK_BINARY_TOPS, 4), "traffic": None, "kernel_ms": round(conv_ms, 4),
                      "pooling_ms": round(pool_ms, 4), "step_frac": round(tops / PEAK_BINARY_TOPS, 4),
                      "slowest_layer_above_1pct_of_time": {"layer": worst[0], "frac": round(worst[1], 4), "ms": round(worst[2], 4)},
                      "peak_note": PEAK_NOTE},
-        "mfma_variant": {"step": "qnn_encode_levels_i8 + qnn_level_conv2d_i8 / qnn_maxpool_levels_i8 per node",
+        "mfma_variant": {"step": "qnn_encode_levels_i8 + qnn_level_conv2d_dilated_i8 / qnn_maxpool_levels_i8 per node",
                          "ms_per_step": round(m_ms, 4), "images_per_s": round(B / (m_ms * 1e-3), 1),
                          "speedup_vs_xor_bitcount_step": round(ms / m_ms, 2),
                          "roofline": {"bound": "mfma", "achieved": round(int8_tops, 1), "peak": 5000.0, "unit": "int8 TOP/s",

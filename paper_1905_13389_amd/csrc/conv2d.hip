@@ -18,7 +18,7 @@ struct ConvParams {
     const uint32_t *a; // [AB][B][H][W][cw]
     const uint32_t *w; // [WB][Cout][kh][kw][cw]
     int64_t B, H, W, Cin, Cout, Ho, Wo;
-    int kh, kw, stride, pad;
+    int kh, kw, stride, pad, dil;
     int64_t cw, nw, M; // words per pixel, reduction words, output pixels
     int64_t a_plane_stride;
     const float *scale;
@@ -40,10 +40,10 @@ __global__ __launch_bounds__(256) void bconv_plain_kernel(ConvParams p, int w_bi
     uint32_t sum = 0;
     int64_t valid_taps = 0;
     for (int ky = 0; ky < p.kh; ++ky) {
-        const int hi = h0 + ky;
+        const int hi = h0 + ky * p.dil;
         if (hi < 0 || hi >= p.H) continue;
         for (int kx = 0; kx < p.kw; ++kx) {
-            const int wi = w0 + kx;
+            const int wi = w0 + kx * p.dil;
             if (wi < 0 || wi >= p.W) continue;
             ++valid_taps;
             for (int i = 0; i < w_bits; ++i) {
@@ -89,9 +89,28 @@ extern "C" int qnn_conv2d(const qnn_conv_desc *d, const uint32_t *a_planes, cons
     return qnn_conv2d_block(d, a_planes, w_planes, scale, nullptr, acc, out, next_planes, next_clip, next_bits, stream);
 }
 
+static int conv_run(const qnn_conv_desc *d, int dilation, const uint32_t *a_planes, const uint32_t *w_planes,
+                    const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                    uint32_t *next_planes, float next_clip, int next_bits, void *stream);
+
 extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes, const uint32_t *w_planes,
                                 const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
                                 uint32_t *next_planes, float next_clip, int next_bits, void *stream)
+{
+    return conv_run(d, 1, a_planes, w_planes, scale, epi, acc, out, next_planes, next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_conv2d_dilated(const qnn_conv_desc *d, int dilation, const uint32_t *a_planes, const uint32_t *w_planes,
+                                  const float *scale, int32_t *acc, float *out, uint32_t *next_planes, float next_clip,
+                                  int next_bits, void *stream)
+{
+    return conv_run(d, dilation, a_planes, w_planes, scale, nullptr, acc, out, next_planes, next_clip, next_bits, stream);
+}
+
+// dilation: distance between neighbouring taps in pixels
+static int conv_run(const qnn_conv_desc *d, int dilation, const uint32_t *a_planes, const uint32_t *w_planes,
+                    const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
+                    uint32_t *next_planes, float next_clip, int next_bits, void *stream)
 {
     if (!d) return fail(QNN_ERR_INVALID_ARG, "qnn_conv2d: NULL descriptor");
     BlockTerms blk;
@@ -104,7 +123,10 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
     if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
         return fail(QNN_ERR_INVALID_ARG, "qnn_conv2d: bad kernel geometry");
     if (d->kh > 7 || d->kw > 7) return fail(QNN_ERR_UNSUPPORTED, "qnn_conv2d: kernel larger than 7x7");
-    if (d->H + 2 * (int64_t)d->pad < d->kh || d->W + 2 * (int64_t)d->pad < d->kw)
+    if (dilation < 1) return fail(QNN_ERR_INVALID_ARG, "qnn_conv2d: dilation must be at least 1");
+    if (dilation > 64) return fail(QNN_ERR_UNSUPPORTED, "qnn_conv2d: dilation above 64");
+    const int64_t eh = (int64_t)dilation * (d->kh - 1) + 1, ew = (int64_t)dilation * (d->kw - 1) + 1; // extent of the taps
+    if (d->H + 2 * (int64_t)d->pad < eh || d->W + 2 * (int64_t)d->pad < ew)
         return fail(QNN_ERR_INVALID_ARG, "qnn_conv2d: kernel larger than the padded image");
     if (!acc && !out && !next_planes) return fail(QNN_ERR_INVALID_ARG, "qnn_conv2d: no output requested");
     if ((out || next_planes) && !scale)
@@ -129,9 +151,9 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
     p.a = a_planes;
     p.w = w_planes;
     p.B = d->B, p.H = d->H, p.W = d->W, p.Cin = d->Cin, p.Cout = d->Cout;
-    p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad;
-    p.Ho = (d->H + 2 * (int64_t)d->pad - d->kh) / d->stride + 1;
-    p.Wo = (d->W + 2 * (int64_t)d->pad - d->kw) / d->stride + 1;
+    p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad, p.dil = dilation;
+    p.Ho = (d->H + 2 * (int64_t)d->pad - eh) / d->stride + 1;
+    p.Wo = (d->W + 2 * (int64_t)d->pad - ew) / d->stride + 1;
     p.cw = ceil_div(d->Cin, 32);
     p.nw = (int64_t)d->kh * d->kw * p.cw;
     if (d->B > (INT64_MAX >> 24) / (p.Ho * p.Wo)) return fail(QNN_ERR_RANGE, "qnn_conv2d: too many output pixels");
@@ -148,7 +170,7 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
     // the register-blocked kernel indexes pixels and plane words with 32-bit integers
     const bool small_index = p.M < (1LL << 29) && p.a_plane_stride * d->a_bits < (1LL << 31) &&
                              p.M * cwo < (1LL << 31) && p.Ho + p.Wo <= kMaxOutExtent &&
-                             ((int64_t)d->kh * d->W + d->kw) * p.cw < (1LL << 24);
+                             (eh * d->W + ew) * p.cw < (1LL << 24);
     bool done = false;
     const bool wide = d->w_bits > 4 || d->a_bits > 4;
     if (p.nw <= kMaxGroups && d->kh * d->kw <= kMaxTaps && small_index && (!wide || acc || out)) {
@@ -156,7 +178,7 @@ extern "C" int qnn_conv2d_block(const qnn_conv_desc *d, const uint32_t *a_planes
         t.a = a_planes, t.w = w_planes, t.scale = scale, t.acc = acc, t.out = out, t.next = next_planes;
         t.H = (int)d->H, t.W = (int)d->W, t.HW = (int)(d->H * d->W), t.Cin = (int)d->Cin, t.Cout = (int)d->Cout;
         t.M = (int)p.M, t.cw = (int)p.cw, t.nw = (int)p.nw, t.cwo = (int)cwo, t.Ho = (int)p.Ho, t.Wo = (int)p.Wo;
-        t.kh = d->kh, t.kw = d->kw, t.stride = d->stride, t.pad = d->pad;
+        t.kh = d->kh, t.kw = d->kw, t.stride = d->stride, t.pad = d->pad, t.dil = dilation;
         t.a_plane_stride = (int)p.a_plane_stride;
         t.top_a = t.shift = t.partial_mode = 0;
         t.n_times_top = 0;

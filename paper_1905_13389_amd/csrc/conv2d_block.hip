@@ -156,6 +156,7 @@ extern "C" int qnn_deconv2d(const qnn_conv_desc *d, const uint32_t *a_planes, co
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     ConvTileParams t = {};
+    t.dil = 1;
     t.a = a_planes, t.scale = scale, t.acc = acc, t.out = out, t.next = next_planes;
     t.H = (int)d->H, t.W = (int)d->W, t.HW = (int)(d->H * d->W), t.Cin = (int)d->Cin, t.Cout = (int)d->Cout;
     t.cw = (int)cw, t.cwo = (int)cwo;

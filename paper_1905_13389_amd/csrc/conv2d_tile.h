@@ -28,6 +28,7 @@ struct ConvTileParams {
     uint32_t *next; // [next_bits][M][cwo]
     int H, W, HW, Cin, Cout, M, cw, nw, cwo, Ho, Wo;
     int kh, kw, stride, pad;
+    int dil; // distance between neighbouring taps in pixels (1: an ordinary convolution)
     int a_plane_stride;
     uint32_t n_times_top; // kh kw Cin (2^WB-1)(2^AB-1)
     int top_a;
@@ -250,7 +251,7 @@ bconv_tile_kernel(ConvTileParams p)
     for (int g = tid; g * VW < p.nw; g += NT) {
         const int kword = g * VW;
         const int tap = kword / p.cw, ci = kword % p.cw;
-        tap_table[g] = ((uint32_t)tap << 24) | (uint32_t)(((tap / p.kw) * p.W + tap % p.kw) * p.cw + ci);
+        tap_table[g] = ((uint32_t)tap << 24) | (uint32_t)(((tap / p.kw) * p.dil * p.W + (tap % p.kw) * p.dil) * p.cw + ci);
     }
     // output row / column -> set of taps that fall outside the image
     for (int o = tid; o < p.Ho + p.Wo; o += NT) {
@@ -258,11 +259,11 @@ bconv_tile_kernel(ConvTileParams p)
         if (o < p.Ho) {
             const int h0 = o * p.stride - pad_y;
             for (int ky = 0; ky < p.kh; ++ky)
-                if ((unsigned)(h0 + ky) >= (unsigned)p.H) m |= ((1u << p.kw) - 1u) << (ky * p.kw);
+                if ((unsigned)(h0 + ky * p.dil) >= (unsigned)p.H) m |= ((1u << p.kw) - 1u) << (ky * p.kw);
         } else {
             const int w0 = (o - p.Ho) * p.stride - pad_x;
             for (int kx = 0; kx < p.kw; ++kx)
-                if ((unsigned)(w0 + kx) >= (unsigned)p.W)
+                if ((unsigned)(w0 + kx * p.dil) >= (unsigned)p.W)
                     for (int ky = 0; ky < p.kh; ++ky) m |= 1u << (ky * p.kw + kx);
         }
         ymask[o] = m; // xmask follows ymask

@@ -151,6 +151,7 @@ struct LevelConvParams {
     float *out;
     int8_t *next;
     int H, W, Cin, Cout, Ho, Wo, kh, kw, stride, pad;
+    int dil;     // distance between neighbouring taps in pixels
     int pixels;  // B Ho Wo
     int nk;      // kh kw Cin
     int units;   // nk / 16
@@ -204,7 +205,7 @@ level_conv_mfma_kernel(LevelConvParams p)
         if (u < p.units) {
             const int kb = 16 * u, tap = (int)fdiv((uint32_t)kb, p.div_cin), c = kb - tap * p.Cin;
             const int ky = (int)fdiv((uint32_t)tap, p.div_kw), kx = tap - ky * p.kw;
-            e = ((uint32_t)tap << 24) | (uint32_t)((ky * p.W + kx) * p.Cin + c);
+            e = ((uint32_t)tap << 24) | (uint32_t)((ky * p.dil * p.W + kx * p.dil) * p.Cin + c);
         }
         tap_table[u] = e;
     }
@@ -239,9 +240,9 @@ level_conv_mfma_kernel(LevelConvParams p)
         // whole kernel rows / columns that fall outside the image
         uint32_t mask = 1u << kMaxMfmaTaps;
         for (int ky = 0; ky < p.kh; ++ky)
-            if ((unsigned)(iy0 + ky) >= (unsigned)p.H) mask |= p.row_taps << (ky * p.kw);
+            if ((unsigned)(iy0 + ky * p.dil) >= (unsigned)p.H) mask |= p.row_taps << (ky * p.kw);
         for (int kx = 0; kx < p.kw; ++kx)
-            if ((unsigned)(ix0 + kx) >= (unsigned)p.W) mask |= p.col_taps << kx;
+            if ((unsigned)(ix0 + kx * p.dil) >= (unsigned)p.W) mask |= p.col_taps << kx;
         a_mask[j] = mask;
     }
 #pragma unroll
@@ -544,7 +545,8 @@ extern "C" int qnn_encode_levels_fp4(const void *src, int dtype, int64_t count, 
 // convolution and must refuse a bad call as a whole).
 static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
                           const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
-                          int8_t *next_levels, float next_clip, int next_bits, void *stream, bool check_only = false)
+                          int8_t *next_levels, float next_clip, int next_bits, void *stream, bool check_only = false,
+                          int dilation = 1)
 {
     const int max_bits = fp4 ? 2 : 7;
     if (!d) return fail(QNN_ERR_INVALID_ARG, "%s: NULL descriptor", who);
@@ -562,7 +564,10 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
         return fail(QNN_ERR_INVALID_ARG, "%s: bad tensor size", who);
     if (d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
         return fail(QNN_ERR_INVALID_ARG, "%s: bad kernel geometry", who);
-    if (d->H + 2 * (int64_t)d->pad < d->kh || d->W + 2 * (int64_t)d->pad < d->kw)
+    if (dilation < 1) return fail(QNN_ERR_INVALID_ARG, "%s: dilation must be at least 1", who);
+    if (dilation > 64) return fail(QNN_ERR_UNSUPPORTED, "%s: dilation above 64", who);
+    const int64_t eh = (int64_t)dilation * (d->kh - 1) + 1, ew = (int64_t)dilation * (d->kw - 1) + 1; // extent of the taps
+    if (d->H + 2 * (int64_t)d->pad < eh || d->W + 2 * (int64_t)d->pad < ew)
         return fail(QNN_ERR_INVALID_ARG, "%s: kernel larger than the padded image", who);
     if (!acc && !out && !next_levels) return fail(QNN_ERR_INVALID_ARG, "%s: no output requested", who);
     if ((out || next_levels) && !scale)
@@ -588,12 +593,12 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
                     d->w_bits, d->a_bits);
     if (fp4 && n * ((1 << d->w_bits) - 1) * ((1 << d->a_bits) - 1) >= (1LL << 24))
         return fail(QNN_ERR_RANGE, "%s: reduction length %lld exceeds the exact range of fp32 accumulation", who, (long long)n);
-    const int64_t Ho = (d->H + 2 * (int64_t)d->pad - d->kh) / d->stride + 1;
-    const int64_t Wo = (d->W + 2 * (int64_t)d->pad - d->kw) / d->stride + 1;
+    const int64_t Ho = (d->H + 2 * (int64_t)d->pad - eh) / d->stride + 1;
+    const int64_t Wo = (d->W + 2 * (int64_t)d->pad - ew) / d->stride + 1;
     // the kernel indexes both tensors and the output pixels with 32-bit integers
     if (d->H > (1 << 20) || d->W > (1 << 20) || d->B > (1LL << 31) / (d->H * d->W * cinb) - 1 ||
         d->B > ((1LL << 31) - 1025) / (Ho * Wo) || d->Cout > ((1LL << 31) - 1) / nk ||
-        ((int64_t)d->kh * d->W + d->kw) * cinb >= (1LL << 24))
+        (eh * d->W + ew) * cinb >= (1LL << 24))
         return fail(QNN_ERR_RANGE, "%s: tensor too large for 32-bit indexing", who);
     if (d->B == 0) return QNN_OK;
     if (!a_levels || !w_levels) return fail(QNN_ERR_INVALID_ARG, "%s: NULL level pointer", who);
@@ -605,7 +610,7 @@ static int level_conv_run(const char *who, bool fp4, const qnn_conv_desc *d, con
     p.a = a_levels, p.w = w_levels, p.scale = scale, p.acc = acc, p.out = out, p.next = next_levels;
     p.blk = blk;
     p.H = (int)d->H, p.W = (int)d->W, p.Cin = (int)cinb, p.Cout = (int)d->Cout, p.Ho = (int)Ho, p.Wo = (int)Wo;
-    p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad;
+    p.kh = d->kh, p.kw = d->kw, p.stride = d->stride, p.pad = d->pad, p.dil = dilation;
     p.pixels = (int)(d->B * Ho * Wo);
     p.nk = (int)nk, p.units = (int)(nk / 16), p.nstages = 0;
     p.tiles_n = 0;
@@ -648,6 +653,14 @@ extern "C" int qnn_level_conv2d_i8(const qnn_conv_desc *d, const int8_t *a_level
 {
     return level_conv_run("qnn_level_conv2d_i8", false, d, a_levels, w_levels, scale, nullptr, acc, out, next_levels,
                           next_clip, next_bits, stream);
+}
+
+extern "C" int qnn_level_conv2d_dilated_i8(const qnn_conv_desc *d, int dilation, const int8_t *a_levels, const int8_t *w_levels,
+                                           const float *scale, int32_t *acc, float *out, int8_t *next_levels,
+                                           float next_clip, int next_bits, void *stream)
+{
+    return level_conv_run("qnn_level_conv2d_dilated_i8", false, d, a_levels, w_levels, scale, nullptr, acc, out, next_levels,
+                          next_clip, next_bits, stream, false, dilation);
 }
 
 extern "C" int qnn_level_conv2d_block_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,

@@ -26,7 +26,7 @@ QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d", "qnn_conv2d_block",
-           "qnn_conv2d_chain_static", "qnn_conv2d_chain_static_max_outputs",
+           "qnn_conv2d_chain_static", "qnn_conv2d_chain_static_max_outputs", "qnn_conv2d_dilated", "qnn_level_conv2d_dilated_i8",
            "qnn_level_conv2d_block_i8", "qnn_deconv_phase_words", "qnn_deconv_pack_weights", "qnn_deconv2d",
            "qnn_quantize_ste_backward", "qnn_encoder_backward",
            "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
@@ -138,6 +138,9 @@ def lib():
         L.qnn_encode_levels_i8.restype = i32
         L.qnn_level_conv2d_i8.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_level_conv2d_i8.restype = i32
+        for f in (L.qnn_conv2d_dilated, L.qnn_level_conv2d_dilated_i8):
+            f.argtypes = [ctypes.POINTER(qnn_conv_desc), i32, vp, vp, vp, vp, vp, vp, f32, i32, vp]
+            f.restype = i32
         L.qnn_deconv_phase_words.argtypes = [i32, i64, i32, i32, i64, i32]
         L.qnn_deconv_phase_words.restype = i64
         L.qnn_deconv_pack_weights.argtypes = [vp, i32, i64, i32, i32, i64, i32, vp, vp]
@@ -414,14 +417,14 @@ def _block_epilogue(bias, res_q, res_bits, res_scale, res_f32, relu=False):
     return qnn_block_epilogue(_ptr(bias), _ptr(res_q), int(res_bits), float(res_scale), _ptr(res_f32), int(bool(relu)))
 
 
-def _conv_out_shape(H, W, kh, kw, stride, pad):
-    if stride < 1:
-        raise ValueError("stride must be positive")
-    return (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+def _conv_out_shape(H, W, kh, kw, stride, pad, dilation=1):
+    if stride < 1 or dilation < 1:
+        raise ValueError("stride and dilation must be positive")
+    return (H + 2 * pad - dilation * (kh - 1) - 1) // stride + 1, (W + 2 * pad - dilation * (kw - 1) - 1) // stride + 1
 
 
 def _level_conv(entry, epi_args, dtypes, per_byte, a_levels, w_levels, stride, pad, a_bits, w_bits, scale, want_acc,
-                want_out, next_clip, next_bits, acc, out, next_levels):
+                want_out, next_clip, next_bits, acc, out, next_levels, dilation=None):
     """Shared by the int8 (per_byte = 1) and fp4 (per_byte = 2 channels per byte) level convolutions."""
     _arg("a_levels", a_levels, dtypes)
     _arg("w_levels", w_levels, dtypes)
@@ -430,7 +433,7 @@ def _level_conv(entry, epi_args, dtypes, per_byte, a_levels, w_levels, stride, p
                          % (tuple(a_levels.shape), tuple(w_levels.shape)))
     B, H, W, cb = (int(e) for e in a_levels.shape)
     cout, kh, kw, _ = (int(e) for e in w_levels.shape)
-    ho, wo = _conv_out_shape(H, W, kh, kw, stride, pad)
+    ho, wo = _conv_out_shape(H, W, kh, kw, stride, pad, 1 if dilation is None else dilation)
     _arg("scale", scale, _F32, shape=(cout,), optional=True)
     d = qnn_conv_desc(B, H, W, per_byte * cb, cout, kh, kw, stride, pad, a_bits, w_bits)
     acc = _out("acc", acc, torch.int32, (B, ho, wo, cout), a_levels, want_acc)
@@ -444,7 +447,7 @@ def _level_conv(entry, epi_args, dtypes, per_byte, a_levels, w_levels, stride, p
         _arg("res_levels", res_levels, dtypes, numel=B * ho * wo * (cout // per_byte), optional=True)
         _arg("res_f32", res_f32, _F32, numel=B * ho * wo * cout, optional=True)
         epi = _block_epilogue(bias, res_levels, res_bits, res_scale, res_f32, relu)
-    head = (ctypes.byref(d), _ptr(a_levels), _ptr(w_levels), _ptr(scale))
+    head = (ctypes.byref(d),) + (() if dilation is None else (int(dilation),)) + (_ptr(a_levels), _ptr(w_levels), _ptr(scale))
     tail = (_ptr(acc), _ptr(out), _ptr(next_levels), float(next_clip) if next_clip is not None else 0.0,
             int(next_bits), _stream())
     _check(entry(*head, *tail) if epi is None else entry(*head, ctypes.byref(epi), *tail))
@@ -457,6 +460,13 @@ def qnn_level_conv2d_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale=N
     entries not requested are None."""
     return _level_conv(lib().qnn_level_conv2d_i8, None, _I8, 1, a_levels, w_levels, stride, pad, a_bits, w_bits, scale,
                        want_acc, want_out, next_clip, next_bits, acc, out, next_levels)
+
+
+def qnn_level_conv2d_dilated_i8(a_levels, w_levels, stride, pad, dilation, a_bits, w_bits, scale=None, want_acc=True,
+                                want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """qnn_level_conv2d_i8 with the taps `dilation` pixels apart."""
+    return _level_conv(lib().qnn_level_conv2d_dilated_i8, None, _I8, 1, a_levels, w_levels, stride, pad, a_bits, w_bits,
+                       scale, want_acc, want_out, next_clip, next_bits, acc, out, next_levels, dilation=dilation)
 
 
 def qnn_level_conv2d_block_i8(a_levels, w_levels, stride, pad, a_bits, w_bits, scale, bias=None, res_levels=None,
@@ -726,11 +736,11 @@ def qnn_dequant_scale(acc, scale, out=None):
 
 
 def _conv(entry, epi_args, a_planes, w_planes, shape, cin, stride, pad, scale, want_acc, want_out, next_clip, next_bits,
-          acc, out, next_planes):
+          acc, out, next_planes, dilation=None):
     B, H, W = shape
     w_bits, cout, kh, kw, _ = _conv_w_planes(w_planes, cin)
     a_bits = _act_planes("a_planes", a_planes, B, H, W, cin)
-    ho, wo = _conv_out_shape(H, W, kh, kw, stride, pad)
+    ho, wo = _conv_out_shape(H, W, kh, kw, stride, pad, 1 if dilation is None else dilation)
     _arg("scale", scale, _F32, shape=(cout,), optional=True)
     d = qnn_conv_desc(B, H, W, cin, cout, kh, kw, stride, pad, a_bits, w_bits)
     acc = _out("acc", acc, torch.int32, (B, ho, wo, cout), a_planes, want_acc)
@@ -748,7 +758,7 @@ def _conv(entry, epi_args, a_planes, w_planes, shape, cin, stride, pad, scale, w
                              % (res_planes.numel(), res_bits, B * ho * wo, (cout + 31) // 32))
         _arg("res_f32", res_f32, _F32, numel=B * ho * wo * cout, optional=True)
         epi = _block_epilogue(bias, res_planes, res_bits, res_scale, res_f32, relu)
-    head = (ctypes.byref(d), _ptr(a_planes), _ptr(w_planes), _ptr(scale))
+    head = (ctypes.byref(d),) + (() if dilation is None else (int(dilation),)) + (_ptr(a_planes), _ptr(w_planes), _ptr(scale))
     tail = (_ptr(acc), _ptr(out), _ptr(next_planes), float(next_clip) if next_clip is not None else 0.0,
             int(next_bits), _stream())
     _check(entry(*head, *tail) if epi is None else entry(*head, ctypes.byref(epi), *tail))
@@ -761,6 +771,13 @@ def qnn_conv2d(a_planes, w_planes, shape, cin, stride, pad, scale=None, want_acc
     [w_bits][Cout][kh][kw][cw].  Returns (acc, out, next_planes); entries not requested are None."""
     return _conv(lib().qnn_conv2d, None, a_planes, w_planes, shape, cin, stride, pad, scale, want_acc, want_out,
                  next_clip, next_bits, acc, out, next_planes)
+
+
+def qnn_conv2d_dilated(a_planes, w_planes, shape, cin, stride, pad, dilation, scale=None, want_acc=True, want_out=False,
+                       next_clip=None, next_bits=0, acc=None, out=None, next_planes=None):
+    """qnn_conv2d with the taps `dilation` pixels apart."""
+    return _conv(lib().qnn_conv2d_dilated, None, a_planes, w_planes, shape, cin, stride, pad, scale, want_acc, want_out,
+                 next_clip, next_bits, acc, out, next_planes, dilation=dilation)
 
 
 def qnn_conv2d_block(a_planes, w_planes, shape, cin, stride, pad, scale, bias=None, res_planes=None, res_scale=0.0,

@@ -140,7 +140,7 @@ def vgg_ssd_stack(batch=32, bits=4, config_index=4, plan=VGG_SSD_PLAN):
 
 
 # --------------------------------------------------------------------------- detection network as one chain
-def _graph_conv(ci, t, name, src, cin, cout, k, bits, stride, pad, head=False):
+def _graph_conv(ci, t, name, src, cin, cout, k, bits, stride, pad, head=False, dilation=1):
     """A convolution node: weights uniform over the odd levels, per-channel scale that keeps unit-variance inputs at
     unit variance (heads: raw box / class scores of unit variance), input quantizer clipping at 3.0."""
     gen_w, gen_s = rng(ci, 10 + 2 * t), rng(ci, 11 + 2 * t)
@@ -149,7 +149,7 @@ def _graph_conv(ci, t, name, src, cin, cout, k, bits, stride, pad, head=False):
     s = g / np.sqrt(n * _uniform_level_variance(bits) * _gaussian_level_variance(bits))
     return {"kind": "conv", "name": name, "src": src, "w": odd_levels(gen_w, (cout, k, k, cin), bits),
             "scale": s.astype(np.float32), "clip": 3.0, "a_bits": bits, "w_bits": bits, "k": k, "stride": stride,
-            "pad": pad, "cin": cin, "cout": cout, "head": head}
+            "pad": pad, "cin": cin, "cout": cout, "head": head, "dilation": dilation}
 
 
 def _graph_pool(name, src, k, stride, pad=0, ceil_mode=False):
@@ -162,8 +162,8 @@ def vgg_ssd_chained(batch=32, bits=4, image=300, config_index=8, heads=True):
     at 75 -> 38), then the layers an SSD-style detector puts on top: a 3x3 stride-1 pooling, a 3x3 and a 1x1
     convolution with 1024 channels, four pairs of 1x1 / 3x3 convolutions that take the map from 19x19 down to
     1x1 (two with stride 2, two without padding), and a 3x3 localisation and a 3x3 class-score convolution on each
-    of the six maps the detector reads (4 or 6 boxes per position, 21 classes).  The original's dilated 3x3
-    convolution is an ordinary 3x3 here (dilation is not built).  Every quantizer clips at 3.0 except the
+    of the six maps the detector reads (4 or 6 boxes per position, 21 classes).  The 3x3 convolution to 1024 channels
+    has its taps 6 pixels apart (padding 6), as in the published network.  Every quantizer clips at 3.0 except the
     first (3 sigma of the input); heads write fp32 scores and feed nothing.
     Returns {"x", "clip0", "bits", "nodes"}: nodes in execution order, each naming its source node ("input" first)."""
     ci = config_index
@@ -171,9 +171,9 @@ def vgg_ssd_chained(batch=32, bits=4, image=300, config_index=8, heads=True):
     clip0 = float(np.float32(3.0 * np.std(x.astype(np.float64))))
     nodes, t = [], 0
 
-    def conv(name, src, cin, cout, k=3, stride=1, pad=1, head=False):
+    def conv(name, src, cin, cout, k=3, stride=1, pad=1, head=False, dilation=1):
         nonlocal t
-        nodes.append(_graph_conv(ci, t, name, src, cin, cout, k, bits, stride, pad, head))
+        nodes.append(_graph_conv(ci, t, name, src, cin, cout, k, bits, stride, pad, head, dilation))
         t += 1
         return name
 
@@ -198,7 +198,7 @@ def vgg_ssd_chained(batch=32, bits=4, image=300, config_index=8, heads=True):
     cur = conv("conv5_2", cur, 512, 512)
     cur = conv("conv5_3", cur, 512, 512)
     cur = pool("pool5", cur, k=3, stride=1, pad=1)
-    cur = conv("conv6", cur, 512, 1024)
+    cur = conv("conv6", cur, 512, 1024, pad=6, dilation=6)
     f2 = cur = conv("conv7", cur, 1024, 1024, k=1, pad=0)
     cur = conv("conv8_1", cur, 1024, 256, k=1, pad=0)
     f3 = cur = conv("conv8_2", cur, 256, 512, stride=2)

@@ -93,7 +93,13 @@ int main()
             EXPECT(qnn_deconv2d(&d, FAKE, FAKE, FF, nullptr, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
         EXPECT(qnn_level_conv2d_i8(&d, F8, F8, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
         EXPECT(qnn_level_conv2d_fp4(&d, FU, FU, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
+        EXPECT(qnn_conv2d_dilated(&d, 2, FAKE, FAKE, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
+        EXPECT(qnn_level_conv2d_dilated_i8(&d, 2, F8, F8, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), ANY_ERROR);
     }
+    EXPECT(qnn_conv2d_dilated(&ok, 0, FAKE, FAKE, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);
+    EXPECT(qnn_conv2d_dilated(&ok, INT32_MAX, FAKE, FAKE, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_UNSUPPORTED);
+    EXPECT(qnn_level_conv2d_dilated_i8(&ok, INT32_MAX, F8, F8, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_UNSUPPORTED);
+    EXPECT(qnn_conv2d_dilated(&ok, 5, FAKE, FAKE, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);
     EXPECT(qnn_conv2d(nullptr, FAKE, FAKE, FF, FI, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);
     EXPECT(qnn_conv2d(&ok, FAKE, FAKE, nullptr, nullptr, nullptr, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);
     EXPECT(qnn_conv2d(&ok, FAKE, FAKE, nullptr, nullptr, FF, nullptr, 0.0f, 0, nullptr), QNN_ERR_INVALID_ARG);

@@ -182,6 +182,25 @@ def test_deconv_argument_errors_and_phase_words(qnn):
     assert call(D(0, 8, 8, 64, 32, 4, 4, 2, 1, 2, 2)) == qnn.QNN_OK
 
 
+def test_dilated_convolution_argument_errors(qnn):
+    L = qnn.lib()
+    D = qnn.qnn_conv_desc
+    ok = D(1, 19, 19, 64, 64, 3, 3, 1, 6, 2, 2)
+    for entry in (L.qnn_conv2d_dilated, L.qnn_level_conv2d_dilated_i8):
+        def call(desc, dil, a=FAKE, w=FAKE, scale=None, acc=FAKE, out=None, nxt=None, clip=0.0, nbits=0):
+            return entry(ctypes.byref(desc) if desc is not None else None, dil, a, w, scale, acc, out, nxt, clip, nbits, None)
+        assert call(None, 1) == qnn.QNN_ERR_INVALID_ARG
+        assert call(ok, 0) == qnn.QNN_ERR_INVALID_ARG
+        assert call(ok, -3) == qnn.QNN_ERR_INVALID_ARG
+        assert call(ok, 65) == qnn.QNN_ERR_UNSUPPORTED
+        assert call(ok, 16) == qnn.QNN_ERR_INVALID_ARG               # taps 32 pixels apart do not fit 19 + 2 * 6
+        assert call(D(1, 8, 8, 64, 64, 3, 3, 1, 1, 2, 2), 2, acc=None) == qnn.QNN_ERR_INVALID_ARG
+        assert call(ok, 6, out=FAKE) == qnn.QNN_ERR_INVALID_ARG      # out without scale
+        assert call(ok, 6, w=ODD) == qnn.QNN_ERR_ALIGNMENT
+        assert call(ok, 6, a=None) == qnn.QNN_ERR_INVALID_ARG
+        assert call(D(0, 19, 19, 64, 64, 3, 3, 1, 6, 2, 2), 6) == qnn.QNN_OK
+
+
 def test_level_deconv_argument_errors_and_workspace(qnn):
     L = qnn.lib()
     D = qnn.qnn_conv_desc

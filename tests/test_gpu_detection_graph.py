@@ -2,8 +2,8 @@
 joined by max-pooling on the codes, the SSD-style extra layers down to 1x1, localisation / class heads on six maps)
 against oracle.layer_graph, on both machine routes:
 
-  planes: qnn_encode_pack -> qnn_conv2d (fused next-layer planes) / qnn_maxpool_planes; heads write fp32
-  levels: qnn_encode_levels_i8 -> qnn_level_conv2d_i8 / qnn_maxpool_levels_i8
+  planes: qnn_encode_pack -> qnn_conv2d / qnn_conv2d_dilated (fused next-layer planes) / qnn_maxpool_planes; heads write fp32
+  levels: qnn_encode_levels_i8 -> qnn_level_conv2d_i8 / qnn_level_conv2d_dilated_i8 / qnn_maxpool_levels_i8
 
 batch 1: every accumulator, every plane / level tensor, every fp32 head output; batch 32 (the benchmark's): every
 plane / level tensor between layers and every head output, in the fused configuration the benchmark times."""
@@ -36,12 +36,16 @@ def run_graph_planes(net, keep_acc):
             continue
         k = nd["k"]
         wp = pack_levels(nd["w"], bits).view(bits, nd["cout"], k, k, -1)
-        ho = (H + 2 * nd["pad"] - k) // nd["stride"] + 1
+        dil = nd.get("dilation", 1)
+        ho = (H + 2 * nd["pad"] - dil * (k - 1) - 1) // nd["stride"] + 1
         head = nd["head"]
         # above 4 bits the plane-chunk launches keep their running sum in acc
-        acc, out, nxt = qnn.qnn_conv2d(planes, wp, (B, H, W), C, nd["stride"], nd["pad"], scale=dev(nd["scale"]),
-                                       want_acc=keep_acc or bits > 4, want_out=head,
-                                       next_clip=None if head else nd["clip"], next_bits=0 if head else bits)
+        kw = dict(scale=dev(nd["scale"]), want_acc=keep_acc or bits > 4, want_out=head,
+                  next_clip=None if head else nd["clip"], next_bits=0 if head else bits)
+        if dil == 1:
+            acc, out, nxt = qnn.qnn_conv2d(planes, wp, (B, H, W), C, nd["stride"], nd["pad"], **kw)
+        else:
+            acc, out, nxt = qnn.qnn_conv2d_dilated(planes, wp, (B, H, W), C, nd["stride"], nd["pad"], dil, **kw)
         vals[nd["name"]] = (nxt, acc if keep_acc else None, out, (ho, ho, nd["cout"]))
     torch.cuda.synchronize()
     return vals
@@ -57,9 +61,13 @@ def run_graph_levels(net, keep_acc):
             vals[nd["name"]] = (qnn.qnn_maxpool_levels_i8(lv, nd["k"], nd["stride"], nd["pad"], nd["ceil_mode"]), None, None)
             continue
         head = nd["head"]
-        acc, out, nxt = qnn.qnn_level_conv2d_i8(lv, dev(nd["w"]), nd["stride"], nd["pad"], bits, bits, scale=dev(nd["scale"]),
-                                                want_acc=keep_acc, want_out=head,
-                                                next_clip=None if head else nd["clip"], next_bits=0 if head else bits)
+        kw = dict(scale=dev(nd["scale"]), want_acc=keep_acc, want_out=head, next_clip=None if head else nd["clip"],
+                  next_bits=0 if head else bits)
+        if nd.get("dilation", 1) == 1:
+            acc, out, nxt = qnn.qnn_level_conv2d_i8(lv, dev(nd["w"]), nd["stride"], nd["pad"], bits, bits, **kw)
+        else:
+            acc, out, nxt = qnn.qnn_level_conv2d_dilated_i8(lv, dev(nd["w"]), nd["stride"], nd["pad"], nd["dilation"], bits,
+                                                            bits, **kw)
         vals[nd["name"]] = (nxt, acc, out)
     torch.cuda.synchronize()
     return vals

@@ -1,0 +1,88 @@
+"""GPU parity of the convolution with dilated taps (qnn_conv2d_dilated on bit-planes, qnn_level_conv2d_dilated_i8 on
+decoded levels) against the CPU oracle: accumulators bit-exact, fp32 out within 1e-5, the next layer's planes /
+levels bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import dev, levels, pack_levels, planes_to_numpy
+
+pytestmark = pytest.mark.gpu
+
+from paper_1905_13389_amd import qnn  # noqa: E402
+
+RTOL = 1e-5
+
+GEOMS = [
+    # B, H, W, Cin, Cout, kh, kw, stride, pad, dilation
+    (2, 19, 19, 64, 48, 3, 3, 1, 6, 6),     # the detection network's layer shape (fewer channels)
+    (1, 19, 19, 512, 64, 3, 3, 1, 6, 6),    # its reduction length: 144 words, streamed in stages
+    (2, 9, 11, 32, 8, 3, 3, 1, 2, 2),
+    (1, 10, 9, 64, 70, 3, 2, 2, 1, 3),      # rectangular kernel, stride 2, two column tiles
+    (1, 7, 7, 96, 5, 2, 2, 1, 0, 4),        # no padding: the output shrinks by dilation (k - 1)
+    (3, 5, 5, 128, 16, 3, 3, 1, 4, 4),      # whole rows of taps outside the image for every pixel but the centre
+    (1, 6, 6, 32, 4, 1, 1, 1, 0, 5),        # 1x1: dilation has no effect
+    (2, 12, 12, 64, 64, 5, 5, 1, 4, 2),     # 25 taps
+    (1, 33, 17, 16, 33, 3, 3, 2, 3, 3),     # ragged everything
+]
+
+
+def _case(geom, w_bits, a_bits):
+    B, H, W, Cin, Cout, kh, kw, stride, pad, dil = geom
+    gen = np.random.default_rng(sum(geom) * 10 + w_bits + a_bits)
+    a, w = levels(gen, (B, H, W, Cin), a_bits), levels(gen, (Cout, kh, kw, Cin), w_bits)
+    var = (4.0 ** w_bits - 1) / 3 * (4.0 ** a_bits - 1) / 3
+    s = (gen.uniform(0.5, 1.5, size=Cout) / np.sqrt(kh * kw * Cin * var)).astype(np.float32)
+    return a, w, s
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+@pytest.mark.parametrize("bits", [(2, 2), (3, 3), (4, 4), (1, 1), (4, 1), (5, 6)])
+def test_dilated_conv_planes(geom, bits):
+    B, H, W, Cin, Cout, kh, kw, stride, pad, dil = geom
+    w_bits, a_bits = bits
+    a, w, s = _case(geom, w_bits, a_bits)
+    wp = pack_levels(w, w_bits).view(w_bits, Cout, kh, kw, -1)
+    acc, out, nxt = qnn.qnn_conv2d_dilated(pack_levels(a, a_bits), wp, (B, H, W), Cin, stride, pad, dil, scale=dev(s),
+                                           want_out=True, next_clip=2.5, next_bits=3)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(a, w, stride, pad, dil)
+    assert acc.shape == want.shape
+    assert np.array_equal(acc.cpu().numpy(), want)
+    wout = oracle.scale(want, s)
+    np.testing.assert_allclose(out.cpu().numpy(), wout, rtol=RTOL, atol=0)
+    lv, _ = oracle.quantize(wout, 2.5, 3)
+    assert np.array_equal(planes_to_numpy(nxt), oracle.pack_planes(lv.reshape(-1, Cout), 3))
+    if dil == 1 or (kh == 1 and kw == 1):
+        acc1, _, _ = qnn.qnn_conv2d(pack_levels(a, a_bits), wp, (B, H, W), Cin, stride, pad)
+        assert torch.equal(acc1, acc)
+
+
+@pytest.mark.parametrize("geom", [g for g in GEOMS if g[3] % 16 == 0])
+@pytest.mark.parametrize("bits", [(2, 2), (4, 4), (7, 7), (3, 1)])
+def test_dilated_conv_levels(geom, bits):
+    B, H, W, Cin, Cout, kh, kw, stride, pad, dil = geom
+    w_bits, a_bits = bits
+    a, w, s = _case(geom, w_bits, a_bits)
+    acc, out, nxt = qnn.qnn_level_conv2d_dilated_i8(dev(a), dev(w), stride, pad, dil, a_bits, w_bits, scale=dev(s),
+                                                    want_out=True, next_clip=2.5, next_bits=3)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(a, w, stride, pad, dil)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    wout = oracle.scale(want, s)
+    np.testing.assert_allclose(out.cpu().numpy(), wout, rtol=RTOL, atol=0)
+    lv, _ = oracle.quantize(wout, 2.5, 3)
+    assert np.array_equal(nxt.cpu().numpy(), lv.astype(np.int8))
+
+
+def test_dilation_one_is_the_plain_convolution():
+    gen = np.random.default_rng(5)
+    a, w = levels(gen, (2, 14, 14, 64), 2), levels(gen, (64, 3, 3, 64), 2)
+    ap, wp = pack_levels(a, 2), pack_levels(w, 2).view(2, 64, 3, 3, -1)
+    acc0, _, _ = qnn.qnn_conv2d(ap, wp, (2, 14, 14), 64, 1, 1)
+    acc1, _, _ = qnn.qnn_conv2d_dilated(ap, wp, (2, 14, 14), 64, 1, 1, 1)
+    lacc0, _, _ = qnn.qnn_level_conv2d_i8(dev(a), dev(w), 1, 1, 2, 2)
+    lacc1, _, _ = qnn.qnn_level_conv2d_dilated_i8(dev(a), dev(w), 1, 1, 1, 2, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(acc0, acc1) and torch.equal(lacc0, lacc1) and torch.equal(acc0, lacc0)

@@ -32,7 +32,7 @@ def test_small_detection_graph_against_library_float64_routines():
         if nd["kind"] == "pool":
             s_out = oracle.pool_out_size(s_in, nd["k"], nd["stride"], nd["pad"], nd["ceil_mode"])
         else:
-            s_out = (s_in + 2 * nd["pad"] - nd["k"]) // nd["stride"] + 1
+            s_out = (s_in + 2 * nd["pad"] - nd.get("dilation", 1) * (nd["k"] - 1) - 1) // nd["stride"] + 1
         if s_out < 1:
             continue
         size[nd["name"]] = s_out
@@ -54,7 +54,7 @@ def test_small_detection_graph_against_library_float64_routines():
             assert np.array_equal(_nhwc(r), got[nd["name"]]["levels"].astype(np.float64)), nd["name"]
             continue
         w = torch.from_numpy(nd["w"].transpose(0, 3, 1, 2).astype(np.float64))
-        acc = F.conv2d(src, w, stride=nd["stride"], padding=nd["pad"])
+        acc = F.conv2d(src, w, stride=nd["stride"], padding=nd["pad"], dilation=nd.get("dilation", 1))
         assert np.array_equal(_nhwc(acc), got[nd["name"]]["acc"].astype(np.float64)), nd["name"]
         # the scale is one fp32 multiply of the exact integer; the next quantizer acts on that fp32 value
         out32 = (_nhwc(acc).astype(np.float32) * nd["scale"].astype(np.float32)[None, None, None, :]).astype(np.float32)
@@ -87,7 +87,7 @@ def test_full_size_graph_shapes_and_busy_levels():
             chans[nd["name"]] = chans[nd["src"]]
         else:
             assert nd["cin"] == chans[nd["src"]], nd["name"]
-            size[nd["name"]] = (s_in + 2 * nd["pad"] - nd["k"]) // nd["stride"] + 1
+            size[nd["name"]] = (s_in + 2 * nd["pad"] - nd.get("dilation", 1) * (nd["k"] - 1) - 1) // nd["stride"] + 1
             chans[nd["name"]] = nd["cout"]
     assert [size[k] for k in ("pool1", "pool2", "pool3", "pool4", "pool5", "conv8_2", "conv9_2", "conv10_2", "conv11_2")] \
         == [150, 75, 38, 19, 19, 10, 5, 3, 1]
