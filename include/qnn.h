@@ -136,7 +136,7 @@ int qnn_conv2d(const qnn_conv_desc *desc, const uint32_t *a_planes, const uint32
  * / stride + 1.  The detection network of the experiments section (SSD on a backbone) has one such layer.  Everything
  * else -- operands, outputs, the fused next-layer epilogue, padding, bit widths, errors -- as qnn_conv2d;
  * dilation = 1 is qnn_conv2d.  QNN_ERR_INVALID_ARG for dilation < 1, QNN_ERR_UNSUPPORTED above 64.
- * qnn_level_conv2d_dilated_i8: the same for qnn_level_conv2d_i8 (matrix-core route).
+ * qnn_level_conv2d_dilated_i8 / _fp4: the same for qnn_level_conv2d_i8 / qnn_level_conv2d_fp4 (matrix-core route).
  */
 int qnn_conv2d_dilated(const qnn_conv_desc *desc, int dilation, const uint32_t *a_planes, const uint32_t *w_planes,
                        const float *scale, int32_t *acc, float *out, uint32_t *next_planes, float next_clip,
@@ -144,6 +144,9 @@ int qnn_conv2d_dilated(const qnn_conv_desc *desc, int dilation, const uint32_t *
 int qnn_level_conv2d_dilated_i8(const qnn_conv_desc *desc, int dilation, const int8_t *a_levels, const int8_t *w_levels,
                                 const float *scale, int32_t *acc, float *out, int8_t *next_levels, float next_clip,
                                 int next_bits, void *stream);
+int qnn_level_conv2d_dilated_fp4(const qnn_conv_desc *desc, int dilation, const uint8_t *a_levels, const uint8_t *w_levels,
+                                 const float *scale, int32_t *acc, float *out, uint8_t *next_levels, float next_clip,
+                                 int next_bits, void *stream);
 
 /*
  * qnn_conv2d_chain_static -- qnn_conv2d in its layer-to-layer form (planes in, the next layer's planes out, no acc

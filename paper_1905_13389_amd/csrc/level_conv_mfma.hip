@@ -663,6 +663,15 @@ extern "C" int qnn_level_conv2d_dilated_i8(const qnn_conv_desc *d, int dilation,
                           next_clip, next_bits, stream, false, dilation);
 }
 
+extern "C" int qnn_level_conv2d_dilated_fp4(const qnn_conv_desc *d, int dilation, const uint8_t *a_levels, const uint8_t *w_levels,
+                                            const float *scale, int32_t *acc, float *out, uint8_t *next_levels,
+                                            float next_clip, int next_bits, void *stream)
+{
+    return level_conv_run("qnn_level_conv2d_dilated_fp4", true, d, reinterpret_cast<const int8_t *>(a_levels),
+                          reinterpret_cast<const int8_t *>(w_levels), scale, nullptr, acc, out,
+                          reinterpret_cast<int8_t *>(next_levels), next_clip, next_bits, stream, false, dilation);
+}
+
 extern "C" int qnn_level_conv2d_block_i8(const qnn_conv_desc *d, const int8_t *a_levels, const int8_t *w_levels,
                                          const float *scale, const qnn_block_epilogue *epi, int32_t *acc, float *out,
                                          int8_t *next_levels, float next_clip, int next_bits, void *stream)

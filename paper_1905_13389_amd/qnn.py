@@ -26,7 +26,7 @@ QNN_DTYPE_BF16 = 1
 QNN_DTYPE_I8 = 2
 
 EXPORTS = ("qnn_encode_pack", "qnn_binary_gemm", "qnn_dequant_scale", "qnn_conv2d", "qnn_conv2d_block",
-           "qnn_conv2d_chain_static", "qnn_conv2d_chain_static_max_outputs", "qnn_conv2d_dilated", "qnn_level_conv2d_dilated_i8",
+           "qnn_conv2d_chain_static", "qnn_conv2d_chain_static_max_outputs", "qnn_conv2d_dilated", "qnn_level_conv2d_dilated_i8", "qnn_level_conv2d_dilated_fp4",
            "qnn_level_conv2d_block_i8", "qnn_deconv_phase_words", "qnn_deconv_pack_weights", "qnn_deconv2d",
            "qnn_quantize_ste_backward", "qnn_encoder_backward",
            "qnn_level_row_bytes", "qnn_plane_sum_i8", "qnn_level_gemm_i8",
@@ -138,7 +138,7 @@ def lib():
         L.qnn_encode_levels_i8.restype = i32
         L.qnn_level_conv2d_i8.argtypes = [ctypes.POINTER(qnn_conv_desc), vp, vp, vp, vp, vp, vp, f32, i32, vp]
         L.qnn_level_conv2d_i8.restype = i32
-        for f in (L.qnn_conv2d_dilated, L.qnn_level_conv2d_dilated_i8):
+        for f in (L.qnn_conv2d_dilated, L.qnn_level_conv2d_dilated_i8, L.qnn_level_conv2d_dilated_fp4):
             f.argtypes = [ctypes.POINTER(qnn_conv_desc), i32, vp, vp, vp, vp, vp, vp, f32, i32, vp]
             f.restype = i32
         L.qnn_deconv_phase_words.argtypes = [i32, i64, i32, i32, i64, i32]
@@ -466,6 +466,13 @@ def qnn_level_conv2d_dilated_i8(a_levels, w_levels, stride, pad, dilation, a_bit
                                 want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
     """qnn_level_conv2d_i8 with the taps `dilation` pixels apart."""
     return _level_conv(lib().qnn_level_conv2d_dilated_i8, None, _I8, 1, a_levels, w_levels, stride, pad, a_bits, w_bits,
+                       scale, want_acc, want_out, next_clip, next_bits, acc, out, next_levels, dilation=dilation)
+
+
+def qnn_level_conv2d_dilated_fp4(a_levels, w_levels, stride, pad, dilation, a_bits, w_bits, scale=None, want_acc=True,
+                                 want_out=False, next_clip=None, next_bits=0, acc=None, out=None, next_levels=None):
+    """qnn_level_conv2d_fp4 with the taps `dilation` pixels apart."""
+    return _level_conv(lib().qnn_level_conv2d_dilated_fp4, None, _U8, 2, a_levels, w_levels, stride, pad, a_bits, w_bits,
                        scale, want_acc, want_out, next_clip, next_bits, acc, out, next_levels, dilation=dilation)
 
 

@@ -186,7 +186,7 @@ def test_dilated_convolution_argument_errors(qnn):
     L = qnn.lib()
     D = qnn.qnn_conv_desc
     ok = D(1, 19, 19, 64, 64, 3, 3, 1, 6, 2, 2)
-    for entry in (L.qnn_conv2d_dilated, L.qnn_level_conv2d_dilated_i8):
+    for entry in (L.qnn_conv2d_dilated, L.qnn_level_conv2d_dilated_i8, L.qnn_level_conv2d_dilated_fp4):
         def call(desc, dil, a=FAKE, w=FAKE, scale=None, acc=FAKE, out=None, nxt=None, clip=0.0, nbits=0):
             return entry(ctypes.byref(desc) if desc is not None else None, dil, a, w, scale, acc, out, nxt, clip, nbits, None)
         assert call(None, 1) == qnn.QNN_ERR_INVALID_ARG

@@ -76,6 +76,32 @@ def test_dilated_conv_levels(geom, bits):
     assert np.array_equal(nxt.cpu().numpy(), lv.astype(np.int8))
 
 
+def _nibbles(lv):
+    lv = np.asarray(lv).astype(np.int64)
+    code = np.where(lv < 0, 8, 0) | np.where(np.abs(lv) == 3, 5, 2)
+    return (code[..., 0::2] | (code[..., 1::2] << 4)).astype(np.uint8)
+
+
+@pytest.mark.parametrize("geom", [g for g in GEOMS if g[3] % 32 == 0])
+@pytest.mark.parametrize("bits", [(2, 2), (1, 2)])
+def test_dilated_conv_fp4_levels(geom, bits):
+    B, H, W, Cin, Cout, kh, kw, stride, pad, dil = geom
+    w_bits, a_bits = bits
+    a, w, s = _case(geom, w_bits, a_bits)
+    even = Cout % 2 == 0
+    acc, out, nxt = qnn.qnn_level_conv2d_dilated_fp4(qnn.qnn_levels_to_fp4(dev(a)), qnn.qnn_levels_to_fp4(dev(w)), stride, pad, dil,
+                                                     a_bits, w_bits, scale=dev(s), want_out=True,
+                                                     next_clip=2.5 if even else None, next_bits=2 if even else 0)
+    torch.cuda.synchronize()
+    want = oracle.conv2d(a, w, stride, pad, dil)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    wout = oracle.scale(want, s)
+    np.testing.assert_allclose(out.cpu().numpy(), wout, rtol=RTOL, atol=0)
+    if even:
+        lv, _ = oracle.quantize(wout, 2.5, 2)
+        assert np.array_equal(nxt.cpu().numpy(), _nibbles(lv))
+
+
 def test_dilation_one_is_the_plain_convolution():
     gen = np.random.default_rng(5)
     a, w = levels(gen, (2, 14, 14, 64), 2), levels(gen, (64, 3, 3, 64), 2)
