@@ -36,7 +36,7 @@ PEAK_NOTE = ("v_xor_b32 at 32 lanes/clk/SIMD (2 cycles per wave64) + v_bcnt_u32_
 
 # HBM bytes of one default-workload GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/bgemm_2x2_4096_hbm_counters.txt); only valid for size 4096, 2x2 bit
-GEMM_2X2_4096_TRAFFIC_BYTES = 205.9e6
+GEMM_2X2_4096_TRAFFIC_BYTES = 206.1e6
 
 # HIP event pairs are put around every EVENT_EVERY-th GEMM launch of a timed region
 EVENT_EVERY = 5
