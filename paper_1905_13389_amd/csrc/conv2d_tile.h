@@ -666,13 +666,24 @@ template <typename K> static int resident_workgroups(K kernel, int threads, size
 // waits, and the streamed reductions gain 5 .. 24 % from the two extra waves; the lane tiles shrink to stay
 // inside 128 registers.  The column tile stays a multiple of 32 channels because the fused epilogue packs whole
 // plane words.
+// One-stage picks, measured again with the pair balance in place (which took away most of what 512 lanes lost to
+// the 256-lane tiles): 2 or 3 planes in all 2 x 4 outputs per lane (-19 .. -25 % against 1 x 4 at 64 -> 64 @56x56,
+// batch 256); 4 planes 1 x 4, or 2 x 4 when every resident workgroup has about ten or more 64-row tiles (-3 % at 2x2
+// bit, -10 % at 1x3 bit for batch 256; +5 .. +20 % with fewer tiles than that: kOneStageTallTiles); 5 planes 2 x 4
+// with 8-byte LDS reads (-7 .. -13 % against 4 x 4 at 256 lanes); 6 planes stay at 4 x 4 on 256 lanes (2 x 4 at 512
+// lanes: +1 % at 3x3 bit, +6 % at 2x4 bit); 7 and 8 planes 1 x 4 (2 x 4: +10 %).
 template <int WB, int AB> struct ConvPickOneStage { // (TM, TN, KV, NT)
     static constexpr int S = WB + AB;
-    static constexpr int TM = S <= 4 ? 1 : S <= 6 ? 4 : 1;
+    static constexpr int TM = S <= 3 ? 2 : S == 4 ? 1 : S == 5 ? 2 : S == 6 ? 4 : 1;
     static constexpr int TN = 4;
-    static constexpr int KV = S <= 4 ? 4 : S <= 5 ? 4 : 2;
-    static constexpr int NT = S <= 4 ? 512 : S <= 6 ? 256 : 512;
+    static constexpr int KV = S <= 4 ? 4 : 2;
+    static constexpr int NT = S == 6 ? 256 : 512;
 };
+// 4 planes in all and many row tiles per workgroup
+template <int WB, int AB> struct ConvPickOneStageTall {
+    static constexpr int TM = 2, TN = 4, KV = 4, NT = 512;
+};
+constexpr int64_t kOneStageTallTiles = 10; // 64-row tiles per resident workgroup from which the taller tile pays
 template <int WB, int AB> struct ConvPickStreamed {
     static constexpr int S = WB + AB;
     static constexpr int TM = 2;
@@ -737,7 +748,16 @@ static int launch_conv_tile(const ConvTileParams &p, hipStream_t st)
 template <int WB, int AB, bool BLK> static int launch_conv(const ConvTileParams &p, hipStream_t st)
 {
     // a reduction of at most kConvKB words is one stage (the stage length chosen above is then kConvKB)
-    if (p.nw <= kConvKB) return launch_conv_tile<WB, AB, BLK, ConvPickOneStage<WB, AB>, true>(p, st);
+    if (p.nw <= kConvKB) {
+        if constexpr (WB + AB == 4) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) == hipSuccess &&
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 &&
+                ceil_div(p.M, 64) * ceil_div(p.Cout, 64) >= kOneStageTallTiles * 2 * cus)
+                return launch_conv_tile<WB, AB, BLK, ConvPickOneStageTall<WB, AB>, true>(p, st);
+        }
+        return launch_conv_tile<WB, AB, BLK, ConvPickOneStage<WB, AB>, true>(p, st);
+    }
     return launch_conv_tile<WB, AB, BLK, ConvPickStreamed<WB, AB>, false>(p, st);
 }
 
