@@ -23,6 +23,11 @@ CASES = [
     (2, 300, 290, 64, 33, 3, 2, 1, 3, 1),    # stride 2: 150 x 145 outputs per image
     (5, 100, 100, 96, 64, 1, 1, 0, 2, 1),    # 1x1 kernel, 50000 rows
     (2, 160, 150, 64, 128, 3, 1, 1, 2, 2),   # two column tiles: 256 workgroups per column
+    # one-stage reductions with 4 planes in all and ten or more 64-row tiles per resident workgroup: the taller
+    # 2 x 4 lane tile is chosen (5120 tiles of 64 rows on a chip that holds 512 workgroups)
+    (7, 230, 210, 32, 64, 3, 1, 1, 2, 2),    # 338100 rows, ragged last tile
+    (6, 250, 230, 64, 40, 3, 1, 1, 1, 3),    # 345000 rows, ragged channels
+    (3, 250, 230, 32, 128, 3, 1, 1, 3, 1),   # two column tiles make up the count
 ]
 
 
