@@ -684,11 +684,14 @@ template <int WB, int AB> struct ConvPickOneStageTall {
     static constexpr int TM = 2, TN = 4, KV = 4, NT = 512;
 };
 constexpr int64_t kOneStageTallTiles = 10; // 64-row tiles per resident workgroup from which the taller tile pays
+// Streamed picks.  7 and 8 planes in all: 2 x 2 outputs per lane and 8-byte LDS reads, the shape the GEMM uses at 4x4 bit;
+// its two stage buffers take 60 KB, so two workgroups share a CU (four waves per SIMD, balanced as a pair), where the
+// 2 x 4 tile's 80 KB left room for one: -2 .. -6 % on the 4x4-bit layers of the detection stack, -16 % at 4x3 bit.
 template <int WB, int AB> struct ConvPickStreamed {
     static constexpr int S = WB + AB;
     static constexpr int TM = 2;
-    static constexpr int TN = S <= 4 ? 4 : S <= 6 ? 2 : 4;
-    static constexpr int KV = S <= 4 ? 2 : 4;
+    static constexpr int TN = S <= 4 ? 4 : 2;
+    static constexpr int KV = S <= 4 ? 2 : S <= 6 ? 4 : 2;
     static constexpr int NT = 512;
 };
 
