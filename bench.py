@@ -93,14 +93,80 @@ def mfma_probe(torch):
         e1.record()
         torch.cuda.synchronize()
         res[name] = round(ops * 16.0 * iters * wgs * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    # the same loops on operands from memory: what they hold sets the power drawn and with it the clock
+    gen = torch.Generator().manual_seed(190513389)
+    n = 256 * 8 * 16
+    clocks = torch.zeros((wgs * 4, 2), dtype=torch.int64, device="cuda")
+    by_data = {}
+    for mode, name, ops in ((0, "int8", 65536.0), (1, "fp4", 131072.0)):
+        lv = 2 * torch.randint(0, 4, (n,), generator=gen) - 3                       # levels of 2-bit codes
+        if mode == 1:
+            nib = torch.tensor([0xD, 0xA, 0x2, 0x5], dtype=torch.uint8)              # E2M1 codes of -3, -1, 1, 3
+            pick = torch.randint(0, 4, (n, 2), generator=gen)
+            levels = nib[pick[:, 0]] | (nib[pick[:, 1]] << 4)
+        else:
+            levels = lv.to(torch.int8).view(torch.uint8)
+        kinds = (("zeros", torch.zeros(n, dtype=torch.uint8)), ("levels_of_2bit_codes", levels),
+                 ("random_bytes", torch.randint(0, 256, (n,), generator=gen).to(torch.uint8)))
+        row = {}
+        for kind, host in kinds:
+            operands = host.cuda()
+            probe.qnn_probe_mfma_operands(mode, wgs, iters // 10, operands, buf)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            probe.qnn_probe_mfma_operands(mode, wgs, iters, operands, buf, clocks)
+            e1.record()
+            torch.cuda.synchronize()
+            c = clocks.double().mean(dim=0).tolist()
+            entry = {"tops": round(ops * 16.0 * iters * wgs * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)}
+            if c[1] > 0 and c[0] / c[1] > 1.5:    # s_memtime counts shader cycles
+                ghz = c[0] / c[1] * 0.1
+                entry["clock_ghz"] = round(ghz, 3)
+                # kernel time x clock / MFMAs per SIMD (a wave's own span is shorter: of the two waves of a SIMD the
+                # older one is served first and ends early)
+                entry["cycles_per_mfma_and_simd"] = round(e0.elapsed_time(e1) * 1e-3 * ghz * 1e9 / (16.0 * iters * wgs * 4 / SIMDS), 2)
+            row[kind] = entry
+        by_data[name] = row
+    res["by_operand_data"] = by_data
     return res
 
 
+SETTLE_MS = 300.0
+SETTLE_MAX_MS = 1500.0
+
+
+def settle(torch, fn):
+    """Call fn untimed, back to back (the clock only rises under load without gaps), in batches of about 20 ms with a
+    device synchronisation after each, until at least SETTLE_MS have passed and a batch is no longer more than 1 %
+    faster per call than the one before it (at most SETTLE_MAX_MS)."""
+    if SETTLE_MS <= 0:          # --no-settle: counter-collection runs, where every launch is serialised anyway
+        return
+    n, prev, spent = 4, None, 0.0
+    while spent < SETTLE_MAX_MS:
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) * 1e3
+        spent += dt
+        per = max(dt / n, 1e-4)
+        if spent >= SETTLE_MS and prev is not None and per > 0.99 * prev:
+            break
+        prev = per if dt >= 10.0 else None      # only batches long enough to show the pace are compared
+        n = min(max(4, int(20.0 / per) + 1), 20000)
+
+
 def timed_ms(torch, fn, steps, warmup):
-    """`warmup` untimed calls, then exactly `steps` calls bracketed by device synchronisations: ms per call."""
+    """`warmup` untimed calls, then exactly `steps` calls bracketed by device synchronisations: ms per call.
+    The chip raises its shader clock to the sustained value only under tens of milliseconds of continuous load (read
+    inside the kernels: an 80 us convolution runs at 2.05 GHz after 50 back-to-back launches and at 2.37 GHz after
+    500, where it takes 70 us; a process that starts from an idle device needs longer), so after the `warmup` calls the
+    workload is called untimed until its pace is steady (settle): the timed region then sees the clock a stream of such
+    steps sees."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
+    settle(torch, fn)       # the warm-up calls' wall time may be one-time set-up, not load: it is not counted
     t0 = time.perf_counter()
     for _ in range(steps):
         fn()
@@ -118,6 +184,9 @@ def parse():
     ap.add_argument("--a-bits", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="default workload only: leave out the summaries of configurations 1, 3, 4, 5")
+    ap.add_argument("--no-settle", action="store_true",
+                    help="skip the untimed calls that bring the clock to its sustained value before each timed region "
+                         "(for counter-collection runs under rocprofv3, which serialise the launches)")
     ap.add_argument("--repeats", type=int, default=5, help="default workload: repetitions of the K timed steps (the median is reported)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     ap.add_argument("--sweep", action="store_true", help="also print GEMM-only times for all 1..4 x 1..4 bits")
@@ -699,7 +768,7 @@ def probe_workload(args):
             "unit": "cycles per xor + count pair per SIMD (best occupancy)", "n_gpus": 1, "steps": 1, "warmup": 1,
             "ms_per_step": None, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
             "config": {"workload": "register-only loops of 64 VALU instructions x %d iterations per wave, 256 CUs" % iters},
-            "probe_matrix": table}
+            "probe_matrix": table, "mfma_probe": mfma_probe(torch)}
 
 
 def timeline_workload(args):
@@ -730,19 +799,17 @@ def timeline_workload(args):
             acc, out, nxt, ref = None, None, torch.empty_like(r_nxt), (r_nxt,)
         row = {}
         for hint in (False, True):
-            buf = torch.zeros((512 * 8, 4), dtype=torch.int64, device="cuda")
+            buf = torch.zeros((512 * 8, 5), dtype=torch.int64, device="cuda")
             probe.qnn_timeline_set(buf, pair_hint=hint)
             launch = lambda: probe.timeline_conv2d(d, ap, wp, sc, acc, out, nxt, 3.0, bits if nxt is not None else 0)  # noqa: E731
-            for _ in range(5):
-                launch()
-            torch.cuda.synchronize()
-            same = all(torch.equal(a, b) for a, b in zip(ref, [t for t in (acc, out, nxt) if t is not None]))
+            settle(torch, launch)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(10):
                 launch()
             e1.record()
             torch.cuda.synchronize()
+            same = all(torch.equal(a, b) for a, b in zip(ref, [t for t in (acc, out, nxt) if t is not None]))
             t = buf.cpu().numpy()
             t = t[t[:, 0] > 0]
             waves = len(t)
@@ -755,6 +822,10 @@ def timeline_workload(args):
                      "prologue_us_mean": round(float((t[:, 1] - t[:, 0]).mean()) * 0.01, 2),
                      "wave_end_us": {"mean": round(float(end.mean()), 1), "p10": round(float(sorted(end)[waves // 10]), 1),
                                      "p90": round(float(sorted(end)[waves * 9 // 10]), 1), "max": round(float(end.max()), 1)}}
+            ratio = float(t[:, 4].sum()) / float((t[:, 2] - t[:, 0]).sum())
+            if ratio > 1.5:      # s_memtime counts shader cycles
+                entry["clock_ghz"] = round(ratio * 0.1, 3)
+                entry["wave_life_cycles_mean"] = round(float(t[:, 4].mean()))
             if wpw:
                 half = 256 * wpw
                 entry["first_dispatched_workgroups_end_us_mean"] = round(float(end[:half].mean()), 1)
@@ -765,9 +836,70 @@ def timeline_workload(args):
             row["pair balance on" if hint else "pair balance off"] = entry
         probe.qnn_timeline_set(None)
         table[label] = row
-    return {"metric": "wave timeline of the convolution kernel", "value": None, "unit": "us", "n_gpus": 1, "steps": 10, "warmup": 5,
-            "ms_per_step": None, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u32 bit-planes",
-            "data": "synthetic", "config": {"workload": "qnn_conv2d of libqnn_timeline.so, 3x3 stride 1 pad 1"}, "timeline": table}
+    return {"metric": "wave timeline of the convolution kernel", "value": None, "unit": "us", "n_gpus": 1, "steps": 10, "warmup": 0,
+            "settle_ms": SETTLE_MS, "ms_per_step": None, "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u32 bit-planes",
+            "data": "synthetic", "config": {"workload": "qnn_conv2d of libqnn_timeline.so, 3x3 stride 1 pad 1"}, "timeline": table,
+            "level_gemm_timeline": level_gemm_timeline(torch)}
+
+
+def level_gemm_timeline(torch):
+    """Wave timestamps of the matrix-core GEMM at 4096^3 (libqnn_timeline.so): how long prologue, reduction loop and
+    epilogue take, how many shader cycles the loop takes against the 65,536 that its 2048 MFMAs per SIMD need at the
+    instruction's published rate, and the clock the chip holds in the loop -- on zeros, on the levels of 2-bit codes
+    and on random bytes, since the power the matrix cores draw depends on what they multiply."""
+    from paper_1905_13389_amd import probe, qnn
+    size = 4096
+    gen = torch.Generator(device="cuda").manual_seed(190513389)
+    sc = torch.rand(size, device="cuda", generator=gen) + 0.5
+    acc = torch.empty((size, size), dtype=torch.int32, device="cuda")
+    out = torch.empty((size, size), dtype=torch.float32, device="cuda")
+    table = {}
+    for fp4 in (False, True):
+        nb = qnn.qnn_fp4_row_bytes(size) if fp4 else qnn.qnn_level_row_bytes(size)
+        nib = torch.tensor([0xD, 0xA, 0x2, 0x5], dtype=torch.uint8, device="cuda")      # E2M1 codes of -3, -1, 1, 3
+        kinds = [("zeros", lambda: torch.zeros((size, nb), dtype=torch.uint8, device="cuda"))]
+        if fp4:
+            kinds.append(("levels of 2-bit codes", lambda: nib[torch.randint(0, 4, (size, nb), device="cuda", generator=gen)]
+                          | (nib[torch.randint(0, 4, (size, nb), device="cuda", generator=gen)] << 4)))
+        else:
+            kinds.append(("levels of 2-bit codes", lambda: (2 * torch.randint(0, 4, (size, nb), device="cuda", generator=gen) - 3)
+                          .to(torch.int8).view(torch.uint8)))
+            kinds.append(("random bytes", lambda: torch.randint(0, 256, (size, nb), device="cuda", generator=gen).to(torch.uint8)))
+        for kind, make in kinds:
+            a, w = make().contiguous(), make().contiguous()
+            view = (lambda t: t) if fp4 else (lambda t: t.view(torch.int8))
+            ref = (qnn.qnn_level_gemm_fp4 if fp4 else qnn.qnn_level_gemm_i8)(view(a), view(w), size, scale=sc)
+            for outs, pa, po in (("acc + out", acc, out), ("acc only", acc, None)):
+                buf = torch.zeros((256 * 8, 6), dtype=torch.int64, device="cuda")
+                probe.qnn_level_gemm_timeline_set(buf)
+                launch = lambda: probe.timeline_level_gemm(a, w, size, size, size, pa, sc, po, fp4=fp4)  # noqa: E731
+                settle(torch, launch)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    launch()
+                e1.record()
+                torch.cuda.synchronize()
+                same = torch.equal(ref[0], acc) and (po is None or torch.equal(ref[1], out))
+                t = buf.cpu().numpy().astype("float64")
+                base = t[:, 0].min()
+                loop_us = (t[:, 2] - t[:, 1]) * 0.01
+                ratio = t[:, 4].sum() / (t[:, 2] - t[:, 1]).sum()
+                entry = {"us_per_launch_10_back_to_back": round(e0.elapsed_time(e1) * 100, 1), "results_equal_libqnn": bool(same),
+                         "start_spread_us": round(float((t[:, 0] - base).max()) * 0.01, 2),
+                         "prologue_us_mean": round(float((t[:, 1] - t[:, 0]).mean()) * 0.01, 2),
+                         "loop_us": {"mean": round(float(loop_us.mean()), 1), "max": round(float(loop_us.max()), 1)},
+                         "epilogue_us_mean": round(float((t[:, 3] - t[:, 2]).mean()) * 0.01, 2),
+                         "last_wave_ends_us": round(float((t[:, 3] - base).max()) * 0.01, 1)}
+                if ratio > 1.5:          # s_memtime counts shader cycles
+                    entry["clock_in_loop_ghz"] = round(float(ratio) * 0.1, 3)
+                    entry["loop_cycles_mean"] = round(float(t[:, 4].mean()))
+                    mf = 65536.0 / (2 if fp4 else 1)    # 2048 (fp4: 1024) MFMAs per SIMD, 32 cycles each
+                    entry["mfma_cycles_needed"] = round(mf)
+                    entry["matrix_core_busy_in_loop"] = round(mf / float(t[:, 4].mean()), 3)
+                table["%s, %s, %s" % ("fp4" if fp4 else "int8", kind, outs)] = entry
+    probe.qnn_level_gemm_timeline_set(None)
+    return table
 
 
 def fc_workload(args):
@@ -1002,7 +1134,10 @@ def config_summaries(args):
 
 
 def main():
+    global SETTLE_MS
     args = parse()
+    if args.no_settle:
+        SETTLE_MS = 0.0
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by output rows with no "
               "exchange; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
@@ -1146,7 +1281,12 @@ def gemm_workload(args):
             "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel<int8>", "achieved": round(int8_tops, 1),
                          "peak": 5000.0, "unit": "int8 TOP/s", "frac": round(int8_tops / 5000.0, 4),
                          "kernel_ms": round(m_gemm_ms, 4), "probe_mfma_loop": mprobe["int8"],
-                         "frac_of_probe": round(int8_tops / mprobe["int8"], 4)}}
+                         "frac_of_probe": round(int8_tops / mprobe["int8"], 4),
+                         "probe_mfma_loop_by_operand_data": mprobe["by_operand_data"]["int8"],
+                         "frac_of_probe_on_level_operands": round(
+                             int8_tops / mprobe["by_operand_data"]["int8"]["levels_of_2bit_codes"]["tops"], 4),
+                         "clock_note": "the published peak is at 2.4 GHz; under MFMA load the clock the chip holds depends on "
+                                       "the operand data (by_operand_data: the register-only loop on zeros, on levels, on random bytes)"}}
 
     # 1- and 2-bit codes also fit the fp4 matrix-core path (levels -3..3 are exact fp4 values)
     if max(wb, ab) <= 2:
@@ -1183,7 +1323,12 @@ def gemm_workload(args):
             "roofline": {"bound": "mfma", "kernel": "level_gemm_mfma_kernel<fp4>", "achieved": round(fp4_tops, 1),
                          "peak": 10100.0, "unit": "fp4 TFLOP/s", "frac": round(fp4_tops / 10100.0, 4),
                          "kernel_ms": round(f_gemm_ms, 4), "probe_mfma_loop": mprobe["fp4"],
-                         "frac_of_probe": round(fp4_tops / mprobe["fp4"], 4)}}
+                         "frac_of_probe": round(fp4_tops / mprobe["fp4"], 4),
+                         "probe_mfma_loop_by_operand_data": mprobe["by_operand_data"]["fp4"],
+                         "frac_of_probe_on_level_operands": round(
+                             fp4_tops / mprobe["by_operand_data"]["fp4"]["levels_of_2bit_codes"]["tops"], 4),
+                         "clock_note": "the published peak is at 2.4 GHz; under MFMA load the clock the chip holds depends on "
+                                       "the operand data (by_operand_data: the register-only loop on zeros, on levels, on random bytes)"}}
 
     if args.sweep:
         sweep = {}

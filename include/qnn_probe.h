@@ -49,6 +49,19 @@ int qnn_probe_valu(int mode, int workgroups, int iters, uint32_t *out, int64_t *
  */
 int qnn_probe_mfma(int mode, int workgroups, int iters, uint32_t *out, void *stream);
 
+/*
+ * qnn_probe_mfma_operands -- the loop of qnn_probe_mfma on operands the caller supplies, with the two counters of
+ * qnn_probe_valu across it: what the operands hold (zeros, constant bytes, quantization levels, random bytes) decides
+ * how much power the matrix cores draw, and with that the clock the chip holds under the loop.
+ *   mode      as qnn_probe_mfma
+ *   operands  DEVICE, 16-byte aligned, 256 lanes * 8 * 16 bytes = 32 KiB, read by every workgroup: lane t takes 4 A
+ *             operands (16 bytes each: 16 int8 values, or 32 fp4 values) at 128 t and 4 B operands at 128 t + 64
+ *   out       DEVICE, workgroups * 256 uint32
+ *   clocks    DEVICE, workgroups * 4 waves * 2 int64, or NULL: as in qnn_probe_valu
+ */
+int qnn_probe_mfma_operands(int mode, int workgroups, int iters, const void *operands, uint32_t *out, int64_t *clocks,
+                            void *stream);
+
 /* Message for the last error returned on the calling thread ("" if none). Never NULL. */
 const char *qnn_probe_last_error(void);
 
@@ -57,15 +70,32 @@ const char *qnn_probe_last_error(void);
  * arguments and results, declared in qnn.h) compiled with wave timestamps, plus:
  *
  * qnn_timeline_set -- where the convolution kernels launched after this call leave their timestamps.
- *   buffer     DEVICE, waves * 4 int64, owned by the caller, or NULL with waves = 0 (nothing is recorded).  Wave w of
+ *   buffer     DEVICE, waves * 5 int64, owned by the caller, or NULL with waves = 0 (nothing is recorded).  Wave w of
  *              workgroup b of a launch with W waves per workgroup writes entry b W + w if it is below `waves`:
  *              [0] the constant 100 MHz counter (s_memrealtime) at its start, [1] after its workgroup's prologue,
- *              [2] at its end, [3] its hardware ids (XCC id << 32 | HW_ID register).  Every launch overwrites.
+ *              [2] at its end, [3] its hardware ids (XCC id << 32 | HW_ID register), [4] the ticks of the shader's
+ *              cycle counter (s_memtime) across its life: [4] / ([2] - [0]) is the clock it ran at, in units of
+ *              100 MHz.  Every launch overwrites.
  *   pair_hint  0: the two workgroups of a CU run with the hardware's default priorities (for comparison);
  *              otherwise they balance their progress as in libqnn.so
  *   Returns 0, or QNN_ERR_INVALID_ARG.  Host state of the process, not thread safe.
  */
 int qnn_timeline_set(int64_t *buffer, int waves, int pair_hint);
+
+/*
+ * libqnn_timeline.so also holds the matrix-core GEMM of libqnn.so (qnn_level_row_bytes, qnn_plane_sum_i8,
+ * qnn_level_gemm_i8, qnn_fp4_row_bytes, qnn_plane_sum_fp4, qnn_level_gemm_fp4: same arguments and results, declared
+ * in qnn.h) compiled with wave timestamps, plus:
+ *
+ * qnn_level_gemm_timeline_set -- where the level GEMM kernels launched after this call leave their timestamps.
+ *   buffer  DEVICE, waves * 6 int64, owned by the caller, or NULL with waves = 0 (nothing is recorded).  Wave w of
+ *           workgroup b (8 waves per workgroup) writes entry 8 b + w if it is below `waves`: the constant 100 MHz
+ *           counter (s_memrealtime) [0] at its start, [1] at the start and [2] at the end of its reduction loop,
+ *           [3] at its end; the ticks of the shader's cycle counter (s_memtime) [4] across the reduction loop and
+ *           [5] across its life.  [4] / ([2] - [1]) is the clock the chip held in the loop, in units of 100 MHz.
+ *   Returns 0, or QNN_ERR_INVALID_ARG.  Host state of the process, not thread safe.
+ */
+int qnn_level_gemm_timeline_set(int64_t *buffer, int waves);
 
 #ifdef __cplusplus
 }

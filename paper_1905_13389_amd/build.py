@@ -23,8 +23,9 @@ SOURCES = ["qnn_api.hip", "encode_pack.hip", "dequant_scale.hip", "binary_gemm.h
            "level_gemm_mfma.hip", "level_conv_mfma.hip", "maxpool.hip", "ste_backward.hip", "dense.hip", "fc_fused.hip",
            "no_alloc.hip"]
 PROBE_SOURCES = ["probe.hip"]
-# the convolution entry points once more, with wave timestamps (-DQNN_TIMELINE): a diagnostic library of its own
-TIMELINE_SOURCES = ["qnn_api.hip", "conv2d.hip", "conv2d_block.hip"]
+# the convolution entry points and the matrix-core GEMM once more, with wave timestamps (-DQNN_TIMELINE): a
+# diagnostic library of its own
+TIMELINE_SOURCES = ["qnn_api.hip", "conv2d.hip", "conv2d_block.hip", "level_gemm_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

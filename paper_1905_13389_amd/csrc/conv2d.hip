@@ -236,7 +236,7 @@ static int conv_run(const qnn_conv_desc *d, int dilation, const uint32_t *a_plan
 #ifdef QNN_TIMELINE
 extern "C" int qnn_timeline_set(long long *buffer, int waves, int pair_hint)
 {
-    if (waves < 0 || (waves > 0 && !buffer)) return fail(QNN_ERR_INVALID_ARG, "qnn_timeline_set: a buffer of waves x 4 int64 is needed");
+    if (waves < 0 || (waves > 0 && !buffer)) return fail(QNN_ERR_INVALID_ARG, "qnn_timeline_set: a buffer of waves x 5 int64 is needed");
     timeline_state() = {waves > 0 ? buffer : nullptr, waves, pair_hint ? 1 : 0};
     return QNN_OK;
 }

@@ -43,7 +43,7 @@ struct ConvTileParams {
     int pair_hint;
     uint32_t pair_tag;
 #ifdef QNN_TIMELINE
-    long long *timeline; // [timeline_waves][4] or nullptr
+    long long *timeline; // [timeline_waves][5] or nullptr
     int timeline_waves;
 #endif
     // Bit widths above 4 run as up to four launches over chunks of at most 4 planes per operand (the
@@ -141,8 +141,8 @@ template <int LANES> __device__ __forceinline__ uint32_t or_reduce_lanes(uint32_
 // pairing other than the assumed one costs the balance, not correctness.  One copy per translation unit.
 #ifdef QNN_TIMELINE
 // Diagnostic build (libqnn_timeline.so, include/qnn_probe.h): every wave of the convolution kernel leaves the
-// constant-rate counter (100 MHz) at its start, after its workgroup's prologue and at its end, plus its hardware
-// ids, in a caller-owned buffer; the pair balance can be switched off for comparison.  The product library is
+// constant-rate counter (100 MHz) at its start, after its workgroup's prologue and at its end, its hardware ids
+// and the shader-clock counter's ticks across its life, in a caller-owned buffer; the pair balance can be switched off for comparison.  The product library is
 // compiled without any of this.
 struct TimelineState {
     long long *buf;
@@ -188,6 +188,7 @@ bconv_tile_kernel(ConvTileParams p)
 
 #ifdef QNN_TIMELINE
     const long long tl_start = __builtin_amdgcn_s_memrealtime();
+    const unsigned long long tl_clock = __builtin_amdgcn_s_memtime();
     long long tl_loop = 0;
 #endif
     const int tid = threadIdx.x;
@@ -638,8 +639,9 @@ bconv_tile_kernel(ConvTileParams p)
             unsigned xcc = 0, hwid = 0;
             asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
             asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
-            long long *t = p.timeline + 4 * (int64_t)w;
+            long long *t = p.timeline + 5 * (int64_t)w;
             t[0] = tl_start, t[1] = tl_loop, t[2] = tl_end, t[3] = ((long long)xcc << 32) | hwid;
+            t[4] = (long long)(__builtin_amdgcn_s_memtime() - tl_clock);
         }
     }
 #endif

@@ -149,7 +149,37 @@ struct LevelGemmParams {
     const float *scale;
     float *out;
     int64_t tiles_n, tiles_m;
+#ifdef QNN_TIMELINE
+    long long *timeline; // [timeline_waves][6] or nullptr
+    int timeline_waves;
+#endif
 };
+
+#ifdef QNN_TIMELINE
+// Diagnostic build (libqnn_timeline.so, include/qnn_probe.h): every wave leaves the constant-rate counter (100 MHz)
+// at its start, at the start and the end of its reduction loop and at its end, and the shader-clock counter's
+// ticks across the loop and across its life, in a caller-owned buffer.  The product library has none of this.
+struct GemmTimelineState {
+    long long *buf;
+    int waves;
+};
+inline GemmTimelineState &gemm_timeline_state()
+{
+    static GemmTimelineState s = {nullptr, 0};
+    return s;
+}
+#define QNN_TL_REAL(k)                                                                                        \
+    if (p.timeline && lane == 0 && (int64_t)blockIdx.x * (kThreads / 64) + wave < p.timeline_waves)            \
+    p.timeline[6 * ((int64_t)blockIdx.x * (kThreads / 64) + wave) + (k)] = (long long)__builtin_amdgcn_s_memrealtime()
+#define QNN_TL_CLOCK(var) const unsigned long long var = __builtin_amdgcn_s_memtime()
+#define QNN_TL_TICKS(k, from, to)                                                                             \
+    if (p.timeline && lane == 0 && (int64_t)blockIdx.x * (kThreads / 64) + wave < p.timeline_waves)            \
+    p.timeline[6 * ((int64_t)blockIdx.x * (kThreads / 64) + wave) + (k)] = (long long)((to) - (from))
+#else
+#define QNN_TL_REAL(k)
+#define QNN_TL_CLOCK(var)
+#define QNN_TL_TICKS(k, from, to)
+#endif
 
 // s_waitcnt on the vector-memory counter only (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 #define QNN_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
@@ -165,6 +195,8 @@ template <bool FP4> __global__ __launch_bounds__(kThreads) void level_gemm_mfma_
     const int wm = wave / kWavesN, wn = wave % kWavesN;
     const int64_t row0 = ((int64_t)blockIdx.x / p.tiles_n) * kMB;
     const int64_t col0 = ((int64_t)blockIdx.x % p.tiles_n) * kNB;
+    QNN_TL_REAL(0);
+    QNN_TL_CLOCK(tl_c0);
 
     using Acc = typename std::conditional<FP4, v16f, v16i>::type;
     Acc acc[kTM][kTN];
@@ -279,8 +311,12 @@ template <bool FP4> __global__ __launch_bounds__(kThreads) void level_gemm_mfma_
         cur = nxt;
     };
     int64_t s = 0;
+    QNN_TL_REAL(1);
+    QNN_TL_CLOCK(tl_c1);
     for (; s + kRing < nstages; ++s) stage_body(s, std::true_type{});
     for (; s < nstages; ++s) stage_body(s, std::false_type{});
+    QNN_TL_REAL(2);
+    QNN_TL_CLOCK(tl_c2);
 
     // Epilogue.  D layout of the 32x32 MFMA: lane holds column lane % 32 and rows 8 (r / 4) + 4 (lane / 32) +
     // r % 4.  Each 32 x 32 tile goes through a private LDS patch of its wave and leaves row-major, one
@@ -334,6 +370,10 @@ template <bool FP4> __global__ __launch_bounds__(kThreads) void level_gemm_mfma_
             __builtin_amdgcn_wave_barrier(); // the patch is rewritten by the next tile
         }
     }
+    QNN_TL_REAL(3);
+    QNN_TL_CLOCK(tl_c3);
+    QNN_TL_TICKS(4, tl_c1, tl_c2);
+    QNN_TL_TICKS(5, tl_c0, tl_c3);
 }
 
 } // namespace qnn
@@ -386,10 +426,23 @@ extern "C" int qnn_level_gemm_i8(const int8_t *a_levels, const int8_t *w_levels,
     p.acc = acc, p.scale = scale, p.out = out;
     p.tiles_m = ceil_div(rows, kMB), p.tiles_n = ceil_div(cols, kNB);
     if (p.tiles_m * p.tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_gemm_i8: too many tiles");
+#ifdef QNN_TIMELINE
+    p.timeline = gemm_timeline_state().buf, p.timeline_waves = gemm_timeline_state().waves;
+#endif
     hipLaunchKernelGGL(level_gemm_mfma_kernel<false>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), p);
     return check_launch("qnn_level_gemm_i8");
 }
+
+#ifdef QNN_TIMELINE
+extern "C" int qnn_level_gemm_timeline_set(long long *buffer, int waves)
+{
+    if (waves < 0 || (waves > 0 && !buffer))
+        return fail(QNN_ERR_INVALID_ARG, "qnn_level_gemm_timeline_set: a buffer of waves x 6 int64 is needed");
+    gemm_timeline_state() = {waves > 0 ? buffer : nullptr, waves};
+    return QNN_OK;
+}
+#endif
 
 extern "C" int64_t qnn_fp4_row_bytes(int64_t n) { return n < 0 ? -1 : ceil_div(n, 2 * kRowPad) * kRowPad; }
 
@@ -430,6 +483,9 @@ extern "C" int qnn_level_gemm_fp4(const uint8_t *a_levels, const uint8_t *w_leve
     p.acc = acc, p.scale = scale, p.out = out;
     p.tiles_m = ceil_div(rows, kMB), p.tiles_n = ceil_div(cols, kNB);
     if (p.tiles_m * p.tiles_n > 0x7fffffffLL) return fail(QNN_ERR_RANGE, "qnn_level_gemm_fp4: too many tiles");
+#ifdef QNN_TIMELINE
+    p.timeline = gemm_timeline_state().buf, p.timeline_waves = gemm_timeline_state().waves;
+#endif
     hipLaunchKernelGGL(level_gemm_mfma_kernel<true>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(kThreads), 0,
                        static_cast<hipStream_t>(stream), p);
     return check_launch("qnn_level_gemm_fp4");

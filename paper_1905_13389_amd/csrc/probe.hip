@@ -173,6 +173,57 @@ template <int MODE> __global__ __launch_bounds__(256) void mfma_probe_kernel(uin
     out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
 }
 
+// The same loop with operands that the caller supplies: lane t of every workgroup takes the 8 x 16 bytes at
+// operands + 128 t (4 A and 4 B operands); acc[k] += A[u] B[k] for u, k = 0..3.  What the operands hold
+// decides how much the matrix cores' data paths toggle, and with that the power the loop draws and the clock
+// the chip holds under it, which the two counters across the loop give per wave.
+template <int MODE>
+__global__ __launch_bounds__(256) void mfma_operand_probe_kernel(const pv4i *__restrict__ operands, uint32_t *out,
+                                                                  int64_t *clocks, int iters)
+{
+    pv4i a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a[i] = operands[threadIdx.x * 8 + i];
+        b[i] = operands[threadIdx.x * 8 + 4 + i];
+    }
+    using Acc = typename std::conditional<MODE == 0, pv16i, pv16f>::type;
+    Acc acc[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[k][r] = 0;
+    const uint64_t c_begin = __builtin_amdgcn_s_memtime();
+    const uint64_t r_begin = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if constexpr (MODE == 0) {
+                    acc[k] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[u], b[k], acc[k], 0, 0, 0);
+                } else {
+                    const pv8i a8 = __builtin_shufflevector(a[u], a[u], 0, 1, 2, 3, -1, -1, -1, -1);
+                    const pv8i b8 = __builtin_shufflevector(b[k], b[k], 0, 1, 2, 3, -1, -1, -1, -1);
+                    acc[k] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, acc[k], 4, 4, 0, 127, 0, 127);
+                }
+            }
+    }
+    const uint64_t c_end = __builtin_amdgcn_s_memtime();
+    const uint64_t r_end = __builtin_amdgcn_s_memrealtime();
+    uint32_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += (uint32_t)(int)acc[k][r];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
+    if (clocks && (threadIdx.x & 63) == 0) {
+        const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        clocks[2 * wave] = (int64_t)(c_end - c_begin);
+        clocks[2 * wave + 1] = (int64_t)(r_end - r_begin);
+    }
+}
+
 int check_probe_args(const char *what, int mode, int modes, int workgroups, int iters, const void *out)
 {
     if (mode < 0 || mode >= modes) return probe_fail("%s: mode must be in [0,%d]", what, modes - 1);
@@ -201,6 +252,20 @@ extern "C" int qnn_probe_mfma(int mode, int workgroups, int iters, uint32_t *out
     if (mode == 0) hipLaunchKernelGGL(mfma_probe_kernel<0>, grid, block, 0, st, out, iters);
     else hipLaunchKernelGGL(mfma_probe_kernel<1>, grid, block, 0, st, out, iters);
     return check_probe_launch("qnn_probe_mfma");
+}
+
+extern "C" int qnn_probe_mfma_operands(int mode, int workgroups, int iters, const void *operands, uint32_t *out,
+                                       int64_t *clocks, void *stream)
+{
+    if (int rc = check_probe_args("qnn_probe_mfma_operands", mode, 2, workgroups, iters, out)) return rc;
+    if (!operands) return probe_fail("qnn_probe_mfma_operands: NULL operand buffer");
+    if (reinterpret_cast<uintptr_t>(operands) % 16 != 0) return probe_fail("qnn_probe_mfma_operands: operands must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)workgroups), block(256);
+    const pv4i *ops = static_cast<const pv4i *>(operands);
+    if (mode == 0) hipLaunchKernelGGL(mfma_operand_probe_kernel<0>, grid, block, 0, st, ops, out, clocks, iters);
+    else hipLaunchKernelGGL(mfma_operand_probe_kernel<1>, grid, block, 0, st, ops, out, clocks, iters);
+    return check_probe_launch("qnn_probe_mfma_operands");
 }
 
 extern "C" int qnn_probe_valu(int mode, int workgroups, int iters, uint32_t *out, int64_t *clocks, void *stream)

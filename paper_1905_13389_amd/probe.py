@@ -10,9 +10,10 @@ import torch
 from . import build as _build
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqnn_probe.so")
-EXPORTS = ("qnn_probe_valu", "qnn_probe_mfma", "qnn_probe_last_error")
+EXPORTS = ("qnn_probe_valu", "qnn_probe_mfma", "qnn_probe_mfma_operands", "qnn_probe_last_error")
 TIMELINE_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libqnn_timeline.so")
-TIMELINE_EXPORTS = ("qnn_timeline_set", "qnn_conv2d", "qnn_conv2d_block", "qnn_deconv2d", "qnn_last_error")
+TIMELINE_EXPORTS = ("qnn_timeline_set", "qnn_conv2d", "qnn_conv2d_block", "qnn_deconv2d", "qnn_last_error",
+                    "qnn_level_gemm_timeline_set", "qnn_level_gemm_i8", "qnn_level_gemm_fp4")
 _lib = None
 _timeline_lib = None
 
@@ -28,6 +29,8 @@ def lib():
         L.qnn_probe_valu.restype = i32
         L.qnn_probe_mfma.argtypes = [i32, i32, i32, vp, vp]
         L.qnn_probe_mfma.restype = i32
+        L.qnn_probe_mfma_operands.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+        L.qnn_probe_mfma_operands.restype = i32
         L.qnn_probe_last_error.argtypes = []
         L.qnn_probe_last_error.restype = ctypes.c_char_p
         _lib = L
@@ -67,6 +70,22 @@ def qnn_probe_mfma(mode, workgroups, iters, out):
     _check(lib().qnn_probe_mfma(int(mode), int(workgroups), int(iters), _buf("out", out, workgroups * 256), _stream()))
 
 
+def qnn_probe_mfma_operands(mode, workgroups, iters, operands, out, clocks=None):
+    """The MFMA loop on caller-supplied operands; operands: 32 KiB (uint8 [256][8][16]); out: int32 [workgroups * 256];
+    clocks: int64 [workgroups * 4][2] or None."""
+    if not (operands.is_cuda and operands.is_contiguous() and operands.dtype in (torch.uint8, torch.int8)
+            and operands.numel() == 256 * 8 * 16):
+        raise ValueError("operands: a contiguous CUDA byte tensor of 32768 elements is needed")
+    cp = None
+    if clocks is not None:
+        if not (clocks.is_cuda and clocks.is_contiguous() and clocks.dtype == torch.int64
+                and clocks.numel() >= workgroups * 8):
+            raise ValueError("clocks: a contiguous CUDA int64 tensor of at least %d elements is needed" % (workgroups * 8))
+        cp = ctypes.c_void_p(clocks.data_ptr())
+    _check(lib().qnn_probe_mfma_operands(int(mode), int(workgroups), int(iters), ctypes.c_void_p(operands.data_ptr()),
+                                         _buf("out", out, workgroups * 256), cp, _stream()))
+
+
 def timeline_lib():
     global _timeline_lib
     if _timeline_lib is None:
@@ -81,19 +100,25 @@ def timeline_lib():
         L.qnn_conv2d.restype = i32
         L.qnn_last_error.argtypes = []
         L.qnn_last_error.restype = ctypes.c_char_p
+        L.qnn_level_gemm_timeline_set.argtypes = [vp, i32]
+        L.qnn_level_gemm_timeline_set.restype = i32
+        i64 = ctypes.c_int64
+        for fn in (L.qnn_level_gemm_i8, L.qnn_level_gemm_fp4):
+            fn.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp]
+            fn.restype = i32
         _timeline_lib = L
     return _timeline_lib
 
 
 def qnn_timeline_set(buffer, pair_hint=True):
-    """buffer: int64 CUDA tensor [waves][4] (or None: stop recording); see include/qnn_probe.h."""
+    """buffer: int64 CUDA tensor [waves][5] (or None: stop recording); see include/qnn_probe.h."""
     L = timeline_lib()
     if buffer is None:
         rc = L.qnn_timeline_set(None, 0, int(bool(pair_hint)))
     else:
         if not (buffer.is_cuda and buffer.is_contiguous() and buffer.dtype == torch.int64 and buffer.dim() == 2
-                and buffer.shape[1] == 4):
-            raise ValueError("buffer: a contiguous CUDA int64 tensor [waves][4] is needed")
+                and buffer.shape[1] == 5):
+            raise ValueError("buffer: a contiguous CUDA int64 tensor [waves][5] is needed")
         rc = L.qnn_timeline_set(ctypes.c_void_p(buffer.data_ptr()), int(buffer.shape[0]), int(bool(pair_hint)))
     if rc != 0:
         raise RuntimeError("libqnn_timeline error %d: %s" % (rc, L.qnn_last_error().decode()))
@@ -106,5 +131,30 @@ def timeline_conv2d(desc, a_planes, w_planes, scale, acc, out, next_planes, next
     L = timeline_lib()
     rc = L.qnn_conv2d(ctypes.byref(desc), ptr(a_planes), ptr(w_planes), ptr(scale), ptr(acc), ptr(out), ptr(next_planes),
                       float(next_clip), int(next_bits), _stream())
+    if rc != 0:
+        raise RuntimeError("libqnn_timeline error %d: %s" % (rc, L.qnn_last_error().decode()))
+
+
+def qnn_level_gemm_timeline_set(buffer):
+    """buffer: int64 CUDA tensor [waves][6] (or None: stop recording); see include/qnn_probe.h."""
+    L = timeline_lib()
+    if buffer is None:
+        rc = L.qnn_level_gemm_timeline_set(None, 0)
+    else:
+        if not (buffer.is_cuda and buffer.is_contiguous() and buffer.dtype == torch.int64 and buffer.dim() == 2
+                and buffer.shape[1] == 6):
+            raise ValueError("buffer: a contiguous CUDA int64 tensor [waves][6] is needed")
+        rc = L.qnn_level_gemm_timeline_set(ctypes.c_void_p(buffer.data_ptr()), int(buffer.shape[0]))
+    if rc != 0:
+        raise RuntimeError("libqnn_timeline error %d: %s" % (rc, L.qnn_last_error().decode()))
+
+
+def timeline_level_gemm(a_levels, w_levels, rows, cols, n, acc, scale, out, fp4=False):
+    """qnn_level_gemm_i8 / _fp4 of libqnn_timeline.so on tensors the caller has checked (level rows padded as
+    qnn_level_row_bytes / qnn_fp4_row_bytes say); None for an output that is not wanted."""
+    ptr = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())  # noqa: E731
+    L = timeline_lib()
+    fn = L.qnn_level_gemm_fp4 if fp4 else L.qnn_level_gemm_i8
+    rc = fn(ptr(a_levels), ptr(w_levels), int(rows), int(cols), int(n), ptr(acc), ptr(scale), ptr(out), _stream())
     if rc != 0:
         raise RuntimeError("libqnn_timeline error %d: %s" % (rc, L.qnn_last_error().decode()))

@@ -287,11 +287,11 @@ def test_probe_library_exports_and_argument_errors():
     # the issue-rate loops live in a library of their own (include/qnn_probe.h), outside the product library
     from paper_1905_13389_amd import probe
     L = probe.lib()
-    assert set(_declared_in("qnn_probe.h")) == set(probe.EXPORTS) | {"qnn_timeline_set"}
+    assert set(_declared_in("qnn_probe.h")) == set(probe.EXPORTS) | {"qnn_timeline_set", "qnn_level_gemm_timeline_set"}
     for n in probe.EXPORTS:
         assert getattr(L, n) is not None
     product = ctypes.CDLL(os.path.join(os.path.dirname(probe.LIB_PATH), "libqnn.so"))
-    for n in ("qnn_probe_valu", "qnn_probe_mfma", "qnn_timeline_set"):
+    for n in ("qnn_probe_valu", "qnn_probe_mfma", "qnn_probe_mfma_operands", "qnn_timeline_set", "qnn_level_gemm_timeline_set"):
         assert not hasattr(product, n)
     assert L.qnn_probe_valu(99, 1, 1, FAKE, None, None) < 0 and b"mode" in L.qnn_probe_last_error()
     assert L.qnn_probe_valu(0, 0, 1, FAKE, None, None) < 0
@@ -300,6 +300,10 @@ def test_probe_library_exports_and_argument_errors():
     assert L.qnn_probe_mfma(2, 1, 1, FAKE, None) < 0
     assert L.qnn_probe_mfma(0, 70000, 1, FAKE, None) < 0
     assert L.qnn_probe_mfma(0, 1, 1, None, None) < 0
+    assert L.qnn_probe_mfma_operands(2, 1, 1, FAKE, FAKE, None, None) < 0 and b"mode" in L.qnn_probe_last_error()
+    assert L.qnn_probe_mfma_operands(0, 1, 1, None, FAKE, None, None) < 0 and b"operand" in L.qnn_probe_last_error()
+    assert L.qnn_probe_mfma_operands(0, 1, 1, ctypes.c_void_p(FAKE.value + 4), FAKE, None, None) < 0
+    assert L.qnn_probe_mfma_operands(0, 1, 1, FAKE, None, None, None) < 0
 
 
 def test_timeline_library_exports_and_argument_errors():
@@ -314,8 +318,14 @@ def test_timeline_library_exports_and_argument_errors():
     import torch
     with pytest.raises(ValueError):
         probe.qnn_timeline_set(torch.zeros((4, 3), dtype=torch.int64))
-    # its convolution entry point checks its arguments like the product's
+    assert L.qnn_level_gemm_timeline_set(None, 8) < 0 and b"buffer" in L.qnn_last_error()
+    assert L.qnn_level_gemm_timeline_set(FAKE, -1) < 0
+    assert L.qnn_level_gemm_timeline_set(None, 0) == 0
+    with pytest.raises(ValueError):
+        probe.qnn_level_gemm_timeline_set(torch.zeros((4, 4), dtype=torch.int64))
+    # its entry points check their arguments like the product's
     from paper_1905_13389_amd import qnn as q
+    assert L.qnn_level_gemm_i8(FAKE, FAKE, 4, 4, 32, None, None, None, None) == q.QNN_ERR_INVALID_ARG
     assert L.qnn_conv2d(ctypes.byref(q.qnn_conv_desc(1, 8, 8, 64, 64, 3, 3, 0, 1, 2, 2)), FAKE, FAKE, None, FAKE, None, None,
                         0.0, 0, None) == q.QNN_ERR_INVALID_ARG
 
