@@ -180,6 +180,7 @@ bconv_tile_kernel(ConvTileParams p)
     constexpr int W_WORDS = T::STAGE_WORDS - T::A_WORDS;
     __shared__ __attribute__((aligned(16))) uint32_t w_resident[KEEPW ? W_WORDS : 4];
     __shared__ uint32_t tap_table[kMaxGroups];
+    __shared__ unsigned wave_ticket; // one stage: the next piece of this workgroup's work that no wave has taken yet
     __shared__ __attribute__((aligned(16))) float bias_lds[BLK ? BN : 4]; // the column tile's shifts (0 without)
     extern __shared__ __attribute__((aligned(16))) int32_t dyn_smem[];
     int32_t *S = dyn_smem;                                                   // [taps][BN]
@@ -211,12 +212,12 @@ bconv_tile_kernel(ConvTileParams p)
         }
     };
     // stage unit u of this lane: plane and tile row it belongs to, 4-word unit inside the row, LDS word offset
-    auto unit = [&](int u, int &plane, int &trow, int &q, int &lds) {
+    auto unit = [&](int u, int &plane, int &trow, int &q, int &lds, int slice) {
         if constexpr (KEEPW) {
             const int idx = lane + u * 64;
             const int rp = idx / UQ, slot = rp % WR; // rp = plane * WR + row of the wave
             q = idx % UQ, plane = rp / WR;
-            trow = 4 * wave + (slot & 3) + RG * (slot >> 2);
+            trow = 4 * slice + (slot & 3) + RG * (slot >> 2);
             lds = wave * CHUNK + rp * T::BKP + 4 * q;
             return WAVE_UNITS % 64 == 0 || idx < WAVE_UNITS;
         } else {
@@ -248,6 +249,7 @@ bconv_tile_kernel(ConvTileParams p)
         for (int e = tid; e < BN; e += NT)
             bias_lds[e] = p.blk.bias && col0 + e < p.Cout ? p.blk.bias[col0 + e] : 0.0f;
     }
+    if (KEEPW && tid == 0) wave_ticket = NW; // pieces 0 .. NW-1 are the waves' first ones
     // reduction word group -> tap number and word offset from the window origin
     for (int g = tid; g * VW < p.nw; g += NT) {
         const int kword = g * VW;
@@ -288,11 +290,11 @@ bconv_tile_kernel(ConvTileParams p)
     // where this lane's stage units start in the activation planes, and their padded taps
     int abase[A_PT];
     uint32_t apad[A_PT];
-    auto locate = [&](int row0) {
+    auto locate = [&](int row0, int slice) {
 #pragma unroll
         for (int u = 0; u < A_PT; ++u) {
             int plane, trow, q, lds;
-            const bool in_stage = unit(u, plane, trow, q, lds);
+            const bool in_stage = unit(u, plane, trow, q, lds, slice);
             const int m = row0 + trow;
             const bool ok = in_stage && m < p.M;
             const uint32_t mm = ok ? (uint32_t)m : 0u;
@@ -311,7 +313,7 @@ bconv_tile_kernel(ConvTileParams p)
 #pragma unroll
         for (int u = 0; u < A_PT; ++u) {
             int plane, trow, q, lds;
-            unit(u, plane, trow, q, lds);
+            unit(u, plane, trow, q, lds, wave);
             ra[u] = gather4<VW>(p.a, tap_table, 4 * q < p.kb ? p.nw : 0, apad[u], abase[u], k0 + 4 * q);
         }
         if (w_staged) return;
@@ -329,7 +331,7 @@ bconv_tile_kernel(ConvTileParams p)
 #pragma unroll
         for (int u = 0; u < A_PT; ++u) {
             int plane, trow, q, lds;
-            if (unit(u, plane, trow, q, lds)) lds_write_unit<KV>(As + lds, ra[u]);
+            if (unit(u, plane, trow, q, lds, wave)) lds_write_unit<KV>(As + lds, ra[u]);
         }
         if (w_staged) return;
         w_staged = keep_w;
@@ -351,8 +353,8 @@ bconv_tile_kernel(ConvTileParams p)
     constexpr int LPW = 32 / EW;            // lanes per 32-channel plane word
     static_assert(LPR <= 16 && BM % RPP == 0 && BM >= RPP, "a pass row lies inside one 16-lane row group; whole passes");
     // tile row of this lane in pass `pass`: consecutive rows, or (KEEPW) rows its own wave owns
-    auto pass_row = [&](int pass) {
-        return KEEPW ? ty + RG * (pass * (16 / LPR) + (tid & 15) / LPR) : pass * RPP + tid / LPR;
+    auto pass_row = [&](int pass, int slice) {
+        return KEEPW ? 4 * slice + (ty & 3) + RG * (pass * (16 / LPR) + (tid & 15) / LPR) : pass * RPP + tid / LPR;
     };
     const int c4 = (tid % LPR) * EW;
     const int cidx = col0 + c4;
@@ -370,10 +372,28 @@ bconv_tile_kernel(ConvTileParams p)
         __hip_atomic_store(&pair_progress[blockIdx.x], (unsigned long long)p.pair_tag << 32, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
 
+    // This workgroup's work as a sequence of pieces.  Streamed reductions: piece k is row tile rt_first + k step,
+    // done by all waves together.  One stage, where every wave gathers, multiplies and finishes rows of its own:
+    // piece j is the rows of slice j % NW of row tile rt_first + (j / NW) step, and a wave that is through with a
+    // piece takes the next one from a counter in LDS -- a SIMD serves its older waves first, so with fixed shares
+    // the younger waves of a workgroup ended several microseconds after the others and ran the tail alone.
+    auto piece_rt = [&](int piece) { return rt_first + (KEEPW ? piece / NW : piece) * p.row_tile_step; };
+    auto piece_slice = [&](int piece) { return KEEPW ? piece % NW : wave; };
+    auto next_piece = [&](int piece) {
+        if constexpr (KEEPW) {
+            unsigned t = 0;
+            if (lane == 0) t = __hip_atomic_fetch_add(&wave_ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            return (int)__builtin_amdgcn_readfirstlane((int)t);
+        } else {
+            return piece + 1;
+        }
+    };
+
     uint32_t P[TM][TN][T::S];
-    __syncthreads(); // tap_table and S are complete
+    __syncthreads(); // tap_table, S and the counter are complete
     int buf = 0;
-    locate(rt_first * BM);
+    int piece = KEEPW ? wave : 0; // row tile rt_first exists (the grid has at most one workgroup per tile)
+    locate(piece_rt(piece) * BM, piece_slice(piece));
     fetch(0);
     stash(0);
     __syncthreads();
@@ -381,9 +401,10 @@ bconv_tile_kernel(ConvTileParams p)
 #ifdef QNN_TIMELINE
     tl_loop = __builtin_amdgcn_s_memrealtime();
 #endif
-    for (int rt = rt_first; rt < p.tiles_m; rt += p.row_tile_step) {
-        const int row0 = rt * BM;
-        const bool next_tile = rt + p.row_tile_step < p.tiles_m;
+    while (piece_rt(piece) < p.tiles_m) {
+        const int row0 = piece_rt(piece) * BM, slice = piece_slice(piece);
+        const int piece_after = next_piece(piece);
+        const bool next_tile = piece_rt(piece_after) < p.tiles_m;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -396,7 +417,7 @@ bconv_tile_kernel(ConvTileParams p)
             if (more) {
                 fetch((c + 1) * p.kb);
             } else if (next_tile) {
-                locate((rt + p.row_tile_step) * BM);
+                locate(piece_rt(piece_after) * BM, piece_slice(piece_after));
                 fetch(0);
             }
             const int left = p.nw - c * p.kb;
@@ -418,16 +439,22 @@ bconv_tile_kernel(ConvTileParams p)
             if (p.pair_hint) {
                 // behind the partner (as of its word read one stage ago): issue first; level or ahead: default.
                 // A tie goes to the second workgroup of the pair, the first has its age.
-                ++pair_steps;
+                // progress: stages done, or (one stage) pieces the workgroup's waves had taken when this wave last took one
+                if constexpr (KEEPW) pair_steps = (unsigned)piece_after;
+                else ++pair_steps;
                 const unsigned seen_tag = (unsigned)__builtin_amdgcn_readfirstlane((int)(pair_seen >> 32));
                 const unsigned seen_steps = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)pair_seen);
-                if (seen_tag == p.pair_tag && (pair_steps < seen_steps || (pair_steps == seen_steps && second_of_pair)))
+                // (one stage: compared in whole tiles, the unit the partner reports in)
+                const unsigned mine = KEEPW ? pair_steps / NW : pair_steps, theirs = KEEPW ? seen_steps / NW : seen_steps;
+                if (seen_tag == p.pair_tag && (mine < theirs || (mine == theirs && second_of_pair)))
                     __builtin_amdgcn_s_setprio(1);
                 else
                     __builtin_amdgcn_s_setprio(0);
-                if (tid == 0)
+                // one stage: the wave that took a tile's first piece reports
+                if (KEEPW ? lane == 0 && pair_steps % NW == 0 : tid == 0) {
                     __hip_atomic_store(&pair_progress[blockIdx.x], ((unsigned long long)p.pair_tag << 32) | pair_steps,
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
                 pair_seen = __hip_atomic_load(&pair_progress[pair_other], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -454,7 +481,7 @@ bconv_tile_kernel(ConvTileParams p)
             const uint32_t *rq = static_cast<const uint32_t *>(p.blk.res_q);
 #pragma unroll
             for (int ps = 0; ps < NPASS; ++ps) {
-                const int r = row0 + pass_row(ps);
+                const int r = row0 + pass_row(ps, slice);
                 const bool rvalid = r < p.M;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -483,7 +510,7 @@ bconv_tile_kernel(ConvTileParams p)
 
         // ---- second half: padding correction, stores, scale, quantize, plane split ----
         auto do_pass = [&](const int pass, const uint32_t (&rqw)[8], const float4 (&rf)[EQ]) {
-            const int rl = pass_row(pass);
+            const int rl = pass_row(pass, slice);
             const int r = row0 + rl;
             const bool rvalid = r < p.M;
             int32_t v[EW];
@@ -630,6 +657,7 @@ bconv_tile_kernel(ConvTileParams p)
             for (int pass = 0; pass < NPASS; ++pass) do_pass(pass, rq_pre[0], rf_pre[0]);
         }
         tile_sync(); // V's stage is about to be refilled by the next tile's pipeline
+        piece = piece_after;
     }
 #ifdef QNN_TIMELINE
     {
@@ -674,12 +702,17 @@ template <typename K> static int resident_workgroups(K kernel, int threads, size
 // bit, -10 % at 1x3 bit for batch 256; +5 .. +20 % with fewer tiles than that: kOneStageTallTiles); 5 planes 2 x 4
 // with 8-byte LDS reads (-7 .. -13 % against 4 x 4 at 256 lanes); 6 planes stay at 4 x 4 on 256 lanes (2 x 4 at 512
 // lanes: +1 % at 3x3 bit, +6 % at 2x4 bit); 7 and 8 planes 1 x 4 (2 x 4: +10 %).
+// With the waves of a workgroup taking their pieces from a counter (see the kernel), one workgroup of 1024 lanes per
+// CU -- sixteen waves behind one counter, the prologue once per CU -- became worth its while for 2 and for 6 planes
+// (at the sustained clock, 64 -> 64 @56x56, batch 256: 1x1 bit 103 -> 93 us, 3x3 bit 480 -> 444 us with 2 x 4 outputs
+// per lane in place of 4 x 4 at 256 lanes); 3, 4, 5 and 8 planes are as fast or faster at 512 lanes (config 3: 70 us
+// against 78 .. 94).
 template <int WB, int AB> struct ConvPickOneStage { // (TM, TN, KV, NT)
     static constexpr int S = WB + AB;
-    static constexpr int TM = S <= 3 ? 2 : S == 4 ? 1 : S == 5 ? 2 : S == 6 ? 4 : 1;
+    static constexpr int TM = S <= 3 ? 2 : S == 4 ? 1 : S <= 6 ? 2 : 1;
     static constexpr int TN = 4;
     static constexpr int KV = S <= 4 ? 4 : 2;
-    static constexpr int NT = S == 6 ? 256 : 512;
+    static constexpr int NT = S == 2 || S == 6 ? 1024 : 512;
 };
 // 4 planes in all and many row tiles per workgroup
 template <int WB, int AB> struct ConvPickOneStageTall {
