@@ -271,22 +271,6 @@ bconv_tile_kernel(ConvTileParams p)
         }
         ymask[o] = m; // xmask follows ymask
     }
-    // S[t][c] = sum over channels of the weight levels of tap t, from the planes
-    for (int e = tid; e < BN * taps; e += NT) {
-        const int t = e / BN, cl = e % BN;
-        const int c = col0 + cl;
-        int32_t s = 0;
-        if (c < p.Cout) {
-            for (int i = 0; i < WB; ++i) {
-                const uint32_t *wp = wbase + ((int64_t)i * p.Cout + c) * p.nw + t * p.cw;
-                int32_t cnt = 0;
-                for (int k = 0; k < p.cw; ++k) cnt += __builtin_popcount(wp[k]);
-                s += (2 * cnt - p.Cin) << i;
-            }
-        }
-        S[e] = s;
-    }
-
     // where this lane's stage units start in the activation planes, and their padded taps
     int abase[A_PT];
     uint32_t apad[A_PT];
@@ -390,13 +374,29 @@ bconv_tile_kernel(ConvTileParams p)
     };
 
     uint32_t P[TM][TN][T::S];
-    __syncthreads(); // tap_table, S and the counter are complete
+    __syncthreads(); // tap_table, the masks and the counter are complete
     int buf = 0;
     int piece = KEEPW ? wave : 0; // row tile rt_first exists (the grid has at most one workgroup per tile)
     locate(piece_rt(piece) * BM, piece_slice(piece));
     fetch(0);
+    // S[t][c] = sum over channels of the weight levels of tap t, from the planes; its loads travel with those of
+    // the first stage, which are already requested
+    for (int e = tid; e < BN * taps; e += NT) {
+        const int t = e / BN, cl = e % BN;
+        const int c = col0 + cl;
+        int32_t s = 0;
+        if (c < p.Cout) {
+            for (int i = 0; i < WB; ++i) {
+                const uint32_t *wp = wbase + ((int64_t)i * p.Cout + c) * p.nw + t * p.cw;
+                int32_t cnt = 0;
+                for (int k = 0; k < p.cw; ++k) cnt += __builtin_popcount(wp[k]);
+                s += (2 * cnt - p.Cin) << i;
+            }
+        }
+        S[e] = s;
+    }
     stash(0);
-    __syncthreads();
+    __syncthreads(); // S and the first stage are complete
 
 #ifdef QNN_TIMELINE
     tl_loop = __builtin_amdgcn_s_memrealtime();
