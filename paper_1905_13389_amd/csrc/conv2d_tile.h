@@ -119,16 +119,18 @@ template <int LANES> __device__ __forceinline__ uint32_t or_reduce_lanes(uint32_
 // nibbles with three DPP ORs.
 // KEEPW: the reduction fits one stage (nchunks == 1) and the weight stage is written to LDS once per
 // workgroup instead of once per row tile; the two stage buffers then hold activations only.  Nothing
-// else is shared between the waves then, so each wave runs its quarter of every tile on its own: a
-// wave owns the tile rows ty + 16 i of its 4 row groups ty, gathers exactly those rows into its own
-// quarter of a stage buffer, hands its accumulators over through the same quarter, and finishes the
-// rows it owns in the row-major half of the epilogue.  The three workgroup barriers per tile become
-// wave-local ordering points, and the waves of a workgroup drift apart instead of idling together
-// (short reductions spend a large share of a tile outside the xor + bitcount block).
+// else is shared between the waves then, so each wave works on a slice of a tile on its own: the tile
+// rows of 4 row groups (slice s: row groups 4 s .. 4 s + 3), which it gathers into its own share of a
+// stage buffer, hands over through the same share, and finishes in the row-major half of the epilogue.
+// The three workgroup barriers per tile become wave-local ordering points, and the waves of a workgroup
+// drift apart instead of idling together (short reductions spend a large share of a tile outside the
+// xor + bitcount block).  Which slice of which tile a wave does next it takes from a counter in LDS, so
+// the waves that the SIMD serves first do more of the workgroup's rows and all of them end together.
 // BLK: the residual-block terms (bias, shortcut) are part of the epilogue.
-// NT: lanes per workgroup.  Two workgroups share a CU either way (LDS), so 256 lanes run two waves per SIMD with
-// up to 256 registers per lane and 512 lanes four waves with up to 128: the same 16 RG x 16 TN tile, each lane
-// holding half as many rows, and twice as many waves to issue from while others wait.
+// NT: lanes per workgroup.  With 256 or 512 lanes two workgroups share a CU (LDS), so 256 lanes run two waves per
+// SIMD with up to 256 registers per lane and 512 lanes four waves with up to 128: the same 16 RG x 16 TN tile, each
+// lane holding half as many rows, and twice as many waves to issue from while others wait.  1024 lanes (one stage
+// only) are one workgroup per CU: the same four waves per SIMD behind one row counter, one prologue per CU.
 // Progress words of the resident workgroups, one per workgroup: (pair_tag << 32) | reduction stages done.
 // Two persistent workgroups share a CU, and a SIMD issues from its older waves first: left alone, the workgroup
 // that was dispatched first gets about four issue slots out of five, finishes its row tiles long before the
