@@ -28,6 +28,10 @@ CASES = [
     (7, 230, 210, 32, 64, 3, 1, 1, 2, 2),    # 338100 rows, ragged last tile
     (6, 250, 230, 64, 40, 3, 1, 1, 1, 3),    # 345000 rows, ragged channels
     (3, 250, 230, 32, 128, 3, 1, 1, 3, 1),   # two column tiles make up the count
+    # one-stage reductions whose waves take their rows from the workgroup's counter, with more tiles than workgroups
+    (3, 120, 120, 32, 64, 3, 1, 1, 3, 3),    # 6 planes: 1024-lane workgroups, 338 tiles of 128 rows on 256 of them
+    (2, 140, 130, 64, 40, 3, 1, 1, 4, 4),    # 8 planes: 1138 tiles of 32 rows, ragged channels
+    (2, 150, 131, 32, 64, 3, 2, 1, 2, 3),    # 5 planes, stride 2, ragged last tile
 ]
 
 
